@@ -1,0 +1,337 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something
+other than itself (brute force written differently, a library attention, closed
+forms, invariants). No GPU. The paper prints no worked numeric example, so all
+pins are mathematical (see tests/golden/README.md).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_18546_amd import inputs as I
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------
+# An independent brute force: complex-number RoPE, materialised score matrix.
+# ---------------------------------------------------------------------------
+def rope_complex(x, pos, base):
+    """x [..., D] rotated at integer positions pos [...] using complex pairs."""
+    D = x.shape[-1]
+    z = x[..., : D // 2] + 1j * x[..., D // 2:]
+    k = np.arange(D // 2, dtype=np.float64)
+    theta = np.exp(-np.log(base) * 2.0 * k / D)
+    w = np.exp(1j * np.asarray(pos, dtype=np.float64)[..., None] * theta)
+    z = z * w
+    return np.concatenate([z.real, z.imag], axis=-1)
+
+
+def brute_force(w: I.Workload, b: int):
+    """Full [Hq, Nq, L] probability tensor for agent b; returns out, mass."""
+    cfg = w.cfg
+    sel = w.agent_sel(b)
+    Hq, Hkv, D, Nq = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n_new
+    ks = [w.k_pool[g, :, : w.lens[g], :].astype(np.float64) for g in sel]
+    vs = [w.v_pool[g, :, : w.lens[g], :].astype(np.float64) for g in sel]
+    ks.append(np.transpose(w.k_new[b].astype(np.float64), (1, 0, 2)))
+    vs.append(np.transpose(w.v_new[b].astype(np.float64), (1, 0, 2)))
+    K = np.concatenate(ks, axis=1)                       # [Hkv, L, D]
+    V = np.concatenate(vs, axis=1)
+    L = K.shape[1]
+    Lc = L - Nq
+    K = rope_complex(K, np.arange(L)[None, :].repeat(Hkv, 0), cfg.rope_base)
+    Q = np.transpose(w.q[b].astype(np.float64), (1, 0, 2))   # [Hq, Nq, D]
+    Q = rope_complex(Q, (Lc + np.arange(Nq))[None, :].repeat(Hq, 0), cfg.rope_base)
+    Kx = np.repeat(K, Hq // Hkv, axis=0)
+    Vx = np.repeat(V, Hq // Hkv, axis=0)
+    s = np.einsum("hid,hjd->hij", Q, Kx) / math.sqrt(D)
+    jj = np.arange(L)[None, :]
+    ii = np.arange(Nq)[:, None]
+    s = np.where(jj <= Lc + ii, s, -np.inf)
+    p = np.exp(s - s.max(axis=-1, keepdims=True))
+    p = p / p.sum(axis=-1, keepdims=True)
+    out = np.einsum("hij,hjd->ihd", p, Vx)               # [Nq, Hq, D]
+    bounds = np.concatenate([[0], np.cumsum([w.lens[g] for g in sel]), [L]]).astype(int)
+    mass = np.stack([p[:, :, bounds[t]:bounds[t + 1]].sum(-1) for t in range(len(sel) + 1)], -1)
+    return out, np.transpose(mass, (1, 0, 2)), p
+
+
+def run_oracle(O, w: I.Workload, rows=None):
+    return O.attention(w.k_pool, w.v_pool, w.lens, w.sel, w.sel_ptr, w.q, w.k_new, w.v_new,
+                       w.cfg.rope_base, rows=rows)
+
+
+def tiny_cfg(seed, **kw):
+    base = dict(name="tiny", seed=seed, dtype=I.F32, n_agents=2, n_q_heads=4, n_kv_heads=2,
+                head_dim=8, n_groups=6, capacity=5, len_lo=0, len_hi=5, n_sel=3, n_new=4,
+                rope_base=100.0)
+    base.update(kw)
+    return I.Config(**base)
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(8))
+def test_brute_force_tiny(oracle, seed):
+    """Whole path vs the materialised-matrix brute force (ragged lens incl. 0,
+    arbitrary order, GQA 2:1, two agents)."""
+    w = I.make_workload(tiny_cfg(seed))
+    out, mass = run_oracle(oracle, w)
+    for b in range(w.cfg.n_agents):
+        bo, bm, _ = brute_force(w, b)
+        np.testing.assert_allclose(out[b], bo, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(mass[b], bm, rtol=0, atol=1e-12)
+
+
+def test_brute_force_c0(oracle):
+    """The first benchmark configuration itself."""
+    w = I.make_workload(I.CONFIGS["c0"])
+    out, mass = run_oracle(oracle, w)
+    bo, bm, _ = brute_force(w, 0)
+    np.testing.assert_allclose(out[0], bo, atol=1e-12)
+    np.testing.assert_allclose(mass[0], bm, atol=1e-12)
+
+
+def test_plan_golden(oracle):
+    """Offsets of the first configuration as stated in words; ordering of the
+    planning prompt (Appendix B): cached groups first, new tokens last."""
+    lines = [l for l in open(os.path.join(GOLD, "c0_plan.txt")) if not l.startswith("#")]
+    want = np.array(lines[0].split(), dtype=np.int32)
+    first_new, last_new = map(int, lines[1].split())
+    w = I.make_workload(I.CONFIGS["c0"])
+    off = oracle.plan(w.lens, w.sel)
+    assert off.dtype == np.int32 and np.array_equal(off, want)
+    assert off[-1] == first_new and off[-1] + w.cfg.n_new - 1 == last_new
+    kinds = [l.split()[1] for l in open(os.path.join(GOLD, "prompt_order.txt"))
+             if not l.startswith("#")]
+    assert kinds == sorted(kinds, key=lambda k: k != "group")   # groups precede new
+
+
+def test_plan_rejects_bad_id(oracle):
+    with pytest.raises(ValueError):
+        oracle.plan(np.array([1, 2, 3]), [0, 3])
+
+
+def test_rope_known_values(oracle):
+    """Direct values: pair (k, k+D/2) turns counter-clockwise by pos*base^(-2k/D)."""
+    y = oracle.rope(np.array([1.0, 0.0]), 3, 10000.0)
+    np.testing.assert_allclose(y, [math.cos(3.0), math.sin(3.0)], atol=1e-15)
+    y = oracle.rope(np.array([0.0, 1.0, 0.0, 0.0]), 7, 100.0)
+    np.testing.assert_allclose(y, [0.0, math.cos(0.7), 0.0, math.sin(0.7)], atol=1e-15)
+    y = oracle.rope(np.array([0.0, 0.0, 0.0, 2.0]), 5, 100.0)
+    np.testing.assert_allclose(y, [0.0, -2 * math.sin(0.5), 0.0, 2 * math.cos(0.5)], atol=1e-15)
+
+
+def test_rope_group_properties(oracle):
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(16)
+    y = rng.standard_normal(16)
+    np.testing.assert_array_equal(oracle.rope(x, 0, 5e5), x)                 # identity at 0
+    for pos in (1, 17, 8191):
+        assert abs(np.linalg.norm(oracle.rope(x, pos, 5e5)) - np.linalg.norm(x)) < 1e-12
+    np.testing.assert_allclose(oracle.rope(oracle.rope(x, 40, 5e5), 2, 5e5),
+                               oracle.rope(x, 42, 5e5), atol=1e-12)          # R(a)R(b)=R(a+b)
+    d0 = oracle.rope(x, 9, 5e5) @ oracle.rope(y, 4, 5e5)
+    d1 = oracle.rope(x, 1009, 5e5) @ oracle.rope(y, 1004, 5e5)               # shift invariance
+    assert abs(d0 - d1) < 1e-10
+    np.testing.assert_allclose(oracle.rope(x, 123, 5e5),
+                               rope_complex(x[None], np.array([123]), 5e5)[0], atol=1e-12)
+
+
+def test_rows_sum_to_one(oracle):
+    w = I.make_workload(tiny_cfg(11, n_new=7, n_sel=4))
+    _, mass = run_oracle(oracle, w)
+    np.testing.assert_allclose(mass.sum(-1), 1.0, atol=1e-12)
+    red = oracle.reduce_mass(mass)
+    np.testing.assert_allclose(red.sum(-1), w.cfg.n_new * w.cfg.n_q_heads, atol=1e-10)
+
+
+def test_closed_form_zero_keys(oracle):
+    """All keys zero => uniform attention: mass_s = len_s/(Lc+i+1), new bucket
+    (i+1)/(Lc+i+1), output = mean of the visible values."""
+    cfg = tiny_cfg(5, n_agents=1, len_lo=1, n_new=5)
+    w = I.make_workload(cfg)
+    w.k_pool[~np.isnan(w.k_pool)] = 0.0
+    w.k_new[:] = 0.0
+    out, mass = run_oracle(oracle, w)
+    sel = w.agent_sel(0)
+    ls = w.lens[sel].astype(np.float64)
+    Lc = int(ls.sum())
+    vis_v = np.concatenate([w.v_pool[g, :, : w.lens[g], :] for g in sel]
+                           + [np.transpose(w.v_new[0], (1, 0, 2))], axis=1).astype(np.float64)
+    r = cfg.n_q_heads // cfg.n_kv_heads
+    for i in range(cfg.n_new):
+        n = Lc + i + 1
+        want = np.concatenate([ls / n, [(i + 1) / n]])
+        for hq in range(cfg.n_q_heads):
+            np.testing.assert_allclose(mass[0, i, hq], want, atol=1e-14)
+            np.testing.assert_allclose(out[0, i, hq], vis_v[hq // r, :n].mean(0), atol=1e-13)
+
+
+@pytest.mark.parametrize("S", [0, 1])
+def test_single_segment_is_causal_attention(oracle, S):
+    """S <= 1: ordinary causal attention over the concatenated sequence, last
+    Nq rows; checked against torch's scaled_dot_product_attention in float64
+    with an explicit mask and the independent complex RoPE."""
+    cfg = tiny_cfg(21 + S, n_agents=1, n_q_heads=2, n_kv_heads=2, head_dim=16, capacity=9,
+                   len_lo=9, len_hi=9, n_sel=S, n_new=6, rope_base=1e4)
+    w = I.make_workload(cfg)
+    out, mass = run_oracle(oracle, w)
+    sel = w.agent_sel(0)
+    Kseq = [w.k_pool[g].astype(np.float64) for g in sel] + [np.transpose(w.k_new[0], (1, 0, 2))]
+    Vseq = [w.v_pool[g].astype(np.float64) for g in sel] + [np.transpose(w.v_new[0], (1, 0, 2))]
+    K = np.concatenate(Kseq, 1)
+    V = np.concatenate(Vseq, 1).astype(np.float64)
+    L = K.shape[1]
+    Lc = L - cfg.n_new
+    K = rope_complex(K, np.arange(L)[None].repeat(2, 0), cfg.rope_base)
+    Q = rope_complex(np.transpose(w.q[0].astype(np.float64), (1, 0, 2)),
+                     (Lc + np.arange(cfg.n_new))[None].repeat(2, 0), cfg.rope_base)
+    allow = torch.tril(torch.ones(L, L, dtype=torch.bool))[Lc:]
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+        attn_mask=allow)[0]
+    np.testing.assert_allclose(out[0], ref.permute(1, 0, 2).numpy(), atol=1e-12)
+    np.testing.assert_allclose(mass.sum(-1), 1.0, atol=1e-12)
+
+
+def test_gqa_equals_expanded_mha(oracle):
+    cfg = tiny_cfg(31)
+    w = I.make_workload(cfg)
+    out, mass = run_oracle(oracle, w)
+    r = cfg.n_q_heads // cfg.n_kv_heads
+    cfg2 = I.variant(cfg, n_kv_heads=cfg.n_q_heads)
+    w2 = I.Workload(cfg2, w.lens, np.repeat(w.k_pool, r, 1), np.repeat(w.v_pool, r, 1),
+                    w.sel, w.sel_ptr, w.q, np.repeat(w.k_new, r, 2), np.repeat(w.v_new, r, 2))
+    out2, mass2 = run_oracle(oracle, w2)
+    np.testing.assert_allclose(out, out2, atol=1e-13)
+    np.testing.assert_allclose(mass, mass2, atol=1e-13)
+
+
+def test_swapping_equal_length_segments(oracle):
+    """Swapping two equal-length segments in the list equals swapping their
+    pool contents; the masses follow the list order."""
+    cfg = tiny_cfg(41, n_agents=1, len_lo=3, len_hi=3, n_sel=3)
+    w = I.make_workload(cfg, sel_lists=[[4, 0, 2]])
+    out_a, mass_a = run_oracle(oracle, w)
+    w2 = I.make_workload(cfg, sel_lists=[[2, 0, 4]])
+    for a in (w2.k_pool, w2.v_pool):
+        a[[2, 4]] = a[[4, 2]]
+    out_b, mass_b = run_oracle(oracle, w2)
+    np.testing.assert_allclose(out_a, out_b, atol=1e-13)
+    np.testing.assert_allclose(mass_a, mass_b, atol=1e-13)
+    # a genuinely different order changes positions, hence the result
+    w3 = I.make_workload(I.variant(cfg, len_lo=1, len_hi=5), sel_lists=[[4, 0, 2]])
+    w4 = I.make_workload(I.variant(cfg, len_lo=1, len_hi=5), sel_lists=[[0, 4, 2]])
+    o3, _ = run_oracle(oracle, w3)
+    o4, _ = run_oracle(oracle, w4)
+    if w3.lens[4] != w3.lens[0]:
+        assert np.abs(o3 - o4).max() > 1e-6
+
+
+def test_prefill_row_equals_decode_step(oracle):
+    """Row i of an Nq-token prefill equals a one-token call whose cached set is
+    the same segments plus one more segment holding new tokens 0..i-1."""
+    cfg = tiny_cfg(51, n_agents=1, len_lo=1, n_new=5, capacity=6)
+    w = I.make_workload(cfg, sel_lists=[[1, 5, 3]])
+    out, mass = run_oracle(oracle, w)
+    for i in range(1, cfg.n_new):
+        G = cfg.n_groups
+        kp = np.concatenate([w.k_pool, np.full((1,) + w.k_pool.shape[1:], np.nan, np.float32)])
+        vp = np.concatenate([w.v_pool, np.full((1,) + w.v_pool.shape[1:], np.nan, np.float32)])
+        kp[G, :, :i] = np.transpose(w.k_new[0, :i], (1, 0, 2))
+        vp[G, :, :i] = np.transpose(w.v_new[0, :i], (1, 0, 2))
+        lens = np.concatenate([w.lens, [i]]).astype(np.int32)
+        sel = np.array([1, 5, 3, G], dtype=np.int32)
+        o1, m1 = oracle.attention(kp, vp, lens, sel, np.array([0, 4], np.int32),
+                                  w.q[:, i:i + 1], w.k_new[:, i:i + 1], w.v_new[:, i:i + 1],
+                                  cfg.rope_base)
+        np.testing.assert_allclose(o1[0, 0], out[0, i], atol=1e-13)
+        np.testing.assert_allclose(m1[0, 0, :, :3], mass[0, i, :, :3], atol=1e-13)
+        np.testing.assert_allclose(m1[0, 0, :, 3] + m1[0, 0, :, 4], mass[0, i, :, 3], atol=1e-13)
+
+
+def test_dominant_key(oracle):
+    """A key with logit about +50 over the rest takes all the mass."""
+    cfg = tiny_cfg(61, n_agents=1, n_q_heads=2, n_kv_heads=2, len_lo=2, n_new=1)
+    w = I.make_workload(cfg, sel_lists=[[0, 3, 5]])
+    Lc = int(w.lens[[0, 3, 5]].sum())
+    off3 = int(w.lens[0])
+    for h in range(2):
+        qr = rope_complex(w.q[0, 0, h][None].astype(np.float64), np.array([Lc]), cfg.rope_base)[0]
+        # unrotated key whose rotation at its position is parallel to the rotated query
+        k = rope_complex(qr[None], np.array([-(off3 + 1)]), cfg.rope_base)[0]
+        k *= 50.0 * math.sqrt(cfg.head_dim) / (qr @ qr)
+        w.k_pool[3, h, 1] = k.astype(np.float32)
+    out, mass = run_oracle(oracle, w)
+    for h in range(2):
+        assert mass[0, 0, h, 1] > 1 - 1e-12
+        np.testing.assert_allclose(out[0, 0, h], w.v_pool[3, h, 1], atol=1e-10)
+
+
+def test_poisoned_padding_is_never_read(oracle):
+    w = I.make_workload(tiny_cfg(71), poison=True)
+    out, mass = run_oracle(oracle, w)
+    assert np.isfinite(out).all() and np.isfinite(mass).all()
+    w2 = I.make_workload(tiny_cfg(71), poison=False)
+    out2, mass2 = run_oracle(oracle, w2)
+    np.testing.assert_array_equal(out, out2)
+    np.testing.assert_array_equal(mass, mass2)
+
+
+def test_row_subset_matches_full(oracle):
+    w = I.make_workload(tiny_cfg(81, n_new=6))
+    out, mass = run_oracle(oracle, w)
+    rows = np.array([[1, 5, 3], [0, 0, 0], [1, 2, 1], [0, 4, 2]], dtype=np.int32)
+    o, m = run_oracle(oracle, w, rows=rows)
+    for n, (b, i, h) in enumerate(rows):
+        np.testing.assert_array_equal(o[n], out[b, i, h])
+        np.testing.assert_array_equal(m[n], mass[b, i, h])
+
+
+def test_gather_rope_matches_bruteforce_layout(oracle):
+    cfg = tiny_cfg(91, n_agents=1)
+    w = I.make_workload(cfg)
+    sel = w.agent_sel(0)
+    kc, vc = oracle.gather_rope(w.k_pool, w.v_pool, w.lens, sel, w.k_new[0], w.v_new[0],
+                                cfg.rope_base)
+    V = np.concatenate([w.v_pool[g, :, : w.lens[g]] for g in sel]
+                       + [np.transpose(w.v_new[0], (1, 0, 2))], 1)
+    K = np.concatenate([w.k_pool[g, :, : w.lens[g]] for g in sel]
+                       + [np.transpose(w.k_new[0], (1, 0, 2))], 1).astype(np.float64)
+    K = rope_complex(K, np.arange(K.shape[1])[None].repeat(cfg.n_kv_heads, 0), cfg.rope_base)
+    np.testing.assert_array_equal(vc, V.astype(np.float64))
+    np.testing.assert_allclose(kc, K, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# Retrieval knapsack, Eq. (1)
+# ---------------------------------------------------------------------------
+def test_knapsack_trivial_cases(oracle):
+    p = np.array([0.9, 0.2, 0.6, 0.55], dtype=np.float32)
+    lens = [4, 1, 3, 3]
+    assert oracle.knapsack(p, lens, 0.5, 0) == []
+    assert oracle.knapsack(p, lens, 0.5, 100) == [0, 2, 3]          # all with P > threshold
+    assert oracle.knapsack(p, lens, 0.5, 4) == [0]                  # 0.4 beats 0.1 / 0.05
+    assert oracle.knapsack(p, lens, 0.5, 6) == [2, 3] or oracle.knapsack(p, lens, 0.5, 6) == [0]
+    # ties: equal values, equal tokens -> smallest id list
+    p = np.array([0.75, 0.75, 0.75], dtype=np.float32)
+    assert oracle.knapsack(p, [2, 2, 2], 0.5, 4) == [0, 1]
+    # ties in value: fewer tokens wins
+    p = np.array([0.75, 0.625, 0.625], dtype=np.float32)
+    assert oracle.knapsack(p, [5, 2, 2], 0.5, 5) == [1, 2]
+
+
+def test_knapsack_dp_matches_bruteforce(oracle):
+    rng = np.random.default_rng(7)
+    for _ in range(150):
+        n = int(rng.integers(1, 13))
+        p = rng.random(n).astype(np.float32)
+        if rng.random() < 0.5:
+            p = (np.round(p * 8) / 8).astype(np.float32)       # force ties
+        lens = rng.integers(0, 7, n)
+        budget = int(rng.integers(0, 25))
+        assert oracle.knapsack_dp(p, lens, 0.375, budget) == \
+            oracle.knapsack_bruteforce(p, lens, 0.375, budget)
