@@ -1,0 +1,221 @@
+/*
+ * efficientnav.h — C ABI of libefficientnav.so (MI355X / gfx950).
+ *
+ * Attention over discretely cached, retrieval-selected KV segments: the
+ * data-parallel hot path of one planning step of EfficientNav
+ * (arXiv 2510.18546).
+ *
+ *   kv_pool_create              one K/V block per navigation-map group, each
+ *                               prefilled on its own (Section 3.2)
+ *   segment_select[_scored]     which groups enter the prompt, in which order,
+ *                               and where each lands (Section 3.4, Eq. (1))
+ *   gather_rope                 load the selected blocks once per planning
+ *                               step and re-position them (Section 3.2)
+ *   segmented_prefill_attention new prompt tokens attend over
+ *                               [selected segments || themselves]
+ *                               (Appendix A; prompt order of Appendix B)
+ *   segment_attention_mass      attention paid to each group, the clustering
+ *                               signal of Section 3.3
+ *
+ * Conventions
+ *   - Every call returns an en_status; en_last_error() gives the text of the
+ *     calling thread's last failure. Nothing throws, nothing aborts.
+ *   - "dev" pointers are device memory owned by the caller (e.g. the
+ *     data_ptr() of a torch tensor on the GPU); "host" pointers are host
+ *     memory. The library never frees or keeps caller host memory. It keeps
+ *     the pool's k/v device pointers inside the en_pool until it is destroyed.
+ *   - The library owns only small bookkeeping inside its opaque handles (the
+ *     rotary table of a pool, the descriptor block of a plan). These are
+ *     uploaded on first GPU use, so the select calls are pure host code.
+ *   - Kernels are enqueued on the caller's hipStream_t (passed as void*, NULL
+ *     = the default stream). No call synchronises the stream.
+ *   - A pool must outlive its plans. Calls on one handle are serialised by the
+ *     caller; a pool may be read by many plans.
+ *   - Notation: G groups of capacity C token slots, len[g] <= C tokens in use,
+ *     Hq query heads, Hkv KV heads (Hq % Hkv == 0, query head h reads KV head
+ *     h / (Hq/Hkv)), head dimension D in {64, 128}, B agents (independent
+ *     planning steps sharing the pool), S_b selected segments of agent b,
+ *     offset[s] = sum_{j<s} len[sel[j]], L_c = offset[S_b], N_q new tokens at
+ *     positions L_c .. L_c+N_q-1.
+ */
+#ifndef EFFICIENTNAV_H
+#define EFFICIENTNAV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum en_status {
+    EN_OK = 0,
+    EN_ERR_INVALID_ARG = 1,   /* null pointer, negative size, bad enum        */
+    EN_ERR_OUT_OF_RANGE = 2,  /* group id outside [0,G) or len outside [0,C]  */
+    EN_ERR_DUPLICATE = 3,     /* a group twice in one agent's selection       */
+    EN_ERR_CAPACITY = 4,      /* L_c + N_q exceeds max_ctx / buffer too small */
+    EN_ERR_UNSUPPORTED = 5,   /* head_dim, head ratio or dtype not supported  */
+    EN_ERR_DEVICE = 6         /* a HIP call failed; see en_last_error()       */
+} en_status;
+
+typedef enum en_dtype { EN_F32 = 0, EN_BF16 = 1 } en_dtype;
+
+typedef struct en_pool en_pool; /* opaque */
+typedef struct en_plan en_plan; /* opaque */
+
+typedef struct en_pool_desc {
+    int32_t n_groups;   /* G                                                  */
+    int32_t capacity;   /* C                                                  */
+    int32_t n_kv_heads; /* Hkv                                                */
+    int32_t n_q_heads;  /* Hq                                                 */
+    int32_t head_dim;   /* D: 64 or 128                                       */
+    int32_t dtype;      /* en_dtype of pool, Q, new K/V, context and output   */
+    int32_t max_ctx;    /* upper bound on L_c + N_q (rotary table rows)       */
+    int32_t reserved;   /* must be 0                                          */
+    double rope_base;   /* theta_k = rope_base^(-2k/D), pairs (k, k + D/2)    */
+} en_pool_desc;
+
+typedef struct en_plan_info {
+    int32_t n_agents;     /* B                                                */
+    int32_t n_new;        /* N_q                                              */
+    int32_t max_segments; /* max_b S_b                                        */
+    int32_t ctx_stride;   /* token stride of the context buffers (>= every
+                             L_c + N_q, multiple of 64)                       */
+    int32_t max_ctx_len;  /* max_b (L_c + N_q)                                */
+    int32_t n_splits;     /* KV splits the attention kernel will use          */
+    int64_t total_pairs;  /* visible (query,key) pairs over all agents, one
+                             head: sum_b N_q*L_c + N_q(N_q+1)/2               */
+    int64_t total_cached; /* sum_b L_c                                        */
+} en_plan_info;
+
+/* ------------------------------------------------------------------------
+ * Pool of per-group K/V blocks (Section 3.2: the KV cache of each group is
+ * computed individually, so it does not depend on which other groups are
+ * selected or on their order).
+ *   k_dev, v_dev : device, [G, Hkv, C, D] of desc->dtype; keys are stored
+ *                  UNROTATED (no position encoding applied). Rows t >= len[g]
+ *                  are never read.
+ *   len_host     : host, int32 [G]; copied.
+ * Errors: INVALID_ARG (null, non-positive sizes, reserved != 0),
+ *         UNSUPPORTED (D not 64/128, Hq % Hkv != 0, unknown dtype),
+ *         OUT_OF_RANGE (a len outside [0, C]).
+ */
+int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
+                   const int32_t *len_host, en_pool **out);
+
+/* Record that group `group` now holds `len` tokens (the caller has written the
+ * rows; Section 3.2: new objects are appended at the end of their group).
+ * Plans made before the change keep the old length. */
+int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len);
+
+int kv_pool_destroy(en_pool *pool);
+
+/* ------------------------------------------------------------------------
+ * Selection, explicit form: the caller's ordered lists are honoured verbatim
+ * (selection changes the order of context in the prompt, Section 3.2; cached
+ * groups precede the new tokens, Appendix B).
+ *   sel_host     : host, int32, the B lists concatenated
+ *   sel_ptr_host : host, int32 [B+1], list b is sel[sel_ptr[b] .. sel_ptr[b+1])
+ *   n_new        : N_q >= 1 new tokens per agent
+ * Computes, per agent, offset[S_b+1] by exclusive prefix sum of the groups'
+ * lengths. Pure host code. S_b = 0 and len = 0 groups are allowed.
+ * Errors: OUT_OF_RANGE (id), DUPLICATE, CAPACITY (L_c + N_q > max_ctx),
+ *         INVALID_ARG.
+ */
+int segment_select(const en_pool *pool, int32_t n_agents, const int32_t *sel_host,
+                   const int32_t *sel_ptr_host, int32_t n_new, en_plan **out);
+
+/* Selection, retrieval form (Section 3.4, Eq. (1)): maximise
+ * sum_i (P_i - threshold) x_i subject to sum_i len_i x_i <= budget_tokens,
+ * x_i in {0,1}; memory is counted in tokens. The objective is evaluated in
+ * fixed point, value_i = nearest-even((double)P_i - (double)threshold) * 2^32,
+ * so ties are exact; groups with value_i <= 0 are never taken; among optimal
+ * sets the one with fewest tokens wins, then the lexicographically smallest
+ * sorted id list. One agent; ids are emitted in ascending order.
+ *   p_host        : host, float [G]
+ *   sel_out_host  : host, int32 [G] (capacity), receives the ids
+ *   n_sel_out     : receives the count
+ *   out           : may be NULL (selection only); else as segment_select.
+ * Errors: INVALID_ARG (null, budget < 0), CAPACITY.
+ */
+int segment_select_scored(const en_pool *pool, const float *p_host, float threshold,
+                          int64_t budget_tokens, int32_t n_new, int32_t *sel_out_host,
+                          int32_t *n_sel_out, en_plan **out);
+
+int en_plan_get_info(const en_plan *plan, en_plan_info *info);
+
+/* offsets_out_host: int32 [S_b + 1] (offset[S_b] = L_c); n_seg_out: S_b.
+ * Either may be NULL. Exact integers, for bit-exact checks of the gather. */
+int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
+                  int32_t *n_seg_out);
+
+/* Override the number of KV splits chosen by segment_select (>= 1, clamped to
+ * the number of 64-key tiles). Must precede en_workspace_bytes. */
+int en_plan_set_splits(en_plan *plan, int32_t n_splits);
+
+int en_plan_destroy(en_plan *plan);
+
+/* ------------------------------------------------------------------------
+ * Context buffers. gather_rope fills them, the attention kernel reads them.
+ * Both have en_context_bytes(pool, plan) bytes. With T = ctx_stride:
+ *   kc_dev : [B, Hkv, T, D]; row j < L_c is token j - offset[s] of group
+ *            sel[s] with rotary encoding applied at position j; rows
+ *            L_c + j are the new tokens' keys rotated at L_c + j; rows from
+ *            L_c + N_q up to the next multiple of 64 are zero.
+ *   vt_dev : EN_BF16: [B, Hkv, D, T], values transposed (token index
+ *            fastest); token j is stored at column j with bits 2 and 3 of j
+ *            exchanged (the order in which the PV matrix instruction consumes
+ *            keys). EN_F32: [B, Hkv, T, D], plain copy. Padding as above.
+ * Values are bit-exact copies of the pool / new-token values.
+ */
+size_t en_context_bytes(const en_pool *pool, const en_plan *plan);
+
+/* Gather the selected blocks once per planning step (Section 3.2: select,
+ * then load the required KV only once) and apply position encoding at the
+ * concatenated positions.
+ *   k_new_dev, v_new_dev : device, [B, N_q, Hkv, D], keys unrotated
+ * Errors: INVALID_ARG, DEVICE.
+ */
+int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                void *kc_dev, void *vt_dev, void *stream);
+
+/* Bytes of scratch the attention call needs for this plan: per-split running
+ * (max, sum), per-(row, segment) partial sums, and, when n_splits > 1, partial
+ * outputs. */
+size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan);
+
+/* softmax(Q K^T / sqrt(D)) V (Appendix A) of the N_q new tokens over the
+ * gathered context: every cached key is visible, new token i also sees new
+ * tokens j <= i. Q is rotated at L_c + i inside the kernel.
+ *   q_dev   : device, [B, N_q, Hq, D], unrotated
+ *   out_dev : device, [B, N_q, Hq, D]
+ *   ws_dev  : device scratch of at least en_workspace_bytes; it receives the
+ *             raw per-segment sums that segment_attention_mass turns into
+ *             masses. NULL is allowed when the plan has n_splits == 1 and no
+ *             masses are wanted.
+ * Errors: INVALID_ARG, CAPACITY (ws_bytes too small), DEVICE.
+ */
+int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
+                                const void *kc_dev, const void *vt_dev, void *out_dev,
+                                void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Per-segment attention mass (Section 3.3: the attention between newly
+ * detected objects and an existing group) from the scratch left by the
+ * attention call on the same plan and stream.
+ *   reduce = 0 : mass_out_dev float [B, N_q, Hq, Smax+1]; for agent b entry
+ *                s < S_b is the softmax probability mass that (query i,
+ *                head h) puts on segment s, entry S_b the mass on the new
+ *                block, entries beyond are 0; each row sums to 1.
+ *   reduce = 1 : mass_out_dev float [B, Smax+1], the above summed over heads
+ *                and query tokens (divide by Hq*N_q for the average).
+ * Errors: INVALID_ARG, DEVICE.
+ */
+int segment_attention_mass(en_pool *pool, en_plan *plan, const void *ws_dev, int32_t reduce,
+                           float *mass_out_dev, void *stream);
+
+const char *en_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EFFICIENTNAV_H */

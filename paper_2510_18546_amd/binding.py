@@ -1,0 +1,238 @@
+"""ctypes binding over the C ABI of libefficientnav.so (include/efficientnav.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels. torch supplies device memory and the stream; there is no fallback
+of any kind: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+EN_F32, EN_BF16 = 0, 1
+STATUS = {0: "EN_OK", 1: "EN_ERR_INVALID_ARG", 2: "EN_ERR_OUT_OF_RANGE", 3: "EN_ERR_DUPLICATE",
+          4: "EN_ERR_CAPACITY", 5: "EN_ERR_UNSUPPORTED", 6: "EN_ERR_DEVICE"}
+
+EXPORTS = [
+    "kv_pool_create", "kv_pool_set_len", "kv_pool_destroy", "segment_select",
+    "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
+    "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
+    "segmented_prefill_attention", "segment_attention_mass", "en_last_error",
+]
+
+
+class EnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"{STATUS.get(code, code)}: {text}")
+        self.code = code
+
+
+class PoolDesc(C.Structure):
+    _fields_ = [("n_groups", C.c_int32), ("capacity", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("n_q_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32),
+                ("max_ctx", C.c_int32), ("reserved", C.c_int32), ("rope_base", C.c_double)]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [("n_agents", C.c_int32), ("n_new", C.c_int32), ("max_segments", C.c_int32),
+                ("ctx_stride", C.c_int32), ("max_ctx_len", C.c_int32), ("n_splits", C.c_int32),
+                ("total_pairs", C.c_int64), ("total_cached", C.c_int64)]
+
+
+_lib = None
+
+
+def load(path: Optional[str] = None) -> C.CDLL:
+    """Load the built library; build it first only if nothing has been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build()
+    lib = C.CDLL(path)
+    vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+    lib.kv_pool_create.argtypes = [C.POINTER(PoolDesc), vp, vp, i32p, C.POINTER(vp)]
+    lib.kv_pool_set_len.argtypes = [vp, C.c_int32, C.c_int32]
+    lib.kv_pool_destroy.argtypes = [vp]
+    lib.segment_select.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(vp)]
+    lib.segment_select_scored.argtypes = [vp, C.POINTER(C.c_float), C.c_float, C.c_int64, C.c_int32,
+                                          i32p, i32p, C.POINTER(vp)]
+    lib.en_plan_get_info.argtypes = [vp, C.POINTER(PlanInfo)]
+    lib.en_plan_query.argtypes = [vp, C.c_int32, i32p, i32p]
+    lib.en_plan_set_splits.argtypes = [vp, C.c_int32]
+    lib.en_plan_destroy.argtypes = [vp]
+    lib.en_context_bytes.argtypes = [vp, vp]
+    lib.en_context_bytes.restype = C.c_size_t
+    lib.en_workspace_bytes.argtypes = [vp, vp]
+    lib.en_workspace_bytes.restype = C.c_size_t
+    lib.gather_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.segmented_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
+    lib.en_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("en_context_bytes", "en_workspace_bytes", "en_last_error"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise EnError(rc, load().en_last_error().decode())
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ip(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(int(stream))
+
+
+class Pool:
+    """Handle of a KV pool. Keeps the K/V tensors alive."""
+
+    def __init__(self, handle, k, v, desc: PoolDesc):
+        self.handle, self.k, self.v, self.desc = handle, k, v, desc
+
+    def close(self):
+        if self.handle:
+            load().kv_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Plan:
+    def __init__(self, handle, pool: Pool):
+        self.handle, self.pool = handle, pool
+
+    @property
+    def info(self) -> PlanInfo:
+        inf = PlanInfo()
+        _check(load().en_plan_get_info(self.handle, C.byref(inf)))
+        return inf
+
+    def offsets(self, agent: int) -> np.ndarray:
+        n = C.c_int32()
+        _check(load().en_plan_query(self.handle, agent, None, C.byref(n)))
+        off = np.zeros(n.value + 1, dtype=np.int32)
+        _check(load().en_plan_query(self.handle, agent, _ip(off), None))
+        return off
+
+    def set_splits(self, n: int):
+        _check(load().en_plan_set_splits(self.handle, int(n)))
+
+    def close(self):
+        if self.handle:
+            load().en_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def kv_pool_create(k_pool, v_pool, lens, n_q_heads: int, rope_base: float, max_ctx: int,
+                   dtype: Optional[int] = None, k_ptr: Optional[int] = None,
+                   v_ptr: Optional[int] = None, shape: Optional[Sequence[int]] = None) -> Pool:
+    """k_pool, v_pool: torch tensors [G,Hkv,C,D] on the GPU (float32 or bfloat16).
+    For host-only planner use, pass k_pool=v_pool=None with ``shape``, ``dtype``
+    and opaque non-null ``k_ptr``/``v_ptr`` values that are never dereferenced."""
+    if k_pool is not None:
+        import torch
+        assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.shape == v_pool.shape
+        shape = tuple(k_pool.shape)
+        dtype = EN_BF16 if k_pool.dtype == torch.bfloat16 else EN_F32
+        k_ptr, v_ptr = k_pool.data_ptr(), v_pool.data_ptr()
+    G, Hkv, Cap, D = shape
+    desc = PoolDesc(G, Cap, Hkv, n_q_heads, D, dtype, max_ctx, 0, rope_base)
+    lens = _i32(lens)
+    h = C.c_void_p()
+    _check(load().kv_pool_create(C.byref(desc), C.c_void_p(k_ptr), C.c_void_p(v_ptr), _ip(lens),
+                                 C.byref(h)))
+    return Pool(h, k_pool, v_pool, desc)
+
+
+def kv_pool_set_len(pool: Pool, group: int, length: int):
+    _check(load().kv_pool_set_len(pool.handle, group, length))
+
+
+def segment_select(pool: Pool, sel, sel_ptr, n_new: int) -> Plan:
+    sel, sel_ptr = _i32(sel), _i32(sel_ptr)
+    h = C.c_void_p()
+    _check(load().segment_select(pool.handle, len(sel_ptr) - 1, _ip(sel), _ip(sel_ptr), n_new,
+                                 C.byref(h)))
+    return Plan(h, pool)
+
+
+def segment_select_scored(pool: Pool, p, threshold: float, budget_tokens: int, n_new: int,
+                          want_plan: bool = True) -> Tuple[np.ndarray, Optional[Plan]]:
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    out = np.zeros(pool.desc.n_groups, dtype=np.int32)
+    n = C.c_int32()
+    h = C.c_void_p()
+    _check(load().segment_select_scored(pool.handle, p.ctypes.data_as(C.POINTER(C.c_float)),
+                                        C.c_float(threshold), C.c_int64(int(budget_tokens)), n_new,
+                                        _ip(out), C.byref(n), C.byref(h) if want_plan else None))
+    return out[:n.value].copy(), (Plan(h, pool) if want_plan else None)
+
+
+def context_bytes(pool: Pool, plan: Plan) -> int:
+    return int(load().en_context_bytes(pool.handle, plan.handle))
+
+
+def workspace_bytes(pool: Pool, plan: Plan) -> int:
+    return int(load().en_workspace_bytes(pool.handle, plan.handle))
+
+
+def alloc_context(pool: Pool, plan: Plan):
+    """Uninitialised context buffers (kc, vt) as flat byte tensors."""
+    import torch
+    n = context_bytes(pool, plan)
+    dev = pool.k.device
+    return (torch.empty(n, dtype=torch.uint8, device=dev), torch.empty(n, dtype=torch.uint8, device=dev))
+
+
+def alloc_workspace(pool: Pool, plan: Plan):
+    import torch
+    return torch.empty(max(workspace_bytes(pool, plan), 256), dtype=torch.uint8, device=pool.k.device)
+
+
+def gather_rope(pool: Pool, plan: Plan, k_new, v_new, kc, vt, stream=None):
+    _check(load().gather_rope(pool.handle, plan.handle, k_new.data_ptr(), v_new.data_ptr(),
+                              kc.data_ptr(), vt.data_ptr(), _stream(stream)))
+    return kc, vt
+
+
+def segmented_prefill_attention(pool: Pool, plan: Plan, q, kc, vt, out, ws=None, stream=None):
+    _check(load().segmented_prefill_attention(
+        pool.handle, plan.handle, q.data_ptr(), kc.data_ptr(), vt.data_ptr(), out.data_ptr(),
+        ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream(stream)))
+    return out
+
+
+def segment_attention_mass(pool: Pool, plan: Plan, ws, reduce: int, mass_out, stream=None):
+    _check(load().segment_attention_mass(pool.handle, plan.handle, ws.data_ptr(), int(reduce),
+                                         mass_out.data_ptr(), _stream(stream)))
+    return mass_out

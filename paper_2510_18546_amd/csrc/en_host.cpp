@@ -1,0 +1,548 @@
+// Host side of libefficientnav.so: handles, the planner (validation, prefix
+// sums, split choice), the retrieval knapsack of Section 3.4 Eq. (1), and the
+// C ABI entry points that marshal arguments into kernel launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "en_internal.h"
+
+// ---------------------------------------------------------------------------
+// error text
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+void en_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *en_last_error(void) { return g_err; }
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int hip_fail(hipError_t e, const char *what)
+{
+    return fail(EN_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+static inline size_t elem_size(int dtype) { return dtype == EN_BF16 ? 2 : 4; }
+
+// ---------------------------------------------------------------------------
+// pool
+// ---------------------------------------------------------------------------
+extern "C" int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
+                              const int32_t *len_host, en_pool **out)
+{
+    if (!desc || !k_dev || !v_dev || !len_host || !out)
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_create: null argument");
+    *out = nullptr;
+    if (desc->n_groups <= 0 || desc->capacity <= 0 || desc->n_kv_heads <= 0 ||
+        desc->n_q_heads <= 0 || desc->max_ctx <= 0 || desc->reserved != 0 ||
+        !(desc->rope_base > 0.0))
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_create: non-positive size, reserved != 0 or bad rope_base");
+    if (desc->dtype != EN_F32 && desc->dtype != EN_BF16)
+        return fail(EN_ERR_UNSUPPORTED, "kv_pool_create: dtype %d", desc->dtype);
+    if (desc->head_dim != 64 && desc->head_dim != 128)
+        return fail(EN_ERR_UNSUPPORTED, "kv_pool_create: head_dim %d (64 or 128)", desc->head_dim);
+    if (desc->n_q_heads % desc->n_kv_heads != 0)
+        return fail(EN_ERR_UNSUPPORTED, "kv_pool_create: n_q_heads %% n_kv_heads != 0");
+    for (int g = 0; g < desc->n_groups; ++g)
+        if (len_host[g] < 0 || len_host[g] > desc->capacity)
+            return fail(EN_ERR_OUT_OF_RANGE, "kv_pool_create: len[%d] = %d outside [0, %d]", g,
+                        len_host[g], desc->capacity);
+    en_pool *p = new (std::nothrow) en_pool;
+    if (!p)
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_create: out of host memory");
+    p->d = *desc;
+    p->k_dev = k_dev;
+    p->v_dev = v_dev;
+    p->len.assign(len_host, len_host + desc->n_groups);
+    p->r = desc->n_q_heads / desc->n_kv_heads;
+    *out = p;
+    return EN_OK;
+}
+
+extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
+{
+    if (!pool)
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_set_len: null pool");
+    if (group < 0 || group >= pool->d.n_groups || len < 0 || len > pool->d.capacity)
+        return fail(EN_ERR_OUT_OF_RANGE, "kv_pool_set_len: group %d len %d", group, len);
+    pool->len[group] = len;
+    return EN_OK;
+}
+
+extern "C" int kv_pool_destroy(en_pool *pool)
+{
+    if (!pool)
+        return EN_OK;
+    if (pool->d_cos)
+        (void)hipFree(pool->d_cos);
+    if (pool->d_sin)
+        (void)hipFree(pool->d_sin);
+    delete pool;
+    return EN_OK;
+}
+
+// Rotary table: cos/sin(pos * base^(-2k/D)) evaluated in double, stored as
+// float, [max_ctx, D/2]. Built once per pool on first GPU use.
+static int pool_ensure_device(en_pool *p)
+{
+    if (p->d_cos)
+        return EN_OK;
+    const int half = p->d.head_dim / 2;
+    const size_t n = size_t(p->d.max_ctx) * half;
+    std::vector<float> c(n), s(n);
+    std::vector<double> theta(half);
+    for (int k = 0; k < half; ++k)
+        theta[k] = std::pow(p->d.rope_base, -2.0 * double(k) / double(p->d.head_dim));
+    for (int pos = 0; pos < p->d.max_ctx; ++pos)
+        for (int k = 0; k < half; ++k) {
+            const double a = double(pos) * theta[k];
+            c[size_t(pos) * half + k] = float(std::cos(a));
+            s[size_t(pos) * half + k] = float(std::sin(a));
+        }
+    hipError_t e;
+    if ((e = hipMalloc((void **)&p->d_cos, n * sizeof(float))) != hipSuccess)
+        return hip_fail(e, "hipMalloc(rotary table)");
+    if ((e = hipMalloc((void **)&p->d_sin, n * sizeof(float))) != hipSuccess)
+        return hip_fail(e, "hipMalloc(rotary table)");
+    if ((e = hipMemcpy(p->d_cos, c.data(), n * sizeof(float), hipMemcpyHostToDevice)) != hipSuccess)
+        return hip_fail(e, "hipMemcpy(rotary table)");
+    if ((e = hipMemcpy(p->d_sin, s.data(), n * sizeof(float), hipMemcpyHostToDevice)) != hipSuccess)
+        return hip_fail(e, "hipMemcpy(rotary table)");
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        p->n_cu = prop.multiProcessorCount;
+    return EN_OK;
+}
+
+// ---------------------------------------------------------------------------
+// planner
+// ---------------------------------------------------------------------------
+static int choose_splits(const en_pool *pool, const en_plan *pl)
+{
+    // One workgroup covers 4 (head, 32-query block) pairs of one KV head. Split
+    // the key range until about two workgroups per compute unit exist, keeping
+    // at least four key tiles per split.
+    const int r = pool->r;
+    const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
+    const int n_ptiles = (r * nqb + EN_WAVES - 1) / EN_WAVES;
+    const long base = long(pl->B) * pool->d.n_kv_heads * n_ptiles;
+    const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
+    long want = (2L * pool->n_cu + base - 1) / base;
+    want = std::min<long>(want, std::max(1, tiles / 4));
+    want = std::max<long>(1, std::min<long>(want, 64));
+    return int(want);
+}
+
+static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const int32_t *sel_ptr,
+                      int32_t n_new, en_plan **out)
+{
+    if (!pool || !sel_ptr || !out || (B > 0 && !sel && sel_ptr[B] > 0))
+        return fail(EN_ERR_INVALID_ARG, "segment_select: null argument");
+    *out = nullptr;
+    if (B <= 0 || n_new <= 0)
+        return fail(EN_ERR_INVALID_ARG, "segment_select: n_agents and n_new must be positive");
+    if (sel_ptr[0] != 0)
+        return fail(EN_ERR_INVALID_ARG, "segment_select: sel_ptr[0] != 0");
+    int Smax = 0;
+    for (int b = 0; b < B; ++b) {
+        if (sel_ptr[b + 1] < sel_ptr[b])
+            return fail(EN_ERR_INVALID_ARG, "segment_select: sel_ptr not monotone at agent %d", b);
+        Smax = std::max(Smax, sel_ptr[b + 1] - sel_ptr[b]);
+    }
+    const int G = pool->d.n_groups;
+    en_plan *pl = new (std::nothrow) en_plan;
+    if (!pl)
+        return fail(EN_ERR_INVALID_ARG, "segment_select: out of host memory");
+    pl->pool = pool;
+    pl->B = B;
+    pl->Nq = n_new;
+    pl->Smax = Smax;
+    pl->nseg.assign(B, 0);
+    pl->sel.assign(size_t(B) * std::max(Smax, 1), -1);
+    pl->bnd.assign(size_t(B) * (Smax + 2), 0);
+    std::vector<int32_t> seen(G, -1);
+    const int sstr = std::max(Smax, 1);
+    for (int b = 0; b < B; ++b) {
+        const int S = sel_ptr[b + 1] - sel_ptr[b];
+        pl->nseg[b] = S;
+        int64_t acc = 0;
+        int32_t *bnd = &pl->bnd[size_t(b) * (Smax + 2)];
+        for (int s = 0; s < S; ++s) {
+            const int g = sel[sel_ptr[b] + s];
+            if (g < 0 || g >= G) {
+                delete pl;
+                return fail(EN_ERR_OUT_OF_RANGE, "segment_select: agent %d entry %d: group %d outside [0,%d)",
+                            b, s, g, G);
+            }
+            if (seen[g] == b) {
+                delete pl;
+                return fail(EN_ERR_DUPLICATE, "segment_select: agent %d selects group %d twice", b, g);
+            }
+            seen[g] = b;
+            pl->sel[size_t(b) * sstr + s] = g;
+            bnd[s] = int32_t(acc);
+            acc += pool->len[g];
+            if (acc + n_new > pool->d.max_ctx) {
+                delete pl;
+                return fail(EN_ERR_CAPACITY, "segment_select: agent %d: L_c + N_q exceeds max_ctx %d", b,
+                            pool->d.max_ctx);
+            }
+        }
+        if (acc + n_new > pool->d.max_ctx) {
+            delete pl;
+            return fail(EN_ERR_CAPACITY, "segment_select: agent %d: L_c + N_q = %lld exceeds max_ctx %d", b,
+                        (long long)(acc + n_new), pool->d.max_ctx);
+        }
+        bnd[S] = int32_t(acc);
+        for (int s = S + 1; s < Smax + 2; ++s)
+            bnd[s] = int32_t(acc + n_new);
+        pl->max_ctx_len = std::max<int>(pl->max_ctx_len, int(acc + n_new));
+        pl->total_cached += acc;
+        pl->total_pairs += int64_t(n_new) * acc + int64_t(n_new) * (n_new + 1) / 2;
+    }
+    pl->ctx_stride = round_up(pl->max_ctx_len, EN_KEY_TILE);
+    pl->n_splits = choose_splits(pool, pl);
+    *out = pl;
+    return EN_OK;
+}
+
+extern "C" int segment_select(const en_pool *pool, int32_t n_agents, const int32_t *sel_host,
+                              const int32_t *sel_ptr_host, int32_t n_new, en_plan **out)
+{
+    return build_plan(pool, n_agents, sel_host, sel_ptr_host, n_new, out);
+}
+
+// Eq. (1) as an exact 0/1 knapsack over token capacity.
+extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, float threshold,
+                                     int64_t budget_tokens, int32_t n_new, int32_t *sel_out_host,
+                                     int32_t *n_sel_out, en_plan **out)
+{
+    if (!pool || !p_host || !sel_out_host || !n_sel_out)
+        return fail(EN_ERR_INVALID_ARG, "segment_select_scored: null argument");
+    if (budget_tokens < 0)
+        return fail(EN_ERR_INVALID_ARG, "segment_select_scored: negative budget");
+    if (out)
+        *out = nullptr;
+    const int G = pool->d.n_groups;
+    struct Item { int id; int64_t v; int w; };
+    std::vector<Item> items;
+    int64_t wsum = 0;
+    for (int g = 0; g < G; ++g) {
+        const double d = double(p_host[g]) - double(threshold);
+        const int64_t v = (int64_t)std::nearbyint(d * 4294967296.0);   // ties to even
+        if (v > 0) {
+            items.push_back({g, v, pool->len[g]});
+            wsum += pool->len[g];
+        }
+    }
+    const int m = int(items.size());
+    const int64_t W = std::min<int64_t>(budget_tokens, wsum);
+    std::vector<int32_t> chosen;
+    if (wsum <= budget_tokens) {
+        for (auto &it : items)
+            chosen.push_back(it.id);
+    } else {
+        // best[a][w] over items a.. with capacity w: maximal value, then minimal
+        // tokens (two rolling rows). take[a][w] records whether taking item a is
+        // optimal at that state, ties included, so that the walk from item 0
+        // prefers the lowest ids (lexicographically smallest sorted list).
+        const size_t cols = size_t(W) + 1;
+        std::vector<int64_t> vcur(cols, 0), vnext(cols, 0);
+        std::vector<int32_t> tcur(cols, 0), tnext(cols, 0);
+        const size_t words = (cols + 63) / 64;
+        std::vector<uint64_t> take(size_t(m) * words, 0);
+        for (int a = m - 1; a >= 0; --a) {
+            const int64_t vi = items[a].v;
+            const int wi = items[a].w;
+            uint64_t *tk = &take[size_t(a) * words];
+            for (int64_t w = 0; w <= W; ++w) {
+                int64_t bv = vnext[w];
+                int32_t bt = tnext[w];
+                if (wi <= w) {
+                    const int64_t tv = vnext[w - wi] + vi;
+                    const int32_t tt = tnext[w - wi] + wi;
+                    if (tv > bv || (tv == bv && tt <= bt)) {
+                        bv = tv;
+                        bt = tt;
+                        tk[w >> 6] |= uint64_t(1) << (w & 63);
+                    }
+                }
+                vcur[w] = bv;
+                tcur[w] = bt;
+            }
+            vcur.swap(vnext);
+            tcur.swap(tnext);
+        }
+        int64_t w = W;
+        for (int a = 0; a < m; ++a) {
+            if (take[size_t(a) * words + (w >> 6)] >> (w & 63) & 1) {
+                chosen.push_back(items[a].id);
+                w -= items[a].w;
+            }
+        }
+    }
+    *n_sel_out = int32_t(chosen.size());
+    std::copy(chosen.begin(), chosen.end(), sel_out_host);
+    if (!out)
+        return EN_OK;
+    const int32_t ptr[2] = {0, int32_t(chosen.size())};
+    return build_plan(pool, 1, chosen.data(), ptr, n_new, out);
+}
+
+extern "C" int en_plan_get_info(const en_plan *plan, en_plan_info *info)
+{
+    if (!plan || !info)
+        return fail(EN_ERR_INVALID_ARG, "en_plan_get_info: null argument");
+    info->n_agents = plan->B;
+    info->n_new = plan->Nq;
+    info->max_segments = plan->Smax;
+    info->ctx_stride = plan->ctx_stride;
+    info->max_ctx_len = plan->max_ctx_len;
+    info->n_splits = plan->n_splits;
+    info->total_pairs = plan->total_pairs;
+    info->total_cached = plan->total_cached;
+    return EN_OK;
+}
+
+extern "C" int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
+                             int32_t *n_seg_out)
+{
+    if (!plan)
+        return fail(EN_ERR_INVALID_ARG, "en_plan_query: null plan");
+    if (agent < 0 || agent >= plan->B)
+        return fail(EN_ERR_OUT_OF_RANGE, "en_plan_query: agent %d outside [0,%d)", agent, plan->B);
+    const int S = plan->nseg[agent];
+    if (n_seg_out)
+        *n_seg_out = S;
+    if (offsets_out_host)
+        std::memcpy(offsets_out_host, &plan->bnd[size_t(agent) * (plan->Smax + 2)],
+                    sizeof(int32_t) * size_t(S + 1));
+    return EN_OK;
+}
+
+extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
+{
+    if (!plan || n_splits < 1)
+        return fail(EN_ERR_INVALID_ARG, "en_plan_set_splits: null plan or n_splits < 1");
+    const int tiles = std::max(1, (plan->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
+    plan->n_splits = std::min(n_splits, tiles);
+    return EN_OK;
+}
+
+extern "C" int en_plan_destroy(en_plan *plan)
+{
+    if (!plan)
+        return EN_OK;
+    if (plan->d_desc)
+        (void)hipFree(plan->d_desc);
+    delete plan;
+    return EN_OK;
+}
+
+static int plan_ensure_device(en_plan *pl, hipStream_t stream)
+{
+    if (pl->uploaded)
+        return EN_OK;
+    const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size();
+    std::vector<int32_t> host;
+    host.reserve(n);
+    host.insert(host.end(), pl->nseg.begin(), pl->nseg.end());
+    host.insert(host.end(), pl->sel.begin(), pl->sel.end());
+    host.insert(host.end(), pl->bnd.begin(), pl->bnd.end());
+    hipError_t e;
+    if ((e = hipMalloc((void **)&pl->d_desc, n * sizeof(int32_t))) != hipSuccess)
+        return hip_fail(e, "hipMalloc(plan descriptors)");
+    // Pageable source: the copy is staged before the call returns, so the
+    // temporary vector may go away; ordering on `stream` is kept.
+    if ((e = hipMemcpyAsync(pl->d_desc, host.data(), n * sizeof(int32_t), hipMemcpyHostToDevice,
+                            stream)) != hipSuccess)
+        return hip_fail(e, "hipMemcpyAsync(plan descriptors)");
+    if ((e = hipStreamSynchronize(stream)) != hipSuccess)
+        return hip_fail(e, "hipStreamSynchronize(plan descriptors)");
+    pl->uploaded = true;
+    return EN_OK;
+}
+
+static inline const int32_t *d_nseg(const en_plan *pl) { return pl->d_desc; }
+static inline const int32_t *d_sel(const en_plan *pl) { return pl->d_desc + pl->nseg.size(); }
+static inline const int32_t *d_bnd(const en_plan *pl)
+{
+    return pl->d_desc + pl->nseg.size() + pl->sel.size();
+}
+
+// ---------------------------------------------------------------------------
+// sizes
+// ---------------------------------------------------------------------------
+extern "C" size_t en_context_bytes(const en_pool *pool, const en_plan *plan)
+{
+    if (!pool || !plan)
+        return 0;
+    return size_t(plan->B) * pool->d.n_kv_heads * plan->ctx_stride * pool->d.head_dim *
+           elem_size(pool->d.dtype);
+}
+
+EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *pl)
+{
+    EnWsLayout L;
+    const size_t rows = size_t(pl->B) * pool->d.n_q_heads * pl->Nq;
+    L.ml_off = 0;
+    L.seg_off = align256(L.ml_off + size_t(pl->n_splits) * rows * 2 * sizeof(float));
+    L.opart_off = align256(L.seg_off + size_t(pl->n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
+    L.total = L.opart_off;
+    if (pl->n_splits > 1)
+        L.total = align256(L.opart_off + size_t(pl->n_splits) * rows * pool->d.head_dim * sizeof(float));
+    return L;
+}
+
+extern "C" size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan)
+{
+    if (!pool || !plan)
+        return 0;
+    return en_ws_layout(pool, plan).total;
+}
+
+// ---------------------------------------------------------------------------
+// GPU entry points
+// ---------------------------------------------------------------------------
+extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                           void *kc_dev, void *vt_dev, void *stream)
+{
+    if (!pool || !plan || !k_new_dev || !v_new_dev || !kc_dev || !vt_dev)
+        return fail(EN_ERR_INVALID_ARG, "gather_rope: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "gather_rope: plan belongs to another pool");
+    int rc;
+    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+        return rc;
+    EnGatherArgs a;
+    a.k_pool = pool->k_dev;
+    a.v_pool = pool->v_dev;
+    a.k_new = k_new_dev;
+    a.v_new = v_new_dev;
+    a.kc = kc_dev;
+    a.vt = vt_dev;
+    a.cos_tab = pool->d_cos;
+    a.sin_tab = pool->d_sin;
+    a.nseg = d_nseg(plan);
+    a.sel = d_sel(plan);
+    a.bnd = d_bnd(plan);
+    a.B = plan->B;
+    a.Hkv = pool->d.n_kv_heads;
+    a.C = pool->d.capacity;
+    a.Nq = plan->Nq;
+    a.Smax = plan->Smax;
+    a.T = plan->ctx_stride;
+    const int e = en_launch_gather(pool, a, plan->max_ctx_len, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "gather_rope launch");
+    return EN_OK;
+}
+
+extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
+                                           const void *kc_dev, const void *vt_dev, void *out_dev,
+                                           void *ws_dev, size_t ws_bytes, void *stream)
+{
+    if (!pool || !plan || !q_dev || !kc_dev || !vt_dev || !out_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: plan belongs to another pool");
+    const EnWsLayout L = en_ws_layout(pool, plan);
+    if (!ws_dev && plan->n_splits > 1)
+        return fail(EN_ERR_INVALID_ARG,
+                    "segmented_prefill_attention: workspace required when the plan has %d splits",
+                    plan->n_splits);
+    if (ws_dev && ws_bytes < L.total)
+        return fail(EN_ERR_CAPACITY, "segmented_prefill_attention: workspace %zu < %zu bytes", ws_bytes,
+                    L.total);
+    if (ws_dev && (reinterpret_cast<uintptr_t>(ws_dev) & 15))
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: workspace must be 16-byte aligned");
+    int rc;
+    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+        return rc;
+    EnAttnArgs a;
+    a.q = q_dev;
+    a.kc = kc_dev;
+    a.vt = vt_dev;
+    a.out = out_dev;
+    a.cos_tab = pool->d_cos;
+    a.sin_tab = pool->d_sin;
+    a.nseg = d_nseg(plan);
+    a.bnd = d_bnd(plan);
+    char *ws = static_cast<char *>(ws_dev);
+    a.ws_ml = ws ? reinterpret_cast<float *>(ws + L.ml_off) : nullptr;
+    a.ws_seg = ws ? reinterpret_cast<float *>(ws + L.seg_off) : nullptr;
+    a.ws_opart = (ws && plan->n_splits > 1) ? reinterpret_cast<float *>(ws + L.opart_off) : nullptr;
+    a.B = plan->B;
+    a.Hq = pool->d.n_q_heads;
+    a.Hkv = pool->d.n_kv_heads;
+    a.Nq = plan->Nq;
+    a.Smax = plan->Smax;
+    a.T = plan->ctx_stride;
+    a.n_splits = plan->n_splits;
+    const int nqb = (plan->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
+    a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
+    a.total_wgs = plan->B * pool->d.n_kv_heads * plan->n_splits * a.n_ptiles;
+    a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
+    int e = en_launch_attention(pool, a, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "segmented_prefill_attention launch");
+    if (plan->n_splits > 1) {
+        e = en_launch_combine(pool, a, stream);
+        if (e != 0)
+            return hip_fail((hipError_t)e, "split combine launch");
+    }
+    return EN_OK;
+}
+
+extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, const void *ws_dev, int32_t reduce,
+                                      float *mass_out_dev, void *stream)
+{
+    if (!pool || !plan || !ws_dev || !mass_out_dev || (reduce != 0 && reduce != 1))
+        return fail(EN_ERR_INVALID_ARG, "segment_attention_mass: null argument or bad reduce mode");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segment_attention_mass: plan belongs to another pool");
+    int rc;
+    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+        return rc;
+    const EnWsLayout L = en_ws_layout(pool, plan);
+    const char *ws = static_cast<const char *>(ws_dev);
+    EnMassArgs a;
+    a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
+    a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
+    a.nseg = d_nseg(plan);
+    a.bnd = d_bnd(plan);
+    a.out = mass_out_dev;
+    a.B = plan->B;
+    a.Hq = pool->d.n_q_heads;
+    a.Nq = plan->Nq;
+    a.Smax = plan->Smax;
+    a.n_splits = plan->n_splits;
+    const int e = en_launch_mass(pool, a, reduce, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "segment_attention_mass launch");
+    return EN_OK;
+}

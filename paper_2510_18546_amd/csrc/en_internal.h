@@ -1,0 +1,82 @@
+// Internal declarations shared by the host planner and the HIP kernels of
+// libefficientnav.so. Not part of the public ABI (that is include/efficientnav.h).
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "efficientnav.h"
+
+constexpr int EN_KEY_TILE = 64;    // keys per attention tile; context rows are padded to it
+constexpr int EN_ROWS_PER_WAVE = 32;
+constexpr int EN_WAVES = 4;
+
+struct en_pool {
+    en_pool_desc d;
+    void *k_dev = nullptr;
+    void *v_dev = nullptr;
+    std::vector<int32_t> len;     // current lengths [G]
+    int r = 1;                    // Hq / Hkv
+    // device side, created on first GPU use
+    float *d_cos = nullptr;       // [max_ctx, D/2]
+    float *d_sin = nullptr;
+    int n_cu = 256;
+};
+
+struct en_plan {
+    const en_pool *pool = nullptr;
+    int B = 0, Nq = 0, Smax = 0;
+    int ctx_stride = 0, max_ctx_len = 0, n_splits = 1;
+    int64_t total_pairs = 0, total_cached = 0;
+    // host descriptors (uniform stride per agent)
+    std::vector<int32_t> nseg;    // [B]
+    std::vector<int32_t> sel;     // [B, Smax]   (-1 padded)
+    std::vector<int32_t> bnd;     // [B, Smax+2] bucket bounds: offset[0..S], then L_c+N_q
+    // device copy: nseg | sel | bnd, created on first GPU use
+    int32_t *d_desc = nullptr;
+    bool uploaded = false;
+};
+
+// Arguments of the device kernels (plain data, passed by value).
+struct EnGatherArgs {
+    const void *k_pool, *v_pool, *k_new, *v_new;
+    void *kc, *vt;
+    const float *cos_tab, *sin_tab;
+    const int32_t *nseg, *sel, *bnd;
+    int B, Hkv, C, Nq, Smax, T;
+};
+
+struct EnAttnArgs {
+    const void *q, *kc, *vt;
+    void *out;
+    const float *cos_tab, *sin_tab;
+    const int32_t *nseg, *bnd;
+    float *ws_ml;      // [n_splits, B*Hq*Nq, 2]  (reference max in log2 units, sum)
+    float *ws_seg;     // [n_splits, B*Hq, Smax+1, Nq, 2] (partial sum, its reference max)
+    float *ws_opart;   // [n_splits, B*Hq*Nq, D] unnormalised partial outputs
+    int B, Hq, Hkv, Nq, Smax, T;
+    int n_splits, n_ptiles, total_wgs;
+    float scale_log2e;
+};
+
+struct EnMassArgs {
+    const float *ws_ml, *ws_seg;
+    const int32_t *nseg, *bnd;
+    float *out;
+    int B, Hq, Nq, Smax, n_splits;
+};
+
+// Workspace layout helper (bytes, every part 256-byte aligned).
+struct EnWsLayout {
+    size_t ml_off, seg_off, opart_off, total;
+};
+EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
+
+// Kernel launchers (en_kernels.hip). Return hipError_t as int.
+int en_launch_gather(const en_pool *pool, const EnGatherArgs &a, int max_ctx_len, void *stream);
+int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
+int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, void *stream);
+int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
+
+void en_set_error(const char *fmt, ...);

@@ -1,0 +1,860 @@
+// HIP kernels of libefficientnav.so for gfx950 (MI355X, CDNA4, wave64).
+//
+//   gather_k / gather_vt   index-driven gather of the selected K/V blocks into
+//                          one contiguous context per agent; keys receive the
+//                          rotary encoding of their concatenated position
+//                          (Section 3.2 of arXiv 2510.18546: select, then load
+//                          each group's KV once per planning step)
+//   attn_bf16              softmax(QK^T/sqrt(D))V of the new tokens over the
+//                          context (Appendix A) on the bf16 matrix cores, with
+//                          an online softmax and per-segment partial sums
+//   attn_f32               the same in fp32 vector arithmetic (small configs)
+//   combine                merge of KV splits by log-sum-exp
+//   mass                   per-segment attention mass (Section 3.3)
+//
+// Softmax runs in the log2 domain: scores are scaled by log2(e)/sqrt(D) and
+// exponentials are exp2.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "en_internal.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#define EN_NEG_INF (-__builtin_inff())
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Exchange a value with the lane 32 positions away.
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+// ---------------------------------------------------------------------------
+// Segment lookup: largest s with bnd[s] <= tok among buckets 0..S (bucket S is
+// the new block). Empty buckets are skipped because of the "largest".
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int find_bucket(const int32_t *bnd, int S, int tok)
+{
+    int lo = 0, hi = S;             // invariant: bnd[lo] <= tok
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (bnd[mid] <= tok)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// Source row of context token `tok` for (agent b, KV head kvh); nullptr for
+// padding rows at or beyond L_c + N_q.
+template <typename T, int D>
+__device__ __forceinline__ const T *context_src(const EnGatherArgs &a, const T *pool, const T *fresh,
+                                               int b, int kvh, int tok)
+{
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Lc = bnd[S];
+    const int Ltot = bnd[S + 1];
+    if (tok >= Ltot)
+        return nullptr;
+    if (tok >= Lc)
+        return fresh + (((size_t)b * a.Nq + (tok - Lc)) * a.Hkv + kvh) * D;
+    const int s = find_bucket(bnd, S, tok);
+    const int sstr = a.Smax > 0 ? a.Smax : 1;
+    const int g = a.sel[(size_t)b * sstr + s];
+    return pool + (((size_t)g * a.Hkv + kvh) * a.C + (tok - bnd[s])) * D;
+}
+
+// ---------------------------------------------------------------------------
+// gather_k: 8 lanes per token row. Lane c owns elements [c*E, c*E+E) of the
+// first half and their rotary partners in the second half (E = D/16).
+// With COPY_V (fp32 path) the value row is copied alongside.
+// grid: (ceil(Lpad/32), Hkv, B), 256 threads.
+// ---------------------------------------------------------------------------
+template <typename T, int D, bool COPY_V>
+__global__ __launch_bounds__(256) void gather_k_kernel(EnGatherArgs a)
+{
+    constexpr int E = D / 16;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int tok = blockIdx.x * 32 + threadIdx.x / 8;
+    const int c = threadIdx.x % 8;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
+    if (tok >= Lpad)
+        return;
+    T *dst = (T *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
+    const T *src = context_src<T, D>(a, (const T *)a.k_pool, (const T *)a.k_new, b, kvh, tok);
+    typedef T tvec __attribute__((ext_vector_type(E)));
+    typedef float fvec __attribute__((ext_vector_type(E)));
+    fvec y1 = 0.f, y2 = 0.f;
+    if (src) {
+        const fvec x1 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + c * E), fvec);
+        const fvec x2 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + D / 2 + c * E), fvec);
+        const fvec cs = *reinterpret_cast<const fvec *>(a.cos_tab + (size_t)tok * (D / 2) + c * E);
+        const fvec sn = *reinterpret_cast<const fvec *>(a.sin_tab + (size_t)tok * (D / 2) + c * E);
+        y1 = x1 * cs - x2 * sn;
+        y2 = x2 * cs + x1 * sn;
+    }
+    *reinterpret_cast<tvec *>(dst + c * E) = __builtin_convertvector(y1, tvec);
+    *reinterpret_cast<tvec *>(dst + D / 2 + c * E) = __builtin_convertvector(y2, tvec);
+    if constexpr (COPY_V) {
+        T *vdst = (T *)a.vt + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
+        const T *vsrc = context_src<T, D>(a, (const T *)a.v_pool, (const T *)a.v_new, b, kvh, tok);
+        tvec v1 = (T)0.f, v2 = (T)0.f;
+        if (vsrc) {
+            v1 = *reinterpret_cast<const tvec *>(vsrc + c * E);
+            v2 = *reinterpret_cast<const tvec *>(vsrc + D / 2 + c * E);
+        }
+        *reinterpret_cast<tvec *>(vdst + c * E) = v1;
+        *reinterpret_cast<tvec *>(vdst + D / 2 + c * E) = v2;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// gather_vt (bf16): values of a 64-token tile are staged in LDS and written
+// transposed, vt[d][column], where token j sits at column j with bits 2 and 3
+// exchanged. grid: (Lpad/64, Hkv, B), 256 threads.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
+{
+    constexpr int STR = D + 2;                 // LDS row stride in elements
+    __shared__ uint16_t tile[EN_KEY_TILE * STR];
+    __shared__ const uint16_t *srcs[EN_KEY_TILE];
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int t0 = blockIdx.x * EN_KEY_TILE;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    if (t0 >= Ltot)
+        return;
+    if (threadIdx.x < EN_KEY_TILE)
+        srcs[threadIdx.x] = context_src<uint16_t, D>(a, (const uint16_t *)a.v_pool,
+                                                     (const uint16_t *)a.v_new, b, kvh,
+                                                     t0 + threadIdx.x);
+    __syncthreads();
+    // load: D/8 chunks of 16 bytes per token
+    constexpr int CH = D / 8;
+    for (int idx = threadIdx.x; idx < EN_KEY_TILE * CH; idx += 256) {
+        const int tk = idx / CH, ch = idx % CH;
+        const uint16_t *s = srcs[tk];
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (s)
+            v = *reinterpret_cast<const uint4 *>(s + ch * 8);
+        uint16_t *d = &tile[tk * STR + ch * 8];
+        // STR is even but not a multiple of 8: store as 4 dwords
+        reinterpret_cast<uint32_t *>(d)[0] = v.x;
+        reinterpret_cast<uint32_t *>(d)[1] = v.y;
+        reinterpret_cast<uint32_t *>(d)[2] = v.z;
+        reinterpret_cast<uint32_t *>(d)[3] = v.w;
+    }
+    __syncthreads();
+    // store: for every d, 8 chunks of 8 columns
+    uint16_t *vt = (uint16_t *)a.vt + ((size_t)b * a.Hkv + kvh) * D * (size_t)a.T + t0;
+    for (int idx = threadIdx.x; idx < D * 8; idx += 256) {
+        const int d = idx / 8, ch = idx % 8;      // columns ch*8 .. ch*8+7
+        const int g16 = ch / 2, hf = ch % 2;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int tk = 16 * g16 + 8 * (e >> 2) + 4 * hf + (e & 3);
+            v[e] = tile[tk * STR + d];
+        }
+        uint4 o;
+        o.x = v[0] | ((uint32_t)v[1] << 16);
+        o.y = v[2] | ((uint32_t)v[3] << 16);
+        o.z = v[4] | ((uint32_t)v[5] << 16);
+        o.w = v[6] | ((uint32_t)v[7] << 16);
+        *reinterpret_cast<uint4 *>(vt + (size_t)d * a.T + ch * 8) = o;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// attn_bf16: matrix-core attention.
+//
+// Work unit: one workgroup of 4 waves = 4 (query head, 32-query block) pairs of
+// one KV head and one KV split. Each wave keeps its 32 rotated, pre-scaled
+// queries in registers and computes S^T = K Q^T per 64-key tile with
+// v_mfma_f32_32x32x16_bf16, so that every lane owns ONE query (column l%32)
+// and 2x16 of its scores; the row maximum and sum then need a single exchange
+// with lane l^32. P^T goes straight back into the matrix core as the B operand
+// of O^T += V^T P^T: no LDS round trip for P. K tiles [64][D] and V^T tiles
+// [D][64] are staged in LDS with padded rows (conflict-free 16-byte reads).
+//
+// Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
+// column l%32.
+// ---------------------------------------------------------------------------
+template <int D>
+struct alignas(16) AttnSmem {
+    static constexpr int KSTR = D + 8;
+    static constexpr int VSTR = EN_KEY_TILE + 8;
+    bf16_t k[EN_KEY_TILE * KSTR];
+    bf16_t v[D * VSTR];
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
+{
+    constexpr int KT = EN_KEY_TILE;
+    constexpr int KSTR = AttnSmem<D>::KSTR;
+    constexpr int VSTR = AttnSmem<D>::VSTR;
+    constexpr int NKS = D / 16;          // k-steps of the QK^T product
+    constexpr int NDB = D / 32;          // 32-row blocks of O^T
+    constexpr int NCH = D / 32;          // 16-byte chunks per thread per tile (K and V each)
+    constexpr float TAU = 8.f;           // lazy rescale threshold (log2 units)
+    __shared__ AttnSmem<D> sm;
+
+    // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
+    const int per_xcd = gridDim.x / 8;
+    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= a.total_wgs)
+        return;
+    int t = logical;
+    const int ptile = t % a.n_ptiles;
+    t /= a.n_ptiles;
+    const int sp = t % a.n_splits;
+    t /= a.n_splits;
+    const int kvh = t % a.Hkv;
+    const int b = t / a.Hkv;
+
+    const int tid = threadIdx.x;
+    const int wave = tid / 64, lane = tid % 64;
+    const int col = lane % 32, half = lane / 32;
+    const int r = a.Hq / a.Hkv;
+    const int nqb = (a.Nq + 31) / 32;
+    const int pair = ptile * EN_WAVES + wave;
+    const bool wave_valid = pair < r * nqb;
+    const int hl = wave_valid ? pair % r : 0;
+    const int qb = wave_valid ? pair / r : 0;
+    const int hq = kvh * r + hl;
+    const int i_row = qb * 32 + col;
+    const bool row_valid = wave_valid && i_row < a.Nq;
+
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Lc = bnd[S];
+    const int Ltot = bnd[S + 1];
+    const int ntiles = (Ltot + KT - 1) / KT;
+    const int t_begin = (int)((long)sp * ntiles / a.n_splits);
+    int t_end = (int)((long)(sp + 1) * ntiles / a.n_splits);
+    const int split_key_begin = t_begin * KT;
+    const int split_key_end = min(t_end * KT, Ltot);
+    {
+        // causal frontier of the workgroup: last key any of its rows may see
+        const int qb_hi = min((ptile * EN_WAVES + EN_WAVES - 1) / r, nqb - 1);
+        const int last_key = Lc + min(a.Nq - 1, qb_hi * 32 + 31);
+        t_end = min(t_end, last_key / KT + 1);
+    }
+    const int i_lo = qb * 32;
+    const int i_hi = min(a.Nq - 1, qb * 32 + 31);
+    const int wave_t_end = wave_valid ? min(t_end, (Lc + i_hi) / KT + 1) : t_begin;
+
+    // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
+    bf16x8 qf[NKS];
+    {
+        float qx[NKS][8];
+        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row_valid)
+                v = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qx[ks][j] = (float)v[j];
+        }
+        const int pos = row_valid ? Lc + i_row : 0;
+        const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
+        const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS / 2; ++ks) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float cs = ct[16 * ks + j], sn = st[16 * ks + j];
+                const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
+                qx[ks][j] = (x1 * cs - x2 * sn) * a.scale_log2e;
+                qx[ks + NKS / 2][j] = (x2 * cs + x1 * sn) * a.scale_log2e;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qf[ks][j] = (bf16_t)qx[ks][j];
+    }
+
+    // ---- state ----
+    f32x16 o[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            o[d][e] = 0.f;
+    float m_ref = EN_NEG_INF;     // reference maximum of this row (log2 units)
+    float l_part = 0.f;           // this lane's share of the row sum
+    float seg_part = 0.f;         // this lane's share of the current bucket's sum
+
+    // bucket tracking (wave-uniform): bucket `cur` covers [bnd[cur], bnd[cur+1])
+    int cur = find_bucket(bnd, S, min(split_key_begin, Ltot - 1));
+    int cur_end = bnd[cur + 1];
+    const size_t row_hq = (size_t)b * a.Hq + hq;
+    float *seg_base = a.ws_seg
+                          ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
+                          : nullptr;
+
+    auto flush_bucket = [&](int bucket) {
+        // called by the whole wave when bucket `bucket` has been fully consumed
+        const float tot = seg_part + xor32(seg_part);
+        if (seg_base && row_valid && half == 0) {
+            f32x2 v = {tot, m_ref};
+            *reinterpret_cast<f32x2 *>(seg_base + ((size_t)bucket * a.Nq + i_row) * 2) = v;
+        }
+        seg_part = 0.f;
+    };
+
+    // ---- global -> register prefetch of one K tile and one V^T tile ----
+    const bf16_t *kg = (const bf16_t *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * D;
+    const bf16_t *vg = (const bf16_t *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T;
+    uint4 kreg[NCH], vreg[NCH];
+    auto prefetch = [&](int tile) {
+        const bf16_t *kt = kg + (size_t)tile * KT * D;
+        const bf16_t *vtile = vg + (size_t)tile * KT;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int idx = c * 256 + tid;
+            kreg[c] = *reinterpret_cast<const uint4 *>(kt + (size_t)idx * 8);
+            const int d = idx / 8, ch = idx % 8;
+            vreg[c] = *reinterpret_cast<const uint4 *>(vtile + (size_t)d * a.T + ch * 8);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int idx = c * 256 + tid;
+            const int row = idx / (D / 8), ch = idx % (D / 8);
+            *reinterpret_cast<uint4 *>(&sm.k[row * KSTR + ch * 8]) = kreg[c];
+            const int d = idx / 8, vch = idx % 8;
+            *reinterpret_cast<uint4 *>(&sm.v[d * VSTR + vch * 8]) = vreg[c];
+        }
+    };
+
+    if (t_begin < t_end)
+        prefetch(t_begin);
+
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        __syncthreads();                  // everyone is done reading the previous tile
+        stage();
+        __syncthreads();
+        if (tile + 1 < t_end)
+            prefetch(tile + 1);
+        if (tile >= wave_t_end)
+            continue;                     // beyond this wave's causal frontier
+
+        const int kb = tile * KT;
+        // ---- S^T = K Q^T ----
+        f32x16 s0, s1;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            s0[e] = s1[e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.k[col * KSTR + 16 * ks + 8 * half]);
+            const bf16x8 a1 =
+                *reinterpret_cast<const bf16x8 *>(&sm.k[(32 + col) * KSTR + 16 * ks + 8 * half]);
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
+        }
+        // ---- causal / padding mask (only tiles that reach past L_c + i_lo) ----
+        if (kb + KT - 1 > Lc + i_lo) {
+            const int lim = Lc + i_row;           // last visible key of this row
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = kb + 8 * (e / 4) + 4 * half + (e % 4);
+                if (key > lim)
+                    s0[e] = EN_NEG_INF;
+                if (key + 32 > lim)
+                    s1[e] = EN_NEG_INF;
+            }
+        }
+        // ---- online softmax with lazy re-referencing ----
+        float mx = s0[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e)
+            mx = fmaxf(mx, s0[e]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            mx = fmaxf(mx, s1[e]);
+        mx = fmaxf(mx, xor32(mx));
+        const float m_new = (mx > m_ref + TAU || m_ref == EN_NEG_INF) ? fmaxf(mx, m_ref) : m_ref;
+        if (__any(m_new != m_ref)) {
+            const float alpha = (m_new == EN_NEG_INF) ? 1.f : fast_exp2(m_ref - m_new);
+#pragma unroll
+            for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    o[d][e] *= alpha;
+            l_part *= alpha;
+            seg_part *= alpha;
+            m_ref = m_new;
+        }
+        const float m_sub = (m_ref == EN_NEG_INF) ? 0.f : m_ref;
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            s0[e] = fast_exp2(s0[e] - m_sub);
+            s1[e] = fast_exp2(s1[e] - m_sub);
+            rs += s0[e] + s1[e];
+        }
+        l_part += rs;
+
+        // ---- per-bucket partial sums ----
+        const int ke = min(kb + KT, split_key_end);
+        if (cur_end >= ke) {
+            seg_part += rs;               // the whole tile lies in bucket `cur`
+        } else {
+            int lo = kb;
+            while (true) {
+                const int hi = min(cur_end, ke);
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kb + 8 * (e / 4) + 4 * half + (e % 4);
+                    part += (key >= lo && key < hi) ? s0[e] : 0.f;
+                    part += (key + 32 >= lo && key + 32 < hi) ? s1[e] : 0.f;
+                }
+                seg_part += part;
+                if (cur_end > ke)
+                    break;
+                if (cur_end > bnd[cur])
+                    flush_bucket(cur);
+                seg_part = 0.f;
+                ++cur;
+                cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
+                lo = hi;
+                if (cur > S)
+                    break;
+            }
+        }
+        while (cur <= S && cur_end <= ke) {       // buckets that end exactly here
+            if (cur_end > bnd[cur])
+                flush_bucket(cur);
+            seg_part = 0.f;
+            ++cur;
+            cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
+        }
+
+        // ---- P^T as bf16 B operands, O^T += V^T P^T ----
+        bf16x8 pf[4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pf[0][j] = (bf16_t)s0[j];
+            pf[1][j] = (bf16_t)s0[8 + j];
+            pf[2][j] = (bf16_t)s1[j];
+            pf[3][j] = (bf16_t)s1[8 + j];
+        }
+#pragma unroll
+        for (int d = 0; d < NDB; ++d) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 av =
+                    *reinterpret_cast<const bf16x8 *>(&sm.v[(32 * d + col) * VSTR + 16 * kk + 8 * half]);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
+            }
+        }
+    }
+
+    if (!wave_valid)
+        return;
+    // Buckets of this split that the wave never reached (beyond its causal
+    // frontier) still get an entry: zero mass.
+    if (seg_base) {
+        // first flush what is pending for the bucket the loop stopped in
+        while (cur <= S && bnd[cur] < split_key_end) {
+            if (bnd[cur + 1] > bnd[cur])
+                flush_bucket(cur);
+            seg_part = 0.f;
+            ++cur;
+        }
+    }
+
+    // ---- epilogue ----
+    const float l_tot = l_part + xor32(l_part);
+    const size_t row = row_hq * a.Nq + i_row;
+    if (a.ws_ml && row_valid && half == 0) {
+        f32x2 v = {m_ref, l_tot};
+        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
+    }
+    if (!row_valid)
+        return;
+    if (a.n_splits == 1) {
+        const float inv = 1.f / l_tot;
+        bf16_t *op = (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = (bf16_t)(o[d][4 * g + e] * inv);
+                *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+            }
+    } else {
+        float *op = a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
+#pragma unroll
+        for (int d = 0; d < NDB; ++d)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v = {o[d][4 * g], o[d][4 * g + 1], o[d][4 * g + 2], o[d][4 * g + 3]};
+                *reinterpret_cast<f32x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// attn_f32: one wave per (agent, head, query) row and KV split. Lanes stride
+// over the keys with a private online softmax; lanes are merged at each bucket
+// end (for the mass) and at the end of the row.
+// grid: (ceil(rows/4), n_splits), 256 threads.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
+{
+    __shared__ float qs[4][D];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+    const size_t row = (size_t)blockIdx.x * 4 + wave;
+    const int sp = blockIdx.y;
+    const bool valid = row < rows;
+    // row = (b*Hq + hq)*Nq + i
+    const int i = valid ? (int)(row % a.Nq) : 0;
+    const int hq = valid ? (int)((row / a.Nq) % a.Hq) : 0;
+    const int b = valid ? (int)(row / ((size_t)a.Nq * a.Hq)) : 0;
+    const int r = a.Hq / a.Hkv;
+    const int kvh = hq / r;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Lc = bnd[S];
+    const int Ltot = bnd[S + 1];
+    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    const int kbeg = (int)((long)sp * ntiles / a.n_splits) * EN_KEY_TILE;
+    const int kend_split = min((int)((long)(sp + 1) * ntiles / a.n_splits) * EN_KEY_TILE, Ltot);
+    const int kend = min(kend_split, Lc + i + 1);       // causal limit
+
+    // rotated, scaled query in LDS
+    if (valid && lane < D / 2) {
+        const float *qp = (const float *)a.q + (((size_t)b * a.Nq + i) * a.Hq + hq) * D;
+        const int pos = Lc + i;
+        const float cs = a.cos_tab[(size_t)pos * (D / 2) + lane];
+        const float sn = a.sin_tab[(size_t)pos * (D / 2) + lane];
+        const float x1 = qp[lane], x2 = qp[lane + D / 2];
+        qs[wave][lane] = (x1 * cs - x2 * sn) * a.scale_log2e;
+        qs[wave][lane + D / 2] = (x2 * cs + x1 * sn) * a.scale_log2e;
+    }
+    __syncthreads();
+    if (!valid)
+        return;
+
+    const float *K = (const float *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * D;
+    const float *V = (const float *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * D;
+    float m = EN_NEG_INF, l = 0.f;
+    float o[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        o[d] = 0.f;
+    float *seg_base = a.ws_seg ? a.ws_seg + ((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1)) * a.Nq * 2
+                               : nullptr;
+
+    for (int bucket = 0; bucket <= S; ++bucket) {
+        const int lo = max(bnd[bucket], kbeg);
+        const int hi = min(bnd[bucket + 1], kend);
+        const bool touches = bnd[bucket + 1] > bnd[bucket] && max(bnd[bucket], kbeg) < min(bnd[bucket + 1], kend_split);
+        float seg = 0.f, seg_m = m;
+        for (int j = lo + lane; j < hi; j += 64) {
+            const float *kr = K + (size_t)j * D;
+            float acc = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; d += 4) {
+                const f32x4 kv = *reinterpret_cast<const f32x4 *>(kr + d);
+                acc += qs[wave][d] * kv[0] + qs[wave][d + 1] * kv[1] + qs[wave][d + 2] * kv[2] +
+                       qs[wave][d + 3] * kv[3];
+            }
+            const float mn = fmaxf(m, acc);
+            const float alpha = exp2f(m - mn);      // m = -inf -> 0
+            const float p = exp2f(acc - mn);
+            l = l * alpha + p;
+            seg = seg * alpha + p;
+            const float *vr = V + (size_t)j * D;
+#pragma unroll
+            for (int d = 0; d < D; d += 4) {
+                const f32x4 vv = *reinterpret_cast<const f32x4 *>(vr + d);
+                o[d] = o[d] * alpha + p * vv[0];
+                o[d + 1] = o[d + 1] * alpha + p * vv[1];
+                o[d + 2] = o[d + 2] * alpha + p * vv[2];
+                o[d + 3] = o[d + 3] * alpha + p * vv[3];
+            }
+            m = mn;
+        }
+        seg_m = m;
+        if (touches && seg_base) {
+            // merge the lanes' partial sums of this bucket
+            const float M = wave_max(seg_m);
+            const float w = (seg_m == EN_NEG_INF) ? 0.f : exp2f(seg_m - M);
+            const float tot = wave_sum(seg * w);
+            if (lane == 0) {
+                f32x2 v = {tot, M};
+                *reinterpret_cast<f32x2 *>(seg_base + ((size_t)bucket * a.Nq + i) * 2) = v;
+            }
+        }
+    }
+    // merge lanes
+    const float M = wave_max(m);
+    const float w = (m == EN_NEG_INF) ? 0.f : exp2f(m - M);
+    const float l_tot = wave_sum(l * w);
+    if (a.ws_ml && lane == 0) {
+        f32x2 v = {M, l_tot};
+        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2) = v;
+    }
+    const float inv = (a.n_splits == 1) ? 1.f / l_tot : 1.f;
+    float *op = (a.n_splits == 1) ? (float *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D
+                                  : a.ws_opart + ((size_t)sp * rows + row) * D;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const float tot = wave_sum(o[d] * w);
+        if (lane == (d & 63))
+            op[d] = tot * inv;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// combine: out = sum_sp o_sp 2^(m_sp - m) / sum_sp l_sp 2^(m_sp - m).
+// One thread per 4 output elements. grid: ceil(rows*D/4/256).
+// ---------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a)
+{
+    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * (D / 4))
+        return;
+    const size_t row = idx / (D / 4);
+    const int d4 = (int)(idx % (D / 4)) * 4;
+    float M = EN_NEG_INF;
+    for (int sp = 0; sp < a.n_splits; ++sp)
+        M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
+    float l = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < a.n_splits; ++sp) {
+        const float ms = a.ws_ml[((size_t)sp * rows + row) * 2];
+        const float ls = a.ws_ml[((size_t)sp * rows + row) * 2 + 1];
+        if (ms == EN_NEG_INF)
+            continue;
+        const float w = exp2f(ms - M);
+        l += ls * w;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(a.ws_opart + ((size_t)sp * rows + row) * D + d4);
+        acc += v * w;
+    }
+    const float inv = 1.f / l;
+    const int i = (int)(row % a.Nq);
+    const int hq = (int)((row / a.Nq) % a.Hq);
+    const int b = (int)(row / ((size_t)a.Nq * a.Hq));
+    T *op = (T *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D + d4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        op[e] = (T)(acc[e] * inv);
+}
+
+// ---------------------------------------------------------------------------
+// mass: probability mass per (row, bucket) from the raw partial sums.
+//   mass = sum over splits touching the bucket of seg * 2^(m_seg - M) / L
+// with (M, L) the row's final reference maximum and sum.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void row_final_ml(const EnMassArgs &a, size_t rows, size_t row, float &M,
+                                             float &L)
+{
+    M = EN_NEG_INF;
+    for (int sp = 0; sp < a.n_splits; ++sp)
+        M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
+    L = 0.f;
+    for (int sp = 0; sp < a.n_splits; ++sp) {
+        const float ms = a.ws_ml[((size_t)sp * rows + row) * 2];
+        if (ms != EN_NEG_INF)
+            L += a.ws_ml[((size_t)sp * rows + row) * 2 + 1] * exp2f(ms - M);
+    }
+}
+
+__device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int hq, int i, int bucket,
+                                                 int blo, int bhi, int ntiles, int Ltot, float M, float L)
+{
+    float acc = 0.f;
+    for (int sp = 0; sp < a.n_splits; ++sp) {
+        const int kb = (int)((long)sp * ntiles / a.n_splits) * EN_KEY_TILE;
+        const int ke = min((int)((long)(sp + 1) * ntiles / a.n_splits) * EN_KEY_TILE, Ltot);
+        if (max(kb, blo) >= min(ke, bhi))
+            continue;
+        const float *p = a.ws_seg +
+                         (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2;
+        const float sv = p[0], sm = p[1];
+        if (sm != EN_NEG_INF)
+            acc += sv * exp2f(sm - M);
+    }
+    return acc / L;
+}
+
+// reduce = 0. grid: (ceil(Nq/256), Hq, B); thread = query i; loops over buckets.
+__global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int hq = blockIdx.y, b = blockIdx.z;
+    if (i >= a.Nq)
+        return;
+    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+    const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    float M, L;
+    row_final_ml(a, rows, row, M, L);
+    float *out = a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * (a.Smax + 1);
+    for (int s = 0; s <= a.Smax; ++s) {
+        float v = 0.f;
+        if (s <= S && bnd[s + 1] > bnd[s])
+            v = row_bucket_mass(a, b, hq, i, s, bnd[s], bnd[s + 1], ntiles, Ltot, M, L);
+        out[s] = v;
+    }
+}
+
+// reduce = 1. grid: (Smax+1, B); the block sums bucket s over all heads and queries.
+__global__ __launch_bounds__(256) void mass_reduce_kernel(EnMassArgs a)
+{
+    __shared__ float red[4];
+    const int s = blockIdx.x, b = blockIdx.y;
+    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    float acc = 0.f;
+    if (s <= S && bnd[s + 1] > bnd[s]) {
+        for (int idx = threadIdx.x; idx < a.Hq * a.Nq; idx += 256) {
+            const int hq = idx / a.Nq, i = idx % a.Nq;
+            const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+            float M, L;
+            row_final_ml(a, rows, row, M, L);
+            acc += row_bucket_mass(a, b, hq, i, s, bnd[s], bnd[s + 1], ntiles, Ltot, M, L);
+        }
+    }
+    acc = wave_sum(acc);
+    if (threadIdx.x % 64 == 0)
+        red[threadIdx.x / 64] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        a.out[(size_t)b * (a.Smax + 1) + s] = red[0] + red[1] + red[2] + red[3];
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+int en_launch_gather(const en_pool *pool, const EnGatherArgs &a, int max_ctx_len, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int Lpad = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
+    const dim3 gk((Lpad + 31) / 32, a.Hkv, a.B), gv(Lpad / EN_KEY_TILE, a.Hkv, a.B), blk(256);
+    const int D = pool->d.head_dim;
+    if (pool->d.dtype == EN_F32) {
+        if (D == 64)
+            hipLaunchKernelGGL((gather_k_kernel<float, 64, true>), gk, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((gather_k_kernel<float, 128, true>), gk, blk, 0, st, a);
+    } else {
+        if (D == 64) {
+            hipLaunchKernelGGL((gather_k_kernel<bf16_t, 64, false>), gk, blk, 0, st, a);
+            hipLaunchKernelGGL((gather_vt_kernel<64>), gv, blk, 0, st, a);
+        } else {
+            hipLaunchKernelGGL((gather_k_kernel<bf16_t, 128, false>), gk, blk, 0, st, a);
+            hipLaunchKernelGGL((gather_vt_kernel<128>), gv, blk, 0, st, a);
+        }
+    }
+    return (int)hipGetLastError();
+}
+
+int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int D = pool->d.head_dim;
+    if (pool->d.dtype == EN_F32) {
+        const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+        const dim3 grid((unsigned)((rows + 3) / 4), a.n_splits), blk(256);
+        if (D == 64)
+            hipLaunchKernelGGL((attn_f32_kernel<64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_f32_kernel<128>), grid, blk, 0, st, a);
+    } else {
+        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(256);
+        if (D == 64)
+            hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, blk, 0, st, a);
+    }
+    return (int)hipGetLastError();
+}
+
+int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int D = pool->d.head_dim;
+    const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / 4);
+    const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
+    if (pool->d.dtype == EN_F32) {
+        if (D == 64)
+            hipLaunchKernelGGL((combine_kernel<float, 64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((combine_kernel<float, 128>), grid, blk, 0, st, a);
+    } else {
+        if (D == 64)
+            hipLaunchKernelGGL((combine_kernel<bf16_t, 64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a);
+    }
+    return (int)hipGetLastError();
+}
+
+int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream)
+{
+    (void)pool;
+    hipStream_t st = (hipStream_t)stream;
+    if (reduce == 0) {
+        const dim3 grid((a.Nq + 255) / 256, a.Hq, a.B), blk(256);
+        hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
+    } else {
+        const dim3 grid(a.Smax + 1, a.B), blk(256);
+        hipLaunchKernelGGL(mass_reduce_kernel, grid, blk, 0, st, a);
+    }
+    return (int)hipGetLastError();
+}

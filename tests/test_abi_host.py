@@ -1,0 +1,165 @@
+"""Host side of the C ABI, no GPU: the library loads, exports every symbol the
+header declares, and the planner / knapsack agree bit-exactly with the oracle.
+Pool device pointers are opaque non-null tokens here; no kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_18546_amd import binding as B
+from paper_2510_18546_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = dict(k_ptr=0x1000, v_ptr=0x2000)
+
+
+def host_pool(lens, cap=8, hkv=2, hq=4, d=64, dtype=B.EN_BF16, max_ctx=4096, base=1e4):
+    return B.kv_pool_create(None, None, lens, hq, base, max_ctx, dtype=dtype,
+                            shape=(len(lens), hkv, cap, d), **FAKE)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    hdr = open(os.path.join(ROOT, "include", "efficientnav.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", hdr)
+    names = sorted(set(n for n in names if not n.startswith("defined")))
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_plan_offsets_bit_exact_vs_oracle(oracle):
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        G = int(rng.integers(1, 40))
+        cap = int(rng.integers(1, 300))
+        lens = rng.integers(0, cap + 1, G).astype(np.int32)
+        Bn = int(rng.integers(1, 5))
+        lists = [rng.choice(G, size=int(rng.integers(0, G + 1)), replace=False).astype(np.int32)
+                 for _ in range(Bn)]
+        ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int32)
+        sel = np.concatenate(lists).astype(np.int32) if ptr[-1] else np.zeros(0, np.int32)
+        nq = int(rng.integers(1, 70))
+        pool = host_pool(lens, cap=cap, max_ctx=G * cap + nq)
+        plan = B.segment_select(pool, sel, ptr, nq)
+        inf = plan.info
+        worst = 0
+        pairs = 0
+        for b in range(Bn):
+            want = oracle.plan(lens, lists[b])
+            got = plan.offsets(b)
+            assert got.dtype == np.int32 and np.array_equal(got, want)
+            worst = max(worst, int(want[-1]) + nq)
+            pairs += nq * int(want[-1]) + nq * (nq + 1) // 2
+        assert inf.n_agents == Bn and inf.n_new == nq
+        assert inf.max_ctx_len == worst and inf.ctx_stride % 64 == 0 and inf.ctx_stride >= worst
+        assert inf.total_pairs == pairs
+        assert inf.max_segments == max(len(l) for l in lists)
+        assert B.context_bytes(pool, plan) == Bn * 2 * inf.ctx_stride * 64 * 2
+        assert B.workspace_bytes(pool, plan) > 0
+
+
+def test_c0_plan_matches_golden():
+    w = I.make_workload(I.CONFIGS["c0"], poison=False)
+    pool = host_pool(w.lens, cap=32, hkv=1, hq=4, d=64, dtype=B.EN_F32, max_ctx=192)
+    plan = B.segment_select(pool, w.sel, w.sel_ptr, 64)
+    assert plan.offsets(0).tolist() == [0, 32, 64, 96, 128]
+    assert plan.info.max_ctx_len == 192
+
+
+def test_error_codes():
+    lens = np.array([3, 0, 5, 8], np.int32)
+    pool = host_pool(lens, max_ctx=20)
+    with pytest.raises(B.EnError) as e:
+        B.segment_select(pool, [0, 4], [0, 2], 4)
+    assert e.value.code == 2                                   # id out of range
+    with pytest.raises(B.EnError) as e:
+        B.segment_select(pool, [0, -1], [0, 2], 4)
+    assert e.value.code == 2
+    with pytest.raises(B.EnError) as e:
+        B.segment_select(pool, [2, 0, 2], [0, 3], 4)
+    assert e.value.code == 3                                   # duplicate
+    B.segment_select(pool, [2, 0, 2, 3], [0, 2, 4], 4)         # same id in two agents is fine
+    with pytest.raises(B.EnError) as e:
+        B.segment_select(pool, [0, 2, 3], [0, 3], 5)           # 16 + 5 > 20
+    assert e.value.code == 4
+    B.segment_select(pool, [0, 2, 3], [0, 3], 4)               # 16 + 4 == 20 fits
+    with pytest.raises(B.EnError) as e:
+        B.segment_select(pool, [0], [0, 1], 0)
+    assert e.value.code == 1
+    with pytest.raises(B.EnError) as e:
+        host_pool(np.array([9], np.int32), cap=8)
+    assert e.value.code == 2                                   # len > capacity
+    with pytest.raises(B.EnError) as e:
+        host_pool(lens, d=96)
+    assert e.value.code == 5
+    with pytest.raises(B.EnError) as e:
+        host_pool(lens, hkv=3, hq=4)
+    assert e.value.code == 5
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_create(None, None, lens, 4, 1e4, 64, dtype=B.EN_BF16, shape=(4, 2, 8, 64),
+                         k_ptr=0, v_ptr=0x10)
+    assert e.value.code == 1                                   # null device pointer
+    assert b"null" in B.load().en_last_error()
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_set_len(pool, 1, 9)
+    assert e.value.code == 2
+
+
+def test_empty_selection_and_empty_groups():
+    lens = np.array([3, 0, 5], np.int32)
+    pool = host_pool(lens)
+    plan = B.segment_select(pool, [], [0, 0], 7)
+    assert plan.offsets(0).tolist() == [0] and plan.info.max_ctx_len == 7
+    plan = B.segment_select(pool, [1, 2, 0], [0, 3], 2)
+    assert plan.offsets(0).tolist() == [0, 0, 5, 8]
+
+
+def test_set_len_affects_later_plans_only():
+    lens = np.array([3, 4], np.int32)
+    pool = host_pool(lens)
+    p1 = B.segment_select(pool, [0, 1], [0, 2], 1)
+    B.kv_pool_set_len(pool, 0, 6)
+    p2 = B.segment_select(pool, [0, 1], [0, 2], 1)
+    assert p1.offsets(0).tolist() == [0, 3, 7] and p2.offsets(0).tolist() == [0, 6, 10]
+
+
+def test_set_splits_clamps():
+    pool = host_pool(np.full(16, 8, np.int32), max_ctx=1024)
+    plan = B.segment_select(pool, np.arange(16), [0, 16], 10)      # 138 keys -> 3 tiles
+    plan.set_splits(100)
+    assert plan.info.n_splits == 3
+    plan.set_splits(1)
+    assert plan.info.n_splits == 1
+
+
+def test_scored_selection_matches_oracle(oracle):
+    rng = np.random.default_rng(5)
+    for trial in range(120):
+        G = int(rng.integers(1, 15)) if trial < 90 else int(rng.integers(17, 60))
+        cap = 12
+        lens = rng.integers(0, cap + 1, G).astype(np.int32)
+        p = rng.random(G).astype(np.float32)
+        if trial % 2:
+            p = (np.round(p * 8) / 8).astype(np.float32)
+        budget = int(rng.integers(0, max(2, int(lens.sum()) + 3)))
+        pool = host_pool(lens, cap=cap, max_ctx=G * cap + 4)
+        got, plan = B.segment_select_scored(pool, p, 0.375, budget, 4)
+        want = oracle.knapsack(p, lens, 0.375, budget)
+        assert got.tolist() == want
+        assert plan.offsets(0).tolist() == oracle.plan(lens, want).tolist()
+        assert int(lens[got].sum()) <= budget
+
+
+def test_scored_selection_edges():
+    lens = np.array([4, 1, 3, 3], np.int32)
+    pool = host_pool(lens)
+    p = np.array([0.9, 0.2, 0.6, 0.55], np.float32)
+    assert B.segment_select_scored(pool, p, 0.5, 0, 1, want_plan=False)[0].tolist() == []
+    assert B.segment_select_scored(pool, p, 0.5, 10 ** 12, 1, want_plan=False)[0].tolist() == [0, 2, 3]
+    with pytest.raises(B.EnError) as e:
+        B.segment_select_scored(pool, p, 0.5, -1, 1)
+    assert e.value.code == 1

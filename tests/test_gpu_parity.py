@@ -1,0 +1,252 @@
+"""Parity of the HIP path (through the C ABI) with the float64 CPU oracle on the
+same seeded inputs. Needs a real MI355X: every test is marked gpu.
+
+Tolerances (per the benchmark contract):
+  fp32 path : |d| <= 1e-5 * max(|ref|, max|ref row|) for outputs,
+              |d| <= 1e-5 * max(ref, 1e-3) for masses
+  bf16 path : outputs 2e-2 absolute, masses 1e-2 absolute
+  integers (plan offsets, gathered V bits, padding) : exact
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2510_18546_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    sys.__stderr__.write(f"[gpu-case] {msg}\n")
+    sys.__stderr__.flush()
+
+
+@pytest.fixture(scope="module")
+def step_mod():
+    import torch
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    from paper_2510_18546_amd import step
+    return step
+
+
+def oracle_full(O, w, rows=None):
+    return O.attention(w.k_pool, w.v_pool, w.lens, w.sel, w.sel_ptr, w.q, w.k_new, w.v_new,
+                       w.cfg.rope_base, rows=rows)
+
+
+def check_out(cfg, got, ref):
+    if cfg.dtype == I.F32:
+        scale = np.maximum(np.abs(ref), np.abs(ref).max(axis=-1, keepdims=True))
+        bad = np.abs(got - ref) > 1e-5 * scale + 1e-30
+        assert not bad.any(), f"fp32 out: max rel {np.max(np.abs(got - ref) / scale):.3e}"
+    else:
+        err = np.abs(got - ref).max()
+        assert err <= 2e-2, f"bf16 out: max abs err {err:.3e}"
+
+
+def check_mass(cfg, got, ref):
+    if cfg.dtype == I.F32:
+        bad = np.abs(got - ref) > 1e-5 * np.maximum(ref, 1e-3)
+        assert not bad.any(), f"fp32 mass: max err {np.abs(got - ref).max():.3e}"
+    else:
+        err = np.abs(got - ref).max()
+        assert err <= 1e-2, f"bf16 mass: max abs err {err:.3e}"
+
+
+def run_case(step_mod, O, cfg, n_splits=None, sel_lists=None, rows=None, name=""):
+    announce(f"{name or cfg.name}: dtype={cfg.dtype} B={cfg.n_agents} Hq={cfg.n_q_heads} "
+             f"Hkv={cfg.n_kv_heads} D={cfg.head_dim} G={cfg.n_groups}x{cfg.capacity} "
+             f"S={cfg.n_sel} Nq={cfg.n_new} seed={cfg.seed} splits={n_splits}")
+    import torch
+    w = I.make_workload(cfg, sel_lists=sel_lists)
+    st = step_mod.PlanningStep(w, n_splits=n_splits)
+    # plan integers, bit-exact
+    for b in range(cfg.n_agents):
+        assert np.array_equal(st.plan.offsets(b), O.plan(w.lens, w.agent_sel(b)))
+    st.run()
+    torch.cuda.synchronize()
+    out, mass, red = st.out_host(), st.mass_host(), st.mass_red_host()
+    assert np.isfinite(out).all() and np.isfinite(mass).all() and np.isfinite(red).all()
+    if rows is None:
+        ref_out, ref_mass = oracle_full(O, w)
+        check_out(cfg, out, ref_out)
+        check_mass(cfg, mass, ref_mass)
+        ref_red = O.reduce_mass(ref_mass)
+    else:
+        ref_out, ref_mass = oracle_full(O, w, rows=rows)
+        sel_out = np.stack([out[b, i, h] for b, i, h in rows])
+        sel_mass = np.stack([mass[b, i, h] for b, i, h in rows])
+        check_out(cfg, sel_out, ref_out)
+        check_mass(cfg, sel_mass, ref_mass)
+        ref_red = None
+    # properties that hold at any size
+    np.testing.assert_allclose(mass.sum(-1), 1.0, atol=2e-3 if cfg.dtype == I.BF16 else 2e-5)
+    np.testing.assert_allclose(red, mass.sum(axis=(1, 2)), rtol=1e-4, atol=1e-3)
+    if ref_red is not None:
+        tol = 1e-2 * cfg.n_new * cfg.n_q_heads if cfg.dtype == I.BF16 else 1e-4 * cfg.n_new * cfg.n_q_heads
+        assert np.abs(red - ref_red).max() <= tol
+    return st, w, out, mass
+
+
+def small(name, seed, dtype=I.BF16, **kw):
+    base = dict(name=name, seed=seed, dtype=dtype, n_agents=1, n_q_heads=8, n_kv_heads=2,
+                head_dim=128, n_groups=12, capacity=96, len_lo=20, len_hi=96, n_sel=5, n_new=70,
+                rope_base=500000.0)
+    base.update(kw)
+    return I.Config(**base)
+
+
+# ---------------------------------------------------------------------------
+# fp32 path
+# ---------------------------------------------------------------------------
+def test_c0_fp32(step_mod, oracle):
+    run_case(step_mod, oracle, I.CONFIGS["c0"])
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3])
+def test_fp32_ragged_splits(step_mod, oracle, splits):
+    cfg = small("f32-ragged", 100 + splits, dtype=I.F32, head_dim=64, n_q_heads=4, n_kv_heads=2,
+                len_lo=0, len_hi=96, n_sel=6, n_new=37, n_agents=2, rope_base=1e4)
+    run_case(step_mod, oracle, cfg, n_splits=splits)
+
+
+def test_fp32_d128_no_selection(step_mod, oracle):
+    cfg = small("f32-S0", 110, dtype=I.F32, n_sel=0, n_new=33, n_q_heads=2, n_kv_heads=2)
+    run_case(step_mod, oracle, cfg)
+
+
+def test_fp32_single_query(step_mod, oracle):
+    cfg = small("f32-decode", 111, dtype=I.F32, head_dim=64, n_new=1, n_agents=3, n_sel=4)
+    run_case(step_mod, oracle, cfg, n_splits=2)
+
+
+# ---------------------------------------------------------------------------
+# bf16 matrix-core path, reduced sizes, full comparison
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("splits", [1, 2, 5])
+def test_bf16_ragged_splits(step_mod, oracle, splits):
+    cfg = small("bf16-ragged", 200 + splits, n_agents=2, len_lo=0, n_sel=7)
+    run_case(step_mod, oracle, cfg, n_splits=splits)
+
+
+@pytest.mark.parametrize("residue", range(0, 64, 7))
+def test_bf16_every_tail_residue(step_mod, oracle, residue):
+    """Context lengths hitting different (L_c + N_q) mod 64 and len mod 64."""
+    cfg = small("bf16-residue", 300 + residue, len_lo=64 + residue, len_hi=64 + residue,
+                capacity=128, n_sel=3, n_new=33 + residue)
+    run_case(step_mod, oracle, cfg)
+
+
+def test_bf16_aligned_segments_like_c2(step_mod, oracle):
+    cfg = small("bf16-aligned", 210, n_q_heads=8, n_kv_heads=2, n_groups=10, capacity=256,
+                len_lo=256, len_hi=256, n_sel=6, n_new=128)
+    run_case(step_mod, oracle, cfg, n_splits=1)
+    run_case(step_mod, oracle, cfg, n_splits=4)
+
+
+def test_bf16_planted_mass(step_mod, oracle):
+    cfg = small("bf16-planted", 220, planted=True, n_sel=6)
+    st, w, out, mass = run_case(step_mod, oracle, cfg)
+    s = list(w.agent_sel(0)).index(w.meta["planted_group"][0])
+    assert mass[0, :, :, s].mean() > 0.5
+
+
+def test_bf16_scaled_activations_like_c1(step_mod, oracle):
+    cfg = small("bf16-scaled", 230, act_scale=128.0 ** -0.5, n_sel=8)
+    run_case(step_mod, oracle, cfg, n_splits=2)
+
+
+@pytest.mark.parametrize("hq,hkv", [(2, 2), (4, 2), (8, 1), (6, 2)])
+def test_bf16_head_ratios(step_mod, oracle, hq, hkv):
+    cfg = small(f"bf16-gqa{hq}:{hkv}", 240 + hq, n_q_heads=hq, n_kv_heads=hkv, n_new=45)
+    run_case(step_mod, oracle, cfg, n_splits=2)
+
+
+def test_bf16_head_dim_64(step_mod, oracle):
+    cfg = small("bf16-d64", 250, head_dim=64, n_q_heads=4, n_kv_heads=1, rope_base=1e4)
+    run_case(step_mod, oracle, cfg, n_splits=1)
+    run_case(step_mod, oracle, cfg, n_splits=3)
+
+
+def test_bf16_no_selection(step_mod, oracle):
+    cfg = small("bf16-S0", 260, n_sel=0, n_new=100)
+    run_case(step_mod, oracle, cfg)
+
+
+def test_bf16_single_query_decode(step_mod, oracle):
+    cfg = small("bf16-decode", 270, n_new=1, n_agents=3, n_sel=6)
+    run_case(step_mod, oracle, cfg, n_splits=1)
+    run_case(step_mod, oracle, cfg, n_splits=4)
+
+
+def test_bf16_agents_with_different_selections(step_mod, oracle):
+    cfg = small("bf16-ragged-agents", 280, n_agents=3, len_lo=0)
+    run_case(step_mod, oracle, cfg, sel_lists=[[3, 1, 7, 9, 0, 2], [], [5]], n_splits=2)
+
+
+def test_bf16_tiny_segments(step_mod, oracle):
+    """Many buckets inside one 64-key tile, including empty ones."""
+    cfg = small("bf16-tiny-seg", 290, capacity=9, len_lo=0, len_hi=9, n_groups=40, n_sel=30, n_new=20)
+    run_case(step_mod, oracle, cfg)
+
+
+# ---------------------------------------------------------------------------
+# gather_rope on its own: indices and values bit-exact, rotation to 1 bf16 ulp
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [I.F32, I.BF16])
+def test_gather_rope_layout(step_mod, oracle, dtype):
+    import torch
+    cfg = small("gather", 400 + dtype, dtype=dtype, n_agents=2, len_lo=0, n_sel=6, n_new=19,
+                head_dim=64 if dtype == I.F32 else 128)
+    announce(f"gather_rope dtype={dtype}")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w)
+    st.kc.fill_(0xFF)
+    st.vt.fill_(0xFF)                    # NaN patterns: every byte must be overwritten
+    st.gather()
+    torch.cuda.synchronize()
+    for b in range(cfg.n_agents):
+        kc, v, kpad, vpad = st.context_host(b)
+        rk, rv = oracle.gather_rope(w.k_pool, w.v_pool, w.lens, w.agent_sel(b), w.k_new[b],
+                                    w.v_new[b], cfg.rope_base)
+        assert np.array_equal(v.astype(np.float64), rv), "gathered values must be bit-exact copies"
+        if dtype == I.F32:
+            assert np.abs(kc - rk).max() <= 1e-6 * max(1.0, np.abs(rk).max())
+        else:
+            ulp = np.maximum(np.abs(rk), 2.0 ** -126) * 2.0 ** -8
+            assert (np.abs(kc - rk) <= 1.01 * ulp + 1e-7).all()
+        L = kc.shape[1]
+        pad_to = -(-L // 64) * 64
+        assert (kpad[:, :pad_to - L] == 0).all() and (vpad[:, :pad_to - L] == 0).all()
+
+
+# ---------------------------------------------------------------------------
+# full benchmark sizes, in the launch configuration the benchmark times
+# (default split choice); sampled rows against the oracle + global properties
+# ---------------------------------------------------------------------------
+def sample_rows(cfg, n, seed=9):
+    rng = np.random.default_rng(seed)
+    rows = np.stack([rng.integers(0, cfg.n_agents, n), rng.integers(0, cfg.n_new, n),
+                     rng.integers(0, cfg.n_q_heads, n)], axis=1).astype(np.int32)
+    rows[0] = (0, 0, 0)
+    rows[1] = (cfg.n_agents - 1, cfg.n_new - 1, cfg.n_q_heads - 1)
+    return rows
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3"])
+def test_full_size_prefill_configs(step_mod, oracle, name):
+    cfg = I.CONFIGS[name]
+    run_case(step_mod, oracle, cfg, rows=sample_rows(cfg, 48))
+
+
+def test_full_size_c1_unscaled_and_planted(step_mod, oracle):
+    cfg = I.variant(I.CONFIGS["c1"], act_scale=1.0, planted=True, name="c1-planted")
+    run_case(step_mod, oracle, cfg, rows=sample_rows(cfg, 48))
+
+
+def test_full_size_decode_c4(step_mod, oracle):
+    cfg = I.CONFIGS["c4"]
+    rows = sample_rows(cfg, 24)
+    rows[:, 0] = np.array([0, 63, 5, 17] * 6)          # four agents only: bounds the oracle's gathers
+    run_case(step_mod, oracle, cfg, rows=rows)
