@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented-attention planning step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic workload:
+segment_select (host plan + descriptor upload) -> gather_rope ->
+segmented_prefill_attention (+ split combine) -> segment_attention_mass
+(reduced over heads and queries). Inputs are resident in HBM before the timed
+region. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+
+The default workload is the 8K-context configuration (32 segments x 256 cached
+tokens + 512 new tokens, Llama-3.2-11B-shaped layer, bf16), the one the
+matrix-core target is quoted on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "segmented prefill attention TFLOP/s + µs per planning step, % bf16 MFMA peak"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+WORKLOAD_TEXT = {
+    "c1": "c1: 32q/8kv heads, D=128, bf16; 16 ragged segments (64..128 tokens) of a 64-group pool + 256 new tokens",
+    "c2": "c2: 32q/8kv heads, D=128, bf16; 32 segments x 256 cached tokens (8192) of a 256-group pool + 512 new tokens; mass summed over heads and queries",
+    "c3": "c3: 16 agents sharing a 512-group pool; 24 ragged segments (32..128 tokens) + 128 new tokens each; 32q/8kv, D=128, bf16",
+    "c4": "c4: decode, 64 agents x 1 new token over 64 segments x 256 tokens (16384) from a 1024-group pool; 32q/8kv, D=128, bf16",
+}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (see profiles/), null where not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_flops(cfg, info) -> int:
+    """4*Hq*D per visible (query, key) pair; causal triangle counted once."""
+    return 4 * cfg.n_q_heads * cfg.head_dim * int(info.total_pairs)
+
+
+def algorithmic_bytes(cfg, info) -> int:
+    """Bytes the attention kernel must move once: gathered K and V^T of the
+    visible context, Q in, O out (2-byte elements)."""
+    es = 2 if cfg.dtype == 1 else 4
+    kv = 2 * cfg.n_kv_heads * cfg.head_dim * (int(info.total_cached) + cfg.n_agents * cfg.n_new) * es
+    qo = 2 * cfg.n_agents * cfg.n_new * cfg.n_q_heads * cfg.head_dim * es
+    return kv + qo
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (every agent, head and segment of a planning "
+                 "step lives on it); --gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2510_18546_amd import binding as B
+    from paper_2510_18546_amd import inputs as I
+    from paper_2510_18546_amd import step
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = I.CONFIGS[args.workload]
+    w = I.make_workload(cfg)
+    st = step.PlanningStep(w)
+    info = st.info
+    flops = algorithmic_flops(cfg, info)
+    hbm_bound = cfg.n_new == 1
+
+    def one_step():
+        st.select()
+        st.gather()
+        st.attention()
+        st.masses(1)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    B.timing_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern_ms = B.timing_collect(args.steps)
+    B.timing_enable(0)
+
+    sec_per_step = (t1 - t0) / args.steps
+    kern_s = float(np.mean(kern_ms)) * 1e-3
+    value = flops / sec_per_step / 1e12
+
+    if hbm_bound:
+        abytes = algorithmic_bytes(cfg, info)
+        roof = {"bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC.get(args.workload)
+    roof["kernel"] = "attn_bf16_kernel<128>"
+    roof["kernel_us"] = kern_s * 1e6
+    roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
+
+    res = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3,
+        "us_per_planning_step": sec_per_step * 1e6,
+        "pct_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "n_splits": int(info.n_splits),
+                   "flops_per_step": flops, "cached_tokens": int(info.total_cached),
+                   "new_tokens": cfg.n_new, "agents": cfg.n_agents},
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        # The float64 oracle, as it stands, on the host cores: the whole workload
+        # when it is small enough, otherwise a bounded sample of output rows.
+        from oracle import oracle as O
+        O.build()
+        rows_total = cfg.n_agents * cfg.n_new * cfg.n_q_heads
+        per_row = flops / rows_total
+        n = rows_total if flops <= 8e10 and cfg.n_agents == 1 else min(rows_total, 2048)
+        rng = np.random.default_rng(9)
+        if n == rows_total and cfg.n_agents == 1:
+            rows, sample = None, f"all {rows_total} output rows of the workload"
+        else:
+            agents = rng.integers(0, min(cfg.n_agents, 4), n)
+            rows = np.stack([agents, rng.integers(0, cfg.n_new, n),
+                             rng.integers(0, cfg.n_q_heads, n)], 1).astype(np.int32)
+            sample = (f"{n} of {rows_total} output rows (agent, query, head drawn uniformly from the "
+                      f"first {min(cfg.n_agents, 4)} agents, seed 9), each agent's gather+RoPE included")
+        c0 = time.perf_counter()
+        O.attention(w.k_pool, w.v_pool, w.lens, w.sel, w.sel_ptr, w.q, w.k_new, w.v_new,
+                    cfg.rope_base, rows=rows)
+        c1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": per_row * n / (c1 - c0) / 1e12, "unit": "TFLOP/s",
+                               "cores": O.threads(), "kind": "oracle", "sample": sample,
+                               "seconds": c1 - c0}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

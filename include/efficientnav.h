@@ -153,6 +153,9 @@ int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
  * the number of 64-key tiles). Must precede en_workspace_bytes. */
 int en_plan_set_splits(en_plan *plan, int32_t n_splits);
 
+/* May be called while work that uses the plan is still queued on a stream,
+ * provided later plans of the same pool are used on that same stream;
+ * otherwise synchronise first. */
 int en_plan_destroy(en_plan *plan);
 
 /* ------------------------------------------------------------------------
@@ -212,6 +215,20 @@ int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
  */
 int segment_attention_mass(en_pool *pool, en_plan *plan, const void *ws_dev, int32_t reduce,
                            float *mass_out_dev, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Measurement aid for callers that need the duration of the attention kernel
+ * itself (the kernel the roofline is quoted on), not of the whole call.
+ * en_timing_enable(n > 0) creates n pairs of HIP events; from then on every
+ * segmented_prefill_attention call records one pair around its main kernel
+ * launch, on the stream it launches on, until n pairs are used.
+ * en_timing_enable(0) frees them. en_timing_collect waits for the recorded
+ * pairs, writes their durations in milliseconds to ms_out_host (at most cap)
+ * and resets the record count. Process-wide, not thread-safe.
+ * Errors: INVALID_ARG, DEVICE.
+ */
+int en_timing_enable(int32_t max_records);
+int en_timing_collect(float *ms_out_host, int32_t cap, int32_t *n_out);
 
 const char *en_last_error(void);
 

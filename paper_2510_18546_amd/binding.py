@@ -22,7 +22,8 @@ EXPORTS = [
     "kv_pool_create", "kv_pool_set_len", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
-    "segmented_prefill_attention", "segment_attention_mass", "en_last_error",
+    "segmented_prefill_attention", "segment_attention_mass", "en_timing_enable",
+    "en_timing_collect", "en_last_error",
 ]
 
 
@@ -74,6 +75,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.gather_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.segmented_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
+    lib.en_timing_enable.argtypes = [C.c_int32]
+    lib.en_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("en_context_bytes", "en_workspace_bytes", "en_last_error"):
@@ -236,3 +239,16 @@ def segment_attention_mass(pool: Pool, plan: Plan, ws, reduce: int, mass_out, st
     _check(load().segment_attention_mass(pool.handle, plan.handle, ws.data_ptr(), int(reduce),
                                          mass_out.data_ptr(), _stream(stream)))
     return mass_out
+
+
+def timing_enable(n: int):
+    _check(load().en_timing_enable(int(n)))
+
+
+def timing_collect(cap: int) -> np.ndarray:
+    """Durations (ms) of the attention kernel launches recorded since the last
+    collect."""
+    ms = np.zeros(cap, dtype=np.float32)
+    n = C.c_int32()
+    _check(load().en_timing_collect(ms.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)))
+    return ms[:n.value].copy()

@@ -99,6 +99,8 @@ extern "C" int kv_pool_destroy(en_pool *pool)
         (void)hipFree(pool->d_cos);
     if (pool->d_sin)
         (void)hipFree(pool->d_sin);
+    for (auto &c : pool->desc_cache)
+        (void)hipFree(c.second);
     delete pool;
     return EN_OK;
 }
@@ -357,8 +359,11 @@ extern "C" int en_plan_destroy(en_plan *plan)
 {
     if (!plan)
         return EN_OK;
+    // The descriptor block goes back to the pool for the next plan: no device
+    // synchronisation here. Work still queued on a stream keeps reading it
+    // safely as long as later plans of this pool are used on that same stream.
     if (plan->d_desc)
-        (void)hipFree(plan->d_desc);
+        plan->pool->desc_cache.emplace_back(plan->d_desc_bytes, plan->d_desc);
     delete plan;
     return EN_OK;
 }
@@ -368,21 +373,31 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream)
     if (pl->uploaded)
         return EN_OK;
     const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size();
-    std::vector<int32_t> host;
-    host.reserve(n);
-    host.insert(host.end(), pl->nseg.begin(), pl->nseg.end());
-    host.insert(host.end(), pl->sel.begin(), pl->sel.end());
-    host.insert(host.end(), pl->bnd.begin(), pl->bnd.end());
+    const size_t bytes = n * sizeof(int32_t);
+    pl->h_desc.clear();
+    pl->h_desc.reserve(n);
+    pl->h_desc.insert(pl->h_desc.end(), pl->nseg.begin(), pl->nseg.end());
+    pl->h_desc.insert(pl->h_desc.end(), pl->sel.begin(), pl->sel.end());
+    pl->h_desc.insert(pl->h_desc.end(), pl->bnd.begin(), pl->bnd.end());
     hipError_t e;
-    if ((e = hipMalloc((void **)&pl->d_desc, n * sizeof(int32_t))) != hipSuccess)
-        return hip_fail(e, "hipMalloc(plan descriptors)");
-    // Pageable source: the copy is staged before the call returns, so the
-    // temporary vector may go away; ordering on `stream` is kept.
-    if ((e = hipMemcpyAsync(pl->d_desc, host.data(), n * sizeof(int32_t), hipMemcpyHostToDevice,
-                            stream)) != hipSuccess)
+    auto &cache = pl->pool->desc_cache;
+    for (size_t i = 0; i < cache.size(); ++i)
+        if (cache[i].first >= bytes) {
+            pl->d_desc = cache[i].second;
+            pl->d_desc_bytes = cache[i].first;
+            cache.erase(cache.begin() + i);
+            break;
+        }
+    if (!pl->d_desc) {
+        const size_t cap = std::max<size_t>(align256(bytes), 4096);
+        if ((e = hipMalloc((void **)&pl->d_desc, cap)) != hipSuccess)
+            return hip_fail(e, "hipMalloc(plan descriptors)");
+        pl->d_desc_bytes = cap;
+    }
+    // Stream-ordered copy; the staging vector lives as long as the plan.
+    if ((e = hipMemcpyAsync(pl->d_desc, pl->h_desc.data(), bytes, hipMemcpyHostToDevice, stream)) !=
+        hipSuccess)
         return hip_fail(e, "hipMemcpyAsync(plan descriptors)");
-    if ((e = hipStreamSynchronize(stream)) != hipSuccess)
-        return hip_fail(e, "hipStreamSynchronize(plan descriptors)");
     pl->uploaded = true;
     return EN_OK;
 }
@@ -423,6 +438,51 @@ extern "C" size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan)
     if (!pool || !plan)
         return 0;
     return en_ws_layout(pool, plan).total;
+}
+
+// ---------------------------------------------------------------------------
+// kernel timing with HIP events (measurement aid)
+// ---------------------------------------------------------------------------
+static std::vector<hipEvent_t> g_ev_start, g_ev_stop;
+static int g_ev_used = 0;
+
+extern "C" int en_timing_enable(int32_t max_records)
+{
+    if (max_records < 0)
+        return fail(EN_ERR_INVALID_ARG, "en_timing_enable: negative count");
+    for (auto e : g_ev_start)
+        (void)hipEventDestroy(e);
+    for (auto e : g_ev_stop)
+        (void)hipEventDestroy(e);
+    g_ev_start.clear();
+    g_ev_stop.clear();
+    g_ev_used = 0;
+    for (int i = 0; i < max_records; ++i) {
+        hipEvent_t a, b;
+        hipError_t e;
+        if ((e = hipEventCreate(&a)) != hipSuccess || (e = hipEventCreate(&b)) != hipSuccess)
+            return hip_fail(e, "hipEventCreate");
+        g_ev_start.push_back(a);
+        g_ev_stop.push_back(b);
+    }
+    return EN_OK;
+}
+
+extern "C" int en_timing_collect(float *ms_out_host, int32_t cap, int32_t *n_out)
+{
+    if (!ms_out_host || !n_out || cap < 0)
+        return fail(EN_ERR_INVALID_ARG, "en_timing_collect: null argument");
+    const int n = std::min<int>(g_ev_used, cap);
+    for (int i = 0; i < n; ++i) {
+        hipError_t e;
+        if ((e = hipEventSynchronize(g_ev_stop[i])) != hipSuccess)
+            return hip_fail(e, "hipEventSynchronize");
+        if ((e = hipEventElapsedTime(&ms_out_host[i], g_ev_start[i], g_ev_stop[i])) != hipSuccess)
+            return hip_fail(e, "hipEventElapsedTime");
+    }
+    *n_out = n;
+    g_ev_used = 0;
+    return EN_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -507,7 +567,12 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
     a.total_wgs = plan->B * pool->d.n_kv_heads * plan->n_splits * a.n_ptiles;
     a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
+    const bool timed = g_ev_used < (int)g_ev_start.size();
+    if (timed)
+        (void)hipEventRecord(g_ev_start[g_ev_used], (hipStream_t)stream);
     int e = en_launch_attention(pool, a, stream);
+    if (timed)
+        (void)hipEventRecord(g_ev_stop[g_ev_used++], (hipStream_t)stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "segmented_prefill_attention launch");
     if (plan->n_splits > 1) {

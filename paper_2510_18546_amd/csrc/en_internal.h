@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 #include "efficientnav.h"
@@ -22,6 +23,8 @@ struct en_pool {
     float *d_cos = nullptr;       // [max_ctx, D/2]
     float *d_sin = nullptr;
     int n_cu = 256;
+    // descriptor blocks of destroyed plans, kept for reuse (bytes, pointer)
+    mutable std::vector<std::pair<size_t, int32_t *>> desc_cache;
 };
 
 struct en_plan {
@@ -35,6 +38,8 @@ struct en_plan {
     std::vector<int32_t> bnd;     // [B, Smax+2] bucket bounds: offset[0..S], then L_c+N_q
     // device copy: nseg | sel | bnd, created on first GPU use
     int32_t *d_desc = nullptr;
+    size_t d_desc_bytes = 0;
+    std::vector<int32_t> h_desc;  // staging copy, alive as long as the plan
     bool uploaded = false;
 };
 

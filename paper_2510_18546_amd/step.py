@@ -70,9 +70,12 @@ class PlanningStep:
             self.ws = B.alloc_workspace(self.pool, self.plan)
             self._ws_bytes = B.workspace_bytes(self.pool, self.plan)
         S1 = inf.max_segments + 1
-        self.mass = torch.empty((self.cfg.n_agents, self.cfg.n_new, self.cfg.n_q_heads, S1),
-                                dtype=torch.float32, device=self.device)
-        self.mass_red = torch.empty((self.cfg.n_agents, S1), dtype=torch.float32, device=self.device)
+        if getattr(self, "_S1", -1) != S1:
+            self.mass = torch.empty((self.cfg.n_agents, self.cfg.n_new, self.cfg.n_q_heads, S1),
+                                    dtype=torch.float32, device=self.device)
+            self.mass_red = torch.empty((self.cfg.n_agents, S1), dtype=torch.float32,
+                                        device=self.device)
+            self._S1 = S1
         return self.plan
 
     def gather(self):
