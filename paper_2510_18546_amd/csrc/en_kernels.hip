@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "en_internal.h"
 
@@ -183,36 +184,66 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
 // attn_bf16: matrix-core attention.
 //
 // Work unit: one workgroup of 4 waves = 4 (query head, 32-query block) pairs of
-// one KV head and one KV split. Each wave keeps its 32 rotated, pre-scaled
-// queries in registers and computes S^T = K Q^T per 64-key tile with
-// v_mfma_f32_32x32x16_bf16, so that every lane owns ONE query (column l%32)
-// and 2x16 of its scores; the row maximum and sum then need a single exchange
-// with lane l^32. P^T goes straight back into the matrix core as the B operand
-// of O^T += V^T P^T: no LDS round trip for P. K tiles [64][D] and V^T tiles
-// [D][64] are staged in LDS with padded rows (conflict-free 16-byte reads).
+// one KV head and one KV split; two workgroups share a compute unit so that
+// one wave's softmax (vector ALU) overlaps another wave's matrix work.
+//
+// Each wave keeps its 32 rotated, pre-scaled queries in registers and computes
+// S^T = K Q^T per 64-key tile with v_mfma_f32_32x32x16_bf16, so that every
+// lane owns ONE query (column l%32) and 2x16 of its scores; the row maximum
+// and sum then need a single exchange with lane l^32. P^T goes straight back
+// into the matrix core as the B operand of O^T += V^T P^T: no LDS round trip
+// for P.
+//
+// K tiles [64][D] and V^T tiles [D][64] go from global memory straight into
+// LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), two
+// stages, one workgroup barrier per tile. Rows are not padded; instead the
+// 16-byte chunks of a row are stored XOR-swizzled (the loader picks which
+// global chunk lands in which slot), which keeps the 16-byte operand reads of
+// 16 consecutive lanes on distinct banks.
 //
 // Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
 // column l%32.
 // ---------------------------------------------------------------------------
-template <int D>
-struct alignas(16) AttnSmem {
-    static constexpr int KSTR = D + 8;
-    static constexpr int VSTR = EN_KEY_TILE + 8;
-    bf16_t k[EN_KEY_TILE * KSTR];
-    bf16_t v[D * VSTR];
-};
+
+// One LDS-DMA load: lane i fetches 16 bytes from sbase + voff and the wave's
+// 1024 bytes land at LDS byte address lds_addr + 16*i. Completion is tracked
+// by vmcnt; the compiler does not see the LDS write, so every wait is explicit.
+__device__ __forceinline__ void dma16(const void *sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+__device__ __forceinline__ void wait_all_memory()
+{
+    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+}
+
+__device__ __forceinline__ float pair_max(float v)
+{
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
 {
     constexpr int KT = EN_KEY_TILE;
-    constexpr int KSTR = AttnSmem<D>::KSTR;
-    constexpr int VSTR = AttnSmem<D>::VSTR;
-    constexpr int NKS = D / 16;          // k-steps of the QK^T product
-    constexpr int NDB = D / 32;          // 32-row blocks of O^T
-    constexpr int NCH = D / 32;          // 16-byte chunks per thread per tile (K and V each)
-    constexpr float TAU = 8.f;           // lazy rescale threshold (log2 units)
-    __shared__ AttnSmem<D> sm;
+    constexpr int NKS = D / 16;                  // k-steps of the QK^T product
+    constexpr int NDB = D / 32;                  // 32-row blocks of O^T
+    constexpr int CK = D / 8;                    // 16-byte chunks per K row
+    constexpr int KSHIFT = (CK == 16) ? 0 : 1;   // K swizzle key = (row >> KSHIFT) & (CK-1)
+    constexpr int ROWB = 2 * D;                  // bytes per K row
+    constexpr int KBYTES = KT * ROWB;
+    constexpr int VROWB = KT * 2;                // bytes per V^T row (128)
+    constexpr int VBYTES = D * VROWB;
+    constexpr int STAGE = KBYTES + VBYTES;
+    constexpr int BPW = KBYTES / 1024 / EN_WAVES;   // 1 KB DMA blocks per wave, K and V each
+    constexpr float TAU = 8.f;                   // lazy rescale threshold (log2 units)
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
     // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
     const int per_xcd = gridDim.x / 8;
@@ -228,7 +259,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
     const int b = t / a.Hkv;
 
     const int tid = threadIdx.x;
-    const int wave = tid / 64, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int lane = tid % 64;
     const int col = lane % 32, half = lane / 32;
     const int r = a.Hq / a.Hkv;
     const int nqb = (a.Nq + 31) / 32;
@@ -258,6 +290,38 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
     const int i_lo = qb * 32;
     const int i_hi = min(a.Nq - 1, qb * 32 + 31);
     const int wave_t_end = wave_valid ? min(t_end, (Lc + i_hi) / KT + 1) : t_begin;
+
+    // ---- loader set-up: per-lane global offsets and LDS block addresses ----
+    const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
+    const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    uint32_t koff[BPW], voff[BPW];
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+        const int blk = wave * BPW + j;
+        const int krow = blk * (64 / CK) + lane / CK;
+        const int kc = (lane % CK) ^ ((krow >> KSHIFT) & (CK - 1));
+        koff[j] = (uint32_t)(krow * ROWB + kc * 16);
+        const int vd = blk * 8 + lane / 8;
+        const int vc = (lane % 8) ^ ((vd >> 1) & 7);
+        voff[j] = (uint32_t)((size_t)vd * a.T * 2 + vc * 16);
+    }
+    auto issue = [&](int stage, int tile) {
+        const char *kt = kg + (size_t)tile * KBYTES;
+        const char *vtile = vg + (size_t)tile * VROWB;
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) {
+            const uint32_t dst = lds0 + stage * STAGE + (wave * BPW + j) * 1024;
+            dma16(kt, koff[j], dst);
+            dma16(vtile, voff[j], dst + KBYTES);
+        }
+    };
+
+    // ---- operand read offsets inside a stage ----
+    const int kkey = (col >> KSHIFT) & (CK - 1);
+    const int vkey = (col >> 1) & 7;
+    const int krow_off = col * ROWB;
+    const int vrow_off = KBYTES + col * VROWB;
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -322,44 +386,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
         seg_part = 0.f;
     };
 
-    // ---- global -> register prefetch of one K tile and one V^T tile ----
-    const bf16_t *kg = (const bf16_t *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * D;
-    const bf16_t *vg = (const bf16_t *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T;
-    uint4 kreg[NCH], vreg[NCH];
-    auto prefetch = [&](int tile) {
-        const bf16_t *kt = kg + (size_t)tile * KT * D;
-        const bf16_t *vtile = vg + (size_t)tile * KT;
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int idx = c * 256 + tid;
-            kreg[c] = *reinterpret_cast<const uint4 *>(kt + (size_t)idx * 8);
-            const int d = idx / 8, ch = idx % 8;
-            vreg[c] = *reinterpret_cast<const uint4 *>(vtile + (size_t)d * a.T + ch * 8);
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int idx = c * 256 + tid;
-            const int row = idx / (D / 8), ch = idx % (D / 8);
-            *reinterpret_cast<uint4 *>(&sm.k[row * KSTR + ch * 8]) = kreg[c];
-            const int d = idx / 8, vch = idx % 8;
-            *reinterpret_cast<uint4 *>(&sm.v[d * VSTR + vch * 8]) = vreg[c];
-        }
-    };
-
-    if (t_begin < t_end)
-        prefetch(t_begin);
-
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        __syncthreads();                  // everyone is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (tile + 1 < t_end)
-            prefetch(tile + 1);
-        if (tile >= wave_t_end)
-            continue;                     // beyond this wave's causal frontier
-
+    auto compute = [&](auto stage_tag, int tile) {
+        constexpr int stage = decltype(stage_tag)::value;
+        const char *sb = smem + stage * STAGE;
         const int kb = tile * KT;
         // ---- S^T = K Q^T ----
         f32x16 s0, s1;
@@ -368,9 +397,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
             s0[e] = s1[e] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(&sm.k[col * KSTR + 16 * ks + 8 * half]);
-            const bf16x8 a1 =
-                *reinterpret_cast<const bf16x8 *>(&sm.k[(32 + col) * KSTR + 16 * ks + 8 * half]);
+            const int slot = ((2 * ks + half) ^ kkey) * 16;
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(sb + krow_off + slot);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(sb + krow_off + 32 * ROWB + slot);
             s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
         }
@@ -387,14 +416,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
             }
         }
         // ---- online softmax with lazy re-referencing ----
-        float mx = s0[0];
+        float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
         for (int e = 1; e < 16; ++e)
-            mx = fmaxf(mx, s0[e]);
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            mx = fmaxf(mx, s1[e]);
-        mx = fmaxf(mx, xor32(mx));
+            mx = fmaxf(mx, fmaxf(s0[e], s1[e]));
+        mx = pair_max(mx);
         const float m_new = (mx > m_ref + TAU || m_ref == EN_NEG_INF) ? fmaxf(mx, m_ref) : m_ref;
         if (__any(m_new != m_ref)) {
             const float alpha = (m_new == EN_NEG_INF) ? 1.f : fast_exp2(m_ref - m_new);
@@ -408,13 +434,35 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
             m_ref = m_new;
         }
         const float m_sub = (m_ref == EN_NEG_INF) ? 0.f : m_ref;
-        float rs = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             s0[e] = fast_exp2(s0[e] - m_sub);
             s1[e] = fast_exp2(s1[e] - m_sub);
-            rs += s0[e] + s1[e];
         }
+        // ---- P^T as bf16 B operands; the row sum is taken from the rounded values ----
+        bf16x8 pf[4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pf[0][j] = (bf16_t)s0[j];
+            pf[1][j] = (bf16_t)s0[8 + j];
+            pf[2][j] = (bf16_t)s1[j];
+            pf[3][j] = (bf16_t)s1[8 + j];
+        }
+        float rs0 = 0.f, rs1 = 0.f;
+        {
+            const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+                for (int j = 0; j < 8; j += 4) {
+                    const bf16x2 p01 = {pf[kk][j], pf[kk][j + 1]};
+                    const bf16x2 p23 = {pf[kk][j + 2], pf[kk][j + 3]};
+                    rs0 = __builtin_amdgcn_fdot2_f32_bf16(p01, ones, rs0, false);
+                    rs1 = __builtin_amdgcn_fdot2_f32_bf16(p23, ones, rs1, false);
+                }
+            }
+        }
+        const float rs = rs0 + rs1;
         l_part += rs;
 
         // ---- per-bucket partial sums ----
@@ -429,8 +477,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int key = kb + 8 * (e / 4) + 4 * half + (e % 4);
-                    part += (key >= lo && key < hi) ? s0[e] : 0.f;
-                    part += (key + 32 >= lo && key + 32 < hi) ? s1[e] : 0.f;
+                    const float p0 = (float)pf[e / 8][e % 8], p1 = (float)pf[2 + e / 8][e % 8];
+                    part += (key >= lo && key < hi) ? p0 : 0.f;
+                    part += (key + 32 >= lo && key + 32 < hi) ? p1 : 0.f;
                 }
                 seg_part += part;
                 if (cur_end > ke)
@@ -453,24 +502,38 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(EnAttnArgs a)
             cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
         }
 
-        // ---- P^T as bf16 B operands, O^T += V^T P^T ----
-        bf16x8 pf[4];
+        // ---- O^T += V^T P^T ----
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            pf[0][j] = (bf16_t)s0[j];
-            pf[1][j] = (bf16_t)s0[8 + j];
-            pf[2][j] = (bf16_t)s1[j];
-            pf[3][j] = (bf16_t)s1[8 + j];
-        }
+        for (int kk = 0; kk < 4; ++kk) {
+            const int slot = ((2 * kk + half) ^ vkey) * 16;
 #pragma unroll
-        for (int d = 0; d < NDB; ++d) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 av =
-                    *reinterpret_cast<const bf16x8 *>(&sm.v[(32 * d + col) * VSTR + 16 * kk + 8 * half]);
+            for (int d = 0; d < NDB; ++d) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(sb + vrow_off + d * 32 * VROWB + slot);
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
             }
         }
+    };
+
+    // ---- main loop: two LDS stages, one barrier per tile. The loads of tile
+    // t+1 are issued right after the barrier of tile t into the stage that was
+    // read during tile t-1, so they have a whole iteration to land. ----
+    if (t_begin < t_end)
+        issue(0, t_begin);
+    for (int tile = t_begin; tile < t_end; tile += 2) {
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        if (tile + 1 < t_end)
+            issue(1, tile + 1);
+        if (tile < wave_t_end)
+            compute(std::integral_constant<int, 0>{}, tile);
+        if (tile + 1 >= t_end)
+            break;
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        if (tile + 2 < t_end)
+            issue(0, tile + 2);
+        if (tile + 1 < wave_t_end)
+            compute(std::integral_constant<int, 1>{}, tile + 1);
     }
 
     if (!wave_valid)
