@@ -426,7 +426,8 @@ EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *pl)
     const size_t rows = size_t(pl->B) * pool->d.n_q_heads * pl->Nq;
     L.ml_off = 0;
     L.seg_off = align256(L.ml_off + size_t(pl->n_splits) * rows * 2 * sizeof(float));
-    L.opart_off = align256(L.seg_off + size_t(pl->n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
+    L.red_off = align256(L.seg_off + size_t(pl->n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
+    L.opart_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
     L.total = L.opart_off;
     if (pl->n_splits > 1)
         L.total = align256(L.opart_off + size_t(pl->n_splits) * rows * pool->d.head_dim * sizeof(float));
@@ -583,7 +584,7 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     return EN_OK;
 }
 
-extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, const void *ws_dev, int32_t reduce,
+extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
                                       float *mass_out_dev, void *stream)
 {
     if (!pool || !plan || !ws_dev || !mass_out_dev || (reduce != 0 && reduce != 1))
@@ -594,10 +595,11 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, const void *
     if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
         return rc;
     const EnWsLayout L = en_ws_layout(pool, plan);
-    const char *ws = static_cast<const char *>(ws_dev);
+    char *ws = static_cast<char *>(ws_dev);
     EnMassArgs a;
     a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
     a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
+    a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
     a.nseg = d_nseg(plan);
     a.bnd = d_bnd(plan);
     a.out = mass_out_dev;

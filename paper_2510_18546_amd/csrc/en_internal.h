@@ -67,6 +67,7 @@ struct EnAttnArgs {
 
 struct EnMassArgs {
     const float *ws_ml, *ws_seg;
+    float *ws_red;     // [B, Smax+1, Hq] per-head partial sums of the reduced masses
     const int32_t *nseg, *bnd;
     float *out;
     int B, Hq, Nq, Smax, n_splits;
@@ -74,7 +75,7 @@ struct EnMassArgs {
 
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
-    size_t ml_off, seg_off, opart_off, total;
+    size_t ml_off, seg_off, red_off, opart_off, total;
 };
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 
 #include "en_internal.h"
@@ -240,10 +242,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
     constexpr int KBYTES = KT * ROWB;
     constexpr int VROWB = KT * 2;                // bytes per V^T row (128)
     constexpr int VBYTES = D * VROWB;
-    constexpr int STAGE = KBYTES + VBYTES;
+    constexpr int KSTAGES = 2, VSTAGES = 3;
+    constexpr int VBASE = KSTAGES * KBYTES;      // V stages follow the K stages
     constexpr int BPW = KBYTES / 1024 / EN_WAVES;   // 1 KB DMA blocks per wave, K and V each
     constexpr float TAU = 8.f;                   // lazy rescale threshold (log2 units)
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) char smem[KSTAGES * KBYTES + VSTAGES * VBYTES];
 
     // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
     const int per_xcd = gridDim.x / 8;
@@ -306,22 +309,28 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
         const int vc = (lane % 8) ^ ((vd >> 1) & 7);
         voff[j] = (uint32_t)((size_t)vd * a.T * 2 + vc * 16);
     }
-    auto issue = [&](int stage, int tile) {
+    auto issue = [&](int tile) {
         const char *kt = kg + (size_t)tile * KBYTES;
         const char *vtile = vg + (size_t)tile * VROWB;
+        const uint32_t kdst = lds0 + (tile % KSTAGES) * KBYTES + wave * BPW * 1024;
+        const uint32_t vdst = lds0 + VBASE + (tile % VSTAGES) * VBYTES + wave * BPW * 1024;
 #pragma unroll
         for (int j = 0; j < BPW; ++j) {
-            const uint32_t dst = lds0 + stage * STAGE + (wave * BPW + j) * 1024;
-            dma16(kt, koff[j], dst);
-            dma16(vtile, voff[j], dst + KBYTES);
+            dma16(kt, koff[j], kdst + j * 1024);
+            dma16(vtile, voff[j], vdst + j * 1024);
         }
     };
 
     // ---- operand read offsets inside a stage ----
     const int kkey = (col >> KSHIFT) & (CK - 1);
     const int vkey = (col >> 1) & 7;
-    const int krow_off = col * ROWB;
-    const int vrow_off = KBYTES + col * VROWB;
+    int kaddr[NKS], vaddr[4];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+        kaddr[ks] = col * ROWB + ((2 * ks + half) ^ kkey) * 16;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        vaddr[kk] = VBASE + col * VROWB + ((2 * kk + half) ^ vkey) * 16;
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -364,7 +373,23 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
             o[d][e] = 0.f;
-    float m_ref = EN_NEG_INF;     // reference maximum of this row (log2 units)
+    bf16x8 pf[4];                 // P^T of the previous tile, not yet multiplied with V
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            pf[kk][j] = (bf16_t)0.f;
+    // Softmax reference of this row (log2 units). It is chosen at the first
+    // tile in which the row sees a key and afterwards only moved when the
+    // exponentials of a tile would overflow (see compute). Scores leave the
+    // matrix core already reduced by it: the accumulators start at -m_ref.
+    float m_ref = 0.f;
+    bool has_ref = false;
+    bool pending = row_valid && Lc + i_row >= split_key_begin;   // the row will see a key in this split
+    f32x16 negm;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        negm[e] = 0.f;
     float l_part = 0.f;           // this lane's share of the row sum
     float seg_part = 0.f;         // this lane's share of the current bucket's sum
 
@@ -380,30 +405,63 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
         // called by the whole wave when bucket `bucket` has been fully consumed
         const float tot = seg_part + xor32(seg_part);
         if (seg_base && row_valid && half == 0) {
-            f32x2 v = {tot, m_ref};
+            f32x2 v = {tot, has_ref ? m_ref : EN_NEG_INF};
             *reinterpret_cast<f32x2 *>(seg_base + ((size_t)bucket * a.Nq + i_row) * 2) = v;
         }
         seg_part = 0.f;
     };
 
-    auto compute = [&](auto stage_tag, int tile) {
-        constexpr int stage = decltype(stage_tag)::value;
-        const char *sb = smem + stage * STAGE;
+    // O^T += V^T(tile) P^T with the P^T held in pf.
+    auto pv_only = [&](int tile) {
+        const char *vb = smem + (tile % VSTAGES) * VBYTES;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int d = 0; d < NDB; ++d) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vb + vaddr[kk] + d * 32 * VROWB);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
+            }
+    };
+
+    // One tile: S^T = K(tile) Q^T, softmax, and, interleaved with the softmax
+    // arithmetic, the P V product of the PREVIOUS tile, so that the matrix core
+    // works while the vector ALU exponentiates.
+    // Scores of one tile relative to m_ref: S^T = K(tile) Q^T - m_ref, with the
+    // causal / padding mask applied on tiles that reach past L_c + i_lo. The
+    // operand reads run PD matrix instructions ahead; scheduling fences keep
+    // that distance in the generated code.
+    auto qk_scores = [&](int tile, f32x16 &s0, f32x16 &s1) {
+        const char *kbuf = smem + (tile % KSTAGES) * KBYTES;
         const int kb = tile * KT;
-        // ---- S^T = K Q^T ----
-        f32x16 s0, s1;
+        {
+            constexpr int PD = 4, NST = 2 * NKS;
+            bf16x8 fr[PD];
+            auto kread = [&](int k) {
+#ifdef EXP_NO_LDSREAD
+                return qf[k % NKS];
+#else
+                return *reinterpret_cast<const bf16x8 *>(kbuf + kaddr[k / 2] + (k % 2) * 32 * ROWB);
+#endif
+            };
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            s0[e] = s1[e] = 0.f;
+            for (int k = 0; k < PD; ++k)
+                fr[k] = kread(k);
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int slot = ((2 * ks + half) ^ kkey) * 16;
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(sb + krow_off + slot);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(sb + krow_off + 32 * ROWB + slot);
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
+            for (int k = 0; k < NST; ++k) {
+                const bf16x8 cur_fr = fr[k % PD];
+                if (k + PD < NST)
+                    fr[k % PD] = kread(k + PD);
+                if (k == 0)
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
+                else if (k == 1)
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
+                else if (k % 2 == 0)
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[k / 2], s0, 0, 0, 0);
+                else
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[k / 2], s1, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        // ---- causal / padding mask (only tiles that reach past L_c + i_lo) ----
         if (kb + KT - 1 > Lc + i_lo) {
             const int lim = Lc + i_row;           // last visible key of this row
 #pragma unroll
@@ -415,15 +473,86 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
                     s1[e] = EN_NEG_INF;
             }
         }
-        // ---- online softmax with lazy re-referencing ----
-        float mx = fmaxf(s0[0], s1[0]);
+    };
+
+    // One tile: scores, exponentials, and, interleaved with the exponentials,
+    // the P V product of the PREVIOUS tile (its V^T is still staged), so that
+    // the wait for the score accumulators is filled with matrix work.
+    auto compute = [&](int tile) {
+        const char *vb = smem + ((tile + VSTAGES - 1) % VSTAGES) * VBYTES;     // V of tile-1
+        const int kb = tile * KT;
+        f32x16 s0, s1;
+        qk_scores(tile, s0, s1);
+
+        bf16x8 pn[4];
+        float rs0 = 0.f, rs1 = 0.f;
+        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+        {
+            constexpr int PD = 3, NST = 4 * NDB;
+            bf16x8 fr[PD];
+            auto vread = [&](int k) {
+#ifdef EXP_NO_LDSREAD
+                return qf[k % NKS];
+#else
+                return *reinterpret_cast<const bf16x8 *>(vb + vaddr[k / NDB] + (k % NDB) * 32 * VROWB);
+#endif
+            };
 #pragma unroll
-        for (int e = 1; e < 16; ++e)
-            mx = fmaxf(mx, fmaxf(s0[e], s1[e]));
-        mx = pair_max(mx);
-        const float m_new = (mx > m_ref + TAU || m_ref == EN_NEG_INF) ? fmaxf(mx, m_ref) : m_ref;
-        if (__any(m_new != m_ref)) {
-            const float alpha = (m_new == EN_NEG_INF) ? 1.f : fast_exp2(m_ref - m_new);
+            for (int k = 0; k < PD; ++k)
+                fr[k] = vread(k);
+#pragma unroll
+            for (int k = 0; k < NST; ++k) {
+                const int kk = k / NDB, d = k % NDB;
+                const bf16x8 cur_fr = fr[k % PD];
+                if (k + PD < NST)
+                    fr[k % PD] = vread(k + PD);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pf[kk], o[d], 0, 0, 0);
+                // scores handled at this step: 8 / NDB of the 8 that make pn[kk]
+#pragma unroll
+                for (int u = 0; u < 8 / NDB; u += 2) {
+                    const int j = d * (8 / NDB) + u;              // index inside pn[kk]
+                    const int e = 8 * (kk % 2) + j;               // index inside s0 / s1
+                    float p0, p1;
+                    if (kk < 2) {
+                        p0 = fast_exp2(s0[e]);
+                        p1 = fast_exp2(s0[e + 1]);
+                    } else {
+                        p0 = fast_exp2(s1[e]);
+                        p1 = fast_exp2(s1[e + 1]);
+                    }
+                    const f32x2 pp = {p0, p1};
+                    const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                    pn[kk][j] = pb[0];
+                    pn[kk][j + 1] = pb[1];
+                    if (u & 2)
+                        rs1 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs1, false);
+                    else
+                        rs0 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs0, false);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        float rs = rs0 + rs1;
+
+        // ---- reference check. Nothing is done as long as every row has a
+        // reference and no exponential came near overflow (any magnitude below
+        // that is harmless: P keeps its relative precision in bf16 and the
+        // accumulators are fp32). Otherwise the wave recomputes the scores,
+        // moves the affected rows to their current maximum, rescales what
+        // they have accumulated and redoes the exponentials. ----
+        constexpr float BIG = 1.0e18f;            // 2^60
+        if (__any(pending || !(rs < BIG))) {
+            qk_scores(tile, s0, s1);
+            float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+            for (int e = 1; e < 16; ++e)
+                mx = fmaxf(mx, fmaxf(s0[e], s1[e]));
+            mx = pair_max(mx);
+            // both lanes of a row must take the same decision
+            const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
+            const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
+            const float delta = fix ? mx : 0.f;
+            const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
 #pragma unroll
             for (int d = 0; d < NDB; ++d)
 #pragma unroll
@@ -431,38 +560,26 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
                     o[d][e] *= alpha;
             l_part *= alpha;
             seg_part *= alpha;
-            m_ref = m_new;
-        }
-        const float m_sub = (m_ref == EN_NEG_INF) ? 0.f : m_ref;
+            m_ref += delta;
+            has_ref = has_ref || fix;
+            pending = pending && !fix;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            s0[e] = fast_exp2(s0[e] - m_sub);
-            s1[e] = fast_exp2(s1[e] - m_sub);
-        }
-        // ---- P^T as bf16 B operands; the row sum is taken from the rounded values ----
-        bf16x8 pf[4];
+            for (int e = 0; e < 16; ++e)
+                negm[e] = -m_ref;
+            rs = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            pf[0][j] = (bf16_t)s0[j];
-            pf[1][j] = (bf16_t)s0[8 + j];
-            pf[2][j] = (bf16_t)s1[j];
-            pf[3][j] = (bf16_t)s1[8 + j];
-        }
-        float rs0 = 0.f, rs1 = 0.f;
-        {
-            const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+            for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-                for (int j = 0; j < 8; j += 4) {
-                    const bf16x2 p01 = {pf[kk][j], pf[kk][j + 1]};
-                    const bf16x2 p23 = {pf[kk][j + 2], pf[kk][j + 3]};
-                    rs0 = __builtin_amdgcn_fdot2_f32_bf16(p01, ones, rs0, false);
-                    rs1 = __builtin_amdgcn_fdot2_f32_bf16(p23, ones, rs1, false);
+                for (int j = 0; j < 8; ++j) {
+                    const int e = 8 * (kk % 2) + j;
+                    const bf16_t pb = (bf16_t)fast_exp2((kk < 2 ? s0[e] : s1[e]) - delta);
+                    pn[kk][j] = pb;
+                    rs += (float)pb;
                 }
-            }
         }
-        const float rs = rs0 + rs1;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            pf[kk] = pn[kk];
         l_part += rs;
 
         // ---- per-bucket partial sums ----
@@ -501,40 +618,43 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
             ++cur;
             cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
         }
-
-        // ---- O^T += V^T P^T ----
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int slot = ((2 * kk + half) ^ vkey) * 16;
-#pragma unroll
-            for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(sb + vrow_off + d * 32 * VROWB + slot);
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
-            }
-        }
     };
 
-    // ---- main loop: two LDS stages, one barrier per tile. The loads of tile
-    // t+1 are issued right after the barrier of tile t into the stage that was
-    // read during tile t-1, so they have a whole iteration to land. ----
-    if (t_begin < t_end)
-        issue(0, t_begin);
-    for (int tile = t_begin; tile < t_end; tile += 2) {
-        wait_all_memory();
-        __builtin_amdgcn_s_barrier();
-        if (tile + 1 < t_end)
-            issue(1, tile + 1);
-        if (tile < wave_t_end)
-            compute(std::integral_constant<int, 0>{}, tile);
-        if (tile + 1 >= t_end)
-            break;
-        wait_all_memory();
-        __builtin_amdgcn_s_barrier();
-        if (tile + 2 < t_end)
-            issue(0, tile + 2);
-        if (tile + 1 < wave_t_end)
-            compute(std::integral_constant<int, 1>{}, tile + 1);
+    // ---- main loop. K has two LDS stages, V^T three (the V of tile t is
+    // consumed one iteration late). The loads of tile t+1 are issued right after
+    // the barrier of tile t into stages last read during tile t-1 (K) and tile
+    // t-2's product (V), so they have a whole iteration to land; one barrier per
+    // tile. The first iteration multiplies a zero P^T with a zero-filled stage. ----
+    {
+        char *vz = smem + VBASE + ((t_begin + VSTAGES - 1) % VSTAGES) * VBYTES;
+        for (int i = tid * 16; i < VBYTES; i += 256 * 16)
+            *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
     }
+    if (t_begin < t_end)
+        issue(t_begin);
+    for (int tile = t_begin; tile < t_end; ++tile) {
+#ifdef EXP_NO_BARRIER
+        if (tile == t_begin)
+#endif
+        {
+            wait_all_memory();
+            __builtin_amdgcn_s_barrier();
+        }
+#ifndef EXP_NO_DMA
+        if (tile + 1 < t_end)
+            issue(tile + 1);
+#endif
+#ifdef EXP_NO_COMPUTE
+        if (false)
+#else
+        if (tile < wave_t_end)
+#endif
+            compute(tile);
+        else if (tile == wave_t_end && tile > t_begin)
+            pv_only(tile - 1);            // the wave's last pending product
+    }
+    if (wave_t_end == t_end && t_end > t_begin)
+        pv_only(t_end - 1);
 
     if (!wave_valid)
         return;
@@ -554,7 +674,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
     const float l_tot = l_part + xor32(l_part);
     const size_t row = row_hq * a.Nq + i_row;
     if (a.ws_ml && row_valid && half == 0) {
-        f32x2 v = {m_ref, l_tot};
+        f32x2 v = {has_ref ? m_ref : EN_NEG_INF, l_tot};
         *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
     }
     if (!row_valid)
@@ -813,11 +933,12 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     }
 }
 
-// reduce = 1. grid: (Smax+1, B); the block sums bucket s over all heads and queries.
-__global__ __launch_bounds__(256) void mass_reduce_kernel(EnMassArgs a)
+// reduce = 1, stage 1. grid: (Smax+1, Hq, B): the block sums bucket s of one
+// head over the queries into partial[b][s][hq].
+__global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
 {
     __shared__ float red[4];
-    const int s = blockIdx.x, b = blockIdx.y;
+    const int s = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
@@ -825,8 +946,7 @@ __global__ __launch_bounds__(256) void mass_reduce_kernel(EnMassArgs a)
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float acc = 0.f;
     if (s <= S && bnd[s + 1] > bnd[s]) {
-        for (int idx = threadIdx.x; idx < a.Hq * a.Nq; idx += 256) {
-            const int hq = idx / a.Nq, i = idx % a.Nq;
+        for (int i = threadIdx.x; i < a.Nq; i += 256) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
             float M, L;
             row_final_ml(a, rows, row, M, L);
@@ -838,7 +958,20 @@ __global__ __launch_bounds__(256) void mass_reduce_kernel(EnMassArgs a)
         red[threadIdx.x / 64] = acc;
     __syncthreads();
     if (threadIdx.x == 0)
-        a.out[(size_t)b * (a.Smax + 1) + s] = red[0] + red[1] + red[2] + red[3];
+        a.ws_red[((size_t)b * (a.Smax + 1) + s) * a.Hq + hq] = red[0] + red[1] + red[2] + red[3];
+}
+
+// reduce = 1, stage 2. One thread per (agent, bucket) sums the heads.
+__global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.B * (a.Smax + 1))
+        return;
+    const float *p = a.ws_red + (size_t)idx * a.Hq;
+    float acc = 0.f;
+    for (int h = 0; h < a.Hq; ++h)
+        acc += p[h];
+    a.out[idx] = acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -880,6 +1013,14 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
             hipLaunchKernelGGL((attn_f32_kernel<128>), grid, blk, 0, st, a);
     } else {
         const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(256);
+        static bool reported = false;
+        if (!reported && getenv("EN_DEBUG")) {
+            reported = true;
+            int n64 = -1, n128 = -1;
+            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 256, 0);
+            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 0);
+            fprintf(stderr, "[efficientnav] attn_bf16 workgroups per CU: D=64 %d, D=128 %d\n", n64, n128);
+        }
         if (D == 64)
             hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, blk, 0, st, a);
         else
@@ -916,8 +1057,10 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         const dim3 grid((a.Nq + 255) / 256, a.Hq, a.B), blk(256);
         hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
     } else {
-        const dim3 grid(a.Smax + 1, a.B), blk(256);
-        hipLaunchKernelGGL(mass_reduce_kernel, grid, blk, 0, st, a);
+        const dim3 grid(a.Smax + 1, a.Hq, a.B), blk(256);
+        hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
+        const dim3 grid2((a.B * (a.Smax + 1) + 255) / 256);
+        hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
     }
     return (int)hipGetLastError();
 }
