@@ -145,15 +145,15 @@ static int pool_ensure_device(en_pool *p)
 // ---------------------------------------------------------------------------
 static int choose_splits(const en_pool *pool, const en_plan *pl)
 {
-    // One workgroup covers 4 (head, 32-query block) pairs of one KV head. Split
-    // the key range until about two workgroups per compute unit exist, keeping
-    // at least four key tiles per split.
+    // One workgroup covers 8 (head, 32-query block) pairs of one KV head and
+    // fills a compute unit. Split the key range until every compute unit has a
+    // workgroup, keeping at least four key tiles per split.
     const int r = pool->r;
     const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     const int n_ptiles = (r * nqb + EN_WAVES - 1) / EN_WAVES;
     const long base = long(pl->B) * pool->d.n_kv_heads * n_ptiles;
     const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
-    long want = (2L * pool->n_cu + base - 1) / base;
+    long want = (long(pool->n_cu) + base - 1) / base;
     want = std::min<long>(want, std::max(1, tiles / 4));
     want = std::max<long>(1, std::min<long>(want, 64));
     return int(want);

@@ -11,7 +11,7 @@
 
 constexpr int EN_KEY_TILE = 64;    // keys per attention tile; context rows are padded to it
 constexpr int EN_ROWS_PER_WAVE = 32;
-constexpr int EN_WAVES = 4;
+constexpr int EN_WAVES = 8;          // waves per attention workgroup
 
 struct en_pool {
     en_pool_desc d;

@@ -185,23 +185,27 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
 // ---------------------------------------------------------------------------
 // attn_bf16: matrix-core attention.
 //
-// Work unit: one workgroup of 4 waves = 4 (query head, 32-query block) pairs of
-// one KV head and one KV split; two workgroups share a compute unit so that
-// one wave's softmax (vector ALU) overlaps another wave's matrix work.
+// Work unit: one workgroup of 8 waves = 8 (query head, 32-query block) pairs of
+// one KV head and one KV split, one workgroup per compute unit.
 //
 // Each wave keeps its 32 rotated, pre-scaled queries in registers and computes
 // S^T = K Q^T per 64-key tile with v_mfma_f32_32x32x16_bf16, so that every
-// lane owns ONE query (column l%32) and 2x16 of its scores; the row maximum
-// and sum then need a single exchange with lane l^32. P^T goes straight back
-// into the matrix core as the B operand of O^T += V^T P^T: no LDS round trip
-// for P.
+// lane owns ONE query (column l%32) and 2x16 of its scores; row reductions
+// then need a single exchange with lane l^32. P^T goes straight back into the
+// matrix core as the B operand of O^T += V^T P^T: no LDS round trip for P.
+//
+// Per tile a wave runs two phases: SCORES (matrix work only) and EXP (the
+// exponentials on the vector ALU, interleaved with the P V product of the
+// previous tile). The two waves that share a SIMD (wave w and w+4) run these
+// phases in opposite order: time is cut into slots by workgroup barriers, and
+// while one wave is in SCORES its partner is in EXP, so the matrix core always
+// has work and the vector ALU work hides behind it.
 //
 // K tiles [64][D] and V^T tiles [D][64] go from global memory straight into
-// LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), two
-// stages, one workgroup barrier per tile. Rows are not padded; instead the
-// 16-byte chunks of a row are stored XOR-swizzled (the loader picks which
-// global chunk lands in which slot), which keeps the 16-byte operand reads of
-// 16 consecutive lanes on distinct banks.
+// LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), three
+// stages each. Rows are padded by 16 bytes (the loader lets one lane in 17 / 9
+// fetch a dummy chunk into the pad), which keeps the 16-byte operand reads of
+// 16 consecutive lanes on distinct banks with plain base + immediate addresses.
 //
 // Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
 // column l%32.
@@ -218,9 +222,11 @@ __device__ __forceinline__ void dma16(const void *sbase, uint32_t voff, uint32_t
                  : "memory");
 }
 
-__device__ __forceinline__ void wait_all_memory()
+// s_waitcnt with lgkmcnt(0) and vmcnt(N), N a compile-time constant
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm0()
 {
-    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070);
 }
 
 __device__ __forceinline__ float pair_max(float v)
@@ -230,23 +236,36 @@ __device__ __forceinline__ float pair_max(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+constexpr int ATT_WAVES = EN_WAVES;       // 8 waves: groups A (0..3) and B (4..7)
+
+#ifdef EXP_TIMING
+__device__ unsigned long long en_dbg[32];
+#define TICK(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
+#define TACC(slot, a, b) dbg_acc[slot] += (b) - (a)
+#else
+#define TICK(var)
+#define TACC(slot, a, b)
+#endif
+
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
+__global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 {
     constexpr int KT = EN_KEY_TILE;
     constexpr int NKS = D / 16;                  // k-steps of the QK^T product
     constexpr int NDB = D / 32;                  // 32-row blocks of O^T
-    constexpr int CK = D / 8;                    // 16-byte chunks per K row
-    constexpr int KSHIFT = (CK == 16) ? 0 : 1;   // K swizzle key = (row >> KSHIFT) & (CK-1)
-    constexpr int ROWB = 2 * D;                  // bytes per K row
-    constexpr int KBYTES = KT * ROWB;
-    constexpr int VROWB = KT * 2;                // bytes per V^T row (128)
-    constexpr int VBYTES = D * VROWB;
-    constexpr int KSTAGES = 2, VSTAGES = 3;
-    constexpr int VBASE = KSTAGES * KBYTES;      // V stages follow the K stages
-    constexpr int BPW = KBYTES / 1024 / EN_WAVES;   // 1 KB DMA blocks per wave, K and V each
-    constexpr float TAU = 8.f;                   // lazy rescale threshold (log2 units)
-    __shared__ __attribute__((aligned(1024))) char smem[KSTAGES * KBYTES + VSTAGES * VBYTES];
+    constexpr int ROWB = 2 * D;                  // bytes per K row in global memory
+    constexpr int KSTR = ROWB + 16;              // padded K row in LDS
+    constexpr int KCPR = KSTR / 16;              // 16-byte chunks per padded K row
+    constexpr int KBYTES = KT * KSTR;            // multiple of 1024
+    constexpr int VSTR = KT * 2 + 16;            // padded V^T row in LDS (144)
+    constexpr int VBYTES = D * VSTR;             // multiple of 1024
+    constexpr int NST = 3;                       // LDS stages of K and of V^T
+    constexpr int VBASE = NST * KBYTES;
+    constexpr int NBK = KBYTES / 1024, NBV = VBYTES / 1024;   // 1 KB loader blocks per tile
+    constexpr int KJ = (NBK + ATT_WAVES - 1) / ATT_WAVES;     // max blocks per wave
+    constexpr int VJ = (NBV + ATT_WAVES - 1) / ATT_WAVES;
+    static_assert(KBYTES % 1024 == 0 && VBYTES % 1024 == 0, "tile must be whole loader blocks");
+    __shared__ __attribute__((aligned(1024))) char smem[NST * (KBYTES + VBYTES)];
 
     // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
     const int per_xcd = gridDim.x / 8;
@@ -263,11 +282,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int grp = wave / 4;                    // 0: group A, 1: group B (one slot behind)
     const int lane = tid % 64;
     const int col = lane % 32, half = lane / 32;
     const int r = a.Hq / a.Hkv;
     const int nqb = (a.Nq + 31) / 32;
-    const int pair = ptile * EN_WAVES + wave;
+    const int pair = ptile * ATT_WAVES + wave;
     const bool wave_valid = pair < r * nqb;
     const int hl = wave_valid ? pair % r : 0;
     const int qb = wave_valid ? pair / r : 0;
@@ -286,51 +306,59 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
     const int split_key_end = min(t_end * KT, Ltot);
     {
         // causal frontier of the workgroup: last key any of its rows may see
-        const int qb_hi = min((ptile * EN_WAVES + EN_WAVES - 1) / r, nqb - 1);
+        const int qb_hi = min((ptile * ATT_WAVES + ATT_WAVES - 1) / r, nqb - 1);
         const int last_key = Lc + min(a.Nq - 1, qb_hi * 32 + 31);
         t_end = min(t_end, last_key / KT + 1);
     }
+    const int nt = max(t_end - t_begin, 0);      // tiles of the workgroup
     const int i_lo = qb * 32;
     const int i_hi = min(a.Nq - 1, qb * 32 + 31);
-    const int wave_t_end = wave_valid ? min(t_end, (Lc + i_hi) / KT + 1) : t_begin;
+    (void)i_hi;
+    // Every wave of the workgroup walks all its tiles: a wave whose own causal
+    // frontier is a tile or two earlier sees only masked scores there, and a
+    // wave without a valid (head, query block) pair computes on zero queries
+    // and writes nothing.
 
-    // ---- loader set-up: per-lane global offsets and LDS block addresses ----
+    // ---- loader set-up. Block blk of a tile is LDS bytes [1024 blk, 1024 blk + 1024);
+    // lane L of it is chunk q = 64 blk + L of the padded tile: row q / CPR, chunk
+    // q % CPR of that row, the last chunk of a row being the pad. ----
     const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
     const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
-    uint32_t koff[BPW], voff[BPW];
+    uint32_t koff[KJ], voff[VJ];
 #pragma unroll
-    for (int j = 0; j < BPW; ++j) {
-        const int blk = wave * BPW + j;
-        const int krow = blk * (64 / CK) + lane / CK;
-        const int kc = (lane % CK) ^ ((krow >> KSHIFT) & (CK - 1));
-        koff[j] = (uint32_t)(krow * ROWB + kc * 16);
-        const int vd = blk * 8 + lane / 8;
-        const int vc = (lane % 8) ^ ((vd >> 1) & 7);
-        voff[j] = (uint32_t)((size_t)vd * a.T * 2 + vc * 16);
+    for (int j = 0; j < KJ; ++j) {
+        const int q = (wave + ATT_WAVES * j) * 64 + lane;
+        const int row = q / KCPR, c = q % KCPR;
+        koff[j] = (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16);
     }
-    auto issue = [&](int tile) {
-        const char *kt = kg + (size_t)tile * KBYTES;
-        const char *vtile = vg + (size_t)tile * VROWB;
-        const uint32_t kdst = lds0 + (tile % KSTAGES) * KBYTES + wave * BPW * 1024;
-        const uint32_t vdst = lds0 + VBASE + (tile % VSTAGES) * VBYTES + wave * BPW * 1024;
 #pragma unroll
-        for (int j = 0; j < BPW; ++j) {
-            dma16(kt, koff[j], kdst + j * 1024);
-            dma16(vtile, voff[j], vdst + j * 1024);
-        }
+    for (int j = 0; j < VJ; ++j) {
+        const int q = (wave + ATT_WAVES * j) * 64 + lane;
+        const int d = q / 9, c = q % 9;
+        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < 8 ? c : 0) * 16);
+    }
+    const int n_vblk = (NBV - wave + ATT_WAVES - 1) / ATT_WAVES;   // V^T blocks this wave loads
+    auto issue_k = [&](int tile) {
+        const char *kt = kg + (size_t)tile * (KT * ROWB);
+        const uint32_t dst = lds0 + (tile % NST) * KBYTES + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            if (wave + ATT_WAVES * j < NBK)
+                dma16(kt, koff[j], dst + j * ATT_WAVES * 1024);
+    };
+    auto issue_v = [&](int tile) {
+        const char *vtile = vg + (size_t)tile * (KT * 2);
+        const uint32_t dst = lds0 + VBASE + (tile % NST) * VBYTES + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < VJ; ++j)
+            if (wave + ATT_WAVES * j < NBV)
+                dma16(vtile, voff[j], dst + j * ATT_WAVES * 1024);
     };
 
-    // ---- operand read offsets inside a stage ----
-    const int kkey = (col >> KSHIFT) & (CK - 1);
-    const int vkey = (col >> 1) & 7;
-    int kaddr[NKS], vaddr[4];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-        kaddr[ks] = col * ROWB + ((2 * ks + half) ^ kkey) * 16;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-        vaddr[kk] = VBASE + col * VROWB + ((2 * kk + half) ^ vkey) * 16;
+    // ---- operand read bases inside a stage (plus immediates per step) ----
+    const int klane = col * KSTR + half * 16;
+    const int vlane = VBASE + col * VSTR + half * 16;
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -366,6 +394,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
                 qf[ks][j] = (bf16_t)qx[ks][j];
     }
 
+#ifdef EXP_TIMING
+    unsigned long long dbg_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
     // ---- state ----
     f32x16 o[NDB];
 #pragma unroll
@@ -379,9 +410,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             pf[kk][j] = (bf16_t)0.f;
+    f32x16 s0, s1;                // scores of the current tile, SCORES phase -> EXP phase
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        s0[e] = s1[e] = 0.f;
     // Softmax reference of this row (log2 units). It is chosen at the first
     // tile in which the row sees a key and afterwards only moved when the
-    // exponentials of a tile would overflow (see compute). Scores leave the
+    // exponentials of a tile would overflow (see exp_phase). Scores leave the
     // matrix core already reduced by it: the accumulators start at -m_ref.
     float m_ref = 0.f;
     bool has_ref = false;
@@ -413,43 +448,36 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
 
     // O^T += V^T(tile) P^T with the P^T held in pf.
     auto pv_only = [&](int tile) {
-        const char *vb = smem + (tile % VSTAGES) * VBYTES;
+        const char *vb = smem + vlane + (tile % NST) * VBYTES;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
             for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vb + vaddr[kk] + d * 32 * VROWB);
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vb + kk * 32 + d * 32 * VSTR);
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
             }
     };
 
-    // One tile: S^T = K(tile) Q^T, softmax, and, interleaved with the softmax
-    // arithmetic, the P V product of the PREVIOUS tile, so that the matrix core
-    // works while the vector ALU exponentiates.
-    // Scores of one tile relative to m_ref: S^T = K(tile) Q^T - m_ref, with the
-    // causal / padding mask applied on tiles that reach past L_c + i_lo. The
-    // operand reads run PD matrix instructions ahead; scheduling fences keep
-    // that distance in the generated code.
-    auto qk_scores = [&](int tile, f32x16 &s0, f32x16 &s1) {
-        const char *kbuf = smem + (tile % KSTAGES) * KBYTES;
+    // SCORES phase: s0, s1 = K(tile) Q^T - m_ref, with the causal / padding mask
+    // on tiles that reach past L_c + i_lo. The operand reads run PD matrix
+    // instructions ahead; scheduling fences keep that distance in the code.
+    auto scores_phase = [&](int tile) {
+        TICK(ts0);
+        const char *kbuf = smem + klane + (tile % NST) * KBYTES;
         const int kb = tile * KT;
         {
-            constexpr int PD = 4, NST = 2 * NKS;
+            constexpr int PD = 4, NSTEP = 2 * NKS;
             bf16x8 fr[PD];
             auto kread = [&](int k) {
-#ifdef EXP_NO_LDSREAD
-                return qf[k % NKS];
-#else
-                return *reinterpret_cast<const bf16x8 *>(kbuf + kaddr[k / 2] + (k % 2) * 32 * ROWB);
-#endif
+                return *reinterpret_cast<const bf16x8 *>(kbuf + (k / 2) * 32 + (k % 2) * 32 * KSTR);
             };
 #pragma unroll
             for (int k = 0; k < PD; ++k)
                 fr[k] = kread(k);
 #pragma unroll
-            for (int k = 0; k < NST; ++k) {
+            for (int k = 0; k < NSTEP; ++k) {
                 const bf16x8 cur_fr = fr[k % PD];
-                if (k + PD < NST)
+                if (k + PD < NSTEP)
                     fr[k % PD] = kread(k + PD);
                 if (k == 0)
                     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
@@ -473,38 +501,33 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
                     s1[e] = EN_NEG_INF;
             }
         }
+        TICK(ts1);
+        TACC(0, ts0, ts1);
     };
 
-    // One tile: scores, exponentials, and, interleaved with the exponentials,
-    // the P V product of the PREVIOUS tile (its V^T is still staged), so that
-    // the wait for the score accumulators is filled with matrix work.
-    auto compute = [&](int tile) {
-        const char *vb = smem + ((tile + VSTAGES - 1) % VSTAGES) * VBYTES;     // V of tile-1
+    // EXP phase of a tile: exponentials of its scores and, interleaved, the
+    // P V product of the PREVIOUS tile (its V^T is still staged).
+    auto exp_phase = [&](int tile) {
+        TICK(te0);
+        const char *vb = smem + vlane + ((tile + NST - 1) % NST) * VBYTES;     // V of tile-1
         const int kb = tile * KT;
-        f32x16 s0, s1;
-        qk_scores(tile, s0, s1);
-
         bf16x8 pn[4];
         float rs0 = 0.f, rs1 = 0.f;
         const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
         {
-            constexpr int PD = 3, NST = 4 * NDB;
+            constexpr int PD = 3, NSTEP = 4 * NDB;
             bf16x8 fr[PD];
             auto vread = [&](int k) {
-#ifdef EXP_NO_LDSREAD
-                return qf[k % NKS];
-#else
-                return *reinterpret_cast<const bf16x8 *>(vb + vaddr[k / NDB] + (k % NDB) * 32 * VROWB);
-#endif
+                return *reinterpret_cast<const bf16x8 *>(vb + (k / NDB) * 32 + (k % NDB) * 32 * VSTR);
             };
 #pragma unroll
             for (int k = 0; k < PD; ++k)
                 fr[k] = vread(k);
 #pragma unroll
-            for (int k = 0; k < NST; ++k) {
+            for (int k = 0; k < NSTEP; ++k) {
                 const int kk = k / NDB, d = k % NDB;
                 const bf16x8 cur_fr = fr[k % PD];
-                if (k + PD < NST)
+                if (k + PD < NSTEP)
                     fr[k % PD] = vread(k + PD);
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pf[kk], o[d], 0, 0, 0);
                 // scores handled at this step: 8 / NDB of the 8 that make pn[kk]
@@ -533,6 +556,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
             }
         }
         float rs = rs0 + rs1;
+        TICK(te1);
+        TACC(1, te0, te1);
 
         // ---- reference check. Nothing is done as long as every row has a
         // reference and no exponential came near overflow (any magnitude below
@@ -542,7 +567,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
         // they have accumulated and redoes the exponentials. ----
         constexpr float BIG = 1.0e18f;            // 2^60
         if (__any(pending || !(rs < BIG))) {
-            qk_scores(tile, s0, s1);
+            scores_phase(tile);
             float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
             for (int e = 1; e < 16; ++e)
@@ -581,6 +606,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
         for (int kk = 0; kk < 4; ++kk)
             pf[kk] = pn[kk];
         l_part += rs;
+        TICK(te2);
+        TACC(2, te1, te2);
 
         // ---- per-bucket partial sums ----
         const int ke = min(kb + KT, split_key_end);
@@ -618,43 +645,88 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(EnAttnArgs a)
             ++cur;
             cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
         }
+        TICK(te3);
+        TACC(3, te2, te3);
     };
 
-    // ---- main loop. K has two LDS stages, V^T three (the V of tile t is
-    // consumed one iteration late). The loads of tile t+1 are issued right after
-    // the barrier of tile t into stages last read during tile t-1 (K) and tile
-    // t-2's product (V), so they have a whole iteration to land; one barrier per
-    // tile. The first iteration multiplies a zero P^T with a zero-filled stage. ----
+    // ---- main loop over slots. Slot s opens with a workgroup barrier.
+    //   phase u = s - grp of a wave: u = 2k   SCORES of tile t_begin + k
+    //                                u = 2k+1 EXP of that tile (+ P V of tile k-1)
+    //   (the last pending P V follows after the loop)
+    //   loads: K of tile t_begin+k is issued in slot 2k-2, V^T in slot 2k-1 (the
+    //   first tile's before the loop). A stage is rewritten three tiles later,
+    //   after its last reader (group B's EXP phase / P V) has passed a barrier.
+    //   Before an even slot every wave waits for its own K loads (the V^T loads
+    //   issued one slot earlier may stay in flight), then the barrier publishes
+    //   them. The first EXP phase multiplies a zero P^T with a zero-filled stage.
     {
-        char *vz = smem + VBASE + ((t_begin + VSTAGES - 1) % VSTAGES) * VBYTES;
-        for (int i = tid * 16; i < VBYTES; i += 256 * 16)
+        char *vz = smem + VBASE + ((t_begin + NST - 1) % NST) * VBYTES;
+        for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
             *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
     }
-    if (t_begin < t_end)
-        issue(t_begin);
-    for (int tile = t_begin; tile < t_end; ++tile) {
-#ifdef EXP_NO_BARRIER
-        if (tile == t_begin)
-#endif
-        {
-            wait_all_memory();
-            __builtin_amdgcn_s_barrier();
-        }
-#ifndef EXP_NO_DMA
-        if (tile + 1 < t_end)
-            issue(tile + 1);
-#endif
-#ifdef EXP_NO_COMPUTE
-        if (false)
-#else
-        if (tile < wave_t_end)
-#endif
-            compute(tile);
-        else if (tile == wave_t_end && tile > t_begin)
-            pv_only(tile - 1);            // the wave's last pending product
+    if (nt > 0) {
+        issue_k(t_begin);
+        issue_v(t_begin);
     }
-    if (wave_t_end == t_end && t_end > t_begin)
-        pv_only(t_end - 1);
+    auto open_slot = [&](int s) {
+        TICK(to0);
+        const int k = s >> 1;
+        if ((s & 1) == 0 && k < nt) {
+            // loads in flight: K of tile k (needed now), V^T of tile k (needed later)
+            if (n_vblk >= 3)
+                wait_vm_lgkm0<3>();
+            else if (n_vblk == 2)
+                wait_vm_lgkm0<2>();
+            else
+                wait_vm_lgkm0<1>();
+        } else {
+            wait_vm_lgkm0<0>();
+        }
+        __builtin_amdgcn_s_barrier();
+        TICK(to1);
+        TACC(4, to0, to1);
+#ifndef EXP_NO_DMA
+        if (k + 1 < nt) {
+            if ((s & 1) == 0)
+                issue_k(t_begin + k + 1);
+            else
+                issue_v(t_begin + k + 1);
+        }
+#endif
+        TICK(to2);
+        TACC(5, to1, to2);
+    };
+    TICK(tl0);
+    // Both groups run the same body; group B is one slot behind, so it opens
+    // one slot before the loop and group A two after it: 2 nt + 2 barriers each.
+    if (grp == 1)
+        open_slot(0);
+    for (int k = 0; k < nt; ++k) {
+        open_slot(2 * k + grp);
+#ifndef EXP_NO_SCORES
+        scores_phase(t_begin + k);
+#endif
+        open_slot(2 * k + 1 + grp);
+#ifdef EXP_PV_ONLY
+        pv_only(t_begin + k);
+#elif !defined(EXP_NO_EXP)
+        exp_phase(t_begin + k);
+#endif
+    }
+    if (grp == 0)
+        open_slot(2 * nt);
+    open_slot(2 * nt + 1);
+    TICK(tl1);
+    TACC(6, tl0, tl1);
+#ifdef EXP_TIMING
+    if (blockIdx.x == 8 && lane == 0 && (wave == 0 || wave == 4))
+        for (int i = 0; i < 8; ++i)
+            en_dbg[(wave / 4) * 8 + i] = dbg_acc[i];
+    if (blockIdx.x == 8 && lane == 0 && wave == 0)
+        en_dbg[16] = nt;
+#endif
+    if (nt > 0)
+        pv_only(t_end - 1);               // the last pending product; its V^T stage is still intact
 
     if (!wave_valid)
         return;
@@ -1012,13 +1084,13 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
         else
             hipLaunchKernelGGL((attn_f32_kernel<128>), grid, blk, 0, st, a);
     } else {
-        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(256);
+        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
         static bool reported = false;
         if (!reported && getenv("EN_DEBUG")) {
             reported = true;
             int n64 = -1, n128 = -1;
-            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 256, 0);
-            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 0);
+            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 64 * ATT_WAVES, 0);
+            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 64 * ATT_WAVES, 0);
             fprintf(stderr, "[efficientnav] attn_bf16 workgroups per CU: D=64 %d, D=128 %d\n", n64, n128);
         }
         if (D == 64)
