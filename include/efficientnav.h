@@ -211,7 +211,8 @@ int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
  *                block, entries beyond are 0; each row sums to 1.
  *   reduce = 1 : mass_out_dev float [B, Smax+1], the above summed over heads
  *                and query tokens (divide by Hq*N_q for the average).
- * The reduced form uses a small part of the scratch for per-head partial sums.
+ * The reduced form also writes a small part of the scratch (per-head partial
+ * sums): two reduced calls on one scratch must not overlap in time.
  * Errors: INVALID_ARG, DEVICE.
  */
 int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,

@@ -427,10 +427,11 @@ EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *pl)
     L.ml_off = 0;
     L.seg_off = align256(L.ml_off + size_t(pl->n_splits) * rows * 2 * sizeof(float));
     L.red_off = align256(L.seg_off + size_t(pl->n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
-    L.opart_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
+    L.mlfin_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
+    L.opart_off = align256(L.mlfin_off + (pl->n_splits > 1 ? rows * 2 * sizeof(float) : 0));
     L.total = L.opart_off;
     if (pl->n_splits > 1)
-        L.total = align256(L.opart_off + size_t(pl->n_splits) * rows * pool->d.head_dim * sizeof(float));
+        L.total = align256(L.opart_off + size_t(pl->n_splits) * rows * pool->d.head_dim * elem_size(pool->d.dtype));
     return L;
 }
 
@@ -556,7 +557,8 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     char *ws = static_cast<char *>(ws_dev);
     a.ws_ml = ws ? reinterpret_cast<float *>(ws + L.ml_off) : nullptr;
     a.ws_seg = ws ? reinterpret_cast<float *>(ws + L.seg_off) : nullptr;
-    a.ws_opart = (ws && plan->n_splits > 1) ? reinterpret_cast<float *>(ws + L.opart_off) : nullptr;
+    a.ws_opart = (ws && plan->n_splits > 1) ? static_cast<void *>(ws + L.opart_off) : nullptr;
+    a.ws_mlfin = (ws && plan->n_splits > 1) ? reinterpret_cast<float *>(ws + L.mlfin_off) : nullptr;
     a.B = plan->B;
     a.Hq = pool->d.n_q_heads;
     a.Hkv = pool->d.n_kv_heads;
@@ -599,6 +601,7 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
     EnMassArgs a;
     a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
     a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
+    a.ws_mlfin = reinterpret_cast<const float *>(ws + L.mlfin_off);
     a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
     a.nseg = d_nseg(plan);
     a.bnd = d_bnd(plan);

@@ -59,15 +59,16 @@ struct EnAttnArgs {
     const int32_t *nseg, *bnd;
     float *ws_ml;      // [n_splits, B*Hq*Nq, 2]  (reference max in log2 units, sum)
     float *ws_seg;     // [n_splits, B*Hq, Smax+1, Nq, 2] (partial sum, its reference max)
-    float *ws_opart;   // [n_splits, B*Hq*Nq, D] unnormalised partial outputs
+    void *ws_opart;    // [n_splits, B*Hq*Nq, D] per-split softmax outputs (pool dtype)
+    float *ws_mlfin;   // [B*Hq*Nq, 2] merged (reference, sum), written by the combine kernel
     int B, Hq, Hkv, Nq, Smax, T;
     int n_splits, n_ptiles, total_wgs;
     float scale_log2e;
 };
 
 struct EnMassArgs {
-    const float *ws_ml, *ws_seg;
-    float *ws_red;     // [B, Smax+1, Hq] per-head partial sums of the reduced masses
+    const float *ws_ml, *ws_seg, *ws_mlfin;
+    float *ws_red;          // [B, Smax+1, Hq] per-head partial sums of the reduced masses
     const int32_t *nseg, *bnd;
     float *out;
     int B, Hq, Nq, Smax, n_splits;
@@ -75,7 +76,7 @@ struct EnMassArgs {
 
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
-    size_t ml_off, seg_off, red_off, opart_off, total;
+    size_t ml_off, seg_off, red_off, mlfin_off, opart_off, total;
 };
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 

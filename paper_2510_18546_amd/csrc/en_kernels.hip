@@ -83,11 +83,11 @@ __device__ __forceinline__ const T *context_src(const EnGatherArgs &a, const T *
 // grid: (ceil(Lpad/32), Hkv, B), 256 threads.
 // ---------------------------------------------------------------------------
 template <typename T, int D, bool COPY_V>
-__global__ __launch_bounds__(256) void gather_k_kernel(EnGatherArgs a)
+__device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx)
 {
     constexpr int E = D / 16;
     const int b = blockIdx.z, kvh = blockIdx.y;
-    const int tok = blockIdx.x * 32 + threadIdx.x / 8;
+    const int tok = bx * 32 + threadIdx.x / 8;
     const int c = threadIdx.x % 8;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
@@ -129,13 +129,13 @@ __global__ __launch_bounds__(256) void gather_k_kernel(EnGatherArgs a)
 // exchanged. grid: (Lpad/64, Hkv, B), 256 threads.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
+__device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx)
 {
     constexpr int STR = D + 2;                 // LDS row stride in elements
     __shared__ uint16_t tile[EN_KEY_TILE * STR];
     __shared__ const uint16_t *srcs[EN_KEY_TILE];
     const int b = blockIdx.z, kvh = blockIdx.y;
-    const int t0 = blockIdx.x * EN_KEY_TILE;
+    const int t0 = bx * EN_KEY_TILE;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
     const int Ltot = bnd[S + 1];
@@ -182,6 +182,21 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
     }
 }
 
+// One launch for the whole gather: the first nk blocks of the grid's x
+// dimension rotate keys (and copy fp32 values), the rest transpose bf16 values.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_kernel(EnGatherArgs a, int nk)
+{
+    if constexpr (sizeof(T) == 4) {
+        gather_k_block<T, D, true>(a, blockIdx.x);
+    } else {
+        if ((int)blockIdx.x < nk)
+            gather_k_block<T, D, false>(a, blockIdx.x);
+        else
+            gather_vt_block<D>(a, blockIdx.x - nk);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // attn_bf16: matrix-core attention.
 //
@@ -189,23 +204,24 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(EnGatherArgs a)
 // one KV head and one KV split, one workgroup per compute unit.
 //
 // Each wave keeps its 32 rotated, pre-scaled queries in registers and computes
-// S^T = K Q^T per 64-key tile with v_mfma_f32_32x32x16_bf16, so that every
-// lane owns ONE query (column l%32) and 2x16 of its scores; row reductions
-// then need a single exchange with lane l^32. P^T goes straight back into the
-// matrix core as the B operand of O^T += V^T P^T: no LDS round trip for P.
+// S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that every lane owns ONE query
+// (column l%32) and 16 scores of a 32-key block; row reductions then need a
+// single exchange with lane l^32. P^T goes straight back into the matrix core
+// as the B operand of O^T += V^T P^T: no LDS round trip for P.
 //
-// Per tile a wave runs two phases: SCORES (matrix work only) and EXP (the
-// exponentials on the vector ALU, interleaved with the P V product of the
-// previous tile). The two waves that share a SIMD (wave w and w+4) run these
-// phases in opposite order: time is cut into slots by workgroup barriers, and
-// while one wave is in SCORES its partner is in EXP, so the matrix core always
-// has work and the vector ALU work hides behind it.
+// The key loop is software-pipelined over 32-key blocks. Phase j issues, step
+// by step, the matrix instructions of S(j+1) = K(j+1) Q^T and of
+// O += V(j-1) P(j-1), and between them the vector work that turns S(j) into
+// P(j). Everything a phase reads was finished one phase earlier, so neither
+// unit waits for the other.
 //
 // K tiles [64][D] and V^T tiles [D][64] go from global memory straight into
 // LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), three
-// stages each. Rows are padded by 16 bytes (the loader lets one lane in 17 / 9
-// fetch a dummy chunk into the pad), which keeps the 16-byte operand reads of
-// 16 consecutive lanes on distinct banks with plain base + immediate addresses.
+// stages each, one workgroup barrier per 64-key tile; the loads of a tile are
+// spread over the steps of the two phases before it is needed. Rows are padded
+// by 16 bytes (the loader lets one lane in 17 / 9 fetch a dummy chunk into the
+// pad), which keeps the 16-byte operand reads of 16 consecutive lanes on
+// distinct banks with plain base + immediate addresses.
 //
 // Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
 // column l%32.
@@ -222,11 +238,9 @@ __device__ __forceinline__ void dma16(const void *sbase, uint32_t voff, uint32_t
                  : "memory");
 }
 
-// s_waitcnt with lgkmcnt(0) and vmcnt(N), N a compile-time constant
-template <int N>
-__device__ __forceinline__ void wait_vm_lgkm0()
+__device__ __forceinline__ void wait_all_memory()
 {
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070);
+    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
 }
 
 __device__ __forceinline__ float pair_max(float v)
@@ -236,7 +250,7 @@ __device__ __forceinline__ float pair_max(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-constexpr int ATT_WAVES = EN_WAVES;       // 8 waves: groups A (0..3) and B (4..7)
+constexpr int ATT_WAVES = EN_WAVES;
 
 #ifdef EXP_TIMING
 __device__ unsigned long long en_dbg[32];
@@ -250,9 +264,12 @@ __device__ unsigned long long en_dbg[32];
 template <int D>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 {
-    constexpr int KT = EN_KEY_TILE;
-    constexpr int NKS = D / 16;                  // k-steps of the QK^T product
+    constexpr int KT = EN_KEY_TILE;              // keys per LDS tile
+    constexpr int KB = 32;                       // keys per pipeline block
+    constexpr int NKS = D / 16;                  // k-steps of one block's QK^T product
     constexpr int NDB = D / 32;                  // 32-row blocks of O^T
+    constexpr int NSTEP = 2 * NKS;               // matrix instructions per phase
+    constexpr int EPS = 16 / NKS;                // scores turned into P per pair of steps
     constexpr int ROWB = 2 * D;                  // bytes per K row in global memory
     constexpr int KSTR = ROWB + 16;              // padded K row in LDS
     constexpr int KCPR = KSTR / 16;              // 16-byte chunks per padded K row
@@ -265,6 +282,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     constexpr int KJ = (NBK + ATT_WAVES - 1) / ATT_WAVES;     // max blocks per wave
     constexpr int VJ = (NBV + ATT_WAVES - 1) / ATT_WAVES;
     static_assert(KBYTES % 1024 == 0 && VBYTES % 1024 == 0, "tile must be whole loader blocks");
+    static_assert(KJ <= 3 && VJ <= 3 && (NSTEP >= 16 || (KJ <= 2 && VJ <= 2)), "loader steps");
     __shared__ __attribute__((aligned(1024))) char smem[NST * (KBYTES + VBYTES)];
 
     // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
@@ -282,12 +300,13 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const int grp = wave / 4;                    // 0: group A, 1: group B (one slot behind)
     const int lane = tid % 64;
     const int col = lane % 32, half = lane / 32;
     const int r = a.Hq / a.Hkv;
     const int nqb = (a.Nq + 31) / 32;
     const int pair = ptile * ATT_WAVES + wave;
+    // A wave without a valid (head, query block) pair computes on zero queries
+    // and writes nothing.
     const bool wave_valid = pair < r * nqb;
     const int hl = wave_valid ? pair % r : 0;
     const int qb = wave_valid ? pair / r : 0;
@@ -305,19 +324,15 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const int split_key_begin = t_begin * KT;
     const int split_key_end = min(t_end * KT, Ltot);
     {
-        // causal frontier of the workgroup: last key any of its rows may see
+        // causal frontier of the workgroup: last key any of its rows may see.
+        // Every wave walks all tiles up to it; a wave whose own frontier is
+        // earlier sees only masked scores in the last ones.
         const int qb_hi = min((ptile * ATT_WAVES + ATT_WAVES - 1) / r, nqb - 1);
         const int last_key = Lc + min(a.Nq - 1, qb_hi * 32 + 31);
         t_end = min(t_end, last_key / KT + 1);
     }
     const int nt = max(t_end - t_begin, 0);      // tiles of the workgroup
     const int i_lo = qb * 32;
-    const int i_hi = min(a.Nq - 1, qb * 32 + 31);
-    (void)i_hi;
-    // Every wave of the workgroup walks all its tiles: a wave whose own causal
-    // frontier is a tile or two earlier sees only masked scores there, and a
-    // wave without a valid (head, query block) pair computes on zero queries
-    // and writes nothing.
 
     // ---- loader set-up. Block blk of a tile is LDS bytes [1024 blk, 1024 blk + 1024);
     // lane L of it is chunk q = 64 blk + L of the padded tile: row q / CPR, chunk
@@ -338,22 +353,28 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         const int d = q / 9, c = q % 9;
         voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < 8 ? c : 0) * 16);
     }
-    const int n_vblk = (NBV - wave + ATT_WAVES - 1) / ATT_WAVES;   // V^T blocks this wave loads
-    auto issue_k = [&](int tile) {
-        const char *kt = kg + (size_t)tile * (KT * ROWB);
-        const uint32_t dst = lds0 + (tile % NST) * KBYTES + wave * 1024;
-#pragma unroll
-        for (int j = 0; j < KJ; ++j)
-            if (wave + ATT_WAVES * j < NBK)
-                dma16(kt, koff[j], dst + j * ATT_WAVES * 1024);
+    // Loader job of the current phase: one tile of K or of V^T, issued block by
+    // block between the matrix instructions.
+    const char *job_base = nullptr;
+    uint32_t job_dst = 0;
+    bool job_on = false;
+    auto dma_k = [&](int j) {
+        if (j < KJ && job_on && wave + ATT_WAVES * j < NBK)
+            dma16(job_base, koff[j < KJ ? j : 0], job_dst + j * ATT_WAVES * 1024);
     };
-    auto issue_v = [&](int tile) {
-        const char *vtile = vg + (size_t)tile * (KT * 2);
-        const uint32_t dst = lds0 + VBASE + (tile % NST) * VBYTES + wave * 1024;
-#pragma unroll
-        for (int j = 0; j < VJ; ++j)
-            if (wave + ATT_WAVES * j < NBV)
-                dma16(vtile, voff[j], dst + j * ATT_WAVES * 1024);
+    auto dma_v = [&](int j) {
+        if (j < VJ && job_on && wave + ATT_WAVES * j < NBV)
+            dma16(job_base, voff[j < VJ ? j : 0], job_dst + j * ATT_WAVES * 1024);
+    };
+    auto job_k = [&](int tile) {
+        job_on = tile < t_end;
+        job_base = kg + (size_t)tile * (KT * ROWB);
+        job_dst = lds0 + (tile % NST) * KBYTES + wave * 1024;
+    };
+    auto job_v = [&](int tile) {
+        job_on = tile < t_end;
+        job_base = vg + (size_t)tile * (KT * 2);
+        job_dst = lds0 + VBASE + (tile % NST) * VBYTES + wave * 1024;
     };
 
     // ---- operand read bases inside a stage (plus immediates per step) ----
@@ -404,19 +425,22 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
             o[d][e] = 0.f;
-    bf16x8 pf[4];                 // P^T of the previous tile, not yet multiplied with V
+    f32x16 sbuf[2];               // scores: block j in sbuf[j%2]
+    bf16x8 pbuf[2][2];            // P^T: block j in pbuf[j%2][0..1] (16 keys each)
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
+    for (int p = 0; p < 2; ++p) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            pf[kk][j] = (bf16_t)0.f;
-    f32x16 s0, s1;                // scores of the current tile, SCORES phase -> EXP phase
+        for (int e = 0; e < 16; ++e)
+            sbuf[p][e] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e)
-        s0[e] = s1[e] = 0.f;
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                pbuf[p][kk][j] = (bf16_t)0.f;
+    }
     // Softmax reference of this row (log2 units). It is chosen at the first
-    // tile in which the row sees a key and afterwards only moved when the
-    // exponentials of a tile would overflow (see exp_phase). Scores leave the
+    // block in which the row sees a key and afterwards only moved when the
+    // exponentials of a block would overflow (see phase). Scores leave the
     // matrix core already reduced by it: the accumulators start at -m_ref.
     float m_ref = 0.f;
     bool has_ref = false;
@@ -428,294 +452,270 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     float l_part = 0.f;           // this lane's share of the row sum
     float seg_part = 0.f;         // this lane's share of the current bucket's sum
 
-    // bucket tracking (wave-uniform): bucket `cur` covers [bnd[cur], bnd[cur+1])
+    // bucket tracking (wave-uniform): bucket `cur` covers [cur_begin, cur_end);
+    // the bound after that is fetched ahead of its use
     int cur = find_bucket(bnd, S, min(split_key_begin, Ltot - 1));
+    int cur_begin = bnd[cur];
     int cur_end = bnd[cur + 1];
+    int nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
     const size_t row_hq = (size_t)b * a.Hq + hq;
     float *seg_base = a.ws_seg
                           ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
                           : nullptr;
 
-    auto flush_bucket = [&](int bucket) {
-        // called by the whole wave when bucket `bucket` has been fully consumed
-        const float tot = seg_part + xor32(seg_part);
-        if (seg_base && row_valid && half == 0) {
-            f32x2 v = {tot, has_ref ? m_ref : EN_NEG_INF};
-            *reinterpret_cast<f32x2 *>(seg_base + ((size_t)bucket * a.Nq + i_row) * 2) = v;
+    // A closed bucket's (sum, reference) pair is written one tile later, right
+    // after the next barrier: a store issued just before a barrier would make
+    // that barrier's wait for the tile loads wait for the store as well.
+    float pend_tot = 0.f, pend_m = 0.f;
+    int pend_bucket = -1;
+    auto write_pending = [&]() {
+        if (pend_bucket >= 0) {
+            if (seg_base && row_valid && half == 0) {
+                f32x2 v = {pend_tot, pend_m};
+                *reinterpret_cast<f32x2 *>(seg_base + ((size_t)pend_bucket * a.Nq + i_row) * 2) = v;
+            }
+            pend_bucket = -1;
+        }
+    };
+    auto close_bucket = [&]() {
+        // the whole wave: bucket `cur` has been fully consumed (or is empty)
+        if (cur_end > cur_begin) {
+            write_pending();
+            pend_tot = seg_part + xor32(seg_part);
+            pend_m = has_ref ? m_ref : EN_NEG_INF;
+            pend_bucket = cur;
         }
         seg_part = 0.f;
+        ++cur;
+        cur_begin = cur_end;
+        cur_end = (cur <= S) ? nxt_end : 0x7fffffff;
+        nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
     };
 
-    // O^T += V^T(tile) P^T with the P^T held in pf.
-    auto pv_only = [&](int tile) {
-        const char *vb = smem + vlane + (tile % NST) * VBYTES;
+    // Scores of block jb of tile `tile` relative to m_ref, unpipelined (slow path).
+    auto block_scores = [&](int tile, int jb, f32x16 &sv) {
+        const char *kbuf = smem + klane + (tile % NST) * KBYTES + jb * KB * KSTR;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-            for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vb + kk * 32 + d * 32 * VSTR);
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
-            }
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(kbuf + ks * 32);
+            if (ks == 0)
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[0], negm, 0, 0, 0);
+            else
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], sv, 0, 0, 0);
+        }
     };
-
-    // SCORES phase: s0, s1 = K(tile) Q^T - m_ref, with the causal / padding mask
-    // on tiles that reach past L_c + i_lo. The operand reads run PD matrix
-    // instructions ahead; scheduling fences keep that distance in the code.
-    auto scores_phase = [&](int tile) {
-        TICK(ts0);
-        const char *kbuf = smem + klane + (tile % NST) * KBYTES;
-        const int kb = tile * KT;
-        {
-            constexpr int PD = 4, NSTEP = 2 * NKS;
-            bf16x8 fr[PD];
-            auto kread = [&](int k) {
-                return *reinterpret_cast<const bf16x8 *>(kbuf + (k / 2) * 32 + (k % 2) * 32 * KSTR);
-            };
-#pragma unroll
-            for (int k = 0; k < PD; ++k)
-                fr[k] = kread(k);
-#pragma unroll
-            for (int k = 0; k < NSTEP; ++k) {
-                const bf16x8 cur_fr = fr[k % PD];
-                if (k + PD < NSTEP)
-                    fr[k % PD] = kread(k + PD);
-                if (k == 0)
-                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
-                else if (k == 1)
-                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
-                else if (k % 2 == 0)
-                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[k / 2], s0, 0, 0, 0);
-                else
-                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[k / 2], s1, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (kb + KT - 1 > Lc + i_lo) {
-            const int lim = Lc + i_row;           // last visible key of this row
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = kb + 8 * (e / 4) + 4 * half + (e % 4);
-                if (key > lim)
-                    s0[e] = EN_NEG_INF;
-                if (key + 32 > lim)
-                    s1[e] = EN_NEG_INF;
-            }
-        }
-        TICK(ts1);
-        TACC(0, ts0, ts1);
-    };
-
-    // EXP phase of a tile: exponentials of its scores and, interleaved, the
-    // P V product of the PREVIOUS tile (its V^T is still staged).
-    auto exp_phase = [&](int tile) {
-        TICK(te0);
-        const char *vb = smem + vlane + ((tile + NST - 1) % NST) * VBYTES;     // V of tile-1
-        const int kb = tile * KT;
-        bf16x8 pn[4];
-        float rs0 = 0.f, rs1 = 0.f;
-        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
-        {
-            constexpr int PD = 3, NSTEP = 4 * NDB;
-            bf16x8 fr[PD];
-            auto vread = [&](int k) {
-                return *reinterpret_cast<const bf16x8 *>(vb + (k / NDB) * 32 + (k % NDB) * 32 * VSTR);
-            };
-#pragma unroll
-            for (int k = 0; k < PD; ++k)
-                fr[k] = vread(k);
-#pragma unroll
-            for (int k = 0; k < NSTEP; ++k) {
-                const int kk = k / NDB, d = k % NDB;
-                const bf16x8 cur_fr = fr[k % PD];
-                if (k + PD < NSTEP)
-                    fr[k % PD] = vread(k + PD);
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pf[kk], o[d], 0, 0, 0);
-                // scores handled at this step: 8 / NDB of the 8 that make pn[kk]
-#pragma unroll
-                for (int u = 0; u < 8 / NDB; u += 2) {
-                    const int j = d * (8 / NDB) + u;              // index inside pn[kk]
-                    const int e = 8 * (kk % 2) + j;               // index inside s0 / s1
-                    float p0, p1;
-                    if (kk < 2) {
-                        p0 = fast_exp2(s0[e]);
-                        p1 = fast_exp2(s0[e + 1]);
-                    } else {
-                        p0 = fast_exp2(s1[e]);
-                        p1 = fast_exp2(s1[e + 1]);
-                    }
-                    const f32x2 pp = {p0, p1};
-                    const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                    pn[kk][j] = pb[0];
-                    pn[kk][j + 1] = pb[1];
-                    if (u & 2)
-                        rs1 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs1, false);
-                    else
-                        rs0 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, rs0, false);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        float rs = rs0 + rs1;
-        TICK(te1);
-        TACC(1, te0, te1);
-
-        // ---- reference check. Nothing is done as long as every row has a
-        // reference and no exponential came near overflow (any magnitude below
-        // that is harmless: P keeps its relative precision in bf16 and the
-        // accumulators are fp32). Otherwise the wave recomputes the scores,
-        // moves the affected rows to their current maximum, rescales what
-        // they have accumulated and redoes the exponentials. ----
-        constexpr float BIG = 1.0e18f;            // 2^60
-        if (__any(pending || !(rs < BIG))) {
-            scores_phase(tile);
-            float mx = fmaxf(s0[0], s1[0]);
-#pragma unroll
-            for (int e = 1; e < 16; ++e)
-                mx = fmaxf(mx, fmaxf(s0[e], s1[e]));
-            mx = pair_max(mx);
-            // both lanes of a row must take the same decision
-            const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
-            const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
-            const float delta = fix ? mx : 0.f;
-            const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
-#pragma unroll
-            for (int d = 0; d < NDB; ++d)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    o[d][e] *= alpha;
-            l_part *= alpha;
-            seg_part *= alpha;
-            m_ref += delta;
-            has_ref = has_ref || fix;
-            pending = pending && !fix;
+    // causal / padding mask of a block starting at key kb
+    auto mask_block = [&](int kb, f32x16 &sv) {
+        if (kb + KB - 1 > Lc + i_lo) {
+            const int rel = Lc + i_row - kb - 4 * half;      // last visible key, block-relative
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                negm[e] = -m_ref;
-            rs = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int e = 8 * (kk % 2) + j;
-                    const bf16_t pb = (bf16_t)fast_exp2((kk < 2 ? s0[e] : s1[e]) - delta);
-                    pn[kk][j] = pb;
-                    rs += (float)pb;
-                }
+                if (8 * (e / 4) + (e % 4) > rel)
+                    sv[e] = EN_NEG_INF;
         }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            pf[kk] = pn[kk];
-        l_part += rs;
-        TICK(te2);
-        TACC(2, te1, te2);
-
-        // ---- per-bucket partial sums ----
-        const int ke = min(kb + KT, split_key_end);
-        if (cur_end >= ke) {
-            seg_part += rs;               // the whole tile lies in bucket `cur`
-        } else {
-            int lo = kb;
-            while (true) {
-                const int hi = min(cur_end, ke);
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = kb + 8 * (e / 4) + 4 * half + (e % 4);
-                    const float p0 = (float)pf[e / 8][e % 8], p1 = (float)pf[2 + e / 8][e % 8];
-                    part += (key >= lo && key < hi) ? p0 : 0.f;
-                    part += (key + 32 >= lo && key + 32 < hi) ? p1 : 0.f;
-                }
-                seg_part += part;
-                if (cur_end > ke)
-                    break;
-                if (cur_end > bnd[cur])
-                    flush_bucket(cur);
-                seg_part = 0.f;
-                ++cur;
-                cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
-                lo = hi;
-                if (cur > S)
-                    break;
-            }
-        }
-        while (cur <= S && cur_end <= ke) {       // buckets that end exactly here
-            if (cur_end > bnd[cur])
-                flush_bucket(cur);
-            seg_part = 0.f;
-            ++cur;
-            cur_end = (cur <= S) ? bnd[cur + 1] : 0x7fffffff;
-        }
-        TICK(te3);
-        TACC(3, te2, te3);
     };
 
-    // ---- main loop over slots. Slot s opens with a workgroup barrier.
-    //   phase u = s - grp of a wave: u = 2k   SCORES of tile t_begin + k
-    //                                u = 2k+1 EXP of that tile (+ P V of tile k-1)
-    //   (the last pending P V follows after the loop)
-    //   loads: K of tile t_begin+k is issued in slot 2k-2, V^T in slot 2k-1 (the
-    //   first tile's before the loop). A stage is rewritten three tiles later,
-    //   after its last reader (group B's EXP phase / P V) has passed a barrier.
-    //   Before an even slot every wave waits for its own K loads (the V^T loads
-    //   issued one slot earlier may stay in flight), then the barrier publishes
-    //   them. The first EXP phase multiplies a zero P^T with a zero-filled stage.
-    {
+    // One phase for block jb = PAR of tile `tile` (global block j = 2 tile + PAR):
+    //   S(j+1) = K(j+1) Q^T - m_ref      NKS matrix instructions (even steps)
+    //   P(j)   = exp2(S(j))              vector ALU, EPS scores per pair of steps
+    //   O     += V(j-1)^T-block P(j-1)   NKS matrix instructions (odd steps)
+    // plus the loader blocks of the phase's job. Operand reads run PD steps ahead.
+    constexpr int PD = 4;         // operand reads run PD steps ahead, across phases too
+    bf16x8 fr[PD];
+    auto operand = [&](int par, int tile, int k) {
+        // operand of step k of the phase (par, tile): even steps read K, odd steps V^T
+        if (k % 2 == 0) {
+            const char *kbuf = smem + klane + ((tile + par) % NST) * KBYTES + (par ^ 1) * KB * KSTR;
+            return *reinterpret_cast<const bf16x8 *>(kbuf + (k / 2) * 32);
+        }
+        const char *vbuf = smem + vlane + ((tile + NST - 1 + par) % NST) * VBYTES + (par ^ 1) * 64;
+        const int i = k / 2, kk = i / NDB, d = i % NDB;
+        return *reinterpret_cast<const bf16x8 *>(vbuf + kk * 32 + d * 32 * VSTR);
+    };
+    auto phase = [&](auto par_tag, int tile) {
+        constexpr int PAR = decltype(par_tag)::value;
+        TICK(tp0);
+        f32x16 &s_cur = sbuf[PAR];
+        f32x16 &s_nxt = sbuf[PAR ^ 1];
+        // K of block j+1: PAR 0 -> second half of this tile, PAR 1 -> first half of the next.
+        // V^T of block j-1: PAR 0 -> keys 32..63 of the previous tile, PAR 1 -> keys 0..31 of this one.
+        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+        float rs = 0.f;
+        bf16x2 pb_hold[EPS / 2];
+        {
+#pragma unroll
+            for (int k = 0; k < NSTEP; ++k) {
+                const int i = k / 2;
+                const bf16x8 cur_fr = fr[k % PD];
+                if (k + PD < NSTEP)
+                    fr[k % PD] = operand(PAR, tile, k + PD);
+                else                               // first operands of the next phase
+                    fr[k % PD] = operand(PAR ^ 1, tile + PAR, k + PD - NSTEP);
+                if (k % 2 == 0) {
+                    if (i == 0)
+                        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
+                    else
+                        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[i], s_nxt, 0, 0, 0);
+                    // exponentials of scores e0 .. e0+EPS-1 of the current block
+#pragma unroll
+                    for (int u = 0; u < EPS; u += 2) {
+                        const int e = i * EPS + u;
+                        const f32x2 pp = {fast_exp2(s_cur[e]), fast_exp2(s_cur[e + 1])};
+                        pb_hold[u / 2] = __builtin_convertvector(pp, bf16x2);
+                        // keep this work in this step (the optimiser would sink it below the loop)
+                        asm volatile("" : "+v"(pb_hold[u / 2]));
+                    }
+                } else {
+                    const int kk = i / NDB, d = i % NDB;
+                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pbuf[PAR ^ 1][kk], o[d], 0, 0, 0);
+                    // file the probabilities made in the previous step and add them up
+#pragma unroll
+                    for (int u = 0; u < EPS; u += 2) {
+                        const int e = i * EPS + u;
+                        pbuf[PAR][e / 8][e % 8] = pb_hold[u / 2][0];
+                        pbuf[PAR][e / 8][e % 8 + 1] = pb_hold[u / 2][1];
+                        rs = __builtin_amdgcn_fdot2_f32_bf16(pb_hold[u / 2], ones, rs, false);
+                        asm volatile("" : "+v"(rs));
+                    }
+                }
+#ifndef EXP_NO_DMA
+                if (k == 2 || k == NSTEP / 2 + 1 || k == NSTEP - 3) {
+                    const int j = (k == 2) ? 0 : (k == NSTEP / 2 + 1 ? 1 : 2);
+                    if (PAR == 0)
+                        dma_k(j);
+                    else
+                        dma_v(j);
+                }
+#endif
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        TICK(tp1);
+        TACC(0, tp0, tp1);
+        const int kb = tile * KT + PAR * KB;          // first key of block j
+        const int ke = min(kb + KB, split_key_end);
+        // Rare cases, one branch for all of them: the next block needs the causal
+        // mask, a bucket ends inside this block, or a row lacks a reference /
+        // came near overflow (any magnitude below that is harmless: P keeps its
+        // relative precision in bf16 and the accumulators are fp32).
+        constexpr float BIG = 1.0e18f;            // 2^60
+        const bool next_masked = kb + 2 * KB - 1 > Lc + i_lo;
+        const bool bucket_edge = !(cur_end > ke);
+        if (!(next_masked || bucket_edge || __any(pending || !(rs < BIG)))) {
+            l_part += rs;
+            seg_part += rs;               // the whole block lies inside bucket `cur`
+        } else {
+            mask_block(kb + KB, s_nxt);
+            // ---- reference check: the wave recomputes the scores of the block,
+            // moves the affected rows to their current maximum, rescales what
+            // they have accumulated and redoes the exponentials ----
+            if (__any(pending || !(rs < BIG))) {
+                f32x16 sv;
+                block_scores(tile, PAR, sv);
+                mask_block(kb, sv);
+                float mx = sv[0];
+#pragma unroll
+                for (int e = 1; e < 16; ++e)
+                    mx = fmaxf(mx, sv[e]);
+                mx = pair_max(mx);
+                // both lanes of a row must take the same decision
+                const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
+                const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
+                const float delta = fix ? mx : 0.f;
+                const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
+#pragma unroll
+                for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        o[d][e] *= alpha;
+                l_part *= alpha;
+                seg_part *= alpha;
+                m_ref += delta;
+                has_ref = has_ref || fix;
+                pending = pending && !fix;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    negm[e] = -m_ref;
+                    s_nxt[e] -= delta;            // the next block was taken against the old reference
+                }
+                rs = 0.f;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const bf16_t pb = (bf16_t)fast_exp2(sv[e] - delta);
+                    pbuf[PAR][e / 8][e % 8] = pb;
+                    rs += (float)pb;
+                }
+            }
+            l_part += rs;
+            // ---- per-bucket partial sums ----
+            if (cur_end > ke) {
+                seg_part += rs;
+            } else if (kb < split_key_end) {
+                int lo = kb;
+                while (true) {
+                    const int hi = min(cur_end, ke);
+                    float part = 0.f;
+                    const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kr = 8 * (e / 4) + (e % 4);
+                        part += (kr >= rlo && kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
+                    }
+                    seg_part += part;
+                    if (cur_end > ke || cur > S)
+                        break;
+                    close_bucket();
+                    lo = hi;
+                }
+            }
+        }
+        TICK(tp3);
+        TACC(2, tp2, tp3);
+    };
+
+    // ---- main loop: one barrier per tile. At the barrier of tile t everything
+    // issued so far has landed: K up to tile t+1, V^T up to tile t. The two
+    // phases of tile t then issue K of tile t+2 and V^T of tile t+1 into stages
+    // whose last readers finished before the barrier. The first product uses a
+    // zero P^T with a zero-filled V^T stage. ----
+    if (nt > 0) {
         char *vz = smem + VBASE + ((t_begin + NST - 1) % NST) * VBYTES;
         for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
             *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
-    }
-    if (nt > 0) {
-        issue_k(t_begin);
-        issue_v(t_begin);
-    }
-    auto open_slot = [&](int s) {
-        TICK(to0);
-        const int k = s >> 1;
-        if ((s & 1) == 0 && k < nt) {
-            // loads in flight: K of tile k (needed now), V^T of tile k (needed later)
-            if (n_vblk >= 3)
-                wait_vm_lgkm0<3>();
-            else if (n_vblk == 2)
-                wait_vm_lgkm0<2>();
-            else
-                wait_vm_lgkm0<1>();
-        } else {
-            wait_vm_lgkm0<0>();
-        }
+        job_k(t_begin);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma_k(j);
+        job_k(t_begin + 1);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma_k(j);
+        job_v(t_begin);
+#pragma unroll
+        for (int j = 0; j < VJ; ++j)
+            dma_v(j);
+        wait_all_memory();
         __builtin_amdgcn_s_barrier();
-        TICK(to1);
-        TACC(4, to0, to1);
-#ifndef EXP_NO_DMA
-        if (k + 1 < nt) {
-            if ((s & 1) == 0)
-                issue_k(t_begin + k + 1);
-            else
-                issue_v(t_begin + k + 1);
-        }
-#endif
-        TICK(to2);
-        TACC(5, to1, to2);
-    };
-    TICK(tl0);
-    // Both groups run the same body; group B is one slot behind, so it opens
-    // one slot before the loop and group A two after it: 2 nt + 2 barriers each.
-    if (grp == 1)
-        open_slot(0);
-    for (int k = 0; k < nt; ++k) {
-        open_slot(2 * k + grp);
-#ifndef EXP_NO_SCORES
-        scores_phase(t_begin + k);
-#endif
-        open_slot(2 * k + 1 + grp);
-#ifdef EXP_PV_ONLY
-        pv_only(t_begin + k);
-#elif !defined(EXP_NO_EXP)
-        exp_phase(t_begin + k);
-#endif
+        // scores of the first block
+        block_scores(t_begin, 0, sbuf[0]);
+        mask_block(t_begin * KT, sbuf[0]);
+#pragma unroll
+        for (int k = 0; k < PD; ++k)
+            fr[k] = operand(0, t_begin, k);
     }
-    if (grp == 0)
-        open_slot(2 * nt);
-    open_slot(2 * nt + 1);
+    TICK(tl0);
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        TICK(tb0);
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        TICK(tb1);
+        TACC(3, tb0, tb1);
+        write_pending();
+        job_k(tile + 2);
+        phase(std::integral_constant<int, 0>{}, tile);
+        job_v(tile + 1);
+        phase(std::integral_constant<int, 1>{}, tile);
+    }
     TICK(tl1);
     TACC(6, tl0, tl1);
 #ifdef EXP_TIMING
@@ -725,21 +725,26 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     if (blockIdx.x == 8 && lane == 0 && wave == 0)
         en_dbg[16] = nt;
 #endif
-    if (nt > 0)
-        pv_only(t_end - 1);               // the last pending product; its V^T stage is still intact
+    if (nt > 0) {
+        // the last pending product: keys 32..63 of the last tile
+        const char *vbuf = smem + vlane + ((t_end - 1) % NST) * VBYTES + 64;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int d = 0; d < NDB; ++d) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vbuf + kk * 32 + d * 32 * VSTR);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pbuf[1][kk], o[d], 0, 0, 0);
+            }
+    }
 
     if (!wave_valid)
         return;
-    // Buckets of this split that the wave never reached (beyond its causal
-    // frontier) still get an entry: zero mass.
+    // Buckets of this split beyond the workgroup's causal frontier still get an
+    // entry (zero mass); the bucket the loop stopped in gets what is pending.
     if (seg_base) {
-        // first flush what is pending for the bucket the loop stopped in
-        while (cur <= S && bnd[cur] < split_key_end) {
-            if (bnd[cur + 1] > bnd[cur])
-                flush_bucket(cur);
-            seg_part = 0.f;
-            ++cur;
-        }
+        while (cur <= S && cur_begin < split_key_end)
+            close_bucket();
+        write_pending();
     }
 
     // ---- epilogue ----
@@ -751,29 +756,22 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     }
     if (!row_valid)
         return;
-    if (a.n_splits == 1) {
-        const float inv = 1.f / l_tot;
-        bf16_t *op = (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D;
+    // One split: the output row. Several: this split's own softmax output
+    // (normalised by its own sum), merged by the combine kernel.
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    bf16_t *op = (a.n_splits == 1)
+                     ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
+                     : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
 #pragma unroll
-        for (int d = 0; d < NDB; ++d)
+    for (int d = 0; d < NDB; ++d)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 v;
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    v[e] = (bf16_t)(o[d][4 * g + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
-            }
-    } else {
-        float *op = a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
-#pragma unroll
-        for (int d = 0; d < NDB; ++d)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 v = {o[d][4 * g], o[d][4 * g + 1], o[d][4 * g + 2], o[d][4 * g + 3]};
-                *reinterpret_cast<f32x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
-            }
-    }
+            for (int e = 0; e < 4; ++e)
+                v[e] = (bf16_t)(o[d][4 * g + e] * inv);
+            *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+        }
 }
 
 // ---------------------------------------------------------------------------
@@ -895,9 +893,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
         f32x2 v = {M, l_tot};
         *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2) = v;
     }
-    const float inv = (a.n_splits == 1) ? 1.f / l_tot : 1.f;
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     float *op = (a.n_splits == 1) ? (float *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D
-                                  : a.ws_opart + ((size_t)sp * rows + row) * D;
+                                  : (float *)a.ws_opart + ((size_t)sp * rows + row) * D;
 #pragma unroll
     for (int d = 0; d < D; ++d) {
         const float tot = wave_sum(o[d] * w);
@@ -907,12 +905,14 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// combine: out = sum_sp o_sp 2^(m_sp - m) / sum_sp l_sp 2^(m_sp - m).
-// One thread per 4 output elements. grid: ceil(rows*D/4/256).
+// combine: out = sum_sp w_sp y_sp / sum_sp w_sp with y_sp the split's own
+// softmax output and w_sp = l_sp 2^(m_sp - m). One thread per 4 output
+// elements. grid: ceil(rows*D/4/256).
 // ---------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a)
 {
+    typedef T tvec4 __attribute__((ext_vector_type(4)));
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= rows * (D / 4))
@@ -929,21 +929,24 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a)
         const float ls = a.ws_ml[((size_t)sp * rows + row) * 2 + 1];
         if (ms == EN_NEG_INF)
             continue;
-        const float w = exp2f(ms - M);
-        l += ls * w;
-        const f32x4 v = *reinterpret_cast<const f32x4 *>(a.ws_opart + ((size_t)sp * rows + row) * D + d4);
-        acc += v * w;
+        const float w = ls * exp2f(ms - M);
+        l += w;
+        const tvec4 v = *reinterpret_cast<const tvec4 *>((const T *)a.ws_opart + ((size_t)sp * rows + row) * D + d4);
+        acc += __builtin_convertvector(v, f32x4) * w;
     }
     const float inv = 1.f / l;
+    if (d4 == 0 && a.ws_mlfin) {
+        f32x2 ml = {M, l};
+        *reinterpret_cast<f32x2 *>(a.ws_mlfin + row * 2) = ml;
+    }
     const int i = (int)(row % a.Nq);
     const int hq = (int)((row / a.Nq) % a.Hq);
     const int b = (int)(row / ((size_t)a.Nq * a.Hq));
     T *op = (T *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D + d4;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-        op[e] = (T)(acc[e] * inv);
+    *reinterpret_cast<tvec4 *>(op) = __builtin_convertvector(acc * inv, tvec4);
 }
 
+// ---------------------------------------------------------------------------
 // ---------------------------------------------------------------------------
 // mass: probability mass per (row, bucket) from the raw partial sums.
 //   mass = sum over splits touching the bucket of seg * 2^(m_seg - M) / L
@@ -952,31 +955,38 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a)
 __device__ __forceinline__ void row_final_ml(const EnMassArgs &a, size_t rows, size_t row, float &M,
                                              float &L)
 {
-    M = EN_NEG_INF;
-    for (int sp = 0; sp < a.n_splits; ++sp)
-        M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
-    L = 0.f;
-    for (int sp = 0; sp < a.n_splits; ++sp) {
-        const float ms = a.ws_ml[((size_t)sp * rows + row) * 2];
-        if (ms != EN_NEG_INF)
-            L += a.ws_ml[((size_t)sp * rows + row) * 2 + 1] * exp2f(ms - M);
+    // one split: its own (reference, sum); several: the pair the combine kernel merged
+    const float *p = (a.n_splits > 1 ? a.ws_mlfin : a.ws_ml) + row * 2;
+    (void)rows;
+    M = p[0];
+    L = p[1];
+}
+
+// Splits whose key range meets bucket [blo, bhi): a contiguous range [lo, hi].
+__device__ __forceinline__ void bucket_splits(int n_splits, int ntiles, int Ltot, int blo, int bhi,
+                                              int &lo, int &hi)
+{
+    lo = n_splits;
+    hi = -1;
+    for (int sp = 0; sp < n_splits; ++sp) {
+        const int kb = (sp * ntiles / n_splits) * EN_KEY_TILE;
+        const int ke = min(((sp + 1) * ntiles / n_splits) * EN_KEY_TILE, Ltot);
+        if (max(kb, blo) < min(ke, bhi)) {
+            lo = min(lo, sp);
+            hi = max(hi, sp);
+        }
     }
 }
 
 __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int hq, int i, int bucket,
-                                                 int blo, int bhi, int ntiles, int Ltot, float M, float L)
+                                                 int sp_lo, int sp_hi, float M, float L)
 {
     float acc = 0.f;
-    for (int sp = 0; sp < a.n_splits; ++sp) {
-        const int kb = (int)((long)sp * ntiles / a.n_splits) * EN_KEY_TILE;
-        const int ke = min((int)((long)(sp + 1) * ntiles / a.n_splits) * EN_KEY_TILE, Ltot);
-        if (max(kb, blo) >= min(ke, bhi))
-            continue;
-        const float *p = a.ws_seg +
-                         (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2;
-        const float sv = p[0], sm = p[1];
-        if (sm != EN_NEG_INF)
-            acc += sv * exp2f(sm - M);
+    for (int sp = sp_lo; sp <= sp_hi; ++sp) {
+        const f32x2 v = *reinterpret_cast<const f32x2 *>(
+            a.ws_seg + (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
+        if (v[1] != EN_NEG_INF)
+            acc += v[0] * exp2f(v[1] - M);
     }
     return acc / L;
 }
@@ -999,14 +1009,19 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     float *out = a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * (a.Smax + 1);
     for (int s = 0; s <= a.Smax; ++s) {
         float v = 0.f;
-        if (s <= S && bnd[s + 1] > bnd[s])
-            v = row_bucket_mass(a, b, hq, i, s, bnd[s], bnd[s + 1], ntiles, Ltot, M, L);
+        if (s <= S && bnd[s + 1] > bnd[s]) {
+            int lo, hi;
+            bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
+            v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+        }
         out[s] = v;
     }
 }
 
 // reduce = 1, stage 1. grid: (Smax+1, Hq, B): the block sums bucket s of one
-// head over the queries into partial[b][s][hq].
+// head over the queries into partial[b][s][hq]. (A single launch that lets the
+// last workgroup finish was measured slower: one device-scope atomic per
+// workgroup on one address serialises.)
 __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
 {
     __shared__ float red[4];
@@ -1018,11 +1033,13 @@ __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float acc = 0.f;
     if (s <= S && bnd[s + 1] > bnd[s]) {
+        int lo, hi;
+        bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
         for (int i = threadIdx.x; i < a.Nq; i += 256) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
             float M, L;
             row_final_ml(a, rows, row, M, L);
-            acc += row_bucket_mass(a, b, hq, i, s, bnd[s], bnd[s + 1], ntiles, Ltot, M, L);
+            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
         }
     }
     acc = wave_sum(acc);
@@ -1033,17 +1050,19 @@ __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
         a.ws_red[((size_t)b * (a.Smax + 1) + s) * a.Hq + hq] = red[0] + red[1] + red[2] + red[3];
 }
 
-// reduce = 1, stage 2. One thread per (agent, bucket) sums the heads.
+// reduce = 1, stage 2. One wave per (agent, bucket) adds up the heads.
 __global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= a.B * (a.Smax + 1))
+    const int pair = blockIdx.x * 4 + threadIdx.x / 64;
+    if (pair >= a.B * (a.Smax + 1))
         return;
-    const float *p = a.ws_red + (size_t)idx * a.Hq;
+    const float *p = a.ws_red + (size_t)pair * a.Hq;
     float acc = 0.f;
-    for (int h = 0; h < a.Hq; ++h)
+    for (int h = threadIdx.x % 64; h < a.Hq; h += 64)
         acc += p[h];
-    a.out[idx] = acc;
+    acc = wave_sum(acc);
+    if (threadIdx.x % 64 == 0)
+        a.out[pair] = acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -1053,21 +1072,21 @@ int en_launch_gather(const en_pool *pool, const EnGatherArgs &a, int max_ctx_len
 {
     hipStream_t st = (hipStream_t)stream;
     const int Lpad = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
-    const dim3 gk((Lpad + 31) / 32, a.Hkv, a.B), gv(Lpad / EN_KEY_TILE, a.Hkv, a.B), blk(256);
+    const int nk = (Lpad + 31) / 32, nv = Lpad / EN_KEY_TILE;
+    const dim3 blk(256);
     const int D = pool->d.head_dim;
     if (pool->d.dtype == EN_F32) {
+        const dim3 grid(nk, a.Hkv, a.B);
         if (D == 64)
-            hipLaunchKernelGGL((gather_k_kernel<float, 64, true>), gk, blk, 0, st, a);
+            hipLaunchKernelGGL((gather_kernel<float, 64>), grid, blk, 0, st, a, nk);
         else
-            hipLaunchKernelGGL((gather_k_kernel<float, 128, true>), gk, blk, 0, st, a);
+            hipLaunchKernelGGL((gather_kernel<float, 128>), grid, blk, 0, st, a, nk);
     } else {
-        if (D == 64) {
-            hipLaunchKernelGGL((gather_k_kernel<bf16_t, 64, false>), gk, blk, 0, st, a);
-            hipLaunchKernelGGL((gather_vt_kernel<64>), gv, blk, 0, st, a);
-        } else {
-            hipLaunchKernelGGL((gather_k_kernel<bf16_t, 128, false>), gk, blk, 0, st, a);
-            hipLaunchKernelGGL((gather_vt_kernel<128>), gv, blk, 0, st, a);
-        }
+        const dim3 grid(nk + nv, a.Hkv, a.B);
+        if (D == 64)
+            hipLaunchKernelGGL((gather_kernel<bf16_t, 64>), grid, blk, 0, st, a, nk);
+        else
+            hipLaunchKernelGGL((gather_kernel<bf16_t, 128>), grid, blk, 0, st, a, nk);
     }
     return (int)hipGetLastError();
 }
@@ -1131,7 +1150,7 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
     } else {
         const dim3 grid(a.Smax + 1, a.Hq, a.B), blk(256);
         hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
-        const dim3 grid2((a.B * (a.Smax + 1) + 255) / 256);
+        const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
         hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
     }
     return (int)hipGetLastError();
