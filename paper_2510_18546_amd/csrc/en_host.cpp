@@ -149,6 +149,15 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
     // fills a compute unit. Split the key range until every compute unit has a
     // workgroup, keeping at least four key tiles per split.
     const int r = pool->r;
+    if (pool->d.dtype == EN_BF16 && r * pl->Nq <= EN_ROWS_PER_WAVE) {
+        // decode path: one wave per (agent, KV head, split), four waves per
+        // compute unit; at least eight 64-key tiles per split
+        const long base = long(pl->B) * pool->d.n_kv_heads;
+        const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
+        long want = (4L * pool->n_cu + base - 1) / base;
+        want = std::min<long>(want, std::max(1, tiles / 8));
+        return int(std::max<long>(1, std::min<long>(want, 64)));
+    }
     const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     const int n_ptiles = (r * nqb + EN_WAVES - 1) / EN_WAVES;
     const long base = long(pl->B) * pool->d.n_kv_heads * n_ptiles;
@@ -568,6 +577,9 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     a.n_splits = plan->n_splits;
     const int nqb = (plan->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
+    a.decode = (pool->d.dtype == EN_BF16 && pool->r * plan->Nq <= EN_ROWS_PER_WAVE) ? 1 : 0;
+    if (a.decode)
+        a.n_ptiles = 1;
     a.total_wgs = plan->B * pool->d.n_kv_heads * plan->n_splits * a.n_ptiles;
     a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
     const bool timed = g_ev_used < (int)g_ev_start.size();

@@ -63,6 +63,7 @@ struct EnAttnArgs {
     float *ws_mlfin;   // [B*Hq*Nq, 2] merged (reference, sum), written by the combine kernel
     int B, Hq, Hkv, Nq, Smax, T;
     int n_splits, n_ptiles, total_wgs;
+    int decode;        // 1: all r*Nq query rows of a KV head fit one wave (attn_decode kernel)
     float scale_log2e;
 };
 

@@ -243,6 +243,13 @@ __device__ __forceinline__ void wait_all_memory()
     __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
 }
 
+// The loader writes LDS behind the compiler's back: after a wait or barrier
+// that publishes loaded data, no LDS read may be moved up across this point.
+__device__ __forceinline__ void lds_data_ready()
+{
+    asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ float pair_max(float v)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -650,6 +657,11 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             // ---- per-bucket partial sums ----
             if (cur_end > ke) {
                 seg_part += rs;
+            } else if (cur_end == ke && cur_begin <= kb) {
+                // the bucket ends exactly with this block (segments aligned to 32 keys)
+                seg_part += rs;
+                while (cur <= S && cur_end <= ke)
+                    close_bucket();
             } else if (kb < split_key_end) {
                 int lo = kb;
                 while (true) {
@@ -696,6 +708,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             dma_v(j);
         wait_all_memory();
         __builtin_amdgcn_s_barrier();
+        lds_data_ready();
         // scores of the first block
         block_scores(t_begin, 0, sbuf[0]);
         mask_block(t_begin * KT, sbuf[0]);
@@ -708,6 +721,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         TICK(tb0);
         wait_all_memory();
         __builtin_amdgcn_s_barrier();
+        lds_data_ready();
         TICK(tb1);
         TACC(3, tb0, tb1);
         write_pending();
@@ -758,6 +772,320 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         return;
     // One split: the output row. Several: this split's own softmax output
     // (normalised by its own sum), merged by the combine kernel.
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    bf16_t *op = (a.n_splits == 1)
+                     ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
+                     : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = (bf16_t)(o[d][4 * g + e] * inv);
+            *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+        }
+}
+
+// ---------------------------------------------------------------------------
+// attn_decode (bf16): few query rows per KV head (r * N_q <= 32, e.g. one new
+// token per agent in the decode phase of a planning step, Section 3.2: about 40
+// tokens are decoded per plan over the KV that was loaded once).
+//
+// This case is bound by reading the gathered K / V^T once from HBM, not by the
+// matrix cores, so the work is cut for bandwidth: one wave per (agent, KV head,
+// KV split), no workgroup barrier at all. All r * N_q query rows of the KV head
+// are columns of the wave's one 32-column Q^T block (column c = head_local *
+// N_q + i). The wave streams its key range in 32-key tiles through its own two
+// LDS stages (the loads of tile j+1 run while tile j is computed) and per tile
+// does S^T = K Q^T, the exponentials and O^T += V^T P^T exactly like the
+// prefill kernel. Partial results of the splits are merged by the same combine
+// and mass kernels.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
+{
+    constexpr int KB = 32;                       // keys per tile
+    constexpr int NKS = D / 16;
+    constexpr int NDB = D / 32;
+    constexpr int ROWB = 2 * D;
+    constexpr int KSTR = ROWB + 16;              // padded K row in LDS
+    constexpr int KCPR = KSTR / 16;
+    constexpr int KCHUNKS = KB * KCPR;           // 16-byte chunks of a K tile
+    constexpr int NBK = (KCHUNKS + 63) / 64;     // loader blocks, the last one partly dummy
+    constexpr int KBYTES = NBK * 1024;
+    constexpr int VSTR = KB * 2 + 16;            // padded V^T row in LDS (80 bytes)
+    constexpr int VCHUNKS = D * 5;
+    constexpr int NBV = VCHUNKS / 64;            // exact: D * 5 / 64
+    constexpr int VBYTES = NBV * 1024;
+    constexpr int STAGE = KBYTES + VBYTES;
+    static_assert(VCHUNKS % 64 == 0, "V^T tile must be whole loader blocks");
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+
+    const int per_xcd = gridDim.x / 8;
+    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= a.total_wgs)
+        return;
+    int t = logical;
+    const int sp = t % a.n_splits;
+    t /= a.n_splits;
+    const int kvh = t % a.Hkv;
+    const int b = t / a.Hkv;
+
+    const int lane = threadIdx.x;
+    const int col = lane % 32, half = lane / 32;
+    const int r = a.Hq / a.Hkv;
+    const bool row_valid = col < r * a.Nq;
+    const int hl = row_valid ? col / a.Nq : 0;
+    const int i_row = row_valid ? col % a.Nq : 0;
+    const int hq = kvh * r + hl;
+
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Lc = bnd[S];
+    const int Ltot = bnd[S + 1];
+    const int ntiles64 = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    // split boundaries are whole 64-key tiles, as everywhere else
+    const int split_key_begin = (int)((long)sp * ntiles64 / a.n_splits) * EN_KEY_TILE;
+    const int split_key_end = min((int)((long)(sp + 1) * ntiles64 / a.n_splits) * EN_KEY_TILE, Ltot);
+    const int t_begin = split_key_begin / KB;
+    const int t_end = (split_key_end + KB - 1) / KB;     // 32-key tiles; context rows are zero up to a multiple of 64
+
+    // ---- loader set-up ----
+    const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
+    const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    uint32_t koff[NBK], voff[NBV];
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) {
+        const int q = j * 64 + lane;
+        const int row = q / KCPR, c = q % KCPR;
+        koff[j] = (q < KCHUNKS) ? (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16) : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < NBV; ++j) {
+        const int q = j * 64 + lane;
+        const int d = q / 5, c = q % 5;
+        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < 4 ? c : 0) * 16);
+    }
+    auto issue = [&](int tile) {
+        const char *kt = kg + (size_t)tile * (KB * ROWB);
+        const char *vtile = vg + (size_t)tile * (KB * 2);
+        const uint32_t dst = lds0 + (tile & 1) * STAGE;
+#pragma unroll
+        for (int j = 0; j < NBK; ++j)
+            dma16(kt, koff[j], dst + j * 1024);
+#pragma unroll
+        for (int j = 0; j < NBV; ++j)
+            dma16(vtile, voff[j], dst + KBYTES + j * 1024);
+    };
+
+    const int klane = col * KSTR + half * 16;
+    const int vlane = KBYTES + col * VSTR + half * 16;
+
+    // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
+    bf16x8 qf[NKS];
+    {
+        float qx[NKS][8];
+        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row_valid)
+                v = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qx[ks][j] = (float)v[j];
+        }
+        const int pos = row_valid ? Lc + i_row : 0;
+        const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
+        const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS / 2; ++ks) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float cs = ct[16 * ks + j], sn = st[16 * ks + j];
+                const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
+                qx[ks][j] = (x1 * cs - x2 * sn) * a.scale_log2e;
+                qx[ks + NKS / 2][j] = (x2 * cs + x1 * sn) * a.scale_log2e;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qf[ks][j] = (bf16_t)qx[ks][j];
+    }
+
+    // ---- state (see the prefill kernel for the softmax reference scheme) ----
+    f32x16 o[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            o[d][e] = 0.f;
+    float m_ref = 0.f;
+    bool has_ref = false;
+    bool pending = row_valid && Lc + i_row >= split_key_begin;
+    f32x16 negm;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        negm[e] = 0.f;
+    float l_part = 0.f, seg_part = 0.f;
+
+    int cur = find_bucket(bnd, S, min(split_key_begin, Ltot - 1));
+    int cur_begin = bnd[cur];
+    int cur_end = bnd[cur + 1];
+    int nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+    const size_t row_hq = (size_t)b * a.Hq + hq;
+    float *seg_base = a.ws_seg
+                          ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
+                          : nullptr;
+    auto close_bucket = [&]() {
+        if (cur_end > cur_begin) {
+            const float tot = seg_part + xor32(seg_part);
+            if (seg_base && row_valid && half == 0) {
+                f32x2 v = {tot, has_ref ? m_ref : EN_NEG_INF};
+                *reinterpret_cast<f32x2 *>(seg_base + ((size_t)cur * a.Nq + i_row) * 2) = v;
+            }
+        }
+        seg_part = 0.f;
+        ++cur;
+        cur_begin = cur_end;
+        cur_end = (cur <= S) ? nxt_end : 0x7fffffff;
+        nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+    };
+
+    if (t_begin < t_end)
+        issue(t_begin);
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const char *sb = smem + (tile & 1) * STAGE;
+        // every LDS read of the previous tile has returned (its matrix
+        // instructions consumed them), so the other stage may be overwritten
+        __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0)
+        if (tile + 1 < t_end) {
+            issue(tile + 1);
+            __builtin_amdgcn_s_waitcnt(((NBK + NBV) & 15) | (((NBK + NBV) >> 4) << 14) | 0x0f70);   // tile's loads landed
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+        }
+        lds_data_ready();
+        const int kb = tile * KB;
+        // ---- S^T = K Q^T - m_ref ----
+        f32x16 sv;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(sb + klane + ks * 32);
+            if (ks == 0)
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[0], negm, 0, 0, 0);
+            else
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], sv, 0, 0, 0);
+        }
+        // causal / padding mask; columns differ in i, so every tile that reaches
+        // past L_c is checked
+        if (kb + KB - 1 > Lc) {
+            const int rel = Lc + i_row - kb - 4 * half;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (8 * (e / 4) + (e % 4) > rel)
+                    sv[e] = EN_NEG_INF;
+        }
+        // ---- reference (first visible tile, or near overflow) ----
+        constexpr float BIG = 1.0e18f;
+        bf16x8 pf[2];
+        float rs = 0.f;
+        {
+            float p[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                p[e] = fast_exp2(sv[e]);
+                rs += p[e];
+            }
+            if (__any(pending || !(rs < BIG))) {
+                float mx = sv[0];
+#pragma unroll
+                for (int e = 1; e < 16; ++e)
+                    mx = fmaxf(mx, sv[e]);
+                mx = pair_max(mx);
+                const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
+                const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
+                const float delta = fix ? mx : 0.f;
+                const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
+#pragma unroll
+                for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        o[d][e] *= alpha;
+                l_part *= alpha;
+                seg_part *= alpha;
+                m_ref += delta;
+                has_ref = has_ref || fix;
+                pending = pending && !fix;
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    negm[e] = -m_ref;
+                rs = 0.f;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    p[e] = fast_exp2(sv[e] - delta);
+                    rs += p[e];
+                }
+            }
+            // the sums use the rounded probabilities, like the products
+            rs = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const bf16_t pb = (bf16_t)p[e];
+                pf[e / 8][e % 8] = pb;
+                rs += (float)pb;
+            }
+        }
+        l_part += rs;
+        // ---- per-bucket partial sums ----
+        const int ke = min(kb + KB, split_key_end);
+        if (cur_end > ke) {
+            seg_part += rs;
+        } else if (kb < split_key_end) {
+            int lo = kb;
+            while (true) {
+                const int hi = min(cur_end, ke);
+                float part = 0.f;
+                const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int kr = 8 * (e / 4) + (e % 4);
+                    part += (kr >= rlo && kr < rhi) ? (float)pf[e / 8][e % 8] : 0.f;
+                }
+                seg_part += part;
+                if (cur_end > ke || cur > S)
+                    break;
+                close_bucket();
+                lo = hi;
+            }
+        }
+        // ---- O^T += V^T P^T ----
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int d = 0; d < NDB; ++d) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(sb + vlane + kk * 32 + d * 32 * VSTR);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
+            }
+    }
+
+    if (seg_base)
+        while (cur <= S && cur_begin < split_key_end)
+            close_bucket();
+
+    const float l_tot = l_part + xor32(l_part);
+    const size_t row = row_hq * a.Nq + i_row;
+    if (a.ws_ml && row_valid && half == 0) {
+        f32x2 v = {has_ref ? m_ref : EN_NEG_INF, l_tot};
+        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
+    }
+    if (!row_valid)
+        return;
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     bf16_t *op = (a.n_splits == 1)
                      ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
@@ -1102,6 +1430,12 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
             hipLaunchKernelGGL((attn_f32_kernel<64>), grid, blk, 0, st, a);
         else
             hipLaunchKernelGGL((attn_f32_kernel<128>), grid, blk, 0, st, a);
+    } else if (a.decode) {
+        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64);
+        if (D == 64)
+            hipLaunchKernelGGL((attn_decode_kernel<64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_decode_kernel<128>), grid, blk, 0, st, a);
     } else {
         const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
         static bool reported = false;
