@@ -34,9 +34,10 @@ WORKLOAD_TEXT = {
     "c4": "c4: decode, 64 agents x 1 new token over 64 segments x 256 tokens (16384) from a 1024-group pool; 32q/8kv, D=128, bf16",
 }
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (see profiles/), null where not measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs, each scaled by what the same counter reads for a plain copy
+# of known size (profiles/attn_bf16_c2_hbm_traffic.md); null where not measured.
+MEASURED_TRAFFIC = {"c2": 64.1e6}
 
 
 def algorithmic_flops(cfg, info) -> int:
@@ -123,7 +124,7 @@ def main():
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(args.workload)
-    roof["kernel"] = "attn_bf16_kernel<128>"
+    roof["kernel"] = "attn_decode_kernel<128>" if hbm_bound else "attn_bf16_kernel<128>"
     roof["kernel_us"] = kern_s * 1e6
     roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
 
