@@ -180,6 +180,23 @@ def test_bf16_single_query_decode(step_mod, oracle):
     run_case(step_mod, oracle, cfg, n_splits=4)
 
 
+@pytest.mark.parametrize("nq,hq,hkv,d", [(4, 8, 2, 128), (8, 4, 1, 128), (3, 6, 2, 64), (1, 8, 8, 128),
+                                         (32, 2, 2, 128)])
+def test_bf16_few_query_rows_decode_kernel(step_mod, oracle, nq, hq, hkv, d):
+    """r * N_q <= 32: all rows of a KV head are columns of one wave (decode kernel),
+    including its causal mask among several new tokens and ragged segments."""
+    cfg = small(f"bf16-decode-nq{nq}", 500 + nq + hq, n_new=nq, n_q_heads=hq, n_kv_heads=hkv,
+                head_dim=d, n_agents=2, len_lo=0, n_sel=7, rope_base=1e4 if d == 64 else 5e5)
+    run_case(step_mod, oracle, cfg, n_splits=1)
+    run_case(step_mod, oracle, cfg, n_splits=3)
+
+
+def test_bf16_decode_over_long_context(step_mod, oracle):
+    """A reduced c4: 4 agents, one new token, 16 x 256 cached tokens, default splits."""
+    cfg = I.Config("c4-small", 44, I.BF16, 4, 32, 8, 128, 64, 256, 256, 256, 16, 1, 500000.0)
+    run_case(step_mod, oracle, cfg)
+
+
 def test_bf16_agents_with_different_selections(step_mod, oracle):
     cfg = small("bf16-ragged-agents", 280, n_agents=3, len_lo=0)
     run_case(step_mod, oracle, cfg, sel_lists=[[3, 1, 7, 9, 0, 2], [], [5]], n_splits=2)
@@ -250,3 +267,96 @@ def test_full_size_decode_c4(step_mod, oracle):
     rows = sample_rows(cfg, 24)
     rows[:, 0] = np.array([0, 63, 5, 17] * 6)          # four agents only: bounds the oracle's gathers
     run_case(step_mod, oracle, cfg, rows=rows)
+
+
+# ---------------------------------------------------------------------------
+# boundary behaviour on the device side
+# ---------------------------------------------------------------------------
+def test_scored_selection_end_to_end(step_mod, oracle):
+    """Retrieval form: knapsack over scores -> plan -> gather -> attention, checked
+    against the oracle run on the oracle's own selection."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = small("scored", 600, n_groups=20, n_sel=0)
+    announce("segment_select_scored end to end")
+    w = I.make_workload(cfg)
+    rng = np.random.default_rng(1)
+    p = rng.random(cfg.n_groups).astype(np.float32)
+    budget = int(w.lens.sum()) // 3
+    want = oracle.knapsack(p, w.lens, 0.4, budget)
+    w.sel = np.asarray(want, np.int32)
+    w.sel_ptr = np.array([0, len(want)], np.int32)
+    st = step_mod.PlanningStep(w, max_ctx=cfg.n_groups * cfg.capacity + cfg.n_new)
+    got, plan = B.segment_select_scored(st.pool, p, 0.4, budget, cfg.n_new)
+    assert got.tolist() == want
+    assert np.array_equal(plan.offsets(0), oracle.plan(w.lens, want))
+    st.plan.close()
+    st.plan = plan
+    st.info = plan.info
+    st.run()
+    torch.cuda.synchronize()
+    ref_out, ref_mass = oracle_full(oracle, w)
+    check_out(cfg, st.out_host(), ref_out)
+    check_mass(cfg, st.mass_host(), ref_mass)
+
+
+def test_device_side_errors_and_timing_aid(step_mod):
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = small("errors", 610)
+    announce("error paths and timing aid")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, n_splits=2)
+    st.gather()
+    small_ws = torch.empty(256, dtype=torch.uint8, device=st.device)
+    with pytest.raises(B.EnError) as e:
+        B.segmented_prefill_attention(st.pool, st.plan, st.q, st.kc, st.vt, st.out, small_ws)
+    assert e.value.code == 4                                  # workspace too small
+    with pytest.raises(B.EnError) as e:
+        B.segmented_prefill_attention(st.pool, st.plan, st.q, st.kc, st.vt, st.out, None)
+    assert e.value.code == 1                                  # splits need a workspace
+    other = step_mod.PlanningStep(w)
+    with pytest.raises(B.EnError) as e:
+        B.gather_rope(other.pool, st.plan, st.k_new, st.v_new, st.kc, st.vt)
+    assert e.value.code == 1                                  # plan of another pool
+    B.timing_enable(3)
+    for _ in range(5):
+        st.attention()
+    torch.cuda.synchronize()
+    ms = B.timing_collect(8)
+    B.timing_enable(0)
+    assert len(ms) == 3 and (ms > 0).all() and (ms < 50).all()
+
+
+def test_no_workspace_single_split(step_mod, oracle):
+    """n_splits == 1 and no masses wanted: the attention call works without scratch."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = small("no-ws", 620)
+    announce("attention without workspace")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, n_splits=1)
+    st.gather()
+    B.segmented_prefill_attention(st.pool, st.plan, st.q, st.kc, st.vt, st.out, None)
+    torch.cuda.synchronize()
+    ref_out, _ = oracle_full(oracle, w)
+    check_out(cfg, st.out_host(), ref_out)
+
+
+def test_plan_reuse_and_repeatability(step_mod, oracle):
+    """The same plan run twice gives bit-identical results (no state leaks through the scratch);
+    a second plan on the same pool reuses the descriptor block."""
+    import torch
+    cfg = small("repeat", 630, n_agents=2)
+    announce("repeatability")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, n_splits=3)
+    st.run()
+    torch.cuda.synchronize()
+    o1, m1, r1 = st.out_host(), st.mass_host(), st.mass_red_host()
+    st.ws.fill_(0xFF)
+    st.select(3)
+    st.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(o1, st.out_host()) and np.array_equal(m1, st.mass_host())
+    assert np.array_equal(r1, st.mass_red_host())
