@@ -201,7 +201,8 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherArgs a, int nk)
 // attn_bf16: matrix-core attention.
 //
 // Work unit: one workgroup of 8 waves = 8 (query head, 32-query block) pairs of
-// one KV head and one KV split, one workgroup per compute unit.
+// one KV head and one KV split, one workgroup per compute unit, two waves per
+// SIMD.
 //
 // Each wave keeps its 32 rotated, pre-scaled queries in registers and computes
 // S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that every lane owns ONE query
@@ -215,21 +216,41 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherArgs a, int nk)
 // P(j). Everything a phase reads was finished one phase earlier, so neither
 // unit waits for the other.
 //
+// What limits a wave here is the number of instructions it issues per matrix
+// instruction (a wave issues in order; scalar instructions cost it about seven
+// cycles each), so the loop is kept free of scalar address arithmetic: it is
+// unrolled over the three LDS stages, which turns every LDS address into a
+// per-lane base plus an immediate, the loader issues unconditionally (tiles
+// past the end are clamped to the last one and land in a dead stage), and the
+// common case of a block is decided by one scalar and one vector comparison.
+//
 // K tiles [64][D] and V^T tiles [D][64] go from global memory straight into
 // LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), three
 // stages each, one workgroup barrier per 64-key tile; the loads of a tile are
-// spread over the steps of the two phases before it is needed. Rows are padded
-// by 16 bytes (the loader lets one lane in 17 / 9 fetch a dummy chunk into the
-// pad), which keeps the 16-byte operand reads of 16 consecutive lanes on
-// distinct banks with plain base + immediate addresses.
+// spread over the steps of the two phases before it is needed. Inside a tile
+// the 16-byte chunks of a row are rotated by the number of the row's 256-byte
+// line (the loader does this through its per-lane source offsets), which
+// keeps the operand reads of 16 consecutive lanes on distinct banks without
+// padding.
 //
 // Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
 // column l%32.
 // ---------------------------------------------------------------------------
 
 // One LDS-DMA load: lane i fetches 16 bytes from sbase + voff and the wave's
-// 1024 bytes land at LDS byte address lds_addr + 16*i. Completion is tracked
-// by vmcnt; the compiler does not see the LDS write, so every wait is explicit.
+// 1024 bytes land at LDS byte address lds_base + IMM + 16*i. Completion is
+// tracked by vmcnt; the compiler does not see the LDS write, so every wait is
+// explicit.
+template <int IMM>
+__device__ __forceinline__ void dma16_imm(const void *sbase, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(sbase), "n"(IMM)
+                 : "memory", "scc");
+}
+
+// The same with a run-time LDS address.
 __device__ __forceinline__ void dma16(const void *sbase, uint32_t voff, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -250,6 +271,16 @@ __device__ __forceinline__ void lds_data_ready()
     asm volatile("" ::: "memory");
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
 __device__ __forceinline__ float pair_max(float v)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -258,15 +289,6 @@ __device__ __forceinline__ float pair_max(float v)
 }
 
 constexpr int ATT_WAVES = EN_WAVES;
-
-#ifdef EXP_TIMING
-__device__ unsigned long long en_dbg[32];
-#define TICK(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
-#define TACC(slot, a, b) dbg_acc[slot] += (b) - (a)
-#else
-#define TICK(var)
-#define TACC(slot, a, b)
-#endif
 
 template <int D>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
@@ -277,19 +299,18 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     constexpr int NDB = D / 32;                  // 32-row blocks of O^T
     constexpr int NSTEP = 2 * NKS;               // matrix instructions per phase
     constexpr int EPS = 16 / NKS;                // scores turned into P per pair of steps
-    constexpr int ROWB = 2 * D;                  // bytes per K row in global memory
-    constexpr int KSTR = ROWB + 16;              // padded K row in LDS
-    constexpr int KCPR = KSTR / 16;              // 16-byte chunks per padded K row
-    constexpr int KBYTES = KT * KSTR;            // multiple of 1024
-    constexpr int VSTR = KT * 2 + 16;            // padded V^T row in LDS (144)
-    constexpr int VBYTES = D * VSTR;             // multiple of 1024
+    constexpr int ROWB = 2 * D;                  // bytes per K row
+    constexpr int KCPR = ROWB / 16;              // 16-byte chunks per K row
+    constexpr int KRPL = 256 / ROWB;             // K rows per 256-byte line
+    constexpr int KBYTES = KT * ROWB;
+    constexpr int VROWB = KT * 2;                // bytes per V^T row of a tile
+    constexpr int VBYTES = D * VROWB;
     constexpr int NST = 3;                       // LDS stages of K and of V^T
     constexpr int VBASE = NST * KBYTES;
     constexpr int NBK = KBYTES / 1024, NBV = VBYTES / 1024;   // 1 KB loader blocks per tile
-    constexpr int KJ = (NBK + ATT_WAVES - 1) / ATT_WAVES;     // max blocks per wave
-    constexpr int VJ = (NBV + ATT_WAVES - 1) / ATT_WAVES;
-    static_assert(KBYTES % 1024 == 0 && VBYTES % 1024 == 0, "tile must be whole loader blocks");
-    static_assert(KJ <= 3 && VJ <= 3 && (NSTEP >= 16 || (KJ <= 2 && VJ <= 2)), "loader steps");
+    constexpr int KJ = NBK / ATT_WAVES, VJ = NBV / ATT_WAVES; // blocks per wave
+    static_assert(NBK % ATT_WAVES == 0 && NBV % ATT_WAVES == 0 && KJ <= 2 && VJ <= 2, "loader blocks");
+    static_assert(KRPL == 1 || KRPL == 2, "row rotation");
     __shared__ __attribute__((aligned(1024))) char smem[NST * (KBYTES + VBYTES)];
 
     // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
@@ -342,51 +363,52 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const int i_lo = qb * 32;
 
     // ---- loader set-up. Block blk of a tile is LDS bytes [1024 blk, 1024 blk + 1024);
-    // lane L of it is chunk q = 64 blk + L of the padded tile: row q / CPR, chunk
-    // q % CPR of that row, the last chunk of a row being the pad. ----
+    // lane L of it is chunk q = 64 blk + L of the tile: row q / CPR, position
+    // q % CPR in that row, which holds the row's chunk (position - line) mod CPR. ----
     const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
     const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem + wave * 1024;
     uint32_t koff[KJ], voff[VJ];
 #pragma unroll
     for (int j = 0; j < KJ; ++j) {
         const int q = (wave + ATT_WAVES * j) * 64 + lane;
-        const int row = q / KCPR, c = q % KCPR;
-        koff[j] = (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16);
+        const int row = q / KCPR, pos = q % KCPR;
+        koff[j] = (uint32_t)(row * ROWB + ((pos - row / KRPL) & (KCPR - 1)) * 16);
     }
 #pragma unroll
     for (int j = 0; j < VJ; ++j) {
         const int q = (wave + ATT_WAVES * j) * 64 + lane;
-        const int d = q / 9, c = q % 9;
-        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < 8 ? c : 0) * 16);
+        const int d = q / 8, pos = q % 8;
+        voff[j] = (uint32_t)((size_t)d * a.T * 2 + ((pos - d / 2) & 7) * 16);
     }
     // Loader job of the current phase: one tile of K or of V^T, issued block by
-    // block between the matrix instructions.
-    const char *job_base = nullptr;
-    uint32_t job_dst = 0;
-    bool job_on = false;
-    auto dma_k = [&](int j) {
-        if (j < KJ && job_on && wave + ATT_WAVES * j < NBK)
-            dma16(job_base, koff[j < KJ ? j : 0], job_dst + j * ATT_WAVES * 1024);
+    // block between the matrix instructions. A tile index past the end is
+    // clamped: the last tile is fetched once more, into a stage nobody reads.
+    uint32_t job_goff = 0;
+    auto job_k = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * KBYTES; };
+    auto job_v = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * (KT * 2); };
+    auto dma_k = [&](auto j_tag, auto stage_tag) {
+        constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
+        if constexpr (j < KJ)
+            dma16_imm<stage * KBYTES + j * ATT_WAVES * 1024>(kg, koff[j] + job_goff, lds_w);
     };
-    auto dma_v = [&](int j) {
-        if (j < VJ && job_on && wave + ATT_WAVES * j < NBV)
-            dma16(job_base, voff[j < VJ ? j : 0], job_dst + j * ATT_WAVES * 1024);
-    };
-    auto job_k = [&](int tile) {
-        job_on = tile < t_end;
-        job_base = kg + (size_t)tile * (KT * ROWB);
-        job_dst = lds0 + (tile % NST) * KBYTES + wave * 1024;
-    };
-    auto job_v = [&](int tile) {
-        job_on = tile < t_end;
-        job_base = vg + (size_t)tile * (KT * 2);
-        job_dst = lds0 + VBASE + (tile % NST) * VBYTES + wave * 1024;
+    auto dma_v = [&](auto j_tag, auto stage_tag) {
+        constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
+        if constexpr (j < VJ)
+            dma16_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vg, voff[j] + job_goff, lds_w);
     };
 
-    // ---- operand read bases inside a stage (plus immediates per step) ----
-    const int klane = col * KSTR + half * 16;
-    const int vlane = VBASE + col * VSTR + half * 16;
+    // ---- operand read addresses inside a stage (plus immediates per step) ----
+    uint32_t kaddr[NKS];          // K row `col` of a 32-key block, chunk 2 ks + half
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+        kaddr[ks] = (uint32_t)(col * ROWB + ((2 * ks + half + col / KRPL) & (KCPR - 1)) * 16);
+    uint32_t vaddr[2][2];         // V^T row `col` of a 32-row block, keys 32 h + 16 kk + 8 half ..
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+            vaddr[h][kk] = (uint32_t)(VBASE + col * VROWB + ((4 * h + 2 * kk + half + col / 2) & 7) * 16);
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -422,9 +444,6 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
                 qf[ks][j] = (bf16_t)qx[ks][j];
     }
 
-#ifdef EXP_TIMING
-    unsigned long long dbg_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
     // ---- state ----
     f32x16 o[NDB];
 #pragma unroll
@@ -465,6 +484,15 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     int cur_begin = bnd[cur];
     int cur_end = bnd[cur + 1];
     int nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+    // Blocks whose first key is at most `calm` need neither the causal mask on
+    // the block after them nor any bucket bookkeeping.
+    auto calm_limit = [&]() {
+        int m = Lc + i_lo - 2 * KB + 1;
+        if (cur_end <= split_key_end)
+            m = min(m, cur_end - KB - 1);
+        return m;
+    };
+    int calm = calm_limit();
     const size_t row_hq = (size_t)b * a.Hq + hq;
     float *seg_base = a.ws_seg
                           ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
@@ -499,12 +527,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
     };
 
-    // Scores of block jb of tile `tile` relative to m_ref, unpipelined (slow path).
-    auto block_scores = [&](int tile, int jb, f32x16 &sv) {
-        const char *kbuf = smem + klane + (tile % NST) * KBYTES + jb * KB * KSTR;
+    // Scores of the 32-key block at byte offset blk_off of the K stages,
+    // relative to m_ref, unpipelined (prologue and rare path).
+    auto block_scores = [&](int blk_off, f32x16 &sv) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(kbuf + ks * 32);
+            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(smem + kaddr[ks] + blk_off);
             if (ks == 0)
                 sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[0], negm, 0, 0, 0);
             else
@@ -522,233 +550,245 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         }
     };
 
-    // One phase for block jb = PAR of tile `tile` (global block j = 2 tile + PAR):
+    // One phase for block jb = PAR of the tile in K stage ST (global block
+    // j = 2 tile + PAR):
     //   S(j+1) = K(j+1) Q^T - m_ref      NKS matrix instructions (even steps)
     //   P(j)   = exp2(S(j))              vector ALU, EPS scores per pair of steps
     //   O     += V(j-1)^T-block P(j-1)   NKS matrix instructions (odd steps)
     // plus the loader blocks of the phase's job. Operand reads run PD steps ahead.
     constexpr int PD = 4;         // operand reads run PD steps ahead, across phases too
     bf16x8 fr[PD];
-    auto operand = [&](int par, int tile, int k) {
-        // operand of step k of the phase (par, tile): even steps read K, odd steps V^T
-        if (k % 2 == 0) {
-            const char *kbuf = smem + klane + ((tile + par) % NST) * KBYTES + (par ^ 1) * KB * KSTR;
-            return *reinterpret_cast<const bf16x8 *>(kbuf + (k / 2) * 32);
+    auto operand = [&](auto par_tag, auto st_tag, auto k_tag) {
+        constexpr int par = decltype(par_tag)::value, st = decltype(st_tag)::value, k = decltype(k_tag)::value;
+        // operand of step k of the phase (par, st): even steps read K, odd steps V^T.
+        // K of block j+1: par 0 -> second half of this tile, par 1 -> first half of the next.
+        // V^T of block j-1: par 0 -> keys 32..63 of the previous tile, par 1 -> keys 0..31 of this one.
+        if constexpr (k % 2 == 0) {
+            constexpr int off = ((st + par) % NST) * KBYTES + (par ^ 1) * KB * ROWB;
+            return *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + off);
+        } else {
+            constexpr int i = k / 2, kk = i / NDB, d = i % NDB;
+            constexpr int off = ((st + NST - 1 + par) % NST) * VBYTES + d * 32 * VROWB;
+            return *reinterpret_cast<const bf16x8 *>(smem + vaddr[par ^ 1][kk] + off);
         }
-        const char *vbuf = smem + vlane + ((tile + NST - 1 + par) % NST) * VBYTES + (par ^ 1) * 64;
-        const int i = k / 2, kk = i / NDB, d = i % NDB;
-        return *reinterpret_cast<const bf16x8 *>(vbuf + kk * 32 + d * 32 * VSTR);
     };
-    auto phase = [&](auto par_tag, int tile) {
-        constexpr int PAR = decltype(par_tag)::value;
-        TICK(tp0);
+    auto phase = [&](auto par_tag, auto st_tag, int tile) {
+        constexpr int PAR = decltype(par_tag)::value, ST = decltype(st_tag)::value;
         f32x16 &s_cur = sbuf[PAR];
         f32x16 &s_nxt = sbuf[PAR ^ 1];
-        // K of block j+1: PAR 0 -> second half of this tile, PAR 1 -> first half of the next.
-        // V^T of block j-1: PAR 0 -> keys 32..63 of the previous tile, PAR 1 -> keys 0..31 of this one.
-        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
         float rs = 0.f;
         bf16x2 pb_hold[EPS / 2];
-        {
+        static_for<NSTEP>([&](auto k_tag) {
+            constexpr int k = decltype(k_tag)::value;
+            constexpr int i = k / 2;
+            const bf16x8 cur_fr = fr[k % PD];
+            if constexpr (k + PD < NSTEP)
+                fr[k % PD] = operand(par_tag, st_tag, std::integral_constant<int, (k + PD) % NSTEP>{});
+            else                               // first operands of the next phase
+                fr[k % PD] = operand(std::integral_constant<int, PAR ^ 1>{},
+                                     std::integral_constant<int, (ST + PAR) % NST>{},
+                                     std::integral_constant<int, (k + PD) % NSTEP>{});
+            if constexpr (k % 2 == 0) {
+                if constexpr (i == 0)
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
+                else
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[i], s_nxt, 0, 0, 0);
+                // exponentials of scores e0 .. e0+EPS-1 of the current block
 #pragma unroll
-            for (int k = 0; k < NSTEP; ++k) {
-                const int i = k / 2;
-                const bf16x8 cur_fr = fr[k % PD];
-                if (k + PD < NSTEP)
-                    fr[k % PD] = operand(PAR, tile, k + PD);
-                else                               // first operands of the next phase
-                    fr[k % PD] = operand(PAR ^ 1, tile + PAR, k + PD - NSTEP);
-                if (k % 2 == 0) {
-                    if (i == 0)
-                        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
-                    else
-                        s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[i], s_nxt, 0, 0, 0);
-                    // exponentials of scores e0 .. e0+EPS-1 of the current block
-#pragma unroll
-                    for (int u = 0; u < EPS; u += 2) {
-                        const int e = i * EPS + u;
-                        const f32x2 pp = {fast_exp2(s_cur[e]), fast_exp2(s_cur[e + 1])};
-                        pb_hold[u / 2] = __builtin_convertvector(pp, bf16x2);
-                        // keep this work in this step (the optimiser would sink it below the loop)
-                        asm volatile("" : "+v"(pb_hold[u / 2]));
-                    }
-                } else {
-                    const int kk = i / NDB, d = i % NDB;
-                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pbuf[PAR ^ 1][kk], o[d], 0, 0, 0);
-                    // file the probabilities made in the previous step and add them up
-#pragma unroll
-                    for (int u = 0; u < EPS; u += 2) {
-                        const int e = i * EPS + u;
-                        pbuf[PAR][e / 8][e % 8] = pb_hold[u / 2][0];
-                        pbuf[PAR][e / 8][e % 8 + 1] = pb_hold[u / 2][1];
-                        rs = __builtin_amdgcn_fdot2_f32_bf16(pb_hold[u / 2], ones, rs, false);
-                        asm volatile("" : "+v"(rs));
-                    }
+                for (int u = 0; u < EPS; u += 2) {
+                    const int e = i * EPS + u;
+                    const f32x2 pp = {fast_exp2(s_cur[e]), fast_exp2(s_cur[e + 1])};
+                    pb_hold[u / 2] = __builtin_convertvector(pp, bf16x2);
+                    // plain adds: the dot-product instructions would occupy the matrix pipeline
+                    rs += pp[0];
+                    rs += pp[1];
+                    // keep this work in this step (the optimiser would sink it below the loop)
+                    asm volatile("" : "+v"(pb_hold[u / 2]), "+v"(rs));
                 }
-#ifndef EXP_NO_DMA
-                if (k == 2 || k == NSTEP / 2 + 1 || k == NSTEP - 3) {
-                    const int j = (k == 2) ? 0 : (k == NSTEP / 2 + 1 ? 1 : 2);
-                    if (PAR == 0)
-                        dma_k(j);
-                    else
-                        dma_v(j);
+            } else {
+                constexpr int kk = i / NDB, d = i % NDB;
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pbuf[PAR ^ 1][kk], o[d], 0, 0, 0);
+                // file the probabilities made in the previous step
+#pragma unroll
+                for (int u = 0; u < EPS; u += 2) {
+                    const int e = i * EPS + u;
+                    pbuf[PAR][e / 8][e % 8] = pb_hold[u / 2][0];
+                    pbuf[PAR][e / 8][e % 8 + 1] = pb_hold[u / 2][1];
                 }
-#endif
-                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        TICK(tp1);
-        TACC(0, tp0, tp1);
+            if constexpr (k == 2 || k == NSTEP / 2 + 1) {
+                using j_tag = std::integral_constant<int, (k == 2) ? 0 : 1>;
+                if constexpr (PAR == 0)
+                    dma_k(j_tag{}, std::integral_constant<int, (ST + 2) % NST>{});
+                else
+                    dma_v(j_tag{}, std::integral_constant<int, (ST + 1) % NST>{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
         const int kb = tile * KT + PAR * KB;          // first key of block j
-        const int ke = min(kb + KB, split_key_end);
         // Rare cases, one branch for all of them: the next block needs the causal
         // mask, a bucket ends inside this block, or a row lacks a reference /
         // came near overflow (any magnitude below that is harmless: P keeps its
         // relative precision in bf16 and the accumulators are fp32).
         constexpr float BIG = 1.0e18f;            // 2^60
-        const bool next_masked = kb + 2 * KB - 1 > Lc + i_lo;
-        const bool bucket_edge = !(cur_end > ke);
-        if (!(next_masked || bucket_edge || __any(pending || !(rs < BIG)))) {
+        if (kb <= calm && !__any(pending || !(rs < BIG))) {
             l_part += rs;
             seg_part += rs;               // the whole block lies inside bucket `cur`
-        } else {
-            mask_block(kb + KB, s_nxt);
-            // ---- reference check: the wave recomputes the scores of the block,
-            // moves the affected rows to their current maximum, rescales what
-            // they have accumulated and redoes the exponentials ----
-            if (__any(pending || !(rs < BIG))) {
-                f32x16 sv;
-                block_scores(tile, PAR, sv);
-                mask_block(kb, sv);
-                float mx = sv[0];
+            return;
+        }
+        const int ke = min(kb + KB, split_key_end);
+        mask_block(kb + KB, s_nxt);
+        // ---- reference check: the wave recomputes the scores of the block,
+        // moves the affected rows to their current maximum, rescales what
+        // they have accumulated and redoes the exponentials ----
+        if (__any(pending || !(rs < BIG))) {
+            f32x16 sv;
+            block_scores(ST * KBYTES + PAR * KB * ROWB, sv);
+            mask_block(kb, sv);
+            float mx = sv[0];
 #pragma unroll
-                for (int e = 1; e < 16; ++e)
-                    mx = fmaxf(mx, sv[e]);
-                mx = pair_max(mx);
-                // both lanes of a row must take the same decision
-                const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
-                const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
-                const float delta = fix ? mx : 0.f;
-                const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
+            for (int e = 1; e < 16; ++e)
+                mx = fmaxf(mx, sv[e]);
+            mx = pair_max(mx);
+            // both lanes of a row must take the same decision
+            const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
+            const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
+            const float delta = fix ? mx : 0.f;
+            const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
 #pragma unroll
-                for (int d = 0; d < NDB; ++d)
+            for (int d = 0; d < NDB; ++d)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        o[d][e] *= alpha;
-                l_part *= alpha;
-                seg_part *= alpha;
-                m_ref += delta;
-                has_ref = has_ref || fix;
-                pending = pending && !fix;
+                for (int e = 0; e < 16; ++e)
+                    o[d][e] *= alpha;
+            l_part *= alpha;
+            seg_part *= alpha;
+            m_ref += delta;
+            has_ref = has_ref || fix;
+            pending = pending && !fix;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    negm[e] = -m_ref;
-                    s_nxt[e] -= delta;            // the next block was taken against the old reference
-                }
-                rs = 0.f;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const bf16_t pb = (bf16_t)fast_exp2(sv[e] - delta);
-                    pbuf[PAR][e / 8][e % 8] = pb;
-                    rs += (float)pb;
-                }
+            for (int e = 0; e < 16; ++e) {
+                negm[e] = -m_ref;
+                s_nxt[e] -= delta;            // the next block was taken against the old reference
             }
-            l_part += rs;
-            // ---- per-bucket partial sums ----
-            if (cur_end > ke) {
-                seg_part += rs;
-            } else if (cur_end == ke && cur_begin <= kb) {
-                // the bucket ends exactly with this block (segments aligned to 32 keys)
-                seg_part += rs;
-                while (cur <= S && cur_end <= ke)
-                    close_bucket();
-            } else if (kb < split_key_end) {
-                int lo = kb;
-                while (true) {
-                    const int hi = min(cur_end, ke);
-                    float part = 0.f;
-                    const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+            rs = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int kr = 8 * (e / 4) + (e % 4);
-                        part += (kr >= rlo && kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
-                    }
-                    seg_part += part;
-                    if (cur_end > ke || cur > S)
-                        break;
-                    close_bucket();
-                    lo = hi;
-                }
+            for (int e = 0; e < 16; ++e) {
+                const bf16_t pb = (bf16_t)fast_exp2(sv[e] - delta);
+                pbuf[PAR][e / 8][e % 8] = pb;
+                rs += (float)pb;
             }
         }
-        TICK(tp3);
-        TACC(2, tp2, tp3);
+        l_part += rs;
+        // ---- per-bucket partial sums ----
+        if (cur_end > ke) {
+            seg_part += rs;
+        } else if (cur_end == ke && cur_begin <= kb) {
+            // the bucket ends exactly with this block (segments aligned to 32 keys)
+            seg_part += rs;
+            while (cur <= S && cur_end <= ke)
+                close_bucket();
+        } else if (kb < split_key_end) {
+            int lo = kb;
+            while (true) {
+                const int hi = min(cur_end, ke);
+                float part = 0.f;
+                const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int kr = 8 * (e / 4) + (e % 4);
+                    part += (kr >= rlo && kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
+                }
+                seg_part += part;
+                if (cur_end > ke || cur > S)
+                    break;
+                close_bucket();
+                lo = hi;
+            }
+        }
+        calm = calm_limit();
     };
 
-    // ---- main loop: one barrier per tile. At the barrier of tile t everything
-    // issued so far has landed: K up to tile t+1, V^T up to tile t. The two
-    // phases of tile t then issue K of tile t+2 and V^T of tile t+1 into stages
-    // whose last readers finished before the barrier. The first product uses a
-    // zero P^T with a zero-filled V^T stage. ----
+    // ---- main loop: one barrier per tile. Tile t_begin + n lives in stage n % 3.
+    // At the barrier of tile t everything issued so far has landed: K up to
+    // tile t+1, V^T up to tile t. The two phases of tile t then issue K of tile
+    // t+2 and V^T of tile t+1 into stages whose last readers finished before the
+    // barrier. The first product uses a zero P^T with a zero-filled V^T stage. ----
+    auto tile_body = [&](auto st_tag, int tile) {
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        lds_data_ready();
+        write_pending();
+        job_k(tile + 2);
+        phase(std::integral_constant<int, 0>{}, st_tag, tile);
+        job_v(tile + 1);
+        phase(std::integral_constant<int, 1>{}, st_tag, tile);
+    };
+    using c0 = std::integral_constant<int, 0>;
+    using c1 = std::integral_constant<int, 1>;
+    using c2 = std::integral_constant<int, 2>;
     if (nt > 0) {
-        char *vz = smem + VBASE + ((t_begin + NST - 1) % NST) * VBYTES;
+        // The loop is unrolled over the three stages; the nt % 3 tiles that do
+        // not fill a round come first, so the first tile's stage s0 is chosen
+        // such that the last tile always sits in stage 2.
+        const int rem = nt % NST;
+        const int s0 = (NST - rem) % NST;
+        const int s1 = (s0 + 1) % NST, s2 = (s0 + 2) % NST;
+        char *vz = smem + VBASE + s2 * VBYTES;
         for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
             *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
         job_k(t_begin);
 #pragma unroll
         for (int j = 0; j < KJ; ++j)
-            dma_k(j);
+            dma16(kg, koff[j] + job_goff, lds_w + s0 * KBYTES + j * ATT_WAVES * 1024);
         job_k(t_begin + 1);
 #pragma unroll
         for (int j = 0; j < KJ; ++j)
-            dma_k(j);
+            dma16(kg, koff[j] + job_goff, lds_w + s1 * KBYTES + j * ATT_WAVES * 1024);
         job_v(t_begin);
 #pragma unroll
         for (int j = 0; j < VJ; ++j)
-            dma_v(j);
+            dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
         wait_all_memory();
         __builtin_amdgcn_s_barrier();
         lds_data_ready();
         // scores of the first block
-        block_scores(t_begin, 0, sbuf[0]);
+        block_scores(s0 * KBYTES, sbuf[0]);
         mask_block(t_begin * KT, sbuf[0]);
+        // first operands of the first phase: K keys 32..63 of the first tile, the zero V^T stage
 #pragma unroll
-        for (int k = 0; k < PD; ++k)
-            fr[k] = operand(0, t_begin, k);
-    }
-    TICK(tl0);
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        TICK(tb0);
-        wait_all_memory();
-        __builtin_amdgcn_s_barrier();
-        lds_data_ready();
-        TICK(tb1);
-        TACC(3, tb0, tb1);
-        write_pending();
-        job_k(tile + 2);
-        phase(std::integral_constant<int, 0>{}, tile);
-        job_v(tile + 1);
-        phase(std::integral_constant<int, 1>{}, tile);
-    }
-    TICK(tl1);
-    TACC(6, tl0, tl1);
-#ifdef EXP_TIMING
-    if (blockIdx.x == 8 && lane == 0 && (wave == 0 || wave == 4))
-        for (int i = 0; i < 8; ++i)
-            en_dbg[(wave / 4) * 8 + i] = dbg_acc[i];
-    if (blockIdx.x == 8 && lane == 0 && wave == 0)
-        en_dbg[16] = nt;
-#endif
-    if (nt > 0) {
-        // the last pending product: keys 32..63 of the last tile
-        const char *vbuf = smem + vlane + ((t_end - 1) % NST) * VBYTES + 64;
+        for (int k = 0; k < PD; ++k) {
+            if (k % 2 == 0) {
+                fr[k] = *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + s0 * KBYTES + KB * ROWB);
+            } else {
+                const int i = k / 2, kk = i / NDB, d = i % NDB;
+                fr[k] = *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + s2 * VBYTES + d * 32 * VROWB);
+            }
+        }
+        int tile = t_begin;
+        if (rem == 2) {
+            tile_body(c1{}, tile);
+            ++tile;
+        }
+        if (rem >= 1) {
+            tile_body(c2{}, tile);
+            ++tile;
+        }
+        for (; tile < t_end; tile += NST) {
+            tile_body(c0{}, tile);
+            tile_body(c1{}, tile + 1);
+            tile_body(c2{}, tile + 2);
+        }
+        // the last pending product: keys 32..63 of the last tile (stage 2)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
             for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(vbuf + kk * 32 + d * 32 * VSTR);
+                const bf16x8 av =
+                    *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + 2 * VBYTES + d * 32 * VROWB);
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pbuf[1][kk], o[d], 0, 0, 0);
             }
+        // loads of the clamped tiles may still be in flight
+        wait_all_memory();
     }
 
     if (!wave_valid)
@@ -1438,14 +1478,6 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
             hipLaunchKernelGGL((attn_decode_kernel<128>), grid, blk, 0, st, a);
     } else {
         const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
-        static bool reported = false;
-        if (!reported && getenv("EN_DEBUG")) {
-            reported = true;
-            int n64 = -1, n128 = -1;
-            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 64 * ATT_WAVES, 0);
-            (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 64 * ATT_WAVES, 0);
-            fprintf(stderr, "[efficientnav] attn_bf16 workgroups per CU: D=64 %d, D=128 %d\n", n64, n128);
-        }
         if (D == 64)
             hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, blk, 0, st, a);
         else
