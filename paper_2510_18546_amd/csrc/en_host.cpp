@@ -377,8 +377,15 @@ extern "C" int en_plan_destroy(en_plan *plan)
     return EN_OK;
 }
 
-static int plan_ensure_device(en_plan *pl, hipStream_t stream)
+// Device block of a plan (taken from the pool's cache of released blocks when
+// one fits) and its host image. With inline_ok the upload is left to the
+// gather kernel, which receives the image in its arguments, provided it is
+// small enough; *inlined says which way it went.
+static int plan_ensure_device(en_plan *pl, hipStream_t stream, bool inline_ok = false,
+                              bool *inlined = nullptr)
 {
+    if (inlined)
+        *inlined = false;
     if (pl->uploaded)
         return EN_OK;
     const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size();
@@ -403,20 +410,21 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream)
             return hip_fail(e, "hipMalloc(plan descriptors)");
         pl->d_desc_bytes = cap;
     }
-    // Stream-ordered copy; the staging vector lives as long as the plan.
-    if ((e = hipMemcpyAsync(pl->d_desc, pl->h_desc.data(), bytes, hipMemcpyHostToDevice, stream)) !=
-        hipSuccess)
-        return hip_fail(e, "hipMemcpyAsync(plan descriptors)");
+    if (inline_ok && n <= size_t(EN_INLINE_DESC_MAX)) {
+        *inlined = true;
+    } else {
+        // Stream-ordered copy; the staging vector lives as long as the plan.
+        if ((e = hipMemcpyAsync(pl->d_desc, pl->h_desc.data(), bytes, hipMemcpyHostToDevice, stream)) !=
+            hipSuccess)
+            return hip_fail(e, "hipMemcpyAsync(plan descriptors)");
+    }
     pl->uploaded = true;
     return EN_OK;
 }
 
 static inline const int32_t *d_nseg(const en_plan *pl) { return pl->d_desc; }
-static inline const int32_t *d_sel(const en_plan *pl) { return pl->d_desc + pl->nseg.size(); }
-static inline const int32_t *d_bnd(const en_plan *pl)
-{
-    return pl->d_desc + pl->nseg.size() + pl->sel.size();
-}
+static inline const int32_t *d_sel(const en_plan *pl) { return d_nseg(pl) + pl->nseg.size(); }
+static inline const int32_t *d_bnd(const en_plan *pl) { return d_sel(pl) + pl->sel.size(); }
 
 // ---------------------------------------------------------------------------
 // sizes
@@ -507,9 +515,12 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
     if (plan->pool != pool)
         return fail(EN_ERR_INVALID_ARG, "gather_rope: plan belongs to another pool");
     int rc;
-    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+    bool inlined = false;
+    if ((rc = pool_ensure_device(pool)) != EN_OK ||
+        (rc = plan_ensure_device(plan, (hipStream_t)stream, true, &inlined)) != EN_OK)
         return rc;
-    EnGatherArgs a;
+    EnGatherLaunch g;
+    EnGatherArgs &a = g.a;
     a.k_pool = pool->k_dev;
     a.v_pool = pool->v_dev;
     a.k_new = k_new_dev;
@@ -527,10 +538,41 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
     a.Nq = plan->Nq;
     a.Smax = plan->Smax;
     a.T = plan->ctx_stride;
-    const int e = en_launch_gather(pool, a, plan->max_ctx_len, stream);
-    if (e != 0)
+    g.nk = 0;
+    g.n_inline = 0;
+    g.off_nseg = 0;
+    g.off_sel = g.off_nseg + int(plan->nseg.size());
+    g.off_bnd = g.off_sel + int(plan->sel.size());
+    g.desc_out = plan->d_desc;
+    if (inlined) {
+        g.n_inline = int(plan->h_desc.size());
+        std::memcpy(g.desc, plan->h_desc.data(), plan->h_desc.size() * sizeof(int32_t));
+    }
+    const int e = en_launch_gather(pool, g, plan->max_ctx_len, stream);
+    if (e != 0) {
+        if (inlined)
+            plan->uploaded = false;       // the block was to be filled by this launch
         return hip_fail((hipError_t)e, "gather_rope launch");
+    }
     return EN_OK;
+}
+
+static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, const EnWsLayout &L)
+{
+    EnMassArgs a;
+    a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
+    a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
+    a.ws_mlfin = reinterpret_cast<const float *>(ws + L.mlfin_off);
+    a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
+    a.nseg = d_nseg(plan);
+    a.bnd = d_bnd(plan);
+    a.out = nullptr;
+    a.B = plan->B;
+    a.Hq = pool->d.n_q_heads;
+    a.Nq = plan->Nq;
+    a.Smax = plan->Smax;
+    a.n_splits = plan->n_splits;
+    return a;
 }
 
 extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
@@ -591,7 +633,8 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     if (e != 0)
         return hip_fail((hipError_t)e, "segmented_prefill_attention launch");
     if (plan->n_splits > 1) {
-        e = en_launch_combine(pool, a, stream);
+        // the same launch also leaves the per-head partial sums of the segment masses
+        e = en_launch_combine(pool, a, mass_args(pool, plan, ws, L), stream);
         if (e != 0)
             return hip_fail((hipError_t)e, "split combine launch");
     }
@@ -610,19 +653,8 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
         return rc;
     const EnWsLayout L = en_ws_layout(pool, plan);
     char *ws = static_cast<char *>(ws_dev);
-    EnMassArgs a;
-    a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
-    a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
-    a.ws_mlfin = reinterpret_cast<const float *>(ws + L.mlfin_off);
-    a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
-    a.nseg = d_nseg(plan);
-    a.bnd = d_bnd(plan);
+    EnMassArgs a = mass_args(pool, plan, ws, L);
     a.out = mass_out_dev;
-    a.B = plan->B;
-    a.Hq = pool->d.n_q_heads;
-    a.Nq = plan->Nq;
-    a.Smax = plan->Smax;
-    a.n_splits = plan->n_splits;
     const int e = en_launch_mass(pool, a, reduce, stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "segment_attention_mass launch");

@@ -36,7 +36,7 @@ struct en_plan {
     std::vector<int32_t> nseg;    // [B]
     std::vector<int32_t> sel;     // [B, Smax]   (-1 padded)
     std::vector<int32_t> bnd;     // [B, Smax+2] bucket bounds: offset[0..S], then L_c+N_q
-    // device copy: nseg | sel | bnd, created on first GPU use
+    // device block: nseg | sel | bnd, created on first GPU use
     int32_t *d_desc = nullptr;
     size_t d_desc_bytes = 0;
     std::vector<int32_t> h_desc;  // staging copy, alive as long as the plan
@@ -50,6 +50,20 @@ struct EnGatherArgs {
     const float *cos_tab, *sin_tab;
     const int32_t *nseg, *sel, *bnd;
     int B, Hkv, C, Nq, Smax, T;
+};
+
+// The gather launch can carry a small plan's descriptor block inside its kernel
+// arguments: the kernel reads the descriptors from there and one workgroup
+// stores them to the plan's device block for the kernels that follow, which
+// saves the separate host-to-device copy.
+constexpr int EN_INLINE_DESC_MAX = 960;      // ints; keeps the argument block under 4 KB
+struct EnGatherLaunch {
+    EnGatherArgs a;
+    int nk;                 // blocks of the grid's x dimension that rotate keys
+    int n_inline;           // ints of `desc` in use, 0: read the device block
+    int off_nseg, off_sel, off_bnd;   // int offsets of the three tables in the block
+    int32_t *desc_out;      // device block to fill when n_inline > 0
+    int32_t desc[EN_INLINE_DESC_MAX];
 };
 
 struct EnAttnArgs {
@@ -82,9 +96,9 @@ struct EnWsLayout {
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 
 // Kernel launchers (en_kernels.hip). Return hipError_t as int.
-int en_launch_gather(const en_pool *pool, const EnGatherArgs &a, int max_ctx_len, void *stream);
+int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream);
 int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
-int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, void *stream);
+int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 
 void en_set_error(const char *fmt, ...);

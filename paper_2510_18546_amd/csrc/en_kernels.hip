@@ -16,6 +16,7 @@
 // exponentials are exp2.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -184,16 +185,30 @@ __device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx)
 
 // One launch for the whole gather: the first nk blocks of the grid's x
 // dimension rotate keys (and copy fp32 values), the rest transpose bf16 values.
+// When the launch carries the plan's descriptor block in its arguments, the
+// tables are read from the argument segment and the first workgroup stores the
+// block to device memory for the kernels that follow on the stream.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_kernel(EnGatherArgs a, int nk)
+__global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
 {
+    EnGatherArgs a = g.a;
+    if (g.n_inline > 0) {
+        const int32_t *img = reinterpret_cast<const int32_t *>(
+            reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + offsetof(EnGatherLaunch, desc));
+        a.nseg = img + g.off_nseg;
+        a.sel = img + g.off_sel;
+        a.bnd = img + g.off_bnd;
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+            for (int i = threadIdx.x; i < g.n_inline; i += 256)
+                g.desc_out[i] = img[i];
+    }
     if constexpr (sizeof(T) == 4) {
         gather_k_block<T, D, true>(a, blockIdx.x);
     } else {
-        if ((int)blockIdx.x < nk)
+        if ((int)blockIdx.x < g.nk)
             gather_k_block<T, D, false>(a, blockIdx.x);
         else
-            gather_vt_block<D>(a, blockIdx.x - nk);
+            gather_vt_block<D>(a, blockIdx.x - g.nk);
     }
 }
 
@@ -1274,44 +1289,56 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
 
 // ---------------------------------------------------------------------------
 // combine: out = sum_sp w_sp y_sp / sum_sp w_sp with y_sp the split's own
-// softmax output and w_sp = l_sp 2^(m_sp - m). One thread per 4 output
-// elements. grid: ceil(rows*D/4/256).
+// softmax output and w_sp = l_sp 2^(m_sp - m). One thread per 16 bytes of an
+// output row. grid: ceil(rows * D / V / 256), V = elements in 16 bytes.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red);
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a)
+__global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m, int n_comb)
 {
-    typedef T tvec4 __attribute__((ext_vector_type(4)));
+    // tail of the grid: per-head partial sums of the segment masses
+    if ((int)blockIdx.x >= n_comb) {
+        __shared__ float red[4];
+        int t = blockIdx.x - n_comb;
+        const int s = t % (m.Smax + 1);
+        t /= (m.Smax + 1);
+        mass_partial_block(m, s, t % m.Hq, t / m.Hq, red);
+        return;
+    }
+    constexpr int V = 16 / sizeof(T);
+    typedef T tvec __attribute__((ext_vector_type(V)));
+    typedef float fvec __attribute__((ext_vector_type(V)));
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * (D / 4))
+    if (idx >= rows * (D / V))
         return;
-    const size_t row = idx / (D / 4);
-    const int d4 = (int)(idx % (D / 4)) * 4;
+    const size_t row = idx / (D / V);
+    const int d0 = (int)(idx % (D / V)) * V;
     float M = EN_NEG_INF;
     for (int sp = 0; sp < a.n_splits; ++sp)
         M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
     float l = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    fvec acc = 0.f;
     for (int sp = 0; sp < a.n_splits; ++sp) {
-        const float ms = a.ws_ml[((size_t)sp * rows + row) * 2];
-        const float ls = a.ws_ml[((size_t)sp * rows + row) * 2 + 1];
-        if (ms == EN_NEG_INF)
+        const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
+        if (ml[0] == EN_NEG_INF)
             continue;
-        const float w = ls * exp2f(ms - M);
+        const float w = ml[1] * exp2f(ml[0] - M);
         l += w;
-        const tvec4 v = *reinterpret_cast<const tvec4 *>((const T *)a.ws_opart + ((size_t)sp * rows + row) * D + d4);
-        acc += __builtin_convertvector(v, f32x4) * w;
+        const tvec v = *reinterpret_cast<const tvec *>((const T *)a.ws_opart + ((size_t)sp * rows + row) * D + d0);
+        acc += __builtin_convertvector(v, fvec) * w;
     }
     const float inv = 1.f / l;
-    if (d4 == 0 && a.ws_mlfin) {
+    if (d0 == 0 && a.ws_mlfin) {
         f32x2 ml = {M, l};
         *reinterpret_cast<f32x2 *>(a.ws_mlfin + row * 2) = ml;
     }
     const int i = (int)(row % a.Nq);
     const int hq = (int)((row / a.Nq) % a.Hq);
     const int b = (int)(row / ((size_t)a.Nq * a.Hq));
-    T *op = (T *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D + d4;
-    *reinterpret_cast<tvec4 *>(op) = __builtin_convertvector(acc * inv, tvec4);
+    T *op = (T *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D + d0;
+    *reinterpret_cast<tvec *>(op) = __builtin_convertvector(acc * inv, tvec);
 }
 
 // ---------------------------------------------------------------------------
@@ -1386,14 +1413,16 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     }
 }
 
-// reduce = 1, stage 1. grid: (Smax+1, Hq, B): the block sums bucket s of one
-// head over the queries into partial[b][s][hq]. (A single launch that lets the
-// last workgroup finish was measured slower: one device-scope atomic per
-// workgroup on one address serialises.)
-__global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
+// reduce = 1, stage 1: block (s, hq, b) sums bucket s of one head over the
+// queries into partial[b][s][hq]. With several KV splits this runs as the tail
+// of the combine launch (the partial sums are a by-product of the attention
+// call, whatever the caller asks of the mass call later) and merges the
+// splits' (reference, sum) pairs itself; with one split it is a launch of its
+// own. (One launch that lets the last workgroup finish needs a device-scope
+// release per workgroup, which writes the L2 back: measured 25 us; one
+// workgroup per bucket is bound by a single compute unit: 14 us.)
+__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red)
 {
-    __shared__ float red[4];
-    const int s = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
@@ -1405,8 +1434,14 @@ __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
         bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
         for (int i = threadIdx.x; i < a.Nq; i += 256) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
-            float M, L;
-            row_final_ml(a, rows, row, M, L);
+            float M = EN_NEG_INF, L = 0.f;
+            for (int sp = 0; sp < a.n_splits; ++sp)
+                M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
+            for (int sp = 0; sp < a.n_splits; ++sp) {
+                const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
+                if (ml[0] != EN_NEG_INF)
+                    L += ml[1] * exp2f(ml[0] - M);
+            }
             acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
         }
     }
@@ -1416,6 +1451,12 @@ __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
     __syncthreads();
     if (threadIdx.x == 0)
         a.ws_red[((size_t)b * (a.Smax + 1) + s) * a.Hq + hq] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
+{
+    __shared__ float red[4];
+    mass_partial_block(a, blockIdx.x, blockIdx.y, blockIdx.z, red);
 }
 
 // reduce = 1, stage 2. One wave per (agent, bucket) adds up the heads.
@@ -1436,25 +1477,27 @@ __global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-int en_launch_gather(const en_pool *pool, const EnGatherArgs &a, int max_ctx_len, void *stream)
+int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream)
 {
+    const EnGatherArgs &a = g.a;
     hipStream_t st = (hipStream_t)stream;
     const int Lpad = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
     const int nk = (Lpad + 31) / 32, nv = Lpad / EN_KEY_TILE;
+    g.nk = nk;
     const dim3 blk(256);
     const int D = pool->d.head_dim;
     if (pool->d.dtype == EN_F32) {
         const dim3 grid(nk, a.Hkv, a.B);
         if (D == 64)
-            hipLaunchKernelGGL((gather_kernel<float, 64>), grid, blk, 0, st, a, nk);
+            hipLaunchKernelGGL((gather_kernel<float, 64>), grid, blk, 0, st, g);
         else
-            hipLaunchKernelGGL((gather_kernel<float, 128>), grid, blk, 0, st, a, nk);
+            hipLaunchKernelGGL((gather_kernel<float, 128>), grid, blk, 0, st, g);
     } else {
         const dim3 grid(nk + nv, a.Hkv, a.B);
         if (D == 64)
-            hipLaunchKernelGGL((gather_kernel<bf16_t, 64>), grid, blk, 0, st, a, nk);
+            hipLaunchKernelGGL((gather_kernel<bf16_t, 64>), grid, blk, 0, st, g);
         else
-            hipLaunchKernelGGL((gather_kernel<bf16_t, 128>), grid, blk, 0, st, a, nk);
+            hipLaunchKernelGGL((gather_kernel<bf16_t, 128>), grid, blk, 0, st, g);
     }
     return (int)hipGetLastError();
 }
@@ -1486,22 +1529,25 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
     return (int)hipGetLastError();
 }
 
-int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, void *stream)
+int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     const int D = pool->d.head_dim;
-    const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / 4);
-    const dim3 grid((unsigned)((n + 255) / 256)), blk(256);
+    const int vec = pool->d.dtype == EN_F32 ? 4 : 8;      // elements in 16 bytes
+    const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec);
+    const int n_comb = (int)((n + 255) / 256);
+    const int n_part = (m.Smax + 1) * m.Hq * m.B;
+    const dim3 grid((unsigned)(n_comb + n_part)), blk(256);
     if (pool->d.dtype == EN_F32) {
         if (D == 64)
-            hipLaunchKernelGGL((combine_kernel<float, 64>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((combine_kernel<float, 64>), grid, blk, 0, st, a, m, n_comb);
         else
-            hipLaunchKernelGGL((combine_kernel<float, 128>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((combine_kernel<float, 128>), grid, blk, 0, st, a, m, n_comb);
     } else {
         if (D == 64)
-            hipLaunchKernelGGL((combine_kernel<bf16_t, 64>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((combine_kernel<bf16_t, 64>), grid, blk, 0, st, a, m, n_comb);
         else
-            hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a, m, n_comb);
     }
     return (int)hipGetLastError();
 }
@@ -1514,8 +1560,10 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         const dim3 grid((a.Nq + 255) / 256, a.Hq, a.B), blk(256);
         hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
     } else {
+        // with several splits stage 1 has already run in the combine launch
         const dim3 grid(a.Smax + 1, a.Hq, a.B), blk(256);
-        hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
+        if (a.n_splits == 1)
+            hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
         const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
         hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
     }
