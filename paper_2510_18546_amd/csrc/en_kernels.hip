@@ -413,6 +413,31 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             dma16_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vg, voff[j] + job_goff, lds_w);
     };
 
+    // ---- first loads, issued before the queries are prepared so that both are in
+    // flight together. The loop is unrolled over the three stages; the nt % 3
+    // tiles that do not fill a round come first, so the first tile's stage s0
+    // is chosen such that the last tile always sits in stage 2. ----
+    const int rem = nt % NST;
+    const int s0 = (NST - rem) % NST;
+    const int s1 = (s0 + 1) % NST, s2 = (s0 + 2) % NST;
+    if (nt > 0) {
+        char *vz = smem + VBASE + s2 * VBYTES;     // the first product reads a zero V^T stage
+        for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
+            *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
+        job_k(t_begin);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma16(kg, koff[j] + job_goff, lds_w + s0 * KBYTES + j * ATT_WAVES * 1024);
+        job_k(t_begin + 1);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma16(kg, koff[j] + job_goff, lds_w + s1 * KBYTES + j * ATT_WAVES * 1024);
+        job_v(t_begin);
+#pragma unroll
+        for (int j = 0; j < VJ; ++j)
+            dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
+    }
+
     // ---- operand read addresses inside a stage (plus immediates per step) ----
     uint32_t kaddr[NKS];          // K row `col` of a 32-key block, chunk 2 ks + half
 #pragma unroll
@@ -742,27 +767,6 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     using c1 = std::integral_constant<int, 1>;
     using c2 = std::integral_constant<int, 2>;
     if (nt > 0) {
-        // The loop is unrolled over the three stages; the nt % 3 tiles that do
-        // not fill a round come first, so the first tile's stage s0 is chosen
-        // such that the last tile always sits in stage 2.
-        const int rem = nt % NST;
-        const int s0 = (NST - rem) % NST;
-        const int s1 = (s0 + 1) % NST, s2 = (s0 + 2) % NST;
-        char *vz = smem + VBASE + s2 * VBYTES;
-        for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
-            *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
-        job_k(t_begin);
-#pragma unroll
-        for (int j = 0; j < KJ; ++j)
-            dma16(kg, koff[j] + job_goff, lds_w + s0 * KBYTES + j * ATT_WAVES * 1024);
-        job_k(t_begin + 1);
-#pragma unroll
-        for (int j = 0; j < KJ; ++j)
-            dma16(kg, koff[j] + job_goff, lds_w + s1 * KBYTES + j * ATT_WAVES * 1024);
-        job_v(t_begin);
-#pragma unroll
-        for (int j = 0; j < VJ; ++j)
-            dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
         wait_all_memory();
         __builtin_amdgcn_s_barrier();
         lds_data_ready();
