@@ -37,7 +37,7 @@ WORKLOAD_TEXT = {
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs, each scaled by what the same counter reads for a plain copy
 # of known size (profiles/attn_bf16_c2_hbm_traffic.md); null where not measured.
-MEASURED_TRAFFIC = {"c2": 64.1e6}
+MEASURED_TRAFFIC = {"c2": 64.6e6}
 
 
 def algorithmic_flops(cfg, info) -> int:
