@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the two measured ceilings (a large bf16 GEMM of the vendor library on normal "
+                         "and on constant data, a device copy) reported under 'ceilings'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -140,6 +143,37 @@ def main():
                    "new_tokens": cfg.n_new, "agents": cfg.n_agents},
         "roofline": roof,
     }
+
+    if not args.no_ceilings:
+        # Two measured ceilings of this machine beside the nominal peaks: a large bf16 GEMM of the vendor
+        # library on the same kind of data (N(0,1) rounded to bf16), and a plain device copy.
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+        n = 8192
+        a = torch.randn(n, n, device="cuda:0").to(torch.bfloat16)
+        b = torch.randn(n, n, device="cuda:0").to(torch.bfloat16)
+        c = torch.empty(n, n, device="cuda:0", dtype=torch.bfloat16)
+        t_gemm = timed(lambda: torch.matmul(a, b, out=c), 20)
+        ones = torch.ones(n, n, device="cuda:0", dtype=torch.bfloat16)
+        t_gemm1 = timed(lambda: torch.matmul(ones, ones, out=c), 20)
+        nb = 1 << 30
+        src = torch.empty(nb, dtype=torch.uint8, device="cuda:0").fill_(3)
+        dst = torch.empty_like(src)
+        t_copy = timed(lambda: dst.copy_(src), 10)
+        res["ceilings"] = {
+            "gemm_bf16_8192_normal_data_tflops": 2.0 * n ** 3 / t_gemm / 1e12,
+            "gemm_bf16_8192_constant_data_tflops": 2.0 * n ** 3 / t_gemm1 / 1e12,
+            "copy_1GiB_read_plus_write_gbs": 2.0 * nb / t_copy / 1e9,
+        }
+        del a, b, c, ones, src, dst
 
     if not args.no_cpu_baseline:
         # The float64 oracle, as it stands, on the host cores: the whole workload
