@@ -108,6 +108,22 @@ int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
  * Plans made before the change keep the old length. */
 int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len);
 
+/* Append to a group (Section 3.2, memory caching: when new objects join a
+ * group only their KV is computed, and it is saved at the end of the group's
+ * cache; the rows already there are not touched).
+ *   k_rows_dev, v_rows_dev : device, [n_tokens, Hkv, D] in the pool dtype, keys
+ *                            UNROTATED, e.g. a token range of a step's
+ *                            new-token block; read on `stream`, not kept.
+ * Enqueues on `stream` the copy of the rows to tokens len .. len+n_tokens-1 of
+ * `group` in both pool arrays and then counts them in (host side, at once):
+ * plans made after the call see the new length and must run on the same stream
+ * or after it; plans made before keep the old one. n_tokens = 0 does nothing.
+ * Errors: INVALID_ARG (null, n_tokens < 0), OUT_OF_RANGE (group),
+ *         CAPACITY (len + n_tokens > C: nothing is copied), DEVICE.
+ */
+int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                   int32_t n_tokens, void *stream);
+
 int kv_pool_destroy(en_pool *pool);
 
 /* ------------------------------------------------------------------------

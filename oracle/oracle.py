@@ -132,6 +132,26 @@ def attention(k_pool, v_pool, lens, sel, sel_ptr, q, k_new, v_new, rope_base,
     return out, mass
 
 
+def append(k_pool, v_pool, lens, group: int, k_rows, v_rows):
+    """Section 3.2, memory caching: the KV of objects that join a group is saved
+    at the end of that group's cache, the rows already there stay untouched.
+    k_rows, v_rows: [n, Hkv, D] (keys unrotated). Returns new (k_pool, v_pool,
+    lens); the inputs are not modified."""
+    k_pool, v_pool, lens = np.array(k_pool, copy=True), np.array(v_pool, copy=True), np.array(lens, copy=True)
+    n = int(k_rows.shape[0])
+    first = int(lens[group])
+    if not 0 <= group < k_pool.shape[0]:
+        raise ValueError("group id out of range")
+    if first + n > k_pool.shape[2]:
+        raise ValueError("capacity exceeded")
+    for t in range(n):
+        for h in range(k_pool.shape[1]):
+            k_pool[group, h, first + t, :] = k_rows[t, h, :]
+            v_pool[group, h, first + t, :] = v_rows[t, h, :]
+    lens[group] = first + n
+    return k_pool, v_pool, lens
+
+
 def reduce_mass(mass: np.ndarray) -> np.ndarray:
     """[B,Nq,Hq,S+1] -> [B,S+1]: mass summed over query tokens and heads
     (Section 3.3's attention between new tokens and a group; dividing by

@@ -19,7 +19,7 @@ STATUS = {0: "EN_OK", 1: "EN_ERR_INVALID_ARG", 2: "EN_ERR_OUT_OF_RANGE", 3: "EN_
           4: "EN_ERR_CAPACITY", 5: "EN_ERR_UNSUPPORTED", 6: "EN_ERR_DEVICE"}
 
 EXPORTS = [
-    "kv_pool_create", "kv_pool_set_len", "kv_pool_destroy", "segment_select",
+    "kv_pool_create", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
     "segmented_prefill_attention", "segment_attention_mass", "en_timing_enable",
@@ -60,6 +60,7 @@ def load(path: Optional[str] = None) -> C.CDLL:
     vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
     lib.kv_pool_create.argtypes = [C.POINTER(PoolDesc), vp, vp, i32p, C.POINTER(vp)]
     lib.kv_pool_set_len.argtypes = [vp, C.c_int32, C.c_int32]
+    lib.kv_pool_append.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp]
     lib.kv_pool_destroy.argtypes = [vp]
     lib.segment_select.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(vp)]
     lib.segment_select_scored.argtypes = [vp, C.POINTER(C.c_float), C.c_float, C.c_int64, C.c_int32,
@@ -178,6 +179,20 @@ def kv_pool_create(k_pool, v_pool, lens, n_q_heads: int, rope_base: float, max_c
 
 def kv_pool_set_len(pool: Pool, group: int, length: int):
     _check(load().kv_pool_set_len(pool.handle, group, length))
+
+
+def kv_pool_append(pool: Pool, group: int, k_rows, v_rows, n_tokens: Optional[int] = None, stream=None):
+    """k_rows, v_rows: torch tensors [n, Hkv, D] (contiguous, pool dtype, keys unrotated) on the GPU;
+    for host-only tests pass integers as opaque pointers together with n_tokens."""
+    if hasattr(k_rows, "data_ptr"):
+        assert k_rows.is_contiguous() and v_rows.is_contiguous() and k_rows.shape == v_rows.shape
+        n_tokens = int(k_rows.shape[0]) if n_tokens is None else int(n_tokens)
+        kp, vp_ = k_rows.data_ptr(), v_rows.data_ptr()
+        stream = _stream(stream)
+    else:
+        kp, vp_ = k_rows, v_rows
+        stream = C.c_void_p(0)
+    _check(load().kv_pool_append(pool.handle, int(group), C.c_void_p(kp), C.c_void_p(vp_), int(n_tokens), stream))
 
 
 def segment_select(pool: Pool, sel, sel_ptr, n_new: int) -> Plan:

@@ -91,6 +91,37 @@ extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
     return EN_OK;
 }
 
+extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                              int32_t n_tokens, void *stream)
+{
+    if (!pool || n_tokens < 0 || (n_tokens > 0 && (!k_rows_dev || !v_rows_dev)))
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_append: null argument or negative count");
+    if (group < 0 || group >= pool->d.n_groups)
+        return fail(EN_ERR_OUT_OF_RANGE, "kv_pool_append: group %d outside [0, %d)", group, pool->d.n_groups);
+    const int len = pool->len[group];
+    if (long(len) + n_tokens > pool->d.capacity)
+        return fail(EN_ERR_CAPACITY, "kv_pool_append: group %d holds %d tokens, %d more exceed capacity %d",
+                    group, len, n_tokens, pool->d.capacity);
+    if (n_tokens == 0)
+        return EN_OK;
+    EnAppendArgs a;
+    a.k_rows = k_rows_dev;
+    a.v_rows = v_rows_dev;
+    a.k_pool = pool->k_dev;
+    a.v_pool = pool->v_dev;
+    a.n = n_tokens;
+    a.Hkv = pool->d.n_kv_heads;
+    a.C = pool->d.capacity;
+    a.group = group;
+    a.first = len;
+    a.row_chunks = pool->d.head_dim * int(elem_size(pool->d.dtype)) / 16;
+    const int e = en_launch_append(pool, a, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "kv_pool_append launch");
+    pool->len[group] = len + n_tokens;
+    return EN_OK;
+}
+
 extern "C" int kv_pool_destroy(en_pool *pool)
 {
     if (!pool)

@@ -89,6 +89,13 @@ struct EnMassArgs {
     int B, Hq, Nq, Smax, n_splits;
 };
 
+struct EnAppendArgs {
+    const void *k_rows, *v_rows;   // [n, Hkv, D]
+    void *k_pool, *v_pool;         // [G, Hkv, C, D]
+    int n, Hkv, C, group, first;   // rows go to tokens first .. first+n-1 of the group
+    int row_chunks;                // 16-byte chunks per (token, head) row
+};
+
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
     size_t ml_off, seg_off, red_off, mlfin_off, opart_off, total;
@@ -99,6 +106,7 @@ EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream);
 int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
 int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
+int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 
 void en_set_error(const char *fmt, ...);

@@ -1479,6 +1479,27 @@ __global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// append: rows [n, Hkv, D] go to tokens first .. first+n-1 of one group's block
+// [Hkv, C, D] in both pool arrays (Section 3.2: new objects' KV is saved at the
+// end of the group's cache). One thread per 16 bytes; grid.y: 0 keys, 1 values.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_kernel(EnAppendArgs a)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)a.n * a.Hkv * a.row_chunks;
+    if (idx >= total)
+        return;
+    const int c = (int)(idx % a.row_chunks);
+    const size_t rowi = idx / a.row_chunks;          // tok * Hkv + h
+    const int h = (int)(rowi % a.Hkv);
+    const int tok = (int)(rowi / a.Hkv);
+    const uint4 *src = reinterpret_cast<const uint4 *>(blockIdx.y == 0 ? a.k_rows : a.v_rows);
+    uint4 *dst = reinterpret_cast<uint4 *>(blockIdx.y == 0 ? a.k_pool : a.v_pool);
+    const size_t drow = ((size_t)a.group * a.Hkv + h) * a.C + a.first + tok;
+    dst[drow * a.row_chunks + c] = src[rowi * a.row_chunks + c];
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream)
@@ -1553,6 +1574,15 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
         else
             hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a, m, n_comb);
     }
+    return (int)hipGetLastError();
+}
+
+int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream)
+{
+    (void)pool;
+    const size_t total = (size_t)a.n * a.Hkv * a.row_chunks;
+    const dim3 grid((unsigned)((total + 255) / 256), 2), blk(256);
+    hipLaunchKernelGGL(append_kernel, grid, blk, 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

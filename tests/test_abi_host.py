@@ -163,3 +163,29 @@ def test_scored_selection_edges():
     with pytest.raises(B.EnError) as e:
         B.segment_select_scored(pool, p, 0.5, -1, 1)
     assert e.value.code == 1
+
+
+def test_append_checks_without_device():
+    """Range and capacity checks of kv_pool_append come before any device work;
+    a rejected append leaves the length as it was."""
+    lens = np.array([3, 8, 0, 5], np.int32)
+    pool = B.kv_pool_create(None, None, lens, n_q_heads=4, rope_base=1e4, max_ctx=64, dtype=B.EN_BF16,
+                            k_ptr=0x1000, v_ptr=0x2000, shape=(4, 2, 8, 64))
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 4, 0x3000, 0x4000, 1)
+    assert e.value.code == 2
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 1, 0x3000, 0x4000, 1)          # group 1 is full
+    assert e.value.code == 4
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 0, 0x3000, 0x4000, 6)          # 3 + 6 > 8
+    assert e.value.code == 4
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 0, 0x3000, 0x4000, -1)
+    assert e.value.code == 1
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 0, 0, 0x4000, 2)
+    assert e.value.code == 1
+    B.kv_pool_append(pool, 0, 0, 0, 0)                        # nothing to do
+    plan = B.segment_select(pool, [0, 3], [0, 2], 4)
+    assert plan.offsets(0).tolist() == [0, 3, 8]

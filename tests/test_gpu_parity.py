@@ -360,3 +360,53 @@ def test_plan_reuse_and_repeatability(step_mod, oracle):
     torch.cuda.synchronize()
     assert np.array_equal(o1, st.out_host()) and np.array_equal(m1, st.mass_host())
     assert np.array_equal(r1, st.mass_red_host())
+
+
+# ---------------------------------------------------------------------------
+# append (next row of the scope table): cache lifecycle
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [I.BF16, I.F32])
+def test_append_then_attend(step_mod, oracle, dtype):
+    """kv_pool_append through the C ABI: the pool arrays equal the oracle's append bit for bit
+    (every group, NaN poison included); a plan made afterwards attends over the appended group."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = small("append", 640, dtype=dtype, n_groups=10, capacity=96, len_lo=10, len_hi=60, n_sel=4,
+                n_new=40, head_dim=128 if dtype == I.BF16 else 64, rope_base=5e5 if dtype == I.BF16 else 1e4)
+    announce(f"kv_pool_append dtype={dtype}")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, max_ctx=5 * cfg.capacity + cfg.n_new)
+    g = next(i for i in range(cfg.n_groups) if i not in set(w.agent_sel(0).tolist()))
+    # the group is emptied, then receives the step's new tokens in two pieces
+    B.kv_pool_set_len(st.pool, g, 0)
+    lens = w.lens.copy()
+    lens[g] = 0
+    kp, vp = w.k_pool, w.v_pool
+    for lo, hi in ((0, 13), (13, 40)):
+        B.kv_pool_append(st.pool, g, st.k_new[0, lo:hi].contiguous(), st.v_new[0, lo:hi].contiguous())
+        kp, vp, lens = oracle.append(kp, vp, lens, g, w.k_new[0, lo:hi], w.v_new[0, lo:hi])
+    torch.cuda.synchronize()
+
+    def bits(t):
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy().view(np.uint32)
+
+    def ref_bits(x):
+        return I.bf16_bits(x) if dtype == I.BF16 else np.ascontiguousarray(x, np.float32).view(np.uint32)
+    assert np.array_equal(bits(st.k_pool), ref_bits(kp))
+    assert np.array_equal(bits(st.v_pool), ref_bits(vp))
+    # attend over [old selection, the appended group]
+    sel = np.concatenate([w.agent_sel(0), [g]]).astype(np.int32)
+    w.k_pool, w.v_pool, w.lens = kp, vp, lens
+    w.sel, w.sel_ptr = sel, np.array([0, len(sel)], np.int32)
+    st.select()
+    assert np.array_equal(st.plan.offsets(0), oracle.plan(lens, sel))
+    st.run()
+    torch.cuda.synchronize()
+    ref_out, ref_mass = oracle_full(oracle, w)
+    check_out(cfg, st.out_host(), ref_out)
+    check_mass(cfg, st.mass_host(), ref_mass)
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(st.pool, g, st.k_new[0].contiguous(), st.v_new[0].contiguous(), 57)   # 40 + 57 > 96
+    assert e.value.code == 4

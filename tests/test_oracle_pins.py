@@ -253,6 +253,37 @@ def test_prefill_row_equals_decode_step(oracle):
         np.testing.assert_allclose(m1[0, 0, :, 3] + m1[0, 0, :, 4], mass[0, i, :, 3], atol=1e-13)
 
 
+def test_append_then_decode_equals_prefill_row(oracle):
+    """Pin of the append: the new tokens of a step, appended one after the other
+    to an EMPTY group of the pool (Section 3.2: saved at the end of the group's
+    cache), turn every later row of the same prefill into a one-token call over
+    [old segments, that group]. Rows placed at a wrong token, head or group, or
+    keys stored rotated, break the equality."""
+    cfg = tiny_cfg(52, n_agents=1, len_lo=1, n_new=5, capacity=6, n_kv_heads=2, n_q_heads=4)
+    w = I.make_workload(cfg, sel_lists=[[1, 5, 3]])
+    out, mass = run_oracle(oracle, w)
+    g = 2                                            # not selected; emptied first
+    lens = w.lens.copy()
+    lens[g] = 0
+    kp, vp = w.k_pool, w.v_pool
+    for i in range(1, cfg.n_new):
+        kp, vp, lens = oracle.append(kp, vp, lens, g, w.k_new[0, i - 1:i], w.v_new[0, i - 1:i])
+        assert lens[g] == i
+        sel = np.array([1, 5, 3, g], dtype=np.int32)
+        o1, m1 = oracle.attention(kp, vp, lens, sel, np.array([0, 4], np.int32),
+                                  w.q[:, i:i + 1], w.k_new[:, i:i + 1], w.v_new[:, i:i + 1],
+                                  cfg.rope_base)
+        np.testing.assert_allclose(o1[0, 0], out[0, i], atol=1e-13)
+        np.testing.assert_allclose(m1[0, 0, :, 3] + m1[0, 0, :, 4], mass[0, i, :, 3], atol=1e-13)
+    # rows of other groups and beyond the new length are untouched (bit patterns, NaN poison included)
+    same = np.ones(w.k_pool.shape[:3], bool)
+    same[g, :, :cfg.n_new - 1] = False
+    assert np.array_equal(kp.view(np.uint32)[same], w.k_pool.view(np.uint32)[same])
+    assert np.array_equal(vp.view(np.uint32)[same], w.v_pool.view(np.uint32)[same])
+    with pytest.raises(ValueError):
+        oracle.append(kp, vp, lens, g, w.k_new[0, :3], w.v_new[0, :3])        # 4 + 3 > capacity 6
+
+
 def test_dominant_key(oracle):
     """A key with logit about +50 over the rest takes all the mass."""
     cfg = tiny_cfg(61, n_agents=1, n_q_heads=2, n_kv_heads=2, len_lo=2, n_new=1)
