@@ -38,13 +38,33 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Exchange a value with the lane 32 positions away.
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+__device__ __forceinline__ float xor32(float v)
+{
+    // v_permlane32_swap exchanges the two halves of the wave in the vector ALU (no LDS crossbar,
+    // hence no wait on the LDS counter that the operand prefetches also use)
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    // lanes 0..31 hold (own, partner) in (r[0], r[1]); lanes 32..63 in (r[1], r[0]): pick the partner
+    const unsigned lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    return __uint_as_float(lane < 32 ? r[1] : r[0]);
+}
 
 // ---------------------------------------------------------------------------
 // Segment lookup: largest s with bnd[s] <= tok among buckets 0..S (bucket S is
 // the new block). Empty buckets are skipped because of the "largest".
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ int find_bucket(const int32_t *bnd, int S, int tok)
+// The plan's tables are read-only for every kernel that takes them from device
+// memory. Addressed through the constant address space, their wave-uniform
+// reads become scalar loads; as plain global reads they would be vector loads
+// whose wait (vmcnt) also waits for every tile load in flight.
+typedef const int32_t __attribute__((address_space(4))) *en_table_ptr;
+__device__ __forceinline__ en_table_ptr as_table(const int32_t *p)
+{
+    return (en_table_ptr)(uintptr_t)p;
+}
+
+template <typename P>
+__device__ __forceinline__ int find_bucket(P bnd, int S, int tok)
 {
     int lo = 0, hi = S;             // invariant: bnd[lo] <= tok
     while (lo < hi) {
@@ -358,7 +378,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const bool row_valid = wave_valid && i_row < a.Nq;
 
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const en_table_ptr bnd = as_table(a.bnd + (size_t)b * (a.Smax + 2));
     const int Lc = bnd[S];
     const int Ltot = bnd[S + 1];
     const int ntiles = (Ltot + KT - 1) / KT;
@@ -534,8 +554,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     };
     int calm = calm_limit();
     const size_t row_hq = (size_t)b * a.Hq + hq;
+    // this lane's row in the per-segment table of this split; bucket s is s * Nq rows further
     float *seg_base = a.ws_seg
-                          ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
+                          ? a.ws_seg + ((((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq + i_row) * 2
                           : nullptr;
 
     // A closed bucket's (sum, reference) pair is written one tile later, right
@@ -547,7 +568,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         if (pend_bucket >= 0) {
             if (seg_base && row_valid && half == 0) {
                 f32x2 v = {pend_tot, pend_m};
-                *reinterpret_cast<f32x2 *>(seg_base + ((size_t)pend_bucket * a.Nq + i_row) * 2) = v;
+                *reinterpret_cast<f32x2 *>(seg_base + (size_t)(pend_bucket * a.Nq) * 2) = v;
             }
             pend_bucket = -1;
         }
@@ -671,7 +692,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         // came near overflow (any magnitude below that is harmless: P keeps its
         // relative precision in bf16 and the accumulators are fp32).
         constexpr float BIG = 1.0e18f;            // 2^60
-        if (kb <= calm && !__any(pending || !(rs < BIG))) {
+        const bool odd_row = __any(pending || !(rs < BIG));     // wave-uniform
+        if (kb <= calm && !odd_row) {
             l_part += rs;
             seg_part += rs;               // the whole block lies inside bucket `cur`
             return;
@@ -681,7 +703,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         // ---- reference check: the wave recomputes the scores of the block,
         // moves the affected rows to their current maximum, rescales what
         // they have accumulated and redoes the exponentials ----
-        if (__any(pending || !(rs < BIG))) {
+        if (odd_row) {
             f32x16 sv;
             block_scores(ST * KBYTES + PAR * KB * ROWB, sv);
             mask_block(kb, sv);
@@ -728,21 +750,27 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             while (cur <= S && cur_end <= ke)
                 close_bucket();
         } else if (kb < split_key_end) {
-            int lo = kb;
+            // buckets end inside the block: every bucket but the last one met takes the sum
+            // of its keys, the last one what is left of the block's sum
+            float rest = rs;
             while (true) {
                 const int hi = min(cur_end, ke);
+                if (cur_end > ke || cur > S) {
+                    seg_part += rest;
+                    break;
+                }
                 float part = 0.f;
-                const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+                const int rhi = hi - kb - 4 * half;     // keys below `hi` not yet given away
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int kr = 8 * (e / 4) + (e % 4);
-                    part += (kr >= rlo && kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
+                    part += (kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
                 }
+                // `part` is the sum over keys kb .. hi-1; what earlier buckets took is in rs - rest
+                part -= rs - rest;
                 seg_part += part;
-                if (cur_end > ke || cur > S)
-                    break;
+                rest -= part;
                 close_bucket();
-                lo = hi;
             }
         }
         calm = calm_limit();
@@ -901,7 +929,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const int hq = kvh * r + hl;
 
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const en_table_ptr bnd = as_table(a.bnd + (size_t)b * (a.Smax + 2));
     const int Lc = bnd[S];
     const int Ltot = bnd[S + 1];
     const int ntiles64 = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
