@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import weakref
 from typing import Optional, Sequence, Tuple
 
 import numpy as np
@@ -111,9 +112,12 @@ class Pool:
 
     def __init__(self, handle, k, v, desc: PoolDesc):
         self.handle, self.k, self.v, self.desc = handle, k, v, desc
+        self._plans = weakref.WeakSet()      # a pool must outlive its plans: it closes them first
 
     def close(self):
         if self.handle:
+            for p in list(self._plans):
+                p.close()
             load().kv_pool_destroy(self.handle)
             self.handle = None
 
@@ -127,6 +131,7 @@ class Pool:
 class Plan:
     def __init__(self, handle, pool: Pool):
         self.handle, self.pool = handle, pool
+        pool._plans.add(self)
 
     @property
     def info(self) -> PlanInfo:

@@ -189,3 +189,17 @@ def test_append_checks_without_device():
     B.kv_pool_append(pool, 0, 0, 0, 0)                        # nothing to do
     plan = B.segment_select(pool, [0, 3], [0, 2], 4)
     assert plan.offsets(0).tolist() == [0, 3, 8]
+
+
+def test_binding_closes_plans_before_their_pool():
+    """Whatever order the garbage collector picks, a plan is never destroyed after its pool."""
+    lens = np.array([3, 8, 0, 5], np.int32)
+    pool = B.kv_pool_create(None, None, lens, n_q_heads=4, rope_base=1e4, max_ctx=64, dtype=B.EN_BF16,
+                            k_ptr=0x1000, v_ptr=0x2000, shape=(4, 2, 8, 64))
+    p1 = B.segment_select(pool, [0, 3], [0, 2], 4)
+    p2 = B.segment_select(pool, [1], [0, 1], 2)
+    pool.close()
+    assert p1.handle is None and p2.handle is None
+    p1.close()
+    p2.close()
+    pool.close()

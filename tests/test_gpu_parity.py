@@ -152,6 +152,44 @@ def test_bf16_planted_mass(step_mod, oracle):
     assert mass[0, :, :, s].mean() > 0.5
 
 
+@pytest.mark.parametrize("splits", [1, 3])
+def test_bf16_reference_moves_mid_stream(step_mod, oracle, splits):
+    """One key of a LATE segment gets a logit of about +80 (agent 1) or +110 (agent 0, whose
+    exponential overflows to infinity against the reference chosen at the first block): the
+    kernel must move the softmax reference mid-stream and rescale what it has accumulated.
+    The key dominates with a wide margin, so the case is well conditioned in bf16."""
+    cfg = small("bf16-reref", 225 + splits, planted=True, n_sel=6, n_new=70, n_agents=2, len_lo=40)
+    announce(f"reference move, splits={splits}")
+    w = I.make_workload(cfg)
+    D = cfg.head_dim
+    u = np.zeros(D, np.float32)
+    u[3 * D // 8:D // 2] = 1.0
+    u /= np.linalg.norm(u)
+    alpha = np.float32((8.0 * np.sqrt(D)) ** 0.5)        # the generator's shared component
+    toks = []
+    for b, gamma in ((0, 14.0), (1, 10.0)):
+        g = w.meta["planted_group"][b]
+        t = int(w.lens[g]) - 3
+        w.k_pool[g, :, t, :] = I.round_to_bf16(np.float32(gamma) * alpha * u)
+        toks.append((g, t))
+    import torch
+    st = step_mod.PlanningStep(w, n_splits=splits)
+    st.run()
+    torch.cuda.synchronize()
+    out, mass = st.out_host(), st.mass_host()
+    assert np.isfinite(out).all() and np.isfinite(mass).all()
+    ref_out, ref_mass = oracle_full(oracle, w)
+    check_out(cfg, out, ref_out)
+    check_mass(cfg, mass, ref_mass)
+    for b, (g, t) in enumerate(toks):
+        s_idx = list(w.agent_sel(b)).index(g)
+        assert mass[b, :, :, s_idx].min() > 0.999
+        r = cfg.n_q_heads // cfg.n_kv_heads
+        for hq in range(cfg.n_q_heads):
+            np.testing.assert_allclose(out[b, :, hq], np.broadcast_to(w.v_pool[g, hq // r, t], out[b, :, hq].shape),
+                                       atol=2e-2)
+
+
 def test_bf16_scaled_activations_like_c1(step_mod, oracle):
     cfg = small("bf16-scaled", 230, act_scale=128.0 ** -0.5, n_sel=8)
     run_case(step_mod, oracle, cfg, n_splits=2)
