@@ -226,6 +226,7 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
     pl->nseg.assign(B, 0);
     pl->sel.assign(size_t(B) * std::max(Smax, 1), -1);
     pl->bnd.assign(size_t(B) * (Smax + 2), 0);
+    pl->hdr.assign(size_t(B) * 4, 0);
     std::vector<int32_t> seen(G, -1);
     const int sstr = std::max(Smax, 1);
     for (int b = 0; b < B; ++b) {
@@ -262,6 +263,9 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
         bnd[S] = int32_t(acc);
         for (int s = S + 1; s < Smax + 2; ++s)
             bnd[s] = int32_t(acc + n_new);
+        pl->hdr[size_t(b) * 4 + 0] = S;
+        pl->hdr[size_t(b) * 4 + 1] = int32_t(acc);
+        pl->hdr[size_t(b) * 4 + 2] = int32_t(acc + n_new);
         pl->max_ctx_len = std::max<int>(pl->max_ctx_len, int(acc + n_new));
         pl->total_cached += acc;
         pl->total_pairs += int64_t(n_new) * acc + int64_t(n_new) * (n_new + 1) / 2;
@@ -419,13 +423,14 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream, bool inline_ok = 
         *inlined = false;
     if (pl->uploaded)
         return EN_OK;
-    const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size();
+    const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size() + pl->hdr.size();
     const size_t bytes = n * sizeof(int32_t);
     pl->h_desc.clear();
     pl->h_desc.reserve(n);
     pl->h_desc.insert(pl->h_desc.end(), pl->nseg.begin(), pl->nseg.end());
     pl->h_desc.insert(pl->h_desc.end(), pl->sel.begin(), pl->sel.end());
     pl->h_desc.insert(pl->h_desc.end(), pl->bnd.begin(), pl->bnd.end());
+    pl->h_desc.insert(pl->h_desc.end(), pl->hdr.begin(), pl->hdr.end());
     hipError_t e;
     auto &cache = pl->pool->desc_cache;
     for (size_t i = 0; i < cache.size(); ++i)
@@ -456,6 +461,7 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream, bool inline_ok = 
 static inline const int32_t *d_nseg(const en_plan *pl) { return pl->d_desc; }
 static inline const int32_t *d_sel(const en_plan *pl) { return d_nseg(pl) + pl->nseg.size(); }
 static inline const int32_t *d_bnd(const en_plan *pl) { return d_sel(pl) + pl->sel.size(); }
+static inline const int32_t *d_hdr(const en_plan *pl) { return d_bnd(pl) + pl->bnd.size(); }
 
 // ---------------------------------------------------------------------------
 // sizes
@@ -636,6 +642,7 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     a.sin_tab = pool->d_sin;
     a.nseg = d_nseg(plan);
     a.bnd = d_bnd(plan);
+    a.hdr = d_hdr(plan);
     char *ws = static_cast<char *>(ws_dev);
     a.ws_ml = ws ? reinterpret_cast<float *>(ws + L.ml_off) : nullptr;
     a.ws_seg = ws ? reinterpret_cast<float *>(ws + L.seg_off) : nullptr;

@@ -36,7 +36,8 @@ struct en_plan {
     std::vector<int32_t> nseg;    // [B]
     std::vector<int32_t> sel;     // [B, Smax]   (-1 padded)
     std::vector<int32_t> bnd;     // [B, Smax+2] bucket bounds: offset[0..S], then L_c+N_q
-    // device block: nseg | sel | bnd, created on first GPU use
+    std::vector<int32_t> hdr;     // [B, 4] S, L_c, L_c+N_q, 0: what a workgroup needs first, in one load
+    // device block: nseg | sel | bnd | hdr, created on first GPU use
     int32_t *d_desc = nullptr;
     size_t d_desc_bytes = 0;
     std::vector<int32_t> h_desc;  // staging copy, alive as long as the plan
@@ -70,7 +71,7 @@ struct EnAttnArgs {
     const void *q, *kc, *vt;
     void *out;
     const float *cos_tab, *sin_tab;
-    const int32_t *nseg, *bnd;
+    const int32_t *nseg, *bnd, *hdr;
     float *ws_ml;      // [n_splits, B*Hq*Nq, 2]  (reference max in log2 units, sum)
     float *ws_seg;     // [n_splits, B*Hq, Smax+1, Nq, 2] (partial sum, its reference max)
     void *ws_opart;    // [n_splits, B*Hq*Nq, D] per-split softmax outputs (pool dtype)

@@ -377,10 +377,23 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const int i_row = qb * 32 + col;
     const bool row_valid = wave_valid && i_row < a.Nq;
 
-    const int S = a.nseg[b];
-    const en_table_ptr bnd = as_table(a.bnd + (size_t)b * (a.Smax + 2));
-    const int Lc = bnd[S];
-    const int Ltot = bnd[S + 1];
+    // What the workgroup needs before it can start loading: the agent's header
+    // {S, L_c, L_c + N_q} in one scalar load and, when they fit one wave, all
+    // bucket bounds at once, one per lane (a binary search over the table would
+    // be six dependent trips to memory, about half of the start-up time).
+    const int32_t *bnd_g = a.bnd + (size_t)b * (a.Smax + 2);
+    const bool bnd_in_lanes = a.Smax + 2 <= 64;
+    int my_bnd = 0x7fffffff;
+    if (bnd_in_lanes && lane <= a.Smax + 1)
+        my_bnd = bnd_g[lane];
+    const en_table_ptr hdr = as_table(a.hdr + 4 * (size_t)b);
+    const int S = hdr[0];
+    const int Lc = hdr[1];
+    const int Ltot = hdr[2];
+    const en_table_ptr bnd = as_table(bnd_g);
+    auto bound_at = [&](int s) {          // s is wave-uniform
+        return bnd_in_lanes ? __builtin_amdgcn_readlane(my_bnd, s) : bnd[s];
+    };
     const int ntiles = (Ltot + KT - 1) / KT;
     const int t_begin = (int)((long)sp * ntiles / a.n_splits);
     int t_end = (int)((long)(sp + 1) * ntiles / a.n_splits);
@@ -540,10 +553,11 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 
     // bucket tracking (wave-uniform): bucket `cur` covers [cur_begin, cur_end);
     // the bound after that is fetched ahead of its use
-    int cur = find_bucket(bnd, S, min(split_key_begin, Ltot - 1));
-    int cur_begin = bnd[cur];
-    int cur_end = bnd[cur + 1];
-    int nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+    const int tok0 = min(split_key_begin, Ltot - 1);
+    int cur = bnd_in_lanes ? (int)__popcll(__ballot(lane <= S && my_bnd <= tok0)) - 1 : find_bucket(bnd, S, tok0);
+    int cur_begin = bound_at(cur);
+    int cur_end = bound_at(cur + 1);
+    int nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     // Blocks whose first key is at most `calm` need neither the causal mask on
     // the block after them nor any bucket bookkeeping.
     auto calm_limit = [&]() {
@@ -585,7 +599,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         ++cur;
         cur_begin = cur_end;
         cur_end = (cur <= S) ? nxt_end : 0x7fffffff;
-        nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+        nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     };
 
     // Scores of the 32-key block at byte offset blk_off of the K stages,
