@@ -16,6 +16,9 @@
  *                               (Appendix A; prompt order of Appendix B)
  *   segment_attention_mass      attention paid to each group, the clustering
  *                               signal of Section 3.3
+ *   segment_cluster_assign      that signal per new object, and the join /
+ *                               new-group decision
+ *   kv_pool_append              new objects' KV saved at the end of their group
  *
  * Conventions
  *   - Every call returns an en_status; en_last_error() gives the text of the
@@ -233,6 +236,38 @@ int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
  */
 int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
                            float *mass_out_dev, void *stream);
+
+/* Clustering signal and decision (Section 3.3, attention-based memory
+ * clustering: a newly detected object joins the existing group it attends to
+ * most if that attention passes a threshold, otherwise it founds a new group).
+ * An object is a span of the new tokens; its score against cached segment s is
+ * the mean, over the span's tokens and over the query heads, of the attention
+ * mass on s (per_key = 0) or of that mass divided by the segment's length,
+ * i.e. the mean attention weight per (query token, key token) pair
+ * (per_key = 1). From the scratch left by the attention call on the same plan
+ * and stream.
+ *   n_obj, span_ptr_host : host int32 [n_obj+1], object o = new tokens
+ *                          [span_ptr[o], span_ptr[o+1]), the same for every
+ *                          agent; 0 <= span_ptr[o] < span_ptr[o+1] <= N_q
+ *   accumulate           : 0 the scores are written; 1 they are added to what
+ *                          score_dev holds (the paper averages the first tenth
+ *                          of the layers: one call per layer)
+ *   scale, threshold     : the decision looks at score * scale (e.g. 1/layers):
+ *                          the cached segment s < S_b with the largest value,
+ *                          the lowest s among equals, if that value >=
+ *                          threshold, else -1 (new group). Empty segments and
+ *                          the new tokens' own bucket never win.
+ *   score_dev            : device float [B, n_obj, Smax+1] (bucket S_b = the new
+ *                          tokens themselves, always a mass, never divided;
+ *                          entries beyond it 0)
+ *   assign_dev           : device int32 [B, n_obj], position in the agent's
+ *                          selection list or -1; may be NULL (scores only)
+ * Errors: INVALID_ARG (null, bad spans, per_key/accumulate not 0/1), DEVICE.
+ */
+int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
+                           const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                           float scale, float threshold, float *score_dev, int32_t *assign_dev,
+                           void *stream);
 
 /* ------------------------------------------------------------------------
  * Measurement aid for callers that need the duration of the attention kernel

@@ -152,6 +152,46 @@ def append(k_pool, v_pool, lens, group: int, k_rows, v_rows):
     return k_pool, v_pool, lens
 
 
+def cluster_scores(mass: np.ndarray, seg_lens: Sequence[int], spans: Sequence[int], per_key: bool) -> np.ndarray:
+    """Section 3.3: attention between a newly detected object and an existing
+    group. mass: [N_q, Hq, S+1] of ONE agent; an object o is the new tokens
+    spans[o] .. spans[o+1]-1. Returns [n_obj, S+1]: the mean over the object's
+    tokens and over the heads of the mass on each bucket; with per_key each
+    cached bucket is further divided by its number of keys (mean attention
+    weight per query-key pair)."""
+    mass = np.asarray(mass, dtype=np.float64)
+    S = len(seg_lens)
+    out = np.zeros((len(spans) - 1, mass.shape[2]))
+    for o in range(len(spans) - 1):
+        lo, hi = int(spans[o]), int(spans[o + 1])
+        for s in range(mass.shape[2]):
+            tot = 0.0
+            for i in range(lo, hi):
+                for h in range(mass.shape[1]):
+                    tot += mass[i, h, s]
+            tot /= (hi - lo) * mass.shape[1]
+            if per_key and s < S and seg_lens[s] > 0:
+                tot /= seg_lens[s]
+            out[o, s] = tot
+    return out
+
+
+def cluster_assign(scores: np.ndarray, seg_lens: Sequence[int], threshold: float) -> np.ndarray:
+    """The decision of Section 3.3: the cached segment with the largest score
+    (the lowest index among equals; empty segments and the new tokens' bucket
+    never win) if that score reaches the threshold, else -1: a new group."""
+    S = len(seg_lens)
+    out = np.full(scores.shape[0], -1, dtype=np.int32)
+    for o in range(scores.shape[0]):
+        best, best_s = -np.inf, -1
+        for s in range(S):
+            if seg_lens[s] > 0 and scores[o, s] > best:
+                best, best_s = scores[o, s], s
+        if best_s >= 0 and best >= threshold:
+            out[o] = best_s
+    return out
+
+
 def reduce_mass(mass: np.ndarray) -> np.ndarray:
     """[B,Nq,Hq,S+1] -> [B,S+1]: mass summed over query tokens and heads
     (Section 3.3's attention between new tokens and a group; dividing by

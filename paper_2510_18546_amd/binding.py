@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import sys
 import weakref
 from typing import Optional, Sequence, Tuple
 
@@ -23,7 +24,7 @@ EXPORTS = [
     "kv_pool_create", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
-    "segmented_prefill_attention", "segment_attention_mass", "en_timing_enable",
+    "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign", "en_timing_enable",
     "en_timing_collect", "en_last_error",
 ]
 
@@ -77,6 +78,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.gather_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.segmented_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
+    lib.segment_cluster_assign.argtypes = [vp, vp, vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_float,
+                                           C.c_float, vp, vp, vp]
     lib.en_timing_enable.argtypes = [C.c_int32]
     lib.en_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
@@ -122,6 +125,9 @@ class Pool:
             self.handle = None
 
     def __del__(self):
+        # at interpreter shutdown the HIP runtime may already be gone: the process frees everything
+        if sys is None or sys.is_finalizing():
+            return
         try:
             self.close()
         except Exception:
@@ -155,6 +161,9 @@ class Plan:
             self.handle = None
 
     def __del__(self):
+        # at interpreter shutdown the HIP runtime may already be gone: the process frees everything
+        if sys is None or sys.is_finalizing():
+            return
         try:
             self.close()
         except Exception:
@@ -259,6 +268,19 @@ def segment_attention_mass(pool: Pool, plan: Plan, ws, reduce: int, mass_out, st
     _check(load().segment_attention_mass(pool.handle, plan.handle, ws.data_ptr(), int(reduce),
                                          mass_out.data_ptr(), _stream(stream)))
     return mass_out
+
+
+def segment_cluster_assign(pool: Pool, plan: Plan, ws, spans, score, assign=None, per_key: bool = False,
+                           accumulate: bool = False, scale: float = 1.0, threshold: float = 0.0, stream=None):
+    """spans: host int32 [n_obj+1]; score: float32 tensor [B, n_obj, Smax+1]; assign: int32 tensor
+    [B, n_obj] or None. For host-only tests ws/score may be integers (opaque pointers)."""
+    spans = _i32(spans)
+    ptr = lambda t: C.c_void_p(t.data_ptr() if hasattr(t, "data_ptr") else t)
+    _check(load().segment_cluster_assign(
+        pool.handle, plan.handle, ptr(ws), len(spans) - 1, _ip(spans), int(per_key), int(accumulate),
+        C.c_float(scale), C.c_float(threshold), ptr(score), ptr(assign) if assign is not None else None,
+        _stream(stream) if hasattr(ws, "data_ptr") else C.c_void_p(0)))
+    return score, assign
 
 
 def timing_enable(n: int):

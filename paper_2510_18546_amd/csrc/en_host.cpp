@@ -698,3 +698,40 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
         return hip_fail((hipError_t)e, "segment_attention_mass launch");
     return EN_OK;
 }
+
+extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
+                                      const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                                      float scale, float threshold, float *score_dev, int32_t *assign_dev,
+                                      void *stream)
+{
+    if (!pool || !plan || !ws_dev || !span_ptr_host || !score_dev || n_obj <= 0 ||
+        (per_key != 0 && per_key != 1) || (accumulate != 0 && accumulate != 1))
+        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: null argument, no objects or bad flag");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: plan belongs to another pool");
+    if (n_obj > EN_MAX_OBJECTS)
+        return fail(EN_ERR_UNSUPPORTED, "segment_cluster_assign: %d objects, at most %d per call", n_obj,
+                    EN_MAX_OBJECTS);
+    for (int o = 0; o < n_obj; ++o)
+        if (span_ptr_host[o] < 0 || span_ptr_host[o] >= span_ptr_host[o + 1] || span_ptr_host[o + 1] > plan->Nq)
+            return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: object %d spans [%d, %d) of %d new tokens", o,
+                        span_ptr_host[o], span_ptr_host[o + 1], plan->Nq);
+    int rc;
+    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+        return rc;
+    const EnWsLayout L = en_ws_layout(pool, plan);
+    EnClusterArgs a;
+    a.m = mass_args(pool, plan, static_cast<char *>(ws_dev), L);
+    a.score = score_dev;
+    a.assign = assign_dev;
+    a.n_obj = n_obj;
+    a.per_key = per_key;
+    a.accumulate = accumulate;
+    a.scale = scale;
+    a.threshold = threshold;
+    std::memcpy(a.spans, span_ptr_host, size_t(n_obj + 1) * sizeof(int32_t));
+    const int e = en_launch_cluster(pool, a, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "segment_cluster_assign launch");
+    return EN_OK;
+}

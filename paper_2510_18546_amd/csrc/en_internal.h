@@ -97,6 +97,16 @@ struct EnAppendArgs {
     int row_chunks;                // 16-byte chunks per (token, head) row
 };
 
+constexpr int EN_MAX_OBJECTS = 255;    // per segment_cluster_assign call (spans travel in the kernel arguments)
+struct EnClusterArgs {
+    EnMassArgs m;                  // the scratch of the attention call (m.out unused)
+    float *score;                  // [B, n_obj, Smax+1]
+    int32_t *assign;               // [B, n_obj] or null
+    int n_obj, per_key, accumulate;
+    float scale, threshold;
+    int32_t spans[EN_MAX_OBJECTS + 1];   // object o = new tokens [spans[o], spans[o+1])
+};
+
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
     size_t ml_off, seg_off, red_off, mlfin_off, opart_off, total;
@@ -108,6 +118,7 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
 int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
 int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
 int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
+int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 
 void en_set_error(const char *fmt, ...);

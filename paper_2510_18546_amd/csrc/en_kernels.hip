@@ -1521,6 +1521,66 @@ __global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// cluster: score of every (object, segment) pair and the join / new-group
+// decision of Section 3.3. grid: (n_obj, B), 256 threads: the block walks the
+// buckets; for each it sums the masses of the object's (token, head) pairs.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cluster_kernel(EnClusterArgs a)
+{
+    __shared__ float red[4];
+    const EnMassArgs &m = a.m;
+    const int o = blockIdx.x, b = blockIdx.y;
+    // the spans are read from the argument segment itself (a run-time index into a
+    // by-value argument would make a private copy of the whole array)
+    const int32_t *spans = reinterpret_cast<const int32_t *>(
+        reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + offsetof(EnClusterArgs, spans));
+    const int lo = spans[o], hi = spans[o + 1];
+    const int n_pairs = (hi - lo) * m.Hq;
+    const size_t rows = (size_t)m.B * m.Hq * m.Nq;
+    const int S = m.nseg[b];
+    const int32_t *bnd = m.bnd + (size_t)b * (m.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    float best = EN_NEG_INF;
+    int best_s = -1;
+    float *score = a.score + ((size_t)b * a.n_obj + o) * (m.Smax + 1);
+    for (int s = 0; s <= m.Smax; ++s) {
+        const int len = s <= S ? bnd[s + 1] - bnd[s] : 0;
+        float acc = 0.f;
+        if (len > 0) {
+            int slo, shi;
+            bucket_splits(m.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], slo, shi);
+            for (int idx = threadIdx.x; idx < n_pairs; idx += 256) {
+                const int i = lo + idx / m.Hq, hq = idx % m.Hq;
+                const size_t row = ((size_t)b * m.Hq + hq) * m.Nq + i;
+                float M, L;
+                row_final_ml(m, rows, row, M, L);
+                acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L);
+            }
+        }
+        acc = wave_sum(acc);
+        __syncthreads();
+        if (threadIdx.x % 64 == 0)
+            red[threadIdx.x / 64] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float v = (red[0] + red[1] + red[2] + red[3]) / (float)n_pairs;
+            if (a.per_key && s < S && len > 0)       // the new tokens' own bucket stays a mass
+                v /= (float)len;
+            if (a.accumulate)
+                v += score[s];
+            score[s] = v;
+            if (s < S && len > 0 && v * a.scale > best) {
+                best = v * a.scale;
+                best_s = s;
+            }
+        }
+    }
+    if (threadIdx.x == 0 && a.assign)
+        a.assign[(size_t)b * a.n_obj + o] = (best_s >= 0 && best >= a.threshold) ? best_s : -1;
+}
+
+// ---------------------------------------------------------------------------
 // append: rows [n, Hkv, D] go to tokens first .. first+n-1 of one group's block
 // [Hkv, C, D] in both pool arrays (Section 3.2: new objects' KV is saved at the
 // end of the group's cache). One thread per 16 bytes; grid.y: 0 keys, 1 values.
@@ -1616,6 +1676,14 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
         else
             hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a, m, n_comb);
     }
+    return (int)hipGetLastError();
+}
+
+int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream)
+{
+    (void)pool;
+    const dim3 grid(a.n_obj, a.m.B), blk(256);
+    hipLaunchKernelGGL(cluster_kernel, grid, blk, 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

@@ -203,3 +203,17 @@ def test_binding_closes_plans_before_their_pool():
     p1.close()
     p2.close()
     pool.close()
+
+
+def test_cluster_assign_checks_without_device():
+    lens = np.array([3, 8, 0, 5], np.int32)
+    pool = B.kv_pool_create(None, None, lens, n_q_heads=4, rope_base=1e4, max_ctx=64, dtype=B.EN_BF16,
+                            k_ptr=0x1000, v_ptr=0x2000, shape=(4, 2, 8, 64))
+    plan = B.segment_select(pool, [0, 3], [0, 2], 6)
+    for spans in ([0, 0, 3], [2, 1], [0, 7], [-1, 2]):
+        with pytest.raises(B.EnError) as e:
+            B.segment_cluster_assign(pool, plan, 0x5000, spans, 0x6000, None)
+        assert e.value.code == 1, spans
+    with pytest.raises(B.EnError) as e:
+        B.segment_cluster_assign(pool, plan, 0x5000, list(range(0, 7)) * 50, 0x6000, None)
+    assert e.value.code in (1, 5)

@@ -448,3 +448,65 @@ def test_append_then_attend(step_mod, oracle, dtype):
     with pytest.raises(B.EnError) as e:
         B.kv_pool_append(st.pool, g, st.k_new[0].contiguous(), st.v_new[0].contiguous(), 57)   # 40 + 57 > 96
     assert e.value.code == 4
+
+
+# ---------------------------------------------------------------------------
+# clustering signal and decision (next row of the scope table)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,splits", [(I.BF16, 1), (I.BF16, 3), (I.F32, 2)])
+def test_cluster_scores_and_assignment(step_mod, oracle, dtype, splits):
+    """segment_cluster_assign through the C ABI against the oracle: scores to the mass tolerance;
+    the decision compared where it is decided in the same precision (recomputed from the GPU's own
+    scores, bit for bit) and against the oracle's where the margin exceeds the tolerance."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = small("cluster", 650 + splits, dtype=dtype, planted=True, n_agents=2, n_sel=5, n_new=48,
+                head_dim=128 if dtype == I.BF16 else 64, rope_base=5e5 if dtype == I.BF16 else 1e4,
+                n_q_heads=8 if dtype == I.BF16 else 4)
+    announce(f"segment_cluster_assign dtype={dtype} splits={splits}")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, n_splits=splits)
+    st.gather()
+    st.attention()
+    spans = np.array([0, 5, 6, 30, 48], np.int32)
+    n_obj = len(spans) - 1
+    S1 = st.info.max_segments + 1
+    tol = 1e-2 if dtype == I.BF16 else 1e-5
+    _, ref_mass = oracle_full(oracle, w)
+    for per_key in (False, True):
+        score = torch.full((cfg.n_agents, n_obj, S1), 7.0, dtype=torch.float32, device=st.device)
+        assign = torch.full((cfg.n_agents, n_obj), -7, dtype=torch.int32, device=st.device)
+        thr = 0.25 if not per_key else 0.004
+        B.segment_cluster_assign(st.pool, st.plan, st.ws, spans, score, assign, per_key=per_key, threshold=thr)
+        torch.cuda.synchronize()
+        got, got_a = score.cpu().numpy().astype(np.float64), assign.cpu().numpy()
+        for b in range(cfg.n_agents):
+            lens = [int(w.lens[g]) for g in w.agent_sel(b)]
+            ref = oracle.cluster_scores(ref_mass[b], lens, spans, per_key)
+            assert np.abs(got[b] - ref).max() <= tol * (1.0 if not per_key else 1.0 / min(lens))
+            # the same decision rule applied to the GPU's own fp32 scores
+            mine = oracle.cluster_assign(score[b].cpu().numpy(), lens, np.float32(thr))
+            assert np.array_equal(got_a[b], mine)
+            ref_a = oracle.cluster_assign(ref, lens, thr)
+            for o in range(n_obj):
+                top = np.sort(ref[o, :len(lens)])[::-1]
+                clear = (top[0] - top[1] > 4 * tol) and abs(top[0] - thr) > 4 * tol
+                if not per_key and clear:
+                    assert got_a[b, o] == ref_a[o]
+        if not per_key:
+            # what the objects join is a planted segment (the pool is shared: an agent may have
+            # selected the other agent's planted group as well)
+            for b in range(cfg.n_agents):
+                joined = {int(w.agent_sel(b)[p]) for p in got_a[b]}
+                assert -1 not in got_a[b] and joined <= set(w.meta["planted_group"])
+    # layer averaging: two accumulated calls, decision on half the sum = the single-call decision
+    score2 = torch.zeros((cfg.n_agents, n_obj, S1), dtype=torch.float32, device=st.device)
+    assign2 = torch.empty((cfg.n_agents, n_obj), dtype=torch.int32, device=st.device)
+    B.segment_cluster_assign(st.pool, st.plan, st.ws, spans, score2, None, accumulate=True)
+    B.segment_cluster_assign(st.pool, st.plan, st.ws, spans, score2, assign2, accumulate=True, scale=0.5,
+                             threshold=0.25)
+    score1 = torch.empty_like(score2)
+    assign1 = torch.empty_like(assign2)
+    B.segment_cluster_assign(st.pool, st.plan, st.ws, spans, score1, assign1, threshold=0.25)
+    torch.cuda.synchronize()
+    assert torch.equal(score2, 2 * score1) and torch.equal(assign1, assign2)

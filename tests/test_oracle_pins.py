@@ -284,6 +284,41 @@ def test_append_then_decode_equals_prefill_row(oracle):
         oracle.append(kp, vp, lens, g, w.k_new[0, :3], w.v_new[0, :3])        # 4 + 3 > capacity 6
 
 
+def test_cluster_scores_closed_form_and_decision(oracle):
+    """With all keys zero attention is uniform, so the mass of segment s for new token i is
+    len_s / (L_c + i + 1): the object scores are means of these rationals, and the per-key
+    scores are equal for all segments (the lowest index wins a tie). A planted segment wins
+    the decision; a threshold above every score founds a new group."""
+    cfg = tiny_cfg(81, n_agents=1, n_new=6, len_lo=1)
+    w = I.make_workload(cfg, sel_lists=[[4, 0, 2]])
+    w.k_pool[:] = 0.0
+    w.k_new[:] = 0.0
+    _, mass = run_oracle(oracle, w)
+    lens = [int(w.lens[g]) for g in (4, 0, 2)]
+    Lc = sum(lens)
+    spans = [0, 2, 6]
+    sc = oracle.cluster_scores(mass[0], lens, spans, per_key=False)
+    pk = oracle.cluster_scores(mass[0], lens, spans, per_key=True)
+    for o, (lo, hi) in enumerate(zip(spans[:-1], spans[1:])):
+        for s in range(3):
+            want = np.mean([lens[s] / (Lc + i + 1) for i in range(lo, hi)])
+            assert abs(sc[o, s] - want) < 1e-14
+            assert abs(pk[o, s] - want / lens[s]) < 1e-14
+        assert abs(sc[o].sum() - 1.0) < 1e-13                  # buckets of an object still sum to 1
+    assert oracle.cluster_assign(sc, lens, 0.0).tolist() == [int(np.argmax(lens))] * 2
+    assert oracle.cluster_assign(pk, lens, 0.0).tolist() in ([0, 0], [int(np.argmax(pk[0, :3]))] * 2)
+    assert oracle.cluster_assign(sc, lens, 2.0).tolist() == [-1, -1]
+    assert oracle.cluster_assign(sc, [0, 0, 0], 0.0).tolist() == [-1, -1]   # only empty segments
+    # planted: queries and one segment share a direction -> that segment is chosen
+    cfg2 = tiny_cfg(82, n_agents=1, n_new=4, len_lo=2, planted=True)
+    w2 = I.make_workload(cfg2, sel_lists=[[1, 3, 5]])
+    _, mass2 = run_oracle(oracle, w2)
+    lens2 = [int(w2.lens[g]) for g in (1, 3, 5)]
+    sc2 = oracle.cluster_scores(mass2[0], lens2, [0, 4], per_key=False)
+    planted = [1, 3, 5].index(w2.meta["planted_group"][0])
+    assert oracle.cluster_assign(sc2, lens2, 0.3).tolist() == [planted]
+
+
 def test_dominant_key(oracle):
     """A key with logit about +50 over the rest takes all the mass."""
     cfg = tiny_cfg(61, n_agents=1, n_q_heads=2, n_kv_heads=2, len_lo=2, n_new=1)
