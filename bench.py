@@ -149,6 +149,63 @@ def main():
                          "attention layer of that step, not comparable in absolute terms.",
     }
 
+    if hbm_bound:
+        # Decode-phase reuse as the paper runs it: the context is gathered ONCE, then 40 tokens are decoded
+        # over it, each step appending its key/value and attending (segmented_decode_step); timed eagerly
+        # and as one HIP graph of the 40 steps.
+        n_dec = 40
+        pool_d = B.kv_pool_create(st.k_pool, st.v_pool, w.lens, cfg.n_q_heads, cfg.rope_base,
+                                  cfg.n_sel * cfg.capacity + n_dec)      # same arrays, room for 40 new tokens
+        plan_d = B.segment_select(pool_d, w.sel, w.sel_ptr, n_dec)
+        kc_d, vt_d = B.alloc_context(pool_d, plan_d)
+        gen = torch.Generator(device="cuda:0").manual_seed(5)
+        dt = torch.bfloat16
+        qd = torch.randn((cfg.n_agents, n_dec, cfg.n_q_heads, cfg.head_dim), generator=gen, device="cuda:0").to(dt)
+        kd = torch.randn((cfg.n_agents, n_dec, cfg.n_kv_heads, cfg.head_dim), generator=gen, device="cuda:0").to(dt)
+        vd = torch.randn((cfg.n_agents, n_dec, cfg.n_kv_heads, cfg.head_dim), generator=gen, device="cuda:0").to(dt)
+        qs = [qd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        ks = [kd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        vs = [vd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        od = [torch.empty_like(q) for q in qs]
+        ws_d = torch.empty(max(B.decode_workspace_bytes(pool_d, plan_d, 1), 256), dtype=torch.uint8, device="cuda:0")
+        B.gather_rope(pool_d, plan_d, torch.zeros_like(kd), torch.zeros_like(vd), kc_d, vt_d)
+
+        def decode_all():
+            for i in range(n_dec):
+                B.segmented_decode_step(pool_d, plan_d, i, qs[i], ks[i], vs[i], kc_d, vt_d, od[i], ws_d)
+        decode_all()
+        torch.cuda.synchronize()
+        B.timing_enable(n_dec)
+        d0 = time.perf_counter()
+        decode_all()
+        torch.cuda.synchronize()
+        d1 = time.perf_counter()
+        dec_kern_ms = B.timing_collect(n_dec)
+        B.timing_enable(0)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                decode_all()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        kv_bytes = 2 * cfg.n_kv_heads * cfg.head_dim * 2 * (int(info.total_cached) + cfg.n_agents * n_dec / 2)
+        res["decode_reuse"] = {
+            "tokens_decoded": n_dec, "context_gathered": "once",
+            "us_per_decode_step_eager": (d1 - d0) / n_dec * 1e6,
+            "us_per_decode_step_graph": (g1 - g0) / n_dec * 1e6,
+            "attention_kernel_us": float(np.mean(dec_kern_ms)) * 1e3,
+            "hbm_gbs_graph": kv_bytes / ((g1 - g0) / n_dec) / 1e9,
+        }
+        plan_d.close()
+        pool_d.close()
+
     if not args.no_ceilings:
         # Two measured ceilings of this machine beside the nominal peaks: a large bf16 GEMM of the vendor
         # library on the same kind of data (N(0,1) rounded to bf16), and a plain device copy.

@@ -19,6 +19,7 @@
  *   segment_cluster_assign      that signal per new object, and the join /
  *                               new-group decision
  *   kv_pool_append              new objects' KV saved at the end of their group
+ *   segmented_decode_step       one decode step over the context gathered once
  *
  * Conventions
  *   - Every call returns an en_status; en_last_error() gives the text of the
@@ -220,6 +221,38 @@ size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan);
 int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
                                 const void *kc_dev, const void *vt_dev, void *out_dev,
                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Decode-phase reuse of a gathered context (Section 3.2: the selected KV is
+ * loaded once per planning step, then about 40 tokens are decoded over it).
+ * A plan made with n_new = N_q reserves N_q new-token slots behind the cached
+ * segments; gather_rope fills the context once (the new-token rows it is given
+ * may be placeholders, but must be finite); each call below then handles new
+ * tokens q_first .. q_first+n_rows-1:
+ *   1. their keys (rotated at positions L_c + q_first + t) and values are
+ *      written into the context buffers,
+ *   2. their queries attend over every key before and including them (the
+ *      same arithmetic and kernels as segmented_prefill_attention; the result
+ *      equals rows q_first .. of one prefill over all tokens up to them),
+ *   3. if mass_out_dev is not NULL, their per-segment masses
+ *      [B, n_rows, Hq, Smax+1] are written as by segment_attention_mass with
+ *      reduce = 0 (bucket S_b = all new tokens visible to the row).
+ * Steps must come in order of q_first on one stream (a step reads the rows
+ * written by the earlier ones). All kernels are enqueued on `stream`; nothing
+ * is allocated, so a sequence of steps can be captured into a HIP graph.
+ *   q_dev                   : device, [B, n_rows, Hq, D], unrotated
+ *   k_rows_dev, v_rows_dev  : device, [B, n_rows, Hkv, D], keys unrotated
+ *   kc_dev, vt_dev          : the context buffers filled by gather_rope (updated)
+ *   out_dev                 : device, [B, n_rows, Hq, D]
+ *   ws_dev, ws_bytes        : scratch of at least en_decode_workspace_bytes(pool,
+ *                             plan, n_rows) (the KV split count of a step is chosen
+ *                             for n_rows, not for the plan's N_q)
+ * Errors: INVALID_ARG, OUT_OF_RANGE (q_first + n_rows > N_q), CAPACITY, DEVICE.
+ */
+size_t en_decode_workspace_bytes(const en_pool *pool, const en_plan *plan, int32_t n_rows);
+int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                          const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                          void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                          void *ws_dev, size_t ws_bytes, void *stream);
 
 /* Per-segment attention mass (Section 3.3: the attention between newly
  * detected objects and an existing group) from the scratch left by the

@@ -24,7 +24,8 @@ EXPORTS = [
     "kv_pool_create", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
-    "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign", "en_timing_enable",
+    "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
+    "en_decode_workspace_bytes", "segmented_decode_step", "en_timing_enable",
     "en_timing_collect", "en_last_error",
 ]
 
@@ -80,11 +81,15 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
     lib.segment_cluster_assign.argtypes = [vp, vp, vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_float,
                                            C.c_float, vp, vp, vp]
+    lib.en_decode_workspace_bytes.argtypes = [vp, vp, C.c_int32]
+    lib.en_decode_workspace_bytes.restype = C.c_size_t
+    lib.segmented_decode_step.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                          C.c_size_t, vp]
     lib.en_timing_enable.argtypes = [C.c_int32]
     lib.en_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("en_context_bytes", "en_workspace_bytes", "en_last_error"):
+        if name not in ("en_context_bytes", "en_workspace_bytes", "en_decode_workspace_bytes", "en_last_error"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -281,6 +286,22 @@ def segment_cluster_assign(pool: Pool, plan: Plan, ws, spans, score, assign=None
         C.c_float(scale), C.c_float(threshold), ptr(score), ptr(assign) if assign is not None else None,
         _stream(stream) if hasattr(ws, "data_ptr") else C.c_void_p(0)))
     return score, assign
+
+
+def decode_workspace_bytes(pool: Pool, plan: Plan, n_rows: int) -> int:
+    return int(load().en_decode_workspace_bytes(pool.handle, plan.handle, int(n_rows)))
+
+
+def segmented_decode_step(pool: Pool, plan: Plan, q_first: int, q, k_rows, v_rows, kc, vt, out, ws,
+                          mass_out=None, stream=None):
+    """q [B,n,Hq,D], k_rows/v_rows [B,n,Hkv,D], out [B,n,Hq,D]: contiguous torch tensors of the step."""
+    n = int(q.shape[1])
+    _check(load().segmented_decode_step(
+        pool.handle, plan.handle, int(q_first), n, q.data_ptr(), k_rows.data_ptr(), v_rows.data_ptr(),
+        kc.data_ptr(), vt.data_ptr(), out.data_ptr(), mass_out.data_ptr() if mass_out is not None else None,
+        ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream(stream)))
+    return out
 
 
 def timing_enable(n: int):

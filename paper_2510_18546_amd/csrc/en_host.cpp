@@ -474,19 +474,25 @@ extern "C" size_t en_context_bytes(const en_pool *pool, const en_plan *plan)
            elem_size(pool->d.dtype);
 }
 
-EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *pl)
+// Scratch layout for n_rows query rows per agent and n_splits KV splits.
+EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *pl, int n_rows, int n_splits)
 {
     EnWsLayout L;
-    const size_t rows = size_t(pl->B) * pool->d.n_q_heads * pl->Nq;
+    const size_t rows = size_t(pl->B) * pool->d.n_q_heads * n_rows;
     L.ml_off = 0;
-    L.seg_off = align256(L.ml_off + size_t(pl->n_splits) * rows * 2 * sizeof(float));
-    L.red_off = align256(L.seg_off + size_t(pl->n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
+    L.seg_off = align256(L.ml_off + size_t(n_splits) * rows * 2 * sizeof(float));
+    L.red_off = align256(L.seg_off + size_t(n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
     L.mlfin_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
-    L.opart_off = align256(L.mlfin_off + (pl->n_splits > 1 ? rows * 2 * sizeof(float) : 0));
+    L.opart_off = align256(L.mlfin_off + (n_splits > 1 ? rows * 2 * sizeof(float) : 0));
     L.total = L.opart_off;
-    if (pl->n_splits > 1)
-        L.total = align256(L.opart_off + size_t(pl->n_splits) * rows * pool->d.head_dim * elem_size(pool->d.dtype));
+    if (n_splits > 1)
+        L.total = align256(L.opart_off + size_t(n_splits) * rows * pool->d.head_dim * elem_size(pool->d.dtype));
     return L;
+}
+
+EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *pl)
+{
+    return en_ws_layout_for(pool, pl, pl->Nq, pl->n_splits);
 }
 
 extern "C" size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan)
@@ -609,27 +615,23 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
     a.Nq = plan->Nq;
     a.Smax = plan->Smax;
     a.n_splits = plan->n_splits;
+    a.q_first = 0;
     return a;
 }
 
-extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
-                                           const void *kc_dev, const void *vt_dev, void *out_dev,
-                                           void *ws_dev, size_t ws_bytes, void *stream)
+// Attention of n_rows query rows per agent (new tokens q_first .. q_first+n_rows-1 of the plan)
+// with n_splits KV splits; the scratch is laid out for exactly these.
+static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const void *kc_dev,
+                         const void *vt_dev, void *out_dev, void *ws_dev, size_t ws_bytes, void *stream,
+                         int q_first, int n_rows, int n_splits, const char *who)
 {
-    if (!pool || !plan || !q_dev || !kc_dev || !vt_dev || !out_dev)
-        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: null argument");
-    if (plan->pool != pool)
-        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: plan belongs to another pool");
-    const EnWsLayout L = en_ws_layout(pool, plan);
-    if (!ws_dev && plan->n_splits > 1)
-        return fail(EN_ERR_INVALID_ARG,
-                    "segmented_prefill_attention: workspace required when the plan has %d splits",
-                    plan->n_splits);
+    const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
+    if (!ws_dev && n_splits > 1)
+        return fail(EN_ERR_INVALID_ARG, "%s: workspace required with %d splits", who, n_splits);
     if (ws_dev && ws_bytes < L.total)
-        return fail(EN_ERR_CAPACITY, "segmented_prefill_attention: workspace %zu < %zu bytes", ws_bytes,
-                    L.total);
+        return fail(EN_ERR_CAPACITY, "%s: workspace %zu < %zu bytes", who, ws_bytes, L.total);
     if (ws_dev && (reinterpret_cast<uintptr_t>(ws_dev) & 15))
-        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: workspace must be 16-byte aligned");
+        return fail(EN_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", who);
     int rc;
     if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
         return rc;
@@ -646,21 +648,22 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     char *ws = static_cast<char *>(ws_dev);
     a.ws_ml = ws ? reinterpret_cast<float *>(ws + L.ml_off) : nullptr;
     a.ws_seg = ws ? reinterpret_cast<float *>(ws + L.seg_off) : nullptr;
-    a.ws_opart = (ws && plan->n_splits > 1) ? static_cast<void *>(ws + L.opart_off) : nullptr;
-    a.ws_mlfin = (ws && plan->n_splits > 1) ? reinterpret_cast<float *>(ws + L.mlfin_off) : nullptr;
+    a.ws_opart = (ws && n_splits > 1) ? static_cast<void *>(ws + L.opart_off) : nullptr;
+    a.ws_mlfin = (ws && n_splits > 1) ? reinterpret_cast<float *>(ws + L.mlfin_off) : nullptr;
     a.B = plan->B;
     a.Hq = pool->d.n_q_heads;
     a.Hkv = pool->d.n_kv_heads;
-    a.Nq = plan->Nq;
+    a.Nq = n_rows;
     a.Smax = plan->Smax;
     a.T = plan->ctx_stride;
-    a.n_splits = plan->n_splits;
-    const int nqb = (plan->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
+    a.q_first = q_first;
+    a.n_splits = n_splits;
+    const int nqb = (n_rows + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
-    a.decode = (pool->d.dtype == EN_BF16 && pool->r * plan->Nq <= EN_ROWS_PER_WAVE) ? 1 : 0;
+    a.decode = (pool->d.dtype == EN_BF16 && pool->r * n_rows <= EN_ROWS_PER_WAVE) ? 1 : 0;
     if (a.decode)
         a.n_ptiles = 1;
-    a.total_wgs = plan->B * pool->d.n_kv_heads * plan->n_splits * a.n_ptiles;
+    a.total_wgs = plan->B * pool->d.n_kv_heads * n_splits * a.n_ptiles;
     a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
     const bool timed = g_ev_used < (int)g_ev_start.size();
     if (timed)
@@ -669,12 +672,100 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
     if (timed)
         (void)hipEventRecord(g_ev_stop[g_ev_used++], (hipStream_t)stream);
     if (e != 0)
-        return hip_fail((hipError_t)e, "segmented_prefill_attention launch");
-    if (plan->n_splits > 1) {
+        return hip_fail((hipError_t)e, who);
+    if (n_splits > 1) {
         // the same launch also leaves the per-head partial sums of the segment masses
-        e = en_launch_combine(pool, a, mass_args(pool, plan, ws, L), stream);
+        EnMassArgs m = mass_args(pool, plan, ws, L);
+        m.Nq = n_rows;
+        m.n_splits = n_splits;
+        m.q_first = q_first;
+        e = en_launch_combine(pool, a, m, stream);
         if (e != 0)
             return hip_fail((hipError_t)e, "split combine launch");
+    }
+    return EN_OK;
+}
+
+extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
+                                           const void *kc_dev, const void *vt_dev, void *out_dev,
+                                           void *ws_dev, size_t ws_bytes, void *stream)
+{
+    if (!pool || !plan || !q_dev || !kc_dev || !vt_dev || !out_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: plan belongs to another pool");
+    return run_attention(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream, 0, plan->Nq,
+                         plan->n_splits, "segmented_prefill_attention");
+}
+
+// KV splits for a step of n_rows query rows (same rule as for a whole plan).
+static int step_splits(const en_pool *pool, const en_plan *plan, int n_rows)
+{
+    en_plan tmp;
+    tmp.pool = pool;
+    tmp.B = plan->B;
+    tmp.Nq = n_rows;
+    tmp.max_ctx_len = plan->max_ctx_len;
+    return choose_splits(pool, &tmp);
+}
+
+extern "C" size_t en_decode_workspace_bytes(const en_pool *pool, const en_plan *plan, int32_t n_rows)
+{
+    if (!pool || !plan || n_rows <= 0)
+        return 0;
+    return en_ws_layout_for(pool, plan, n_rows, step_splits(pool, plan, n_rows)).total;
+}
+
+extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                     const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                                     void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                                     void *ws_dev, size_t ws_bytes, void *stream)
+{
+    if (!pool || !plan || !q_dev || !k_rows_dev || !v_rows_dev || !kc_dev || !vt_dev || !out_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step: plan belongs to another pool");
+    if (q_first < 0 || n_rows <= 0 || q_first + n_rows > plan->Nq)
+        return fail(EN_ERR_OUT_OF_RANGE, "segmented_decode_step: new tokens [%d, %d) outside the plan's %d",
+                    q_first, q_first + n_rows, plan->Nq);
+    if (mass_out_dev && !ws_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step: masses need the workspace");
+    int rc;
+    if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
+        return rc;
+    // 1. the step's keys (rotated at their positions) and values join the gathered context
+    EnCtxAppendArgs c;
+    c.k_rows = k_rows_dev;
+    c.v_rows = v_rows_dev;
+    c.kc = kc_dev;
+    c.vt = vt_dev;
+    c.cos_tab = pool->d_cos;
+    c.sin_tab = pool->d_sin;
+    c.hdr = d_hdr(plan);
+    c.B = plan->B;
+    c.Hkv = pool->d.n_kv_heads;
+    c.n = n_rows;
+    c.T = plan->ctx_stride;
+    c.q_first = q_first;
+    int e = en_launch_ctx_append(pool, c, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "segmented_decode_step context append");
+    // 2. attention of the step's rows over everything before and including them
+    const int n_splits = step_splits(pool, plan, n_rows);
+    if ((rc = run_attention(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream, q_first, n_rows,
+                            n_splits, "segmented_decode_step")) != EN_OK)
+        return rc;
+    // 3. per-row masses, if wanted
+    if (mass_out_dev) {
+        const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
+        EnMassArgs m = mass_args(pool, plan, static_cast<char *>(ws_dev), L);
+        m.Nq = n_rows;
+        m.n_splits = n_splits;
+        m.q_first = q_first;
+        m.out = mass_out_dev;
+        e = en_launch_mass(pool, m, 0, stream);
+        if (e != 0)
+            return hip_fail((hipError_t)e, "segmented_decode_step mass");
     }
     return EN_OK;
 }

@@ -77,6 +77,8 @@ struct EnAttnArgs {
     void *ws_opart;    // [n_splits, B*Hq*Nq, D] per-split softmax outputs (pool dtype)
     float *ws_mlfin;   // [B*Hq*Nq, 2] merged (reference, sum), written by the combine kernel
     int B, Hq, Hkv, Nq, Smax, T;
+    int q_first;       // the Nq query rows are new tokens q_first .. q_first+Nq-1 of the plan: every key
+                       // before L_c + q_first is visible to all of them (0 for a whole prefill)
     int n_splits, n_ptiles, total_wgs;
     int decode;        // 1: all r*Nq query rows of a KV head fit one wave (attn_decode kernel)
     float scale_log2e;
@@ -88,6 +90,7 @@ struct EnMassArgs {
     const int32_t *nseg, *bnd;
     float *out;
     int B, Hq, Nq, Smax, n_splits;
+    int q_first;            // as in EnAttnArgs
 };
 
 struct EnAppendArgs {
@@ -107,11 +110,20 @@ struct EnClusterArgs {
     int32_t spans[EN_MAX_OBJECTS + 1];   // object o = new tokens [spans[o], spans[o+1])
 };
 
+struct EnCtxAppendArgs {
+    const void *k_rows, *v_rows;   // [B, n, Hkv, D], keys unrotated
+    void *kc, *vt;                 // the context buffers
+    const float *cos_tab, *sin_tab;
+    const int32_t *hdr;            // per agent {S, L_c, ...}
+    int B, Hkv, n, T, q_first;
+};
+
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
     size_t ml_off, seg_off, red_off, mlfin_off, opart_off, total;
 };
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
+EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *plan, int n_rows, int n_splits);
 
 // Kernel launchers (en_kernels.hip). Return hipError_t as int.
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream);
@@ -119,6 +131,7 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
 int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
 int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
 int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream);
+int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 
 void en_set_error(const char *fmt, ...);

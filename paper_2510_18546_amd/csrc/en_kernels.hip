@@ -388,8 +388,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         my_bnd = bnd_g[lane];
     const en_table_ptr hdr = as_table(a.hdr + 4 * (size_t)b);
     const int S = hdr[0];
-    const int Lc = hdr[1];
-    const int Ltot = hdr[2];
+    // the rows are new tokens q_first .. q_first+Nq-1: everything before them counts as context
+    const int Lc = hdr[1] + a.q_first;
+    const int Ltot = Lc + a.Nq;
     const en_table_ptr bnd = as_table(bnd_g);
     auto bound_at = [&](int s) {          // s is wave-uniform
         return bnd_in_lanes ? __builtin_amdgcn_readlane(my_bnd, s) : bnd[s];
@@ -944,8 +945,8 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 
     const int S = a.nseg[b];
     const en_table_ptr bnd = as_table(a.bnd + (size_t)b * (a.Smax + 2));
-    const int Lc = bnd[S];
-    const int Ltot = bnd[S + 1];
+    const int Lc = bnd[S] + a.q_first;       // rows are new tokens q_first .. q_first+Nq-1
+    const int Ltot = Lc + a.Nq;
     const int ntiles64 = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     // split boundaries are whole 64-key tiles, as everywhere else
     const int split_key_begin = (int)((long)sp * ntiles64 / a.n_splits) * EN_KEY_TILE;
@@ -1241,8 +1242,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
     const int kvh = hq / r;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Lc = bnd[S];
-    const int Ltot = bnd[S + 1];
+    const int Lc = bnd[S] + a.q_first;       // rows are new tokens q_first .. q_first+Nq-1
+    const int Ltot = Lc + a.Nq;
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     const int kbeg = (int)((long)sp * ntiles / a.n_splits) * EN_KEY_TILE;
     const int kend_split = min((int)((long)(sp + 1) * ntiles / a.n_splits) * EN_KEY_TILE, Ltot);
@@ -1339,6 +1340,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
 // output row. grid: ceil(rows * D / V / 256), V = elements in 16 bytes.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red);
+__device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_t pair);
+constexpr int EN_MASS_FEW_ROWS = 64;      // below this many query rows per head the partial sums go thread-wise
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m, int n_comb)
@@ -1347,6 +1350,10 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
     if ((int)blockIdx.x >= n_comb) {
         __shared__ float red[4];
         int t = blockIdx.x - n_comb;
+        if (m.Nq < EN_MASS_FEW_ROWS) {
+            mass_partial_few_rows(m, (size_t)t * 256 + threadIdx.x);
+            return;
+        }
         const int s = t % (m.Smax + 1);
         t /= (m.Smax + 1);
         mass_partial_block(m, s, t % m.Hq, t / m.Hq, red);
@@ -1443,7 +1450,7 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S + 1];
+    const int Ltot = bnd[S] + a.q_first + a.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float M, L;
     row_final_ml(a, rows, row, M, L);
@@ -1472,7 +1479,7 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, i
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S + 1];
+    const int Ltot = bnd[S] + a.q_first + a.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float acc = 0.f;
     if (s <= S && bnd[s + 1] > bnd[s]) {
@@ -1499,10 +1506,48 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, i
         a.ws_red[((size_t)b * (a.Smax + 1) + s) * a.Hq + hq] = red[0] + red[1] + red[2] + red[3];
 }
 
+// The same for few query rows per head (decode steps): one THREAD per (agent, bucket, head) walks
+// the rows, so that a step of one token does not launch a workgroup per (bucket, head).
+__device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_t pair)
+{
+    if (pair >= (size_t)a.B * (a.Smax + 1) * a.Hq)
+        return;
+    const int hq = (int)(pair % a.Hq);
+    const int s = (int)((pair / a.Hq) % (a.Smax + 1));
+    const int b = (int)(pair / ((size_t)a.Hq * (a.Smax + 1)));
+    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S] + a.q_first + a.Nq;
+    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    float acc = 0.f;
+    if (s <= S && bnd[s + 1] > bnd[s]) {
+        int lo, hi;
+        bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
+        for (int i = 0; i < a.Nq; ++i) {
+            const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+            float M = EN_NEG_INF, L = 0.f;
+            for (int sp = 0; sp < a.n_splits; ++sp)
+                M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
+            for (int sp = 0; sp < a.n_splits; ++sp) {
+                const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
+                if (ml[0] != EN_NEG_INF)
+                    L += ml[1] * exp2f(ml[0] - M);
+            }
+            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+        }
+    }
+    a.ws_red[pair] = acc;              // [b][s][hq]
+}
+
+// grid: (Smax+1, Hq, B), or ceil(B (Smax+1) Hq / 256) blocks when Nq < EN_MASS_FEW_ROWS
 __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
 {
     __shared__ float red[4];
-    mass_partial_block(a, blockIdx.x, blockIdx.y, blockIdx.z, red);
+    if (a.Nq < EN_MASS_FEW_ROWS)
+        mass_partial_few_rows(a, (size_t)blockIdx.x * 256 + threadIdx.x);
+    else
+        mass_partial_block(a, blockIdx.x, blockIdx.y, blockIdx.z, red);
 }
 
 // reduce = 1, stage 2. One wave per (agent, bucket) adds up the heads.
@@ -1518,6 +1563,38 @@ __global__ __launch_bounds__(256) void mass_final_kernel(EnMassArgs a)
     acc = wave_sum(acc);
     if (threadIdx.x % 64 == 0)
         a.out[pair] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// ctx_append: the keys and values of a decode step's new tokens join the
+// gathered context at positions L_c + q_first + t (keys rotated there; values
+// in the context's layout). grid: (n, Hkv, B), D/2 threads: thread c owns the
+// rotary pair (c, c + D/2).
+// ---------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(D / 2) void ctx_append_kernel(EnCtxAppendArgs a)
+{
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int c = threadIdx.x;
+    const int pos = a.hdr[4 * b + 1] + a.q_first + t;
+    const T *kr = (const T *)a.k_rows + (((size_t)b * a.n + t) * a.Hkv + h) * D;
+    const T *vr = (const T *)a.v_rows + (((size_t)b * a.n + t) * a.Hkv + h) * D;
+    const float cs = a.cos_tab[(size_t)pos * (D / 2) + c], sn = a.sin_tab[(size_t)pos * (D / 2) + c];
+    const float x1 = (float)kr[c], x2 = (float)kr[c + D / 2];
+    T *kd = (T *)a.kc + (((size_t)b * a.Hkv + h) * a.T + pos) * D;
+    kd[c] = (T)(x1 * cs - x2 * sn);
+    kd[c + D / 2] = (T)(x2 * cs + x1 * sn);
+    if constexpr (sizeof(T) == 4) {
+        T *vd = (T *)a.vt + (((size_t)b * a.Hkv + h) * a.T + pos) * D;
+        vd[c] = vr[c];
+        vd[c + D / 2] = vr[c + D / 2];
+    } else {
+        // transposed layout [D][T], token j in column j with bits 2 and 3 exchanged
+        const int col = (pos & ~0xC) | ((pos & 4) << 1) | ((pos & 8) >> 1);
+        T *vd = (T *)a.vt + ((size_t)b * a.Hkv + h) * (size_t)D * a.T + col;
+        vd[(size_t)c * a.T] = vr[c];
+        vd[(size_t)(c + D / 2) * a.T] = vr[c + D / 2];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1539,7 +1616,7 @@ __global__ __launch_bounds__(256) void cluster_kernel(EnClusterArgs a)
     const size_t rows = (size_t)m.B * m.Hq * m.Nq;
     const int S = m.nseg[b];
     const int32_t *bnd = m.bnd + (size_t)b * (m.Smax + 2);
-    const int Ltot = bnd[S + 1];
+    const int Ltot = bnd[S] + m.q_first + m.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float best = EN_NEG_INF;
     int best_s = -1;
@@ -1663,7 +1740,8 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     const int vec = pool->d.dtype == EN_F32 ? 4 : 8;      // elements in 16 bytes
     const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec);
     const int n_comb = (int)((n + 255) / 256);
-    const int n_part = (m.Smax + 1) * m.Hq * m.B;
+    const int n_part = m.Nq < EN_MASS_FEW_ROWS ? ((m.Smax + 1) * m.Hq * m.B + 255) / 256
+                                               : (m.Smax + 1) * m.Hq * m.B;
     const dim3 grid((unsigned)(n_comb + n_part)), blk(256);
     if (pool->d.dtype == EN_F32) {
         if (D == 64)
@@ -1675,6 +1753,25 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
             hipLaunchKernelGGL((combine_kernel<bf16_t, 64>), grid, blk, 0, st, a, m, n_comb);
         else
             hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a, m, n_comb);
+    }
+    return (int)hipGetLastError();
+}
+
+int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *stream)
+{
+    const int D = pool->d.head_dim;
+    const dim3 grid(a.n, a.Hkv, a.B), blk(D / 2);
+    hipStream_t st = (hipStream_t)stream;
+    if (pool->d.dtype == EN_F32) {
+        if (D == 64)
+            hipLaunchKernelGGL((ctx_append_kernel<float, 64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((ctx_append_kernel<float, 128>), grid, blk, 0, st, a);
+    } else {
+        if (D == 64)
+            hipLaunchKernelGGL((ctx_append_kernel<bf16_t, 64>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((ctx_append_kernel<bf16_t, 128>), grid, blk, 0, st, a);
     }
     return (int)hipGetLastError();
 }
@@ -1705,7 +1802,9 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
     } else {
         // with several splits stage 1 has already run in the combine launch
-        const dim3 grid(a.Smax + 1, a.Hq, a.B), blk(256);
+        const dim3 blk(256);
+        const dim3 grid = a.Nq < EN_MASS_FEW_ROWS ? dim3(((a.Smax + 1) * a.Hq * a.B + 255) / 256)
+                                                  : dim3(a.Smax + 1, a.Hq, a.B);
         if (a.n_splits == 1)
             hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
         const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);

@@ -510,3 +510,98 @@ def test_cluster_scores_and_assignment(step_mod, oracle, dtype, splits):
     B.segment_cluster_assign(st.pool, st.plan, st.ws, spans, score1, assign1, threshold=0.25)
     torch.cuda.synchronize()
     assert torch.equal(score2, 2 * score1) and torch.equal(assign1, assign2)
+
+
+# ---------------------------------------------------------------------------
+# decode steps over a context gathered once (next row of the scope table)
+# ---------------------------------------------------------------------------
+def _decode_case(step_mod, dtype, seed, n_new=11):
+    cfg = small("decode-loop", seed, dtype=dtype, n_agents=2, n_sel=5, n_new=n_new, len_lo=10,
+                n_q_heads=8, n_kv_heads=2, head_dim=128 if dtype == I.BF16 else 64,
+                rope_base=5e5 if dtype == I.BF16 else 1e4)
+    w = I.make_workload(cfg)
+    return cfg, w, step_mod.PlanningStep(w)
+
+
+@pytest.mark.parametrize("dtype", [I.BF16, I.F32])
+def test_decode_steps_equal_prefill_rows(step_mod, oracle, dtype):
+    """The context is gathered once with placeholder rows for the new tokens; steps of 1, 1, 3, 1 and 5
+    tokens then append their keys/values and attend. Outputs and masses of every step equal the rows
+    of one prefill over all tokens (the oracle); the context ends up as a plain gather makes it."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg, w, st = _decode_case(step_mod, dtype, 660)
+    announce(f"segmented_decode_step dtype={dtype}")
+    ref_out, ref_mass = oracle_full(oracle, w)
+    B.gather_rope(st.pool, st.plan, torch.zeros_like(st.k_new), torch.zeros_like(st.v_new), st.kc, st.vt)
+    S1 = st.info.max_segments + 1
+    q0 = 0
+    for n in (1, 1, 3, 1, 5):
+        q = st.q[:, q0:q0 + n].contiguous()
+        k = st.k_new[:, q0:q0 + n].contiguous()
+        v = st.v_new[:, q0:q0 + n].contiguous()
+        out = torch.empty_like(q)
+        mass = torch.empty((cfg.n_agents, n, cfg.n_q_heads, S1), dtype=torch.float32, device=st.device)
+        ws = torch.empty(max(B.decode_workspace_bytes(st.pool, st.plan, n), 256), dtype=torch.uint8,
+                         device=st.device)
+        B.segmented_decode_step(st.pool, st.plan, q0, q, k, v, st.kc, st.vt, out, ws, mass_out=mass)
+        torch.cuda.synchronize()
+        got = step_mod._to_host(out).astype(np.float64)
+        check_out(cfg, got, ref_out[:, q0:q0 + n])
+        check_mass(cfg, mass.cpu().numpy().astype(np.float64), ref_mass[:, q0:q0 + n])
+        q0 += n
+    # the context now holds what a plain gather with the real rows writes
+    kc_steps, vt_steps = st.kc.clone(), st.vt.clone()
+    st.gather()
+    torch.cuda.synchronize()
+    assert torch.equal(vt_steps, st.vt)                          # values are copies: bit for bit
+    if dtype == I.F32:
+        a, b_ = kc_steps.view(torch.float32), st.kc.view(torch.float32)
+    else:
+        a, b_ = kc_steps.view(torch.bfloat16).float(), st.kc.view(torch.bfloat16).float()
+    assert (a - b_).abs().max().item() <= (2e-6 if dtype == I.F32 else 4e-2)   # rotated keys: rounding order only
+    with pytest.raises(B.EnError) as e:
+        B.segmented_decode_step(st.pool, st.plan, 9, st.q[:, :3].contiguous(), st.k_new[:, :3].contiguous(),
+                                st.v_new[:, :3].contiguous(), st.kc, st.vt, torch.empty_like(st.q[:, :3]), None)
+    assert e.value.code == 2
+
+
+def test_decode_steps_in_a_graph(step_mod, oracle):
+    """Eight one-token steps captured into one HIP graph (the steps allocate nothing and only launch
+    kernels); three replays, each after an eager re-gather, reproduce the eager results bit for bit."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg, w, st = _decode_case(step_mod, I.BF16, 670, n_new=8)
+    announce("segmented_decode_step in a graph")
+    zk, zv = torch.zeros_like(st.k_new), torch.zeros_like(st.v_new)
+    qs = [st.q[:, i:i + 1].contiguous() for i in range(cfg.n_new)]
+    ks = [st.k_new[:, i:i + 1].contiguous() for i in range(cfg.n_new)]
+    vs = [st.v_new[:, i:i + 1].contiguous() for i in range(cfg.n_new)]
+    outs = [torch.empty_like(q) for q in qs]
+    ws = torch.empty(max(B.decode_workspace_bytes(st.pool, st.plan, 1), 256), dtype=torch.uint8, device=st.device)
+
+    def steps():
+        for i in range(cfg.n_new):
+            B.segmented_decode_step(st.pool, st.plan, i, qs[i], ks[i], vs[i], st.kc, st.vt, outs[i], ws)
+    B.gather_rope(st.pool, st.plan, zk, zv, st.kc, st.vt)
+    steps()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    ref_out, _ = oracle_full(oracle, w)
+    check_out(cfg, np.concatenate([step_mod._to_host(o) for o in eager], 1).astype(np.float64), ref_out)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            steps()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for o in outs:
+            o.fill_(7.0)
+        B.gather_rope(st.pool, st.plan, zk, zv, st.kc, st.vt)     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e)
