@@ -20,6 +20,8 @@
  *                               new-group decision
  *   kv_pool_append              new objects' KV saved at the end of their group
  *   segmented_decode_step       one decode step over the context gathered once
+ *   kv_tier_*                   which groups are in device memory, loads of the
+ *                               others from a host store, cache hit rate
  *
  * Conventions
  *   - Every call returns an en_status; en_last_error() gives the text of the
@@ -301,6 +303,88 @@ int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n
                            const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
                            float scale, float threshold, float *score_dev, int32_t *assign_dev,
                            void *stream);
+
+/* ------------------------------------------------------------------------
+ * Residency tier (Section 3.2: the KV cache of all groups is kept in a large,
+ * slow store and only the selected groups are loaded into device memory, once
+ * per planning step; a group selected in consecutive steps is already there.
+ * Section 4, "memory caching distribution and cache hit rate": the share of the
+ * selected groups found in device memory, as a function of the device budget).
+ *
+ * The tier owns a store of n_groups_total blocks in pinned host memory and
+ * manages desc->n_groups device slots, each one block [Hkv, C, D] of K and of
+ * V, in the caller's arrays k_dev / v_dev ([slots, Hkv, C, D], as for
+ * kv_pool_create). kv_tier_pool() is an en_pool over those arrays whose group
+ * ids are SLOT numbers: pass the slots that kv_tier_fetch returns to
+ * segment_select / gather_rope. A device budget in bytes buys
+ * budget / kv_tier_slot_bytes(desc) slots.
+ * With k_dev = v_dev = NULL the tier only keeps the books (same decisions and
+ * counters, no memory, no HIP call): for sizing a budget from a trace.
+ *
+ * Policy. A fetch first marks every asked-for group that is resident as used
+ * now; then, in list order, each missing group takes the slot used least
+ * recently (never-used slots first, lowest slot number among equals) and is
+ * loaded. A group that was resident because of an earlier fetch counts as a
+ * hit, one brought in by kv_tier_prefetch as prefetched, the others as misses:
+ * hit rate = hits / requested.
+ *
+ * Ordering. Loads run on a stream of the tier's own. kv_tier_fetch makes
+ * `stream` wait for the loads it needs, so work enqueued on `stream` after the
+ * call sees the data. Before a slot is overwritten, the kernels that read it
+ * must be done: all such reads are assumed to be enqueued on `stream` (the
+ * same one in every call). kv_tier_fence(stream) says "every read of the slots
+ * handed out so far is already enqueued on `stream`" (call it after
+ * gather_rope: the attention kernels read the gathered context, not the
+ * slots); loads then wait only for that point and run beside the kernels
+ * enqueued after it. Without a fence a fetch that has to load waits for
+ * everything enqueued on `stream` so far.
+ * kv_tier_prefetch loads groups that a later fetch is expected to ask for
+ * (e.g. the same selection for the next layer) into slots whose readers the
+ * last fence covers, least recently used first, and never waits for anything
+ * else; it loads fewer groups than asked if such slots run out.
+ *
+ *   kv_tier_put   : k_host, v_host host [Hkv, len, D] in the pool dtype, keys
+ *                   unrotated; copied into the store before the call returns
+ *                   (waits for loads in flight). A device copy of the group
+ *                   becomes stale and is dropped.
+ *   kv_tier_select_scored : Eq. (1) as in segment_select_scored, over the
+ *                   store's groups and lengths (groups never put are not
+ *                   candidates); groups_out_host int32 [n_groups_total].
+ *   kv_tier_fetch : groups_host int32 [n], distinct, n <= slots;
+ *                   slots_out_host int32 [n] receives the slot of each.
+ *   kv_tier_residency : slot_of_group_out_host int32 [n_groups_total], the
+ *                   slot each group occupies or -1.
+ * One tier is used by one thread at a time.
+ * Errors: INVALID_ARG, OUT_OF_RANGE (group outside the store or never put,
+ *         len > C), DUPLICATE, CAPACITY (more groups than slots), UNSUPPORTED
+ *         (as kv_pool_create), DEVICE.
+ */
+typedef struct en_tier en_tier;
+typedef struct en_tier_stats {
+    int64_t fetches;      /* kv_tier_fetch calls                               */
+    int64_t requested;    /* groups they asked for                             */
+    int64_t hits;         /* ... resident from an earlier fetch                */
+    int64_t prefetched;   /* ... resident because of a prefetch                */
+    int64_t misses;       /* ... loaded by the fetch itself                    */
+    int64_t loads;        /* blocks copied, fetch and prefetch together        */
+    int64_t bytes_loaded; /* their bytes (len tokens of K and V each)          */
+    int64_t evictions;    /* loads that displaced a resident group             */
+} en_tier_stats;
+
+int64_t kv_tier_slot_bytes(const en_pool_desc *desc);
+int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev, void *v_dev,
+                   en_tier **out);
+en_pool *kv_tier_pool(en_tier *tier);
+int kv_tier_put(en_tier *tier, int32_t group, const void *k_host, const void *v_host, int32_t len);
+int kv_tier_select_scored(const en_tier *tier, const float *p_host, float threshold,
+                          int64_t budget_tokens, int32_t *groups_out_host, int32_t *n_out);
+int kv_tier_fetch(en_tier *tier, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,
+                  void *stream);
+int kv_tier_fence(en_tier *tier, void *stream);
+int kv_tier_prefetch(en_tier *tier, const int32_t *groups_host, int32_t n, int32_t *n_loaded_out);
+int kv_tier_get_stats(const en_tier *tier, en_tier_stats *out);
+int kv_tier_residency(const en_tier *tier, int32_t *slot_of_group_out_host);
+int kv_tier_destroy(en_tier *tier);
 
 /* ------------------------------------------------------------------------
  * Measurement aid for callers that need the duration of the attention kernel

@@ -27,6 +27,9 @@ EXPORTS = [
     "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
     "en_decode_workspace_bytes", "segmented_decode_step", "en_timing_enable",
     "en_timing_collect", "en_last_error",
+    "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_select_scored",
+    "kv_tier_fetch", "kv_tier_fence", "kv_tier_prefetch", "kv_tier_get_stats", "kv_tier_residency",
+    "kv_tier_destroy",
 ]
 
 
@@ -46,6 +49,11 @@ class PlanInfo(C.Structure):
     _fields_ = [("n_agents", C.c_int32), ("n_new", C.c_int32), ("max_segments", C.c_int32),
                 ("ctx_stride", C.c_int32), ("max_ctx_len", C.c_int32), ("n_splits", C.c_int32),
                 ("total_pairs", C.c_int64), ("total_cached", C.c_int64)]
+
+
+class TierStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("fetches", "requested", "hits", "prefetched", "misses", "loads",
+                                         "bytes_loaded", "evictions")]
 
 
 _lib = None
@@ -88,8 +96,22 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_timing_enable.argtypes = [C.c_int32]
     lib.en_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
+    lib.kv_tier_slot_bytes.argtypes = [C.POINTER(PoolDesc)]
+    lib.kv_tier_slot_bytes.restype = C.c_int64
+    lib.kv_tier_create.argtypes = [C.POINTER(PoolDesc), C.c_int32, vp, vp, C.POINTER(vp)]
+    lib.kv_tier_pool.argtypes = [vp]
+    lib.kv_tier_pool.restype = vp
+    lib.kv_tier_put.argtypes = [vp, C.c_int32, vp, vp, C.c_int32]
+    lib.kv_tier_select_scored.argtypes = [vp, C.POINTER(C.c_float), C.c_float, C.c_int64, i32p, i32p]
+    lib.kv_tier_fetch.argtypes = [vp, i32p, C.c_int32, i32p, vp]
+    lib.kv_tier_fence.argtypes = [vp, vp]
+    lib.kv_tier_prefetch.argtypes = [vp, i32p, C.c_int32, i32p]
+    lib.kv_tier_get_stats.argtypes = [vp, C.POINTER(TierStats)]
+    lib.kv_tier_residency.argtypes = [vp, i32p]
+    lib.kv_tier_destroy.argtypes = [vp]
     for name in EXPORTS:
-        if name not in ("en_context_bytes", "en_workspace_bytes", "en_decode_workspace_bytes", "en_last_error"):
+        if name not in ("en_context_bytes", "en_workspace_bytes", "en_decode_workspace_bytes", "en_last_error",
+                        "kv_tier_slot_bytes", "kv_tier_pool"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -118,15 +140,17 @@ def _stream(stream) -> C.c_void_p:
 class Pool:
     """Handle of a KV pool. Keeps the K/V tensors alive."""
 
-    def __init__(self, handle, k, v, desc: PoolDesc):
+    def __init__(self, handle, k, v, desc: PoolDesc, owned: bool = True):
         self.handle, self.k, self.v, self.desc = handle, k, v, desc
+        self._owned = owned                  # False: the handle belongs to a tier, which destroys it
         self._plans = weakref.WeakSet()      # a pool must outlive its plans: it closes them first
 
     def close(self):
         if self.handle:
             for p in list(self._plans):
                 p.close()
-            load().kv_pool_destroy(self.handle)
+            if self._owned:
+                load().kv_pool_destroy(self.handle)
             self.handle = None
 
     def __del__(self):
@@ -302,6 +326,111 @@ def segmented_decode_step(pool: Pool, plan: Plan, q_first: int, q, k_rows, v_row
         ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
         _stream(stream)))
     return out
+
+
+class Tier:
+    """Handle of a residency tier. ``pool`` is the pool over the device slots (None for a tier that only
+    keeps the books)."""
+
+    def __init__(self, handle, pool: Optional[Pool], n_groups_total: int, desc: PoolDesc):
+        self.handle, self.pool, self.n_groups_total, self.desc = handle, pool, n_groups_total, desc
+
+    @property
+    def stats(self) -> TierStats:
+        st = TierStats()
+        _check(load().kv_tier_get_stats(self.handle, C.byref(st)))
+        return st
+
+    def residency(self) -> np.ndarray:
+        out = np.zeros(self.n_groups_total, dtype=np.int32)
+        _check(load().kv_tier_residency(self.handle, _ip(out)))
+        return out
+
+    def close(self):
+        if self.handle:
+            if self.pool is not None:
+                self.pool.close()
+            load().kv_tier_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        if sys is None or sys.is_finalizing():
+            return
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def kv_tier_slot_bytes(shape: Sequence[int], dtype: int) -> int:
+    """Bytes of one device slot (K and V) for blocks [Hkv, C, D]."""
+    Hkv, Cap, D = shape
+    desc = PoolDesc(1, Cap, Hkv, Hkv, D, dtype, 1, 0, 1.0)
+    return int(load().kv_tier_slot_bytes(C.byref(desc)))
+
+
+def kv_tier_create(k_slots, v_slots, n_groups_total: int, n_q_heads: int, rope_base: float, max_ctx: int,
+                   dtype: Optional[int] = None, shape: Optional[Sequence[int]] = None) -> Tier:
+    """k_slots, v_slots: torch tensors [slots, Hkv, C, D] on the GPU, or None with ``shape`` and
+    ``dtype`` for a tier that only keeps the books."""
+    kp = vp_ = None
+    if k_slots is not None:
+        import torch
+        assert k_slots.is_contiguous() and v_slots.is_contiguous() and k_slots.shape == v_slots.shape
+        shape = tuple(k_slots.shape)
+        dtype = EN_BF16 if k_slots.dtype == torch.bfloat16 else EN_F32
+        kp, vp_ = k_slots.data_ptr(), v_slots.data_ptr()
+    n_slots, Hkv, Cap, D = shape
+    desc = PoolDesc(n_slots, Cap, Hkv, n_q_heads, D, dtype, max_ctx, 0, rope_base)
+    h = C.c_void_p()
+    _check(load().kv_tier_create(C.byref(desc), int(n_groups_total), C.c_void_p(kp), C.c_void_p(vp_), C.byref(h)))
+    ph = load().kv_tier_pool(h)
+    pool = Pool(C.c_void_p(ph), k_slots, v_slots, desc, owned=False) if ph else None
+    return Tier(h, pool, int(n_groups_total), desc)
+
+
+def kv_tier_put(tier: Tier, group: int, k_rows, v_rows, length: Optional[int] = None):
+    """k_rows, v_rows: host arrays or CPU tensors [Hkv, len, D] in the tier's dtype (contiguous); for a
+    tier that only keeps the books pass None and ``length``."""
+    if k_rows is None:
+        _check(load().kv_tier_put(tier.handle, int(group), None, None, int(length)))
+        return
+    assert k_rows.is_contiguous() and v_rows.is_contiguous() and k_rows.shape == v_rows.shape
+    assert k_rows.device.type == "cpu" and v_rows.device.type == "cpu"
+    length = int(k_rows.shape[1]) if length is None else int(length)
+    _check(load().kv_tier_put(tier.handle, int(group), C.c_void_p(k_rows.data_ptr()),
+                              C.c_void_p(v_rows.data_ptr()), length))
+
+
+def kv_tier_select_scored(tier: Tier, p, threshold: float, budget_tokens: int) -> np.ndarray:
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    assert p.shape == (tier.n_groups_total,)
+    out = np.zeros(tier.n_groups_total, dtype=np.int32)
+    n = C.c_int32()
+    _check(load().kv_tier_select_scored(tier.handle, p.ctypes.data_as(C.POINTER(C.c_float)), C.c_float(threshold),
+                                        C.c_int64(int(budget_tokens)), _ip(out), C.byref(n)))
+    return out[:n.value].copy()
+
+
+def kv_tier_fetch(tier: Tier, groups, stream=None) -> np.ndarray:
+    """Make the groups resident; returns the slot of each (ids for segment_select on ``tier.pool``)."""
+    groups = _i32(groups)
+    slots = np.zeros(len(groups), dtype=np.int32)
+    st = C.c_void_p(0) if tier.pool is None else _stream(stream)
+    _check(load().kv_tier_fetch(tier.handle, _ip(groups), len(groups), _ip(slots), st))
+    return slots
+
+
+def kv_tier_fence(tier: Tier, stream=None):
+    st = C.c_void_p(0) if tier.pool is None else _stream(stream)
+    _check(load().kv_tier_fence(tier.handle, st))
+
+
+def kv_tier_prefetch(tier: Tier, groups) -> int:
+    groups = _i32(groups)
+    n = C.c_int32()
+    _check(load().kv_tier_prefetch(tier.handle, _ip(groups), len(groups), C.byref(n)))
+    return n.value
 
 
 def timing_enable(n: int):

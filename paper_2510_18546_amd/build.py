@@ -12,7 +12,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libefficientnav.so")
-SOURCES = [os.path.join(_HERE, "csrc", "en_host.cpp"), os.path.join(_HERE, "csrc", "en_kernels.hip")]
+SOURCES = [os.path.join(_HERE, "csrc", "en_host.cpp"), os.path.join(_HERE, "csrc", "en_tier.cpp"),
+           os.path.join(_HERE, "csrc", "en_kernels.hip")]
 HEADERS = [os.path.join(_HERE, "csrc", "en_internal.h"), os.path.join(_ROOT, "include", "efficientnav.h")]
 
 HIPCC_FLAGS = [

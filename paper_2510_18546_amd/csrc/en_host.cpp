@@ -282,7 +282,71 @@ extern "C" int segment_select(const en_pool *pool, int32_t n_agents, const int32
     return build_plan(pool, n_agents, sel_host, sel_ptr_host, n_new, out);
 }
 
-// Eq. (1) as an exact 0/1 knapsack over token capacity.
+// Eq. (1) as an exact 0/1 knapsack over token capacity: the groups with
+// p > threshold whose lengths fit the budget and whose summed (p - threshold) is
+// largest; among those the fewest tokens, then the lowest ids.
+void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
+                 std::vector<int32_t> &chosen)
+{
+    chosen.clear();
+    struct Item { int id; int64_t v; int w; };
+    std::vector<Item> items;
+    int64_t wsum = 0;
+    for (int g = 0; g < G; ++g) {
+        const double d = double(p_host[g]) - double(threshold);
+        const int64_t v = (int64_t)std::nearbyint(d * 4294967296.0);   // ties to even
+        if (v > 0) {
+            items.push_back({g, v, len[g]});
+            wsum += len[g];
+        }
+    }
+    const int m = int(items.size());
+    const int64_t W = std::min<int64_t>(budget_tokens, wsum);
+    if (wsum <= budget_tokens) {
+        for (auto &it : items)
+            chosen.push_back(it.id);
+        return;
+    }
+    // best[a][w] over items a.. with capacity w: maximal value, then minimal
+    // tokens (two rolling rows). take[a][w] records whether taking item a is
+    // optimal at that state, ties included, so that the walk from item 0
+    // prefers the lowest ids (lexicographically smallest sorted list).
+    const size_t cols = size_t(W) + 1;
+    std::vector<int64_t> vcur(cols, 0), vnext(cols, 0);
+    std::vector<int32_t> tcur(cols, 0), tnext(cols, 0);
+    const size_t words = (cols + 63) / 64;
+    std::vector<uint64_t> take(size_t(m) * words, 0);
+    for (int a = m - 1; a >= 0; --a) {
+        const int64_t vi = items[a].v;
+        const int wi = items[a].w;
+        uint64_t *tk = &take[size_t(a) * words];
+        for (int64_t w = 0; w <= W; ++w) {
+            int64_t bv = vnext[w];
+            int32_t bt = tnext[w];
+            if (wi <= w) {
+                const int64_t tv = vnext[w - wi] + vi;
+                const int32_t tt = tnext[w - wi] + wi;
+                if (tv > bv || (tv == bv && tt <= bt)) {
+                    bv = tv;
+                    bt = tt;
+                    tk[w >> 6] |= uint64_t(1) << (w & 63);
+                }
+            }
+            vcur[w] = bv;
+            tcur[w] = bt;
+        }
+        vcur.swap(vnext);
+        tcur.swap(tnext);
+    }
+    int64_t w = W;
+    for (int a = 0; a < m; ++a) {
+        if (take[size_t(a) * words + (w >> 6)] >> (w & 63) & 1) {
+            chosen.push_back(items[a].id);
+            w -= items[a].w;
+        }
+    }
+}
+
 extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, float threshold,
                                      int64_t budget_tokens, int32_t n_new, int32_t *sel_out_host,
                                      int32_t *n_sel_out, en_plan **out)
@@ -293,64 +357,8 @@ extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, f
         return fail(EN_ERR_INVALID_ARG, "segment_select_scored: negative budget");
     if (out)
         *out = nullptr;
-    const int G = pool->d.n_groups;
-    struct Item { int id; int64_t v; int w; };
-    std::vector<Item> items;
-    int64_t wsum = 0;
-    for (int g = 0; g < G; ++g) {
-        const double d = double(p_host[g]) - double(threshold);
-        const int64_t v = (int64_t)std::nearbyint(d * 4294967296.0);   // ties to even
-        if (v > 0) {
-            items.push_back({g, v, pool->len[g]});
-            wsum += pool->len[g];
-        }
-    }
-    const int m = int(items.size());
-    const int64_t W = std::min<int64_t>(budget_tokens, wsum);
     std::vector<int32_t> chosen;
-    if (wsum <= budget_tokens) {
-        for (auto &it : items)
-            chosen.push_back(it.id);
-    } else {
-        // best[a][w] over items a.. with capacity w: maximal value, then minimal
-        // tokens (two rolling rows). take[a][w] records whether taking item a is
-        // optimal at that state, ties included, so that the walk from item 0
-        // prefers the lowest ids (lexicographically smallest sorted list).
-        const size_t cols = size_t(W) + 1;
-        std::vector<int64_t> vcur(cols, 0), vnext(cols, 0);
-        std::vector<int32_t> tcur(cols, 0), tnext(cols, 0);
-        const size_t words = (cols + 63) / 64;
-        std::vector<uint64_t> take(size_t(m) * words, 0);
-        for (int a = m - 1; a >= 0; --a) {
-            const int64_t vi = items[a].v;
-            const int wi = items[a].w;
-            uint64_t *tk = &take[size_t(a) * words];
-            for (int64_t w = 0; w <= W; ++w) {
-                int64_t bv = vnext[w];
-                int32_t bt = tnext[w];
-                if (wi <= w) {
-                    const int64_t tv = vnext[w - wi] + vi;
-                    const int32_t tt = tnext[w - wi] + wi;
-                    if (tv > bv || (tv == bv && tt <= bt)) {
-                        bv = tv;
-                        bt = tt;
-                        tk[w >> 6] |= uint64_t(1) << (w & 63);
-                    }
-                }
-                vcur[w] = bv;
-                tcur[w] = bt;
-            }
-            vcur.swap(vnext);
-            tcur.swap(tnext);
-        }
-        int64_t w = W;
-        for (int a = 0; a < m; ++a) {
-            if (take[size_t(a) * words + (w >> 6)] >> (w & 63) & 1) {
-                chosen.push_back(items[a].id);
-                w -= items[a].w;
-            }
-        }
-    }
+    en_knapsack(p_host, pool->len.data(), pool->d.n_groups, threshold, budget_tokens, chosen);
     *n_sel_out = int32_t(chosen.size());
     std::copy(chosen.begin(), chosen.end(), sel_out_host);
     if (!out)

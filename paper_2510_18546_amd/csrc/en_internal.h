@@ -135,3 +135,7 @@ int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *st
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 
 void en_set_error(const char *fmt, ...);
+
+// Retrieval knapsack of Eq. (1) over `G` candidates with lengths `len` (tokens); ids ascending.
+void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
+                 std::vector<int32_t> &chosen);

@@ -1,0 +1,441 @@
+// libefficientnav.so — residency tier: which groups' K/V blocks are in device
+// memory, and the loads of those that are not (Section 3.2: the KV cache lives
+// in a large, slow store and only the selected groups are loaded, once per
+// planning step; groups selected in consecutive steps are already in device
+// memory. Section 4, cache hit rate: the share of the selected groups found
+// there).
+//
+// The device side is an ordinary en_pool whose "groups" are the tier's slots;
+// the store is pinned host memory in the same [Hkv, C, D] block layout, so a
+// load is one strided copy per array. Loads run on a stream of the tier's own;
+// two events order them against the caller's stream (see kv_tier_fetch).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "en_internal.h"
+
+struct en_tier {
+    en_pool_desc d;                // n_groups = number of slots
+    int G = 0;                     // groups in the store
+    bool dry = false;              // accounting only: no memory, no HIP calls
+    en_pool *pool = nullptr;       // over the caller's slot arrays
+    char *k_host = nullptr;        // pinned, [G, Hkv, C, D]
+    char *v_host = nullptr;
+    size_t block_bytes = 0;        // Hkv * C * D * elem
+    size_t row_bytes = 0;          // D * elem
+    std::vector<int32_t> len;      // [G], -1: never put
+    std::vector<int32_t> slot_of;  // [G], -1: not resident
+    std::vector<int32_t> group_in; // [slots], -1: free
+    std::vector<int64_t> last_use; // [slots], tick of the last fetch / prefetch that asked for it, -1: never
+    std::vector<char> ahead;       // [slots], loaded or kept by a prefetch and not yet asked for by a fetch
+    int64_t tick = 0;              // fetches so far
+    int64_t fence_tick = -1;       // readers of every slot handed out by fetches <= this tick are covered by ev_fence
+    bool have_fence = false;
+    bool unjoined = false;         // copies issued that no fetch has made the caller's stream wait for
+    hipStream_t copy = nullptr;
+    hipEvent_t ev_fence = nullptr, ev_copy = nullptr;
+    en_tier_stats st{};
+};
+
+static int tfail(int code, const char *msg)
+{
+    en_set_error("%s", msg);
+    return code;
+}
+
+static int thip(hipError_t e, const char *what)
+{
+    en_set_error("%s: %s", what, hipGetErrorString(e));
+    return EN_ERR_DEVICE;
+}
+
+static size_t tier_elem(int dtype) { return dtype == EN_BF16 ? 2 : 4; }
+
+extern "C" int64_t kv_tier_slot_bytes(const en_pool_desc *desc)
+{
+    if (!desc || desc->capacity <= 0 || desc->n_kv_heads <= 0 || desc->head_dim <= 0)
+        return 0;
+    return int64_t(2) * desc->n_kv_heads * desc->capacity * desc->head_dim * int64_t(tier_elem(desc->dtype));
+}
+
+extern "C" int kv_tier_destroy(en_tier *t)
+{
+    if (!t)
+        return EN_OK;
+    if (!t->dry) {
+        if (t->copy)
+            (void)hipStreamSynchronize(t->copy);
+        if (t->ev_fence)
+            (void)hipEventDestroy(t->ev_fence);
+        if (t->ev_copy)
+            (void)hipEventDestroy(t->ev_copy);
+        if (t->copy)
+            (void)hipStreamDestroy(t->copy);
+        if (t->k_host)
+            (void)hipHostFree(t->k_host);
+        if (t->v_host)
+            (void)hipHostFree(t->v_host);
+        if (t->pool)
+            (void)kv_pool_destroy(t->pool);
+    }
+    delete t;
+    return EN_OK;
+}
+
+extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev, void *v_dev,
+                              en_tier **out)
+{
+    if (!desc || !out)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: null argument");
+    *out = nullptr;
+    if ((k_dev == nullptr) != (v_dev == nullptr))
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: k_dev and v_dev must both be given or both be null");
+    if (n_groups_total <= 0 || desc->n_groups <= 0)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: non-positive group or slot count");
+    en_tier *t = new (std::nothrow) en_tier;
+    if (!t)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: out of host memory");
+    t->d = *desc;
+    t->G = n_groups_total;
+    t->dry = (k_dev == nullptr);
+    const int n_slots = desc->n_groups;
+    t->len.assign(size_t(n_groups_total), -1);
+    t->slot_of.assign(size_t(n_groups_total), -1);
+    t->group_in.assign(size_t(n_slots), -1);
+    t->last_use.assign(size_t(n_slots), -1);
+    t->ahead.assign(size_t(n_slots), 0);
+    if (t->dry) {
+        if (desc->capacity <= 0) {
+            delete t;
+            return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: non-positive capacity");
+        }
+        *out = t;
+        return EN_OK;
+    }
+    std::vector<int32_t> zeros(size_t(n_slots), 0);
+    int rc = kv_pool_create(desc, k_dev, v_dev, zeros.data(), &t->pool);   // validates the description
+    if (rc != EN_OK) {
+        delete t;
+        return rc;
+    }
+    t->row_bytes = size_t(desc->head_dim) * tier_elem(desc->dtype);
+    t->block_bytes = size_t(desc->n_kv_heads) * size_t(desc->capacity) * t->row_bytes;
+    hipError_t e;
+    const size_t store = t->block_bytes * size_t(n_groups_total);
+    if ((e = hipHostMalloc((void **)&t->k_host, store, hipHostMallocDefault)) != hipSuccess ||
+        (e = hipHostMalloc((void **)&t->v_host, store, hipHostMallocDefault)) != hipSuccess) {
+        rc = thip(e, "kv_tier_create: hipHostMalloc(store)");
+        kv_tier_destroy(t);
+        return rc;
+    }
+    if ((e = hipStreamCreateWithFlags(&t->copy, hipStreamNonBlocking)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&t->ev_fence, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&t->ev_copy, hipEventDisableTiming)) != hipSuccess) {
+        rc = thip(e, "kv_tier_create: stream / event");
+        kv_tier_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return EN_OK;
+}
+
+extern "C" en_pool *kv_tier_pool(en_tier *t) { return t ? t->pool : nullptr; }
+
+// Forget the device copy of a group. The slot keeps its age: kernels of the
+// caller may still be reading it, so it is reused under the same ordering rules
+// as a slot that holds a group.
+static void drop_resident(en_tier *t, int group)
+{
+    const int s = t->slot_of[group];
+    if (s < 0)
+        return;
+    t->slot_of[group] = -1;
+    t->group_in[s] = -1;
+    t->ahead[s] = 0;
+    if (t->pool)
+        t->pool->len[s] = 0;
+}
+
+extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const void *v_host, int32_t len)
+{
+    if (!t || len < 0)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_put: null tier or negative length");
+    if (group < 0 || group >= t->G)
+        return tfail(EN_ERR_OUT_OF_RANGE, "kv_tier_put: group outside the store");
+    if (len > t->d.capacity)
+        return tfail(EN_ERR_OUT_OF_RANGE, "kv_tier_put: length exceeds the capacity of a block");
+    if (!t->dry) {
+        if (len > 0 && (!k_host || !v_host))
+            return tfail(EN_ERR_INVALID_ARG, "kv_tier_put: null rows");
+        // a load of this block may still be reading the store
+        const hipError_t e = hipStreamSynchronize(t->copy);
+        if (e != hipSuccess)
+            return thip(e, "kv_tier_put: hipStreamSynchronize");
+        const size_t head_src = size_t(len) * t->row_bytes;
+        const size_t head_dst = size_t(t->d.capacity) * t->row_bytes;
+        for (int h = 0; h < t->d.n_kv_heads && len > 0; ++h) {
+            std::memcpy(t->k_host + size_t(group) * t->block_bytes + h * head_dst,
+                        (const char *)k_host + h * head_src, head_src);
+            std::memcpy(t->v_host + size_t(group) * t->block_bytes + h * head_dst,
+                        (const char *)v_host + h * head_src, head_src);
+        }
+    }
+    t->len[group] = len;
+    drop_resident(t, group);      // the device copy, if any, is stale
+    return EN_OK;
+}
+
+extern "C" int kv_tier_select_scored(const en_tier *t, const float *p_host, float threshold,
+                                     int64_t budget_tokens, int32_t *groups_out_host, int32_t *n_out)
+{
+    if (!t || !p_host || !groups_out_host || !n_out)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_select_scored: null argument");
+    if (budget_tokens < 0)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_select_scored: negative budget");
+    // groups never put are not candidates: give them a length no budget admits
+    std::vector<int32_t> len(t->len);
+    std::vector<float> p(p_host, p_host + t->G);
+    for (int g = 0; g < t->G; ++g)
+        if (len[g] < 0) {
+            len[g] = 0;
+            p[g] = threshold;     // value 0: never taken
+        }
+    std::vector<int32_t> chosen;
+    en_knapsack(p.data(), len.data(), t->G, threshold, budget_tokens, chosen);
+    *n_out = int32_t(chosen.size());
+    std::copy(chosen.begin(), chosen.end(), groups_out_host);
+    return EN_OK;
+}
+
+static int check_groups(const en_tier *t, const int32_t *groups, int n, const char *who)
+{
+    if (!t || n < 0 || (n > 0 && !groups)) {
+        en_set_error("%s: null argument or negative count", who);
+        return EN_ERR_INVALID_ARG;
+    }
+    if (n > t->d.n_groups) {
+        en_set_error("%s: %d groups asked for, the tier has %d slots", who, n, t->d.n_groups);
+        return EN_ERR_CAPACITY;
+    }
+    std::vector<char> seen(size_t(t->G), 0);
+    for (int i = 0; i < n; ++i) {
+        const int g = groups[i];
+        if (g < 0 || g >= t->G || t->len[g] < 0) {
+            en_set_error("%s: group %d is outside the store or was never put", who, g);
+            return EN_ERR_OUT_OF_RANGE;
+        }
+        if (seen[g]) {
+            en_set_error("%s: group %d twice", who, g);
+            return EN_ERR_DUPLICATE;
+        }
+        seen[g] = 1;
+    }
+    return EN_OK;
+}
+
+// Least recently used slot among those with keep[s] == 0 and last_use <= limit;
+// free slots (last_use -1) come first, ties go to the lowest index. -1: none.
+static int pick_victim(const en_tier *t, const std::vector<char> &keep, int64_t limit)
+{
+    int best = -1;
+    for (int s = 0; s < t->d.n_groups; ++s) {
+        if (keep[s] || t->last_use[s] > limit)
+            continue;
+        if (best < 0 || t->last_use[s] < t->last_use[best])
+            best = s;
+    }
+    return best;
+}
+
+// Enqueue the copy of `group` into `slot` on the tier's stream.
+static int load_block(en_tier *t, int group, int slot)
+{
+    const int len = t->len[group];
+    t->st.loads += 1;
+    t->st.bytes_loaded += int64_t(2) * t->d.n_kv_heads * int64_t(len) * t->d.head_dim * int64_t(tier_elem(t->d.dtype));
+    if (t->dry || len == 0)
+        return EN_OK;
+    const size_t pitch = size_t(t->d.capacity) * t->row_bytes;
+    const size_t width = size_t(len) * t->row_bytes;
+    char *kd = (char *)t->pool->k_dev + size_t(slot) * t->block_bytes;
+    char *vd = (char *)t->pool->v_dev + size_t(slot) * t->block_bytes;
+    const char *ks = t->k_host + size_t(group) * t->block_bytes;
+    const char *vs = t->v_host + size_t(group) * t->block_bytes;
+    hipError_t e;
+    if (len == t->d.capacity) {
+        if ((e = hipMemcpyAsync(kd, ks, t->block_bytes, hipMemcpyHostToDevice, t->copy)) != hipSuccess ||
+            (e = hipMemcpyAsync(vd, vs, t->block_bytes, hipMemcpyHostToDevice, t->copy)) != hipSuccess)
+            return thip(e, "kv_tier: hipMemcpyAsync");
+    } else {
+        if ((e = hipMemcpy2DAsync(kd, pitch, ks, pitch, width, size_t(t->d.n_kv_heads), hipMemcpyHostToDevice,
+                                  t->copy)) != hipSuccess ||
+            (e = hipMemcpy2DAsync(vd, pitch, vs, pitch, width, size_t(t->d.n_kv_heads), hipMemcpyHostToDevice,
+                                  t->copy)) != hipSuccess)
+            return thip(e, "kv_tier: hipMemcpy2DAsync");
+    }
+    t->unjoined = true;
+    return EN_OK;
+}
+
+static void place(en_tier *t, int group, int slot)
+{
+    const int old = t->group_in[slot];
+    if (old >= 0) {
+        t->slot_of[old] = -1;
+        t->st.evictions += 1;
+    }
+    t->group_in[slot] = group;
+    t->slot_of[group] = slot;
+    if (t->pool)
+        t->pool->len[slot] = t->len[group];
+}
+
+extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,
+                             void *stream)
+{
+    int rc = check_groups(t, groups_host, n, "kv_tier_fetch");
+    if (rc != EN_OK)
+        return rc;
+    if (n > 0 && !slots_out_host)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_fetch: null slots_out");
+    hipStream_t st = (hipStream_t)stream;
+    t->tick += 1;
+    t->st.fetches += 1;
+    t->st.requested += n;
+    const int n_slots = t->d.n_groups;
+    std::vector<char> keep(size_t(n_slots), 0);
+    // first every group that is already there, so that none of them is a victim
+    for (int i = 0; i < n; ++i) {
+        const int s = t->slot_of[groups_host[i]];
+        if (s < 0)
+            continue;
+        keep[s] = 1;
+        t->last_use[s] = t->tick;
+        if (t->ahead[s]) {
+            t->ahead[s] = 0;
+            t->st.prefetched += 1;
+        } else {
+            t->st.hits += 1;
+        }
+        slots_out_host[i] = s;
+    }
+    bool waited = false;
+    for (int i = 0; i < n; ++i) {
+        const int g = groups_host[i];
+        if (t->slot_of[g] >= 0)
+            continue;
+        const int s = pick_victim(t, keep, t->tick - 1);
+        if (s < 0)
+            return tfail(EN_ERR_CAPACITY, "kv_tier_fetch: no slot left");      // cannot happen: n <= slots
+        if (!t->dry && !waited) {
+            // Kernels of the caller that read the slots handed out earlier must
+            // be done before a slot is overwritten. A fence the caller set after
+            // enqueuing them covers fetches up to fence_tick; otherwise everything
+            // queued on the caller's stream so far is waited for.
+            hipError_t e;
+            if (t->tick > 1 && t->fence_tick < t->tick - 1) {
+                if ((e = hipEventRecord(t->ev_fence, st)) != hipSuccess)
+                    return thip(e, "kv_tier_fetch: hipEventRecord");
+                t->fence_tick = t->tick - 1;
+                t->have_fence = true;
+            }
+            if (t->have_fence && (e = hipStreamWaitEvent(t->copy, t->ev_fence, 0)) != hipSuccess)
+                return thip(e, "kv_tier_fetch: hipStreamWaitEvent");
+            waited = true;
+        }
+        t->st.misses += 1;
+        place(t, g, s);
+        keep[s] = 1;
+        t->last_use[s] = t->tick;
+        t->ahead[s] = 0;
+        slots_out_host[i] = s;
+        if ((rc = load_block(t, g, s)) != EN_OK)
+            return rc;
+    }
+    if (!t->dry && t->unjoined) {
+        hipError_t e;
+        if ((e = hipEventRecord(t->ev_copy, t->copy)) != hipSuccess ||
+            (e = hipStreamWaitEvent(st, t->ev_copy, 0)) != hipSuccess)
+            return thip(e, "kv_tier_fetch: join of the loads");
+        t->unjoined = false;
+    }
+    return EN_OK;
+}
+
+extern "C" int kv_tier_fence(en_tier *t, void *stream)
+{
+    if (!t)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_fence: null tier");
+    if (!t->dry) {
+        const hipError_t e = hipEventRecord(t->ev_fence, (hipStream_t)stream);
+        if (e != hipSuccess)
+            return thip(e, "kv_tier_fence: hipEventRecord");
+    }
+    t->have_fence = true;
+    t->fence_tick = t->tick;
+    return EN_OK;
+}
+
+extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *n_loaded_out)
+{
+    int rc = check_groups(t, groups_host, n, "kv_tier_prefetch");
+    if (rc != EN_OK)
+        return rc;
+    const int n_slots = t->d.n_groups;
+    std::vector<char> keep(size_t(n_slots), 0);
+    for (int i = 0; i < n; ++i) {
+        const int s = t->slot_of[groups_host[i]];
+        if (s >= 0)
+            keep[s] = 1;              // stays; its age is left as it is
+    }
+    int loaded = 0;
+    bool waited = false;
+    for (int i = 0; i < n; ++i) {
+        const int g = groups_host[i];
+        if (t->slot_of[g] >= 0)
+            continue;
+        // only slots whose readers the fence covers: the copy may then run
+        // beside whatever the caller has queued since
+        const int s = pick_victim(t, keep, t->fence_tick);
+        if (s < 0)
+            break;
+        if (!t->dry && !waited) {
+            hipError_t e;
+            if (t->have_fence && (e = hipStreamWaitEvent(t->copy, t->ev_fence, 0)) != hipSuccess)
+                return thip(e, "kv_tier_prefetch: hipStreamWaitEvent");
+            waited = true;
+        }
+        place(t, g, s);
+        keep[s] = 1;
+        // as old as the fence allows: a fetch that does not ask for it may
+        // take the slot back without waiting for anything new
+        t->last_use[s] = t->fence_tick;
+        t->ahead[s] = 1;
+        if ((rc = load_block(t, g, s)) != EN_OK)
+            return rc;
+        loaded += 1;
+    }
+    if (n_loaded_out)
+        *n_loaded_out = loaded;
+    return EN_OK;
+}
+
+extern "C" int kv_tier_get_stats(const en_tier *t, en_tier_stats *out)
+{
+    if (!t || !out)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_get_stats: null argument");
+    *out = t->st;
+    return EN_OK;
+}
+
+extern "C" int kv_tier_residency(const en_tier *t, int32_t *slot_of_group_out_host)
+{
+    if (!t || !slot_of_group_out_host)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_residency: null argument");
+    std::copy(t->slot_of.begin(), t->slot_of.end(), slot_of_group_out_host);
+    return EN_OK;
+}

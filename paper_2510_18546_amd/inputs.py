@@ -177,3 +177,17 @@ def make_workload(cfg: Config, poison: bool = True,
 
     return Workload(cfg, lens, k_pool, v_pool, sel, sel_ptr, q, k_new, v_new, meta)
 
+
+
+def drifting_scores(seed: int, n_groups: int, n_steps: int, rho: float = 0.95) -> np.ndarray:
+    """Relevance scores of ``n_groups`` groups over ``n_steps`` planning steps, float32
+    [n_steps, n_groups]: a stationary first-order autoregression per group with unit variance,
+    s[t] = rho * s[t-1] + sqrt(1 - rho^2) * noise. Stands in for the similarity between the goal
+    and each group's description along an episode (Section 3.4), which changes little between
+    adjacent planning steps (Section 4, cache hit rate): rho sets how little."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    s = np.empty((n_steps, n_groups), dtype=np.float64)
+    s[0] = rng.standard_normal(n_groups)
+    for t in range(1, n_steps):
+        s[t] = rho * s[t - 1] + np.sqrt(1.0 - rho * rho) * rng.standard_normal(n_groups)
+    return s.astype(np.float32)
