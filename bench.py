@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the two measured ceilings (a large bf16 GEMM of the vendor library on normal "
                          "and on constant data, a device copy) reported under 'ceilings'")
+    ap.add_argument("--no-residency", action="store_true",
+                    help="skip the residency-tier figures (hit rate against the device budget, planning "
+                         "steps whose groups are loaded from the host store) reported under 'residency'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -205,6 +208,103 @@ def main():
         }
         plan_d.close()
         pool_d.close()
+
+    if not hbm_bound and cfg.n_agents == 1 and not args.no_residency:
+        # Residency tier (Section 3.2, Section 4 "cache hit rate"): every group's K/V lives in a pinned host
+        # store, the device holds a budget of slots, a step loads only the selected groups that are not
+        # there. Selections: Eq. (1) over relevance scores that drift slowly from step to step.
+        G, n_sel, T = cfg.n_groups, cfg.n_sel, 120
+        rho = 0.98
+        scores = I.drifting_scores(cfg.seed + 100, G, T, rho=rho)
+        blk = (cfg.n_kv_heads, cfg.capacity, cfg.head_dim)
+
+        def book_tier(n_slots):
+            t = B.kv_tier_create(None, None, G, cfg.n_q_heads, cfg.rope_base, 1, dtype=B.EN_BF16,
+                                 shape=(n_slots,) + blk)
+            for g in range(G):
+                B.kv_tier_put(t, g, None, None, int(w.lens[g]))
+            return t
+        t0_ = book_tier(n_sel)
+        sels = [B.kv_tier_select_scored(t0_, scores[t], -8.0, n_sel * cfg.capacity) for t in range(T)]
+        t0_.close()
+        slot_mb = B.kv_tier_slot_bytes(blk, B.EN_BF16) / 1e6
+        curve = []
+        for n_slots in sorted({n_sel, n_sel * 5 // 4, n_sel * 3 // 2, n_sel * 2, n_sel * 3, n_sel * 4, G}):
+            t_ = book_tier(n_slots)
+            for sel in sels:
+                B.kv_tier_fetch(t_, sel)
+            curve.append({"slots": n_slots, "device_budget_MB": n_slots * slot_mb,
+                          "hit_rate": t_.stats.hits / t_.stats.requested})
+            t_.close()
+
+        n_slots = 2 * n_sel
+        dt = torch.bfloat16
+        k_slots = torch.zeros((n_slots,) + blk, dtype=dt, device="cuda:0")
+        v_slots = torch.zeros((n_slots,) + blk, dtype=dt, device="cuda:0")
+        tier = B.kv_tier_create(k_slots, v_slots, G, cfg.n_q_heads, cfg.rope_base,
+                                cfg.n_sel * cfg.capacity + cfg.n_new)
+        for g in range(G):
+            n = int(w.lens[g])
+            kh = torch.from_numpy(I.bf16_bits(np.ascontiguousarray(w.k_pool[g, :, :n])).view(np.int16)).view(dt)
+            vh = torch.from_numpy(I.bf16_bits(np.ascontiguousarray(w.v_pool[g, :, :n])).view(np.int16)).view(dt)
+            B.kv_tier_put(tier, g, kh, vh)
+
+        def tier_steps(ahead, sels=sels):
+            plans = []
+            T = len(sels)
+            for t, sel in enumerate(sels):
+                slots = B.kv_tier_fetch(tier, sel)
+                plan = B.segment_select(tier.pool, slots, [0, len(slots)], cfg.n_new)
+                assert B.context_bytes(tier.pool, plan) <= st.kc.numel() * st.kc.element_size()
+                B.gather_rope(tier.pool, plan, st.k_new, st.v_new, st.kc, st.vt)
+                B.kv_tier_fence(tier)
+                if ahead and t + 1 < T:
+                    B.kv_tier_prefetch(tier, sels[t + 1])
+                B.segmented_prefill_attention(tier.pool, plan, st.q, st.kc, st.vt, st.out, st.ws)
+                B.segment_attention_mass(tier.pool, plan, st.ws, 1, st.mass_red)
+                plans.append(plan)
+            torch.cuda.synchronize()
+            for p_ in plans:
+                p_.close()
+
+        timed_tier = {}
+        for name, ahead in (("on_demand", False), ("selection_known_one_step_ahead", True)):
+            tier_steps(ahead)                   # warm: slots filled, steady state
+            before = tier.stats
+            b0 = (before.hits, before.prefetched, before.misses, before.bytes_loaded, before.requested)
+            r0 = time.perf_counter()
+            tier_steps(ahead)
+            r1 = time.perf_counter()
+            a = tier.stats
+            req = a.requested - b0[4]
+            timed_tier[name] = {
+                "us_per_planning_step": (r1 - r0) / T * 1e6,
+                "hit_rate": (a.hits - b0[0]) / req, "prefetched_rate": (a.prefetched - b0[1]) / req,
+                "groups_loaded_late_per_step": (a.misses - b0[2]) / T,
+                "MB_loaded_per_step": (a.bytes_loaded - b0[3]) / T / 1e6,
+            }
+        # nothing resident: three disjoint selections in turn displace one another in 2 * n_sel slots
+        cold = [np.arange(i * n_sel, (i + 1) * n_sel, dtype=np.int32) for i in range(3)] * 10
+        tier_steps(False, cold)
+        b0 = tier.stats
+        r0 = time.perf_counter()
+        tier_steps(False, cold)
+        r1 = time.perf_counter()
+        a = tier.stats
+        assert a.hits == b0.hits and a.prefetched == b0.prefetched
+        timed_tier["nothing_resident"] = {
+            "us_per_planning_step": (r1 - r0) / len(cold) * 1e6, "hit_rate": 0.0,
+            "MB_loaded_per_step": (a.bytes_loaded - b0.bytes_loaded) / len(cold) / 1e6,
+            "host_to_device_GBs_incl_step": (a.bytes_loaded - b0.bytes_loaded) / (r1 - r0) / 1e9,
+        }
+        res["residency"] = {
+            "store_groups": G, "selected_per_step": n_sel, "steps": T, "score_drift_rho": rho,
+            "slot_MB": slot_mb, "hit_rate_vs_device_budget": curve,
+            "timed_slots": n_slots, "timed": timed_tier,
+            "all_resident_us_per_planning_step": sec_per_step * 1e6,
+        }
+        tier.close()
+        del k_slots, v_slots
 
     if not args.no_ceilings:
         # Two measured ceilings of this machine beside the nominal peaks: a large bf16 GEMM of the vendor

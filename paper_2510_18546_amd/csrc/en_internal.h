@@ -110,6 +110,18 @@ struct EnClusterArgs {
     int32_t spans[EN_MAX_OBJECTS + 1];   // object o = new tokens [spans[o], spans[o+1])
 };
 
+// One launch loads up to EN_TIER_LOAD_MAX blocks from the pinned host store into device slots.
+constexpr int EN_TIER_LOAD_MAX = 128;
+struct EnTierLoadArgs {
+    const char *k_store, *v_store;   // device-visible addresses of the store, blocks [G, Hkv, C, D]
+    char *k_slots, *v_slots;         // device, blocks [slots, Hkv, C, D]
+    unsigned long long block_bytes;  // Hkv * C * D * elem
+    int head_bytes;                  // C * D * elem
+    int row_bytes;                   // D * elem
+    int Hkv, n;
+    int32_t desc[EN_TIER_LOAD_MAX * 3];   // per block: group, slot, tokens
+};
+
 struct EnCtxAppendArgs {
     const void *k_rows, *v_rows;   // [B, n, Hkv, D], keys unrotated
     void *kc, *vt;                 // the context buffers
@@ -133,6 +145,7 @@ int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
 int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream);
 int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
+int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream);
 
 void en_set_error(const char *fmt, ...);
 

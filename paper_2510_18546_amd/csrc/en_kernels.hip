@@ -1658,6 +1658,40 @@ __global__ __launch_bounds__(256) void cluster_kernel(EnClusterArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// tier load: blocks of the pinned host store go to device slots (Section 3.2:
+// the selected groups' KV is loaded from the slow store, once). The kernel
+// reads host memory directly, 16 bytes per lane and four loads in flight per
+// lane, so one launch moves every missing block of a step and, unlike a chain
+// of copy commands, queues behind an event without holding up the host.
+// grid: (chunks of 16 KB along a head's used rows, 2 * Hkv, blocks), 256 threads.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tier_load_kernel(EnTierLoadArgs a)
+{
+    const int32_t *desc = reinterpret_cast<const int32_t *>(
+        reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + offsetof(EnTierLoadArgs, desc));
+    const int m = blockIdx.z;
+    const int group = desc[3 * m], slot = desc[3 * m + 1], tokens = desc[3 * m + 2];
+    const int h = blockIdx.y >> 1, is_v = blockIdx.y & 1;
+    const int units = tokens * (a.row_bytes / 16);           // 16-byte units of this head in use
+    const int first = blockIdx.x * 1024 + threadIdx.x;
+    if (blockIdx.x * 1024 >= units)
+        return;
+    const size_t head_off = (size_t)h * a.head_bytes;
+    const uint4 *src = reinterpret_cast<const uint4 *>((is_v ? a.v_store : a.k_store) +
+                                                       (size_t)group * a.block_bytes + head_off);
+    uint4 *dst = reinterpret_cast<uint4 *>((is_v ? a.v_slots : a.k_slots) + (size_t)slot * a.block_bytes + head_off);
+    uint4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (first + 256 * j < units)
+            v[j] = src[first + 256 * j];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (first + 256 * j < units)
+            dst[first + 256 * j] = v[j];
+}
+
+// ---------------------------------------------------------------------------
 // append: rows [n, Hkv, D] go to tokens first .. first+n-1 of one group's block
 // [Hkv, C, D] in both pool arrays (Section 3.2: new objects' KV is saved at the
 // end of the group's cache). One thread per 16 bytes; grid.y: 0 keys, 1 values.
@@ -1781,6 +1815,14 @@ int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream)
     (void)pool;
     const dim3 grid(a.n_obj, a.m.B), blk(256);
     hipLaunchKernelGGL(cluster_kernel, grid, blk, 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream)
+{
+    const int units = max_tokens * (a.row_bytes / 16);
+    const dim3 grid((units + 1023) / 1024, 2 * a.Hkv, a.n), blk(256);
+    hipLaunchKernelGGL(tier_load_kernel, grid, blk, 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

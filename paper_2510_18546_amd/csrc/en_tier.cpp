@@ -6,9 +6,10 @@
 // there).
 //
 // The device side is an ordinary en_pool whose "groups" are the tier's slots;
-// the store is pinned host memory in the same [Hkv, C, D] block layout, so a
-// load is one strided copy per array. Loads run on a stream of the tier's own;
-// two events order them against the caller's stream (see kv_tier_fetch).
+// the store is pinned host memory in the same [Hkv, C, D] block layout, which a
+// kernel reads directly: one launch loads every missing block of a step. Loads
+// run on a stream of the tier's own; two events order them against the caller's
+// stream (see kv_tier_fetch).
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
@@ -36,6 +37,9 @@ struct en_tier {
     int64_t fence_tick = -1;       // readers of every slot handed out by fetches <= this tick are covered by ev_fence
     bool have_fence = false;
     bool unjoined = false;         // copies issued that no fetch has made the caller's stream wait for
+    const char *k_store_dev = nullptr;   // the store as the device sees it
+    const char *v_store_dev = nullptr;
+    std::vector<int32_t> pending;  // blocks to load with the next launch: group, slot, tokens
     hipStream_t copy = nullptr;
     hipEvent_t ev_fence = nullptr, ev_copy = nullptr;
     en_tier_stats st{};
@@ -132,6 +136,15 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
         kv_tier_destroy(t);
         return rc;
     }
+    void *kd = nullptr, *vd = nullptr;
+    if ((e = hipHostGetDevicePointer(&kd, t->k_host, 0)) != hipSuccess ||
+        (e = hipHostGetDevicePointer(&vd, t->v_host, 0)) != hipSuccess) {
+        rc = thip(e, "kv_tier_create: hipHostGetDevicePointer");
+        kv_tier_destroy(t);
+        return rc;
+    }
+    t->k_store_dev = (const char *)kd;
+    t->v_store_dev = (const char *)vd;
     if ((e = hipStreamCreateWithFlags(&t->copy, hipStreamNonBlocking)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&t->ev_fence, hipEventDisableTiming)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&t->ev_copy, hipEventDisableTiming)) != hipSuccess) {
@@ -251,33 +264,48 @@ static int pick_victim(const en_tier *t, const std::vector<char> &keep, int64_t 
     return best;
 }
 
-// Enqueue the copy of `group` into `slot` on the tier's stream.
-static int load_block(en_tier *t, int group, int slot)
+// Count the load of `group` into `slot` and queue it for the next launch.
+static void load_block(en_tier *t, int group, int slot)
 {
     const int len = t->len[group];
     t->st.loads += 1;
     t->st.bytes_loaded += int64_t(2) * t->d.n_kv_heads * int64_t(len) * t->d.head_dim * int64_t(tier_elem(t->d.dtype));
     if (t->dry || len == 0)
-        return EN_OK;
-    const size_t pitch = size_t(t->d.capacity) * t->row_bytes;
-    const size_t width = size_t(len) * t->row_bytes;
-    char *kd = (char *)t->pool->k_dev + size_t(slot) * t->block_bytes;
-    char *vd = (char *)t->pool->v_dev + size_t(slot) * t->block_bytes;
-    const char *ks = t->k_host + size_t(group) * t->block_bytes;
-    const char *vs = t->v_host + size_t(group) * t->block_bytes;
-    hipError_t e;
-    if (len == t->d.capacity) {
-        if ((e = hipMemcpyAsync(kd, ks, t->block_bytes, hipMemcpyHostToDevice, t->copy)) != hipSuccess ||
-            (e = hipMemcpyAsync(vd, vs, t->block_bytes, hipMemcpyHostToDevice, t->copy)) != hipSuccess)
-            return thip(e, "kv_tier: hipMemcpyAsync");
-    } else {
-        if ((e = hipMemcpy2DAsync(kd, pitch, ks, pitch, width, size_t(t->d.n_kv_heads), hipMemcpyHostToDevice,
-                                  t->copy)) != hipSuccess ||
-            (e = hipMemcpy2DAsync(vd, pitch, vs, pitch, width, size_t(t->d.n_kv_heads), hipMemcpyHostToDevice,
-                                  t->copy)) != hipSuccess)
-            return thip(e, "kv_tier: hipMemcpy2DAsync");
+        return;
+    t->pending.push_back(group);
+    t->pending.push_back(slot);
+    t->pending.push_back(len);
+}
+
+// Launch the queued loads on the tier's stream, EN_TIER_LOAD_MAX blocks per launch.
+static int flush_loads(en_tier *t)
+{
+    const size_t n_blocks = t->pending.size() / 3;
+    for (size_t first = 0; first < n_blocks; first += EN_TIER_LOAD_MAX) {
+        EnTierLoadArgs a;
+        a.k_store = t->k_store_dev;
+        a.v_store = t->v_store_dev;
+        a.k_slots = (char *)t->pool->k_dev;
+        a.v_slots = (char *)t->pool->v_dev;
+        a.block_bytes = t->block_bytes;
+        a.head_bytes = int(size_t(t->d.capacity) * t->row_bytes);
+        a.row_bytes = int(t->row_bytes);
+        a.Hkv = t->d.n_kv_heads;
+        a.n = int(std::min<size_t>(EN_TIER_LOAD_MAX, n_blocks - first));
+        int max_tokens = 0;
+        for (int i = 0; i < a.n; ++i) {
+            for (int j = 0; j < 3; ++j)
+                a.desc[3 * i + j] = t->pending[3 * (first + i) + j];
+            max_tokens = std::max(max_tokens, a.desc[3 * i + 2]);
+        }
+        const int e = en_launch_tier_load(a, max_tokens, t->copy);
+        if (e != 0) {
+            t->pending.clear();
+            return thip((hipError_t)e, "kv_tier: load launch");
+        }
+        t->unjoined = true;
     }
-    t->unjoined = true;
+    t->pending.clear();
     return EN_OK;
 }
 
@@ -303,6 +331,7 @@ extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, 
     if (n > 0 && !slots_out_host)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_fetch: null slots_out");
     hipStream_t st = (hipStream_t)stream;
+    t->pending.clear();
     t->tick += 1;
     t->st.fetches += 1;
     t->st.requested += n;
@@ -353,9 +382,10 @@ extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, 
         t->last_use[s] = t->tick;
         t->ahead[s] = 0;
         slots_out_host[i] = s;
-        if ((rc = load_block(t, g, s)) != EN_OK)
-            return rc;
+        load_block(t, g, s);
     }
+    if (!t->dry && (rc = flush_loads(t)) != EN_OK)
+        return rc;
     if (!t->dry && t->unjoined) {
         hipError_t e;
         if ((e = hipEventRecord(t->ev_copy, t->copy)) != hipSuccess ||
@@ -394,6 +424,7 @@ extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t 
     }
     int loaded = 0;
     bool waited = false;
+    t->pending.clear();
     for (int i = 0; i < n; ++i) {
         const int g = groups_host[i];
         if (t->slot_of[g] >= 0)
@@ -415,10 +446,11 @@ extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t 
         // take the slot back without waiting for anything new
         t->last_use[s] = t->fence_tick;
         t->ahead[s] = 1;
-        if ((rc = load_block(t, g, s)) != EN_OK)
-            return rc;
+        load_block(t, g, s);
         loaded += 1;
     }
+    if (!t->dry && (rc = flush_loads(t)) != EN_OK)
+        return rc;
     if (n_loaded_out)
         *n_loaded_out = loaded;
     return EN_OK;
