@@ -31,6 +31,7 @@ WORKLOAD_TEXT = {
     "c1": "c1: 32q/8kv heads, D=128, bf16; 16 ragged segments (64..128 tokens) of a 64-group pool + 256 new tokens",
     "c2": "c2: 32q/8kv heads, D=128, bf16; 32 segments x 256 cached tokens (8192) of a 256-group pool + 512 new tokens; mass summed over heads and queries",
     "c3": "c3: 16 agents sharing a 512-group pool; 24 ragged segments (32..128 tokens) + 128 new tokens each; 32q/8kv, D=128, bf16",
+    "c5": "c5: c2's map on a LLaVA-34b-shaped layer: 56q/8kv heads, D=128, bf16; 32 segments x 256 cached tokens + 512 new tokens",
     "c4": "c4: decode, 64 agents x 1 new token over 64 segments x 256 tokens (16384) from a 1024-group pool; 32q/8kv, D=128, bf16",
 }
 

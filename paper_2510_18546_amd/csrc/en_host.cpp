@@ -177,8 +177,10 @@ static int pool_ensure_device(en_pool *p)
 static int choose_splits(const en_pool *pool, const en_plan *pl)
 {
     // One workgroup covers 8 (head, 32-query block) pairs of one KV head and
-    // fills a compute unit. Split the key range until every compute unit has a
-    // workgroup, keeping at least four key tiles per split.
+    // fills a compute unit. The key range is split so that the rounds of
+    // workgroups the compute units go through, times the length of one
+    // workgroup (its key tiles plus a start-up and wind-down worth about six
+    // tiles), is shortest; at least four key tiles per split.
     const int r = pool->r;
     if (pool->d.dtype == EN_BF16 && r * pl->Nq <= EN_ROWS_PER_WAVE) {
         // decode path: one wave per (agent, KV head, split), four waves per
@@ -193,10 +195,18 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
     const int n_ptiles = (r * nqb + EN_WAVES - 1) / EN_WAVES;
     const long base = long(pl->B) * pool->d.n_kv_heads * n_ptiles;
     const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
-    long want = (long(pool->n_cu) + base - 1) / base;
-    want = std::min<long>(want, std::max(1, tiles / 4));
-    want = std::max<long>(1, std::min<long>(want, 64));
-    return int(want);
+    const int n_max = std::max(1, std::min(64, tiles / 4));
+    int best = 1;
+    long best_cost = -1;
+    for (int n = 1; n <= n_max; ++n) {
+        const long rounds = (base * n + pool->n_cu - 1) / pool->n_cu;
+        const long cost = rounds * ((tiles + n - 1) / n + 6);
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best = n;
+        }
+    }
+    return best;
 }
 
 static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const int32_t *sel_ptr,

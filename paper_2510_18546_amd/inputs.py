@@ -1,7 +1,7 @@
 """Seeded synthetic workloads for the segmented-attention planning step.
 
 This module only draws random tensors and index lists with the shapes of the
-five benchmark configurations. It contains none of the method's arithmetic
+benchmark configurations. It contains none of the method's arithmetic
 (no RoPE, no softmax, no prefix sums) so that both the HIP path and the CPU
 oracle can be fed from it without sharing any computation.
 
@@ -64,6 +64,11 @@ CONFIGS: Dict[str, Config] = {
     # decode: 64 agents, one new token, 16K-token contexts
     "c4": Config("c4", 4, BF16, 64, 32, 8, 128, 1024, 256, 256, 256, 64, 1,
                  500000.0),
+    # the large map of c2 on a layer of the paper's largest planner (Appendix C, Table 7: LLaVA-34b,
+    # hidden size 7168 = 56 heads of 128). The paper does not give the head split; 8 KV heads is
+    # the published configuration of that backbone family and is taken as the reading here.
+    "c5": Config("c5", 5, BF16, 1, 56, 8, 128, 256, 256, 256, 256, 32, 512,
+                 5000000.0),
 }
 
 

@@ -289,7 +289,7 @@ def sample_rows(cfg, n, seed=9):
     return rows
 
 
-@pytest.mark.parametrize("name", ["c1", "c2", "c3"])
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c5"])
 def test_full_size_prefill_configs(step_mod, oracle, name):
     cfg = I.CONFIGS[name]
     run_case(step_mod, oracle, cfg, rows=sample_rows(cfg, 48))
