@@ -246,6 +246,16 @@ def test_bf16_tiny_segments(step_mod, oracle):
     run_case(step_mod, oracle, cfg)
 
 
+@pytest.mark.parametrize("dtype,n_agents", [(I.BF16, 1), (I.BF16, 9), (I.F32, 2)])
+def test_more_segments_than_lanes(step_mod, oracle, dtype, n_agents):
+    """More than 62 selected segments per agent: the bucket bounds no longer fit one per lane, and
+    with nine agents the plan's tables no longer travel inside the gather launch's arguments."""
+    cfg = small(f"many-seg-{dtype}-{n_agents}", 295 + n_agents, dtype=dtype, capacity=9, len_lo=0, len_hi=9,
+                n_groups=120, n_sel=90, n_new=70, n_agents=n_agents, head_dim=128 if dtype == I.BF16 else 64)
+    run_case(step_mod, oracle, cfg)
+    run_case(step_mod, oracle, cfg, n_splits=3)
+
+
 # ---------------------------------------------------------------------------
 # gather_rope on its own: indices and values bit-exact, rotation to 1 bf16 ulp
 # ---------------------------------------------------------------------------
