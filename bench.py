@@ -38,7 +38,7 @@ WORKLOAD_TEXT = {
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs, each scaled by what the same counter reads for a plain copy
 # of known size (profiles/attn_bf16_c2_hbm_traffic.md); null where not measured.
-MEASURED_TRAFFIC = {"c2": 64.6e6, "c4": 5.342e9}     # c4: profiles/attn_decode_c4_hbm_traffic.md (an upper bound)
+MEASURED_TRAFFIC = {"c2": 64.6e6, "c4": 4.318e9}     # c4: profiles/attn_decode_c4_hbm_traffic.md
 
 
 def algorithmic_flops(cfg, info) -> int:

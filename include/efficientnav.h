@@ -35,8 +35,9 @@
  *     uploaded on first GPU use, so the select calls are pure host code.
  *   - Kernels are enqueued on the caller's hipStream_t (passed as void*, NULL
  *     = the default stream). No call synchronises the stream.
- *   - A pool must outlive its plans. Calls on one handle are serialised by the
- *     caller; a pool may be read by many plans.
+ *   - A pool should outlive its plans: of a plan whose pool has been destroyed
+ *     only en_plan_destroy may still be called. Calls on one handle are
+ *     serialised by the caller; a pool may be read by many plans.
  *   - Notation: G groups of capacity C token slots, len[g] <= C tokens in use,
  *     Hq query heads, Hkv KV heads (Hq % Hkv == 0, query head h reads KV head
  *     h / (Hq/Hkv)), head dimension D in {64, 128}, B agents (independent

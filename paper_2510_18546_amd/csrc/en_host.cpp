@@ -132,6 +132,8 @@ extern "C" int kv_pool_destroy(en_pool *pool)
         (void)hipFree(pool->d_sin);
     for (auto &c : pool->desc_cache)
         (void)hipFree(c.second);
+    for (en_plan *pl : pool->plans)
+        pl->pool = nullptr;               // only en_plan_destroy may still be called on these
     delete pool;
     return EN_OK;
 }
@@ -183,8 +185,10 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
     // tiles), is shortest; at least four key tiles per split.
     const int r = pool->r;
     if (pool->d.dtype == EN_BF16 && r * pl->Nq <= EN_ROWS_PER_WAVE) {
-        // decode path: one wave per (agent, KV head, split), four waves per
-        // compute unit; at least eight 64-key tiles per split
+        // decode path: one wave per (agent, KV head, split); the two LDS stages
+        // of a wave let two waves share a compute unit. Two rounds of waves
+        // measured faster than one (0.73 against 0.78 ms on 64 agents x 16 K
+        // tokens); at least eight 64-key tiles per split
         const long base = long(pl->B) * pool->d.n_kv_heads;
         const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
         long want = (4L * pool->n_cu + base - 1) / base;
@@ -282,6 +286,7 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
     }
     pl->ctx_stride = round_up(pl->max_ctx_len, EN_KEY_TILE);
     pl->n_splits = choose_splits(pool, pl);
+    pool->plans.push_back(pl);
     *out = pl;
     return EN_OK;
 }
@@ -424,8 +429,14 @@ extern "C" int en_plan_destroy(en_plan *plan)
     // The descriptor block goes back to the pool for the next plan: no device
     // synchronisation here. Work still queued on a stream keeps reading it
     // safely as long as later plans of this pool are used on that same stream.
-    if (plan->d_desc)
-        plan->pool->desc_cache.emplace_back(plan->d_desc_bytes, plan->d_desc);
+    if (plan->pool) {
+        auto &live = plan->pool->plans;
+        live.erase(std::remove(live.begin(), live.end(), plan), live.end());
+        if (plan->d_desc)
+            plan->pool->desc_cache.emplace_back(plan->d_desc_bytes, plan->d_desc);
+    } else if (plan->d_desc) {
+        (void)hipFree(plan->d_desc);      // the pool went first: nothing to give the block back to
+    }
     delete plan;
     return EN_OK;
 }

@@ -25,6 +25,9 @@ struct en_pool {
     int n_cu = 256;
     // descriptor blocks of destroyed plans, kept for reuse (bytes, pointer)
     mutable std::vector<std::pair<size_t, int32_t *>> desc_cache;
+    // plans made on this pool and not yet destroyed: a pool that is destroyed
+    // first cuts them loose, so that destroying them later stays safe
+    mutable std::vector<struct en_plan *> plans;
 };
 
 struct en_plan {

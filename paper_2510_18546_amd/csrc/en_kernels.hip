@@ -899,34 +899,42 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 // matrix cores, so the work is cut for bandwidth: one wave per (agent, KV head,
 // KV split), no workgroup barrier at all. All r * N_q query rows of the KV head
 // are columns of the wave's one 32-column Q^T block (column c = head_local *
-// N_q + i). The wave streams its key range in 32-key tiles through its own two
-// LDS stages (the loads of tile j+1 run while tile j is computed) and per tile
-// does S^T = K Q^T, the exponentials and O^T += V^T P^T exactly like the
-// prefill kernel. Partial results of the splits are merged by the same combine
+// N_q + i). The wave streams its key range in 64-key load tiles through its own
+// two LDS stages (the loads of tile j+1 run while tile j is computed): 64 keys
+// are one whole 128-byte line of every V^T row, and reading V^T in half lines
+// costs a fifth of the bandwidth. A tile is two 32-key blocks whose score
+// chains, exponentials and products are independent of each other, which is
+// all the instruction-level parallelism a wave that is alone on its SIMD has:
+// S^T = K Q^T, the exponentials and O^T += V^T P^T as in the prefill kernel. Partial results of the splits are merged by the same combine
 // and mass kernels.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 {
-    constexpr int KB = 32;                       // keys per tile
+    constexpr int KB = 32;                       // keys per matrix-instruction block
+    constexpr int LB = EN_KEY_TILE;              // keys per tile
+    constexpr int NU = LB / KB;                  // blocks per tile
     constexpr int NKS = D / 16;
     constexpr int NDB = D / 32;
     constexpr int ROWB = 2 * D;
     constexpr int KSTR = ROWB + 16;              // padded K row in LDS
     constexpr int KCPR = KSTR / 16;
-    constexpr int KCHUNKS = KB * KCPR;           // 16-byte chunks of a K tile
-    constexpr int NBK = (KCHUNKS + 63) / 64;     // loader blocks, the last one partly dummy
+    constexpr int KCHUNKS = LB * KCPR;           // 16-byte chunks of a K tile
+    constexpr int NBK = KCHUNKS / 64;            // loader blocks
     constexpr int KBYTES = NBK * 1024;
-    constexpr int VSTR = KB * 2 + 16;            // padded V^T row in LDS (80 bytes)
-    constexpr int VCHUNKS = D * 5;
-    constexpr int NBV = VCHUNKS / 64;            // exact: D * 5 / 64
+    constexpr int VSTR = LB * 2 + 16;            // padded V^T row in LDS (144 bytes)
+    constexpr int VCPR = VSTR / 16;
+    constexpr int VCHUNKS = D * VCPR;
+    constexpr int NBV = VCHUNKS / 64;
     constexpr int VBYTES = NBV * 1024;
     constexpr int STAGE = KBYTES + VBYTES;
-    static_assert(VCHUNKS % 64 == 0, "V^T tile must be whole loader blocks");
+    static_assert(KCHUNKS % 64 == 0 && VCHUNKS % 64 == 0, "tiles must be whole loader blocks");
+    static_assert(NBK + NBV < 64, "the loads of one tile must fit the counter of outstanding loads");
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
 
-    const int per_xcd = gridDim.x / 8;
-    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    // no tile is shared between waves here, so consecutive workgroups (which go
+    // to different XCDs) simply take consecutive (agent, KV head, split) units
+    const int logical = blockIdx.x;
     if (logical >= a.total_wgs)
         return;
     int t = logical;
@@ -951,8 +959,9 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     // split boundaries are whole 64-key tiles, as everywhere else
     const int split_key_begin = (int)((long)sp * ntiles64 / a.n_splits) * EN_KEY_TILE;
     const int split_key_end = min((int)((long)(sp + 1) * ntiles64 / a.n_splits) * EN_KEY_TILE, Ltot);
-    const int t_begin = split_key_begin / KB;
-    const int t_end = (split_key_end + KB - 1) / KB;     // 32-key tiles; context rows are zero up to a multiple of 64
+    const int t_begin = split_key_begin, t_end = split_key_end;
+    const int lt_begin = split_key_begin / LB;           // load tiles; splits begin on them
+    const int lt_end = (split_key_end + LB - 1) / LB;    // context rows are zero up to a multiple of 64
 
     // ---- loader set-up ----
     const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
@@ -963,17 +972,17 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     for (int j = 0; j < NBK; ++j) {
         const int q = j * 64 + lane;
         const int row = q / KCPR, c = q % KCPR;
-        koff[j] = (q < KCHUNKS) ? (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16) : 0u;
+        koff[j] = (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16);      // the pad chunk re-reads chunk 0
     }
 #pragma unroll
     for (int j = 0; j < NBV; ++j) {
         const int q = j * 64 + lane;
-        const int d = q / 5, c = q % 5;
-        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < 4 ? c : 0) * 16);
+        const int d = q / VCPR, c = q % VCPR;
+        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < VCPR - 1 ? c : 0) * 16);
     }
-    auto issue = [&](int tile) {
-        const char *kt = kg + (size_t)tile * (KB * ROWB);
-        const char *vtile = vg + (size_t)tile * (KB * 2);
+    auto issue = [&](int tile) {                 // tile: a load tile
+        const char *kt = kg + (size_t)tile * (LB * ROWB);
+        const char *vtile = vg + (size_t)tile * (LB * 2);
         const uint32_t dst = lds0 + (tile & 1) * STAGE;
 #pragma unroll
         for (int j = 0; j < NBK; ++j)
@@ -1060,55 +1069,60 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     };
 
     if (t_begin < t_end)
-        issue(t_begin);
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        const char *sb = smem + (tile & 1) * STAGE;
+        issue(lt_begin);
+    for (int lt = lt_begin; lt < lt_end; ++lt) {
+        const char *stg = smem + (lt & 1) * STAGE;
         // every LDS read of the previous tile has returned (its matrix
         // instructions consumed them), so the other stage may be overwritten
         __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0)
-        if (tile + 1 < t_end) {
-            issue(tile + 1);
-            __builtin_amdgcn_s_waitcnt(((NBK + NBV) & 15) | (((NBK + NBV) >> 4) << 14) | 0x0f70);   // tile's loads landed
+        if (lt + 1 < lt_end) {
+            issue(lt + 1);
+            __builtin_amdgcn_s_waitcnt(((NBK + NBV) & 15) | (((NBK + NBV) >> 4) << 14) | 0x0f70);   // this tile's loads landed
         } else {
             __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
         }
         lds_data_ready();
-        const int kb = tile * KB;
-        // ---- S^T = K Q^T - m_ref ----
-        f32x16 sv;
+        const int kb = lt * LB;
+        // ---- S^T = K Q^T - m_ref, the two 32-key blocks as independent chains ----
+        f32x16 sv[NU];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(sb + klane + ks * 32);
-            if (ks == 0)
-                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[0], negm, 0, 0, 0);
-            else
-                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], sv, 0, 0, 0);
-        }
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(stg + u * (KB * KSTR) + klane + ks * 32);
+                sv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], ks == 0 ? negm : sv[u], 0, 0, 0);
+            }
         // causal / padding mask; columns differ in i, so every tile that reaches
-        // past L_c is checked
-        if (kb + KB - 1 > Lc) {
+        // past L_c is checked. Element e of block u is key 32 u + 8 (e / 4) + e % 4 + 4 half of the tile.
+        if (kb + LB - 1 > Lc) {
             const int rel = Lc + i_row - kb - 4 * half;
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                if (8 * (e / 4) + (e % 4) > rel)
-                    sv[e] = EN_NEG_INF;
+            for (int u = 0; u < NU; ++u)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (KB * u + 8 * (e / 4) + (e % 4) > rel)
+                        sv[u][e] = EN_NEG_INF;
         }
         // ---- reference (first visible tile, or near overflow) ----
         constexpr float BIG = 1.0e18f;
-        bf16x8 pf[2];
+        bf16x8 pf[NU][2];
         float rs = 0.f;
         {
-            float p[16];
+            float p[NU][16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                p[e] = fast_exp2(sv[e]);
-                rs += p[e];
-            }
+            for (int u = 0; u < NU; ++u)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    p[u][e] = fast_exp2(sv[u][e]);
+                    rs += p[u][e];
+                }
             if (__any(pending || !(rs < BIG))) {
-                float mx = sv[0];
+                float mx = sv[0][0];
 #pragma unroll
-                for (int e = 1; e < 16; ++e)
-                    mx = fmaxf(mx, sv[e]);
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        mx = fmaxf(mx, sv[u][e]);
                 mx = pair_max(mx);
                 const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
                 const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
@@ -1127,25 +1141,26 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     negm[e] = -m_ref;
-                rs = 0.f;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    p[e] = fast_exp2(sv[e] - delta);
-                    rs += p[e];
-                }
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        p[u][e] = fast_exp2(sv[u][e] - delta);
             }
             // the sums use the rounded probabilities, like the products
             rs = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const bf16_t pb = (bf16_t)p[e];
-                pf[e / 8][e % 8] = pb;
-                rs += (float)pb;
-            }
+            for (int u = 0; u < NU; ++u)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const bf16_t pb = (bf16_t)p[u][e];
+                    pf[u][e / 8][e % 8] = pb;
+                    rs += (float)pb;
+                }
         }
         l_part += rs;
         // ---- per-bucket partial sums ----
-        const int ke = min(kb + KB, split_key_end);
+        const int ke = min(kb + LB, split_key_end);
         if (cur_end > ke) {
             seg_part += rs;
         } else if (kb < split_key_end) {
@@ -1155,10 +1170,12 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
                 float part = 0.f;
                 const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int kr = 8 * (e / 4) + (e % 4);
-                    part += (kr >= rlo && kr < rhi) ? (float)pf[e / 8][e % 8] : 0.f;
-                }
+                for (int u = 0; u < NU; ++u)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kr = KB * u + 8 * (e / 4) + (e % 4);
+                        part += (kr >= rlo && kr < rhi) ? (float)pf[u][e / 8][e % 8] : 0.f;
+                    }
                 seg_part += part;
                 if (cur_end > ke || cur > S)
                     break;
@@ -1168,12 +1185,14 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         }
         // ---- O^T += V^T P^T ----
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
+        for (int u = 0; u < NU; ++u)
 #pragma unroll
-            for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(sb + vlane + kk * 32 + d * 32 * VSTR);
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[kk], o[d], 0, 0, 0);
-            }
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int d = 0; d < NDB; ++d) {
+                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(stg + u * (KB * 2) + vlane + kk * 32 + d * 32 * VSTR);
+                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[u][kk], o[d], 0, 0, 0);
+                }
     }
 
     if (seg_base)

@@ -191,6 +191,19 @@ def test_append_checks_without_device():
     assert plan.offsets(0).tolist() == [0, 3, 8]
 
 
+def test_pool_destroyed_before_its_plans_host_side():
+    lib = B.load()
+    pool = B.kv_pool_create(None, None, [3, 4, 5], 4, 1e4, 64, dtype=B.EN_F32, k_ptr=8, v_ptr=8,
+                            shape=(3, 1, 8, 64))
+    p1 = B.segment_select(pool, [0, 2], [0, 2], 4)
+    p2 = B.segment_select(pool, [1], [0, 1], 4)
+    p1.close()                            # one leaves the pool's list the ordinary way
+    h_pool, h_plan = pool.handle, p2.handle
+    pool.handle = p2.handle = None
+    assert lib.kv_pool_destroy(h_pool) == 0
+    assert lib.en_plan_destroy(h_plan) == 0
+
+
 def test_binding_closes_plans_before_their_pool():
     """Whatever order the garbage collector picks, a plan is never destroyed after its pool."""
     lens = np.array([3, 8, 0, 5], np.int32)

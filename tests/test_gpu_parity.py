@@ -376,6 +376,24 @@ def test_device_side_errors_and_timing_aid(step_mod):
     assert len(ms) == 3 and (ms > 0).all() and (ms < 50).all()
 
 
+def test_pool_destroyed_before_its_plan(step_mod):
+    """Handles released in the wrong order (as a garbage collector may do): the plan, which holds a
+    device block by now, is still destroyed cleanly."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    announce("destroy order: pool first, then a plan that was used on the device")
+    w = I.make_workload(small("destroy-order", 930))
+    st = step_mod.PlanningStep(w)
+    st.run()
+    torch.cuda.synchronize()
+    lib = B.load()
+    plan_handle, pool_handle = st.plan.handle, st.pool.handle
+    st.plan.handle = None                 # the wrappers must not release them again
+    st.pool.handle = None
+    assert lib.kv_pool_destroy(pool_handle) == 0
+    assert lib.en_plan_destroy(plan_handle) == 0
+
+
 def test_no_workspace_single_split(step_mod, oracle):
     """n_splits == 1 and no masses wanted: the attention call works without scratch."""
     import torch
