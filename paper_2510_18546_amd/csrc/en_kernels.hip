@@ -1458,30 +1458,45 @@ __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int
     return acc / L;
 }
 
-// reduce = 0. grid: (ceil(Nq/256), Hq, B); thread = query i; loops over buckets.
+// reduce = 0. grid: (ceil(Nq/64), Hq, B), 256 threads: the block takes 64 queries of one head.
+// The scratch is laid out query-fastest, the result bucket-fastest: each wave computes the
+// masses of its share of the buckets for the 64 queries (coalesced reads), the block transposes
+// them through LDS, 64 buckets at a time, and writes whole runs of buckets per query.
 __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    constexpr int SB = 64;                       // buckets per pass
+    __shared__ float tile[64][SB + 1];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int i = blockIdx.x * 64 + lane;
     const int hq = blockIdx.y, b = blockIdx.z;
-    if (i >= a.Nq)
-        return;
+    const bool valid = i < a.Nq;
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
-    const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+    const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + (valid ? i : 0);
     const int S = a.nseg[b];
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
     const int Ltot = bnd[S] + a.q_first + a.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     float M, L;
     row_final_ml(a, rows, row, M, L);
-    float *out = a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * (a.Smax + 1);
-    for (int s = 0; s <= a.Smax; ++s) {
-        float v = 0.f;
-        if (s <= S && bnd[s + 1] > bnd[s]) {
-            int lo, hi;
-            bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
-            v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+    for (int s0 = 0; s0 <= a.Smax; s0 += SB) {
+        const int n = min(SB, a.Smax + 1 - s0);
+        for (int c = wave; c < n; c += 4) {
+            const int s = s0 + c;
+            float v = 0.f;
+            if (valid && s <= S && bnd[s + 1] > bnd[s]) {
+                int lo, hi;
+                bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
+                v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+            }
+            tile[lane][c] = v;
         }
-        out[s] = v;
+        __syncthreads();
+        for (int r = wave; r < 64; r += 4) {
+            const int ir = blockIdx.x * 64 + r;
+            if (ir < a.Nq && lane < n)
+                a.out[(((size_t)b * a.Nq + ir) * a.Hq + hq) * (a.Smax + 1) + s0 + lane] = tile[r][lane];
+        }
+        __syncthreads();
     }
 }
 
@@ -1618,14 +1633,15 @@ __global__ __launch_bounds__(D / 2) void ctx_append_kernel(EnCtxAppendArgs a)
 
 // ---------------------------------------------------------------------------
 // cluster: score of every (object, segment) pair and the join / new-group
-// decision of Section 3.3. grid: (n_obj, B), 256 threads: the block walks the
-// buckets; for each it sums the masses of the object's (token, head) pairs.
+// decision of Section 3.3. Scores: grid (Smax+1, n_obj, B), 256 threads, the
+// block sums the masses that the object's (token, head) pairs put on one bucket.
+// Decision: one thread per (agent, object) walks that object's scores.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void cluster_kernel(EnClusterArgs a)
+__global__ __launch_bounds__(256) void cluster_score_kernel(EnClusterArgs a)
 {
     __shared__ float red[4];
     const EnMassArgs &m = a.m;
-    const int o = blockIdx.x, b = blockIdx.y;
+    const int s = blockIdx.x, o = blockIdx.y, b = blockIdx.z;
     // the spans are read from the argument segment itself (a run-time index into a
     // by-value argument would make a private copy of the whole array)
     const int32_t *spans = reinterpret_cast<const int32_t *>(
@@ -1637,43 +1653,55 @@ __global__ __launch_bounds__(256) void cluster_kernel(EnClusterArgs a)
     const int32_t *bnd = m.bnd + (size_t)b * (m.Smax + 2);
     const int Ltot = bnd[S] + m.q_first + m.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
-    float best = EN_NEG_INF;
-    int best_s = -1;
-    float *score = a.score + ((size_t)b * a.n_obj + o) * (m.Smax + 1);
-    for (int s = 0; s <= m.Smax; ++s) {
-        const int len = s <= S ? bnd[s + 1] - bnd[s] : 0;
-        float acc = 0.f;
-        if (len > 0) {
-            int slo, shi;
-            bucket_splits(m.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], slo, shi);
-            for (int idx = threadIdx.x; idx < n_pairs; idx += 256) {
-                const int i = lo + idx / m.Hq, hq = idx % m.Hq;
-                const size_t row = ((size_t)b * m.Hq + hq) * m.Nq + i;
-                float M, L;
-                row_final_ml(m, rows, row, M, L);
-                acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L);
-            }
-        }
-        acc = wave_sum(acc);
-        __syncthreads();
-        if (threadIdx.x % 64 == 0)
-            red[threadIdx.x / 64] = acc;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float v = (red[0] + red[1] + red[2] + red[3]) / (float)n_pairs;
-            if (a.per_key && s < S && len > 0)       // the new tokens' own bucket stays a mass
-                v /= (float)len;
-            if (a.accumulate)
-                v += score[s];
-            score[s] = v;
-            if (s < S && len > 0 && v * a.scale > best) {
-                best = v * a.scale;
-                best_s = s;
-            }
+    const int len = s <= S ? bnd[s + 1] - bnd[s] : 0;
+    float acc = 0.f;
+    if (len > 0) {
+        int slo, shi;
+        bucket_splits(m.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], slo, shi);
+        for (int idx = threadIdx.x; idx < n_pairs; idx += 256) {
+            // token fastest: neighbouring lanes read neighbouring scratch entries
+            const int hq = idx / (hi - lo), i = lo + idx % (hi - lo);
+            const size_t row = ((size_t)b * m.Hq + hq) * m.Nq + i;
+            float M, L;
+            row_final_ml(m, rows, row, M, L);
+            acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L);
         }
     }
-    if (threadIdx.x == 0 && a.assign)
-        a.assign[(size_t)b * a.n_obj + o] = (best_s >= 0 && best >= a.threshold) ? best_s : -1;
+    acc = wave_sum(acc);
+    if (threadIdx.x % 64 == 0)
+        red[threadIdx.x / 64] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float *score = a.score + ((size_t)b * a.n_obj + o) * (m.Smax + 1) + s;
+        float v = (red[0] + red[1] + red[2] + red[3]) / (float)n_pairs;
+        if (a.per_key && s < S && len > 0)       // the new tokens' own bucket stays a mass
+            v /= (float)len;
+        if (a.accumulate)
+            v += *score;
+        *score = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void cluster_decide_kernel(EnClusterArgs a)
+{
+    const EnMassArgs &m = a.m;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= m.B * a.n_obj)
+        return;
+    const int b = idx / a.n_obj;
+    const int S = m.nseg[b];
+    const int32_t *bnd = m.bnd + (size_t)b * (m.Smax + 2);
+    const float *score = a.score + (size_t)idx * (m.Smax + 1);
+    float best = EN_NEG_INF;
+    int best_s = -1;
+    for (int s = 0; s < S; ++s) {
+        const float v = score[s] * a.scale;
+        if (bnd[s + 1] > bnd[s] && v > best) {   // empty segments never win; the lowest s among equals
+            best = v;
+            best_s = s;
+        }
+    }
+    a.assign[idx] = (best_s >= 0 && best >= a.threshold) ? best_s : -1;
 }
 
 // ---------------------------------------------------------------------------
@@ -1832,8 +1860,12 @@ int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *st
 int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream)
 {
     (void)pool;
-    const dim3 grid(a.n_obj, a.m.B), blk(256);
-    hipLaunchKernelGGL(cluster_kernel, grid, blk, 0, (hipStream_t)stream, a);
+    const dim3 grid(a.m.Smax + 1, a.n_obj, a.m.B), blk(256);
+    hipLaunchKernelGGL(cluster_score_kernel, grid, blk, 0, (hipStream_t)stream, a);
+    if (a.assign) {
+        const dim3 grid2((a.m.B * a.n_obj + 255) / 256);
+        hipLaunchKernelGGL(cluster_decide_kernel, grid2, blk, 0, (hipStream_t)stream, a);
+    }
     return (int)hipGetLastError();
 }
 
@@ -1859,7 +1891,7 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
     (void)pool;
     hipStream_t st = (hipStream_t)stream;
     if (reduce == 0) {
-        const dim3 grid((a.Nq + 255) / 256, a.Hq, a.B), blk(256);
+        const dim3 grid((a.Nq + 63) / 64, a.Hq, a.B), blk(256);
         hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
     } else {
         // with several splits stage 1 has already run in the combine launch
