@@ -348,6 +348,14 @@ int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n
  *                   unrotated; copied into the store before the call returns
  *                   (waits for loads in flight). A device copy of the group
  *                   becomes stale and is dropped.
+ *   kv_tier_append: as kv_pool_append (Section 3.2: new objects' KV is saved at
+ *                   the end of the group's cache), for a group of the store:
+ *                   k_rows_dev, v_rows_dev device [n_tokens, Hkv, D]. Enqueues
+ *                   on `stream` the copy of the rows to the end of the block in
+ *                   the store and, if the group is resident, in its slot, and
+ *                   counts them in at once (plans made later see the new
+ *                   length). Loads issued later wait for it. CAPACITY if the
+ *                   block cannot hold them.
  *   kv_tier_select_scored : Eq. (1) as in segment_select_scored, over the
  *                   store's groups and lengths (groups never put are not
  *                   candidates); groups_out_host int32 [n_groups_total].
@@ -355,7 +363,8 @@ int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n
  *                   slots_out_host int32 [n] receives the slot of each.
  *   kv_tier_residency : slot_of_group_out_host int32 [n_groups_total], the
  *                   slot each group occupies or -1.
- * One tier is used by one thread at a time.
+ * One tier is used by one thread at a time. The calls record and wait for events:
+ * they are not for streams under graph capture.
  * Errors: INVALID_ARG, OUT_OF_RANGE (group outside the store or never put,
  *         len > C), DUPLICATE, CAPACITY (more groups than slots), UNSUPPORTED
  *         (as kv_pool_create), DEVICE.
@@ -377,6 +386,8 @@ int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev
                    en_tier **out);
 en_pool *kv_tier_pool(en_tier *tier);
 int kv_tier_put(en_tier *tier, int32_t group, const void *k_host, const void *v_host, int32_t len);
+int kv_tier_append(en_tier *tier, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                   int32_t n_tokens, void *stream);
 int kv_tier_select_scored(const en_tier *tier, const float *p_host, float threshold,
                           int64_t budget_tokens, int32_t *groups_out_host, int32_t *n_out);
 int kv_tier_fetch(en_tier *tier, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,

@@ -27,7 +27,8 @@ EXPORTS = [
     "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
     "en_decode_workspace_bytes", "segmented_decode_step", "en_timing_enable",
     "en_timing_collect", "en_last_error",
-    "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_select_scored",
+    "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_append",
+    "kv_tier_select_scored",
     "kv_tier_fetch", "kv_tier_fence", "kv_tier_prefetch", "kv_tier_get_stats", "kv_tier_residency",
     "kv_tier_destroy",
 ]
@@ -102,6 +103,7 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.kv_tier_pool.argtypes = [vp]
     lib.kv_tier_pool.restype = vp
     lib.kv_tier_put.argtypes = [vp, C.c_int32, vp, vp, C.c_int32]
+    lib.kv_tier_append.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp]
     lib.kv_tier_select_scored.argtypes = [vp, C.POINTER(C.c_float), C.c_float, C.c_int64, i32p, i32p]
     lib.kv_tier_fetch.argtypes = [vp, i32p, C.c_int32, i32p, vp]
     lib.kv_tier_fence.argtypes = [vp, vp]
@@ -400,6 +402,18 @@ def kv_tier_put(tier: Tier, group: int, k_rows, v_rows, length: Optional[int] = 
     length = int(k_rows.shape[1]) if length is None else int(length)
     _check(load().kv_tier_put(tier.handle, int(group), C.c_void_p(k_rows.data_ptr()),
                               C.c_void_p(v_rows.data_ptr()), length))
+
+
+def kv_tier_append(tier: Tier, group: int, k_rows, v_rows, n_tokens: Optional[int] = None, stream=None):
+    """k_rows, v_rows: torch tensors [n, Hkv, D] on the GPU (contiguous, tier dtype, keys unrotated); for a
+    tier that only keeps the books pass None and n_tokens."""
+    if k_rows is None:
+        _check(load().kv_tier_append(tier.handle, int(group), None, None, int(n_tokens), C.c_void_p(0)))
+        return
+    assert k_rows.is_contiguous() and v_rows.is_contiguous() and k_rows.shape == v_rows.shape
+    n_tokens = int(k_rows.shape[0]) if n_tokens is None else int(n_tokens)
+    _check(load().kv_tier_append(tier.handle, int(group), C.c_void_p(k_rows.data_ptr()),
+                                 C.c_void_p(v_rows.data_ptr()), n_tokens, _stream(stream)))
 
 
 def kv_tier_select_scored(tier: Tier, p, threshold: float, budget_tokens: int) -> np.ndarray:

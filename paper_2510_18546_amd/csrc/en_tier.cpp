@@ -41,7 +41,8 @@ struct en_tier {
     const char *v_store_dev = nullptr;
     std::vector<int32_t> pending;  // blocks to load with the next launch: group, slot, tokens
     hipStream_t copy = nullptr;
-    hipEvent_t ev_fence = nullptr, ev_copy = nullptr;
+    hipEvent_t ev_fence = nullptr, ev_copy = nullptr, ev_append = nullptr;
+    bool append_pending = false;   // an append is writing the store on the caller's stream
     en_tier_stats st{};
 };
 
@@ -77,6 +78,10 @@ extern "C" int kv_tier_destroy(en_tier *t)
             (void)hipEventDestroy(t->ev_fence);
         if (t->ev_copy)
             (void)hipEventDestroy(t->ev_copy);
+        if (t->ev_append) {
+            (void)hipEventSynchronize(t->ev_append);
+            (void)hipEventDestroy(t->ev_append);
+        }
         if (t->copy)
             (void)hipStreamDestroy(t->copy);
         if (t->k_host)
@@ -147,7 +152,8 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
     t->v_store_dev = (const char *)vd;
     if ((e = hipStreamCreateWithFlags(&t->copy, hipStreamNonBlocking)) != hipSuccess ||
         (e = hipEventCreateWithFlags(&t->ev_fence, hipEventDisableTiming)) != hipSuccess ||
-        (e = hipEventCreateWithFlags(&t->ev_copy, hipEventDisableTiming)) != hipSuccess) {
+        (e = hipEventCreateWithFlags(&t->ev_copy, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&t->ev_append, hipEventDisableTiming)) != hipSuccess) {
         rc = thip(e, "kv_tier_create: stream / event");
         kv_tier_destroy(t);
         return rc;
@@ -184,10 +190,14 @@ extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const 
     if (!t->dry) {
         if (len > 0 && (!k_host || !v_host))
             return tfail(EN_ERR_INVALID_ARG, "kv_tier_put: null rows");
-        // a load of this block may still be reading the store
-        const hipError_t e = hipStreamSynchronize(t->copy);
+        // a load of this block may still be reading the store, an append writing it
+        hipError_t e = hipStreamSynchronize(t->copy);
+        if (e == hipSuccess && t->append_pending) {
+            e = hipEventSynchronize(t->ev_append);
+            t->append_pending = false;
+        }
         if (e != hipSuccess)
-            return thip(e, "kv_tier_put: hipStreamSynchronize");
+            return thip(e, "kv_tier_put: wait for the store");
         const size_t head_src = size_t(len) * t->row_bytes;
         const size_t head_dst = size_t(t->d.capacity) * t->row_bytes;
         for (int h = 0; h < t->d.n_kv_heads && len > 0; ++h) {
@@ -199,6 +209,65 @@ extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const 
     }
     t->len[group] = len;
     drop_resident(t, group);      // the device copy, if any, is stale
+    return EN_OK;
+}
+
+extern "C" int kv_tier_append(en_tier *t, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                              int32_t n_tokens, void *stream)
+{
+    if (!t || n_tokens < 0)
+        return tfail(EN_ERR_INVALID_ARG, "kv_tier_append: null tier or negative count");
+    if (group < 0 || group >= t->G || t->len[group] < 0)
+        return tfail(EN_ERR_OUT_OF_RANGE, "kv_tier_append: group outside the store or never put");
+    const int len = t->len[group];
+    if (long(len) + n_tokens > t->d.capacity)
+        return tfail(EN_ERR_CAPACITY, "kv_tier_append: the block is full");
+    if (n_tokens == 0)
+        return EN_OK;
+    if (!t->dry) {
+        if (!k_rows_dev || !v_rows_dev)
+            return tfail(EN_ERR_INVALID_ARG, "kv_tier_append: null rows");
+        hipStream_t st = (hipStream_t)stream;
+        hipError_t e;
+        // loads still in flight may be reading this block of the store, or filling the slot
+        if (t->unjoined) {
+            if ((e = hipEventRecord(t->ev_copy, t->copy)) != hipSuccess ||
+                (e = hipStreamWaitEvent(st, t->ev_copy, 0)) != hipSuccess)
+                return thip(e, "kv_tier_append: join of the loads");
+            t->unjoined = false;
+        }
+        EnAppendArgs a;
+        a.k_rows = k_rows_dev;
+        a.v_rows = v_rows_dev;
+        a.n = n_tokens;
+        a.Hkv = t->d.n_kv_heads;
+        a.C = t->d.capacity;
+        a.first = len;
+        a.row_chunks = int(t->row_bytes / 16);
+        // the store: the same copy kernel, writing host memory
+        a.k_pool = const_cast<char *>(t->k_store_dev);
+        a.v_pool = const_cast<char *>(t->v_store_dev);
+        a.group = group;
+        int rc = en_launch_append(t->pool, a, stream);
+        const int slot = t->slot_of[group];
+        if (rc == 0 && slot >= 0) {        // and the device copy, if there is one
+            a.k_pool = t->pool->k_dev;
+            a.v_pool = t->pool->v_dev;
+            a.group = slot;
+            rc = en_launch_append(t->pool, a, stream);
+        }
+        if (rc != 0)
+            return thip((hipError_t)rc, "kv_tier_append: launch");
+        // later loads of the block must see the new rows
+        if ((e = hipEventRecord(t->ev_append, st)) != hipSuccess ||
+            (e = hipStreamWaitEvent(t->copy, t->ev_append, 0)) != hipSuccess)
+            return thip(e, "kv_tier_append: ordering of later loads");
+        t->append_pending = true;
+    }
+    t->len[group] = len + n_tokens;
+    const int slot = t->slot_of[group];
+    if (slot >= 0 && t->pool)
+        t->pool->len[slot] = len + n_tokens;
     return EN_OK;
 }
 

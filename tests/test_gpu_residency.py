@@ -181,3 +181,55 @@ def test_put_replaces_a_resident_group(mods):
     plan = B.segment_select(tier.pool, s1, [0, 1], 4)
     assert plan.offsets(0).tolist() == [0, 7]          # the slot carries the new length
     tier.close()
+
+
+@pytest.mark.parametrize("base", ["c1", "c0"])
+def test_append_reaches_the_store_and_the_resident_copy(mods, base):
+    """Section 3.2: the KV of objects that join a group is saved at the end of the group's cache. With a
+    tier that is the store's block and, if the group is resident, its slot; a group that is displaced
+    and loaded again comes back with the appended rows."""
+    import torch
+    B, _ = mods
+    cfg = I.variant(I.CONFIGS[base], n_groups=4, seed=17, n_sel=2, fixed_sel=None,
+                    len_lo=5, len_hi=I.CONFIGS[base].capacity - 9)
+    w = I.make_workload(cfg)
+    announce(f"tier append: {base} dtype={cfg.dtype} G=4 slots=2 lens={w.lens.tolist()}")
+    tier, blocks = make_tier(B, cfg, w, 2, 4096)
+    dt = blocks[0][0].dtype
+    gen = torch.Generator().manual_seed(3)
+    new = {g: (torch.randn((n, cfg.n_kv_heads, cfg.head_dim), generator=gen).to(dt),
+               torch.randn((n, cfg.n_kv_heads, cfg.head_dim), generator=gen).to(dt))
+           for g, n in ((0, 7), (2, 3))}
+
+    def expect(g):
+        k, v = blocks[g]
+        if g in new:
+            k = torch.cat([k, new[g][0].permute(1, 0, 2)], dim=1)
+            v = torch.cat([v, new[g][1].permute(1, 0, 2)], dim=1)
+        return k, v
+
+    def check(groups, slots):
+        torch.cuda.synchronize()
+        for g, s in zip(groups, slots):
+            k, v = expect(g)
+            n = k.shape[1]
+            assert tier.pool.desc.capacity >= n
+            assert np.array_equal(bits(tier.pool.k[s, :, :n, :]), bits(k)), g
+            assert np.array_equal(bits(tier.pool.v[s, :, :n, :]), bits(v)), g
+            plan = B.segment_select(tier.pool, [s], [0, 1], 4)
+            assert plan.offsets(0).tolist() == [0, n]
+            plan.close()
+
+    s01 = B.kv_tier_fetch(tier, [0, 1])
+    for g in (0, 2):                       # 0 is resident, 2 is not
+        B.kv_tier_append(tier, g, new[g][0].cuda(), new[g][1].cuda())
+    check([0, 1], s01)
+    s23 = B.kv_tier_fetch(tier, [2, 3])     # displaces 0 and 1; 2 comes from the store with its new rows
+    check([2, 3], s23)
+    s01 = B.kv_tier_fetch(tier, [1, 0])     # 0 comes back from the store with its new rows
+    check([1, 0], s01)
+    with pytest.raises(B.EnError) as e:
+        B.kv_tier_append(tier, 1, torch.zeros((cfg.capacity, cfg.n_kv_heads, cfg.head_dim), dtype=dt).cuda(),
+                         torch.zeros((cfg.capacity, cfg.n_kv_heads, cfg.head_dim), dtype=dt).cuda())
+    assert e.value.code == 4
+    tier.close()

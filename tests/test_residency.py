@@ -229,3 +229,20 @@ def test_hit_rate_grows_with_the_budget_on_drifting_scores():
         t.close()
     assert rates == sorted(rates)
     assert rates[-1] > 0.9 and rates[0] < rates[-1]
+
+
+def test_tier_append_bookkeeping():
+    t = B.kv_tier_create(None, None, 3, 32, 1e4, 4096, dtype=B.EN_BF16, shape=(2,) + SHAPE)
+    B.kv_tier_put(t, 0, None, None, 4)
+    B.kv_tier_put(t, 1, None, None, SHAPE[1] - 1)
+    B.kv_tier_append(t, 0, None, None, 5)
+    B.kv_tier_fetch(t, [0])
+    Hkv, Cap, D = SHAPE
+    assert t.stats.bytes_loaded == 2 * Hkv * D * 2 * 9           # the appended rows are part of the block
+    B.kv_tier_append(t, 1, None, None, 1)
+    for group, n, code in ((1, 1, 4), (2, 1, 2), (3, 1, 2), (0, -1, 1)):
+        with pytest.raises(B.EnError) as e:
+            B.kv_tier_append(t, group, None, None, n)
+        assert e.value.code == code, (group, n)
+    assert B.kv_tier_select_scored(t, np.array([1, 1, 1], np.float32), 0.0, 9).tolist() == [0]
+    t.close()
