@@ -230,3 +230,29 @@ def test_cluster_assign_checks_without_device():
     with pytest.raises(B.EnError) as e:
         B.segment_cluster_assign(pool, plan, 0x5000, list(range(0, 7)) * 50, 0x6000, None)
     assert e.value.code in (1, 5)
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The oracle is test infrastructure: nothing under the package imports it, and the oracle imports
+    nothing of the package; only the seeded input generators serve both."""
+    import ast
+    import glob
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imported(path):
+        names = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                names.update(a.name.split(".")[0] for a in node.names)
+            elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+                names.add(node.module.split(".")[0])
+        return names
+    for path in glob.glob(os.path.join(root, "paper_2510_18546_amd", "*.py")):
+        assert "oracle" not in imported(path), path
+    for path in glob.glob(os.path.join(root, "oracle", "*.py")):
+        assert "paper_2510_18546_amd" not in imported(path), path
+    # the C sources of the two sides include nothing of each other
+    for path in glob.glob(os.path.join(root, "paper_2510_18546_amd", "csrc", "*")):
+        assert "oracle" not in open(path).read().lower(), path
+    assert "efficientnav.h" not in open(os.path.join(root, "oracle", "en_oracle.c")).read()
