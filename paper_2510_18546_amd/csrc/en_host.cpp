@@ -186,13 +186,19 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
     const int r = pool->r;
     if (pool->d.dtype == EN_BF16 && r * pl->Nq <= EN_ROWS_PER_WAVE) {
         // decode path: one wave per (agent, KV head, split); the two LDS stages
-        // of a wave let two waves share a compute unit. Two rounds of waves
-        // measured faster than one (0.73 against 0.78 ms on 64 agents x 16 K
-        // tokens); at least eight 64-key tiles per split
+        // of a wave let two waves share a compute unit, and a wave takes about
+        // 2 us per 64-key tile whatever the load: as many splits as give every
+        // compute unit its two waves (measured on 1 and 4 agents x 8 K tokens:
+        // more waves than that only add start-up and merge work), at least four
+        // tiles per split. Long contexts of many agents are the exception: two
+        // splits measured faster than one (0.73 against 0.78 ms on 64 agents x
+        // 16 K tokens).
         const long base = long(pl->B) * pool->d.n_kv_heads;
         const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
-        long want = (4L * pool->n_cu + base - 1) / base;
-        want = std::min<long>(want, std::max(1, tiles / 8));
+        long want = (2L * pool->n_cu + base - 1) / base;
+        if (want < 2 && tiles >= 64)
+            want = 2;
+        want = std::min<long>(want, std::max(1, tiles / 4));
         return int(std::max<long>(1, std::min<long>(want, 64)));
     }
     const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;

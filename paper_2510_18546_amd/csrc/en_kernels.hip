@@ -911,6 +911,10 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 template <int D>
 __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 {
+    // two LDS stages; a third (two tiles in flight per wave) was tried for grids of at most one
+    // wave per compute unit and changed nothing: a lone wave is bound by issuing its own
+    // instructions (about 2 us per tile), not by waiting for its loads
+    constexpr int NST = 2;
     constexpr int KB = 32;                       // keys per matrix-instruction block
     constexpr int LB = EN_KEY_TILE;              // keys per tile
     constexpr int NU = LB / KB;                  // blocks per tile
@@ -930,7 +934,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     constexpr int STAGE = KBYTES + VBYTES;
     static_assert(KCHUNKS % 64 == 0 && VCHUNKS % 64 == 0, "tiles must be whole loader blocks");
     static_assert(NBK + NBV < 64, "the loads of one tile must fit the counter of outstanding loads");
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE];
 
     // no tile is shared between waves here, so consecutive workgroups (which go
     // to different XCDs) simply take consecutive (agent, KV head, split) units
@@ -980,10 +984,10 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         const int d = q / VCPR, c = q % VCPR;
         voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < VCPR - 1 ? c : 0) * 16);
     }
-    auto issue = [&](int tile) {                 // tile: a load tile
+    auto issue = [&](int tile, int stage) {
         const char *kt = kg + (size_t)tile * (LB * ROWB);
         const char *vtile = vg + (size_t)tile * (LB * 2);
-        const uint32_t dst = lds0 + (tile & 1) * STAGE;
+        const uint32_t dst = lds0 + stage * STAGE;
 #pragma unroll
         for (int j = 0; j < NBK; ++j)
             dma16(kt, koff[j], dst + j * 1024);
@@ -1069,15 +1073,18 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     };
 
     if (t_begin < t_end)
-        issue(lt_begin);
+        issue(lt_begin, 0);
+    int stage = 0;                               // of tile lt
     for (int lt = lt_begin; lt < lt_end; ++lt) {
-        const char *stg = smem + (lt & 1) * STAGE;
+        const char *stg = smem + stage * STAGE;
         // every LDS read of the previous tile has returned (its matrix
-        // instructions consumed them), so the other stage may be overwritten
+        // instructions consumed them), so its stage may be overwritten
         __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0)
+        constexpr int PER_TILE = NBK + NBV;
         if (lt + 1 < lt_end) {
-            issue(lt + 1);
-            __builtin_amdgcn_s_waitcnt(((NBK + NBV) & 15) | (((NBK + NBV) >> 4) << 14) | 0x0f70);   // this tile's loads landed
+            issue(lt + 1, stage ^ 1);
+            // this tile's loads have landed when at most the next tile's are outstanding
+            __builtin_amdgcn_s_waitcnt((PER_TILE & 15) | ((PER_TILE >> 4) << 14) | 0x0f70);
         } else {
             __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
         }
@@ -1193,6 +1200,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
                     const bf16x8 av = *reinterpret_cast<const bf16x8 *>(stg + u * (KB * 2) + vlane + kk * 32 + d * 32 * VSTR);
                     o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[u][kk], o[d], 0, 0, 0);
                 }
+        stage ^= 1;
     }
 
     if (seg_base)
@@ -1359,20 +1367,18 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
 // output row. grid: ceil(rows * D / V / 256), V = elements in 16 bytes.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red);
-__device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_t pair);
 constexpr int EN_MASS_FEW_ROWS = 64;      // below this many query rows per head the partial sums go thread-wise
 
-template <typename T, int D>
+// With many splits (decode over a long context by few agents) G = 4 neighbouring lanes share a
+// (row, 16-byte chunk): lane g takes the splits g, g + 4, ... and the four partial results are
+// merged with lane shuffles, so that the chain of dependent loads is a quarter as long.
+template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m, int n_comb)
 {
     // tail of the grid: per-head partial sums of the segment masses
     if ((int)blockIdx.x >= n_comb) {
         __shared__ float red[4];
         int t = blockIdx.x - n_comb;
-        if (m.Nq < EN_MASS_FEW_ROWS) {
-            mass_partial_few_rows(m, (size_t)t * 256 + threadIdx.x);
-            return;
-        }
         const int s = t % (m.Smax + 1);
         t /= (m.Smax + 1);
         mass_partial_block(m, s, t % m.Hq, t / m.Hq, red);
@@ -1382,24 +1388,63 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
     typedef T tvec __attribute__((ext_vector_type(V)));
     typedef float fvec __attribute__((ext_vector_type(V)));
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int g = (int)(idx % G);
+    idx /= G;
     if (idx >= rows * (D / V))
         return;
     const size_t row = idx / (D / V);
     const int d0 = (int)(idx % (D / V)) * V;
+    // the splits are read in batches of independent loads: one after the other, the latencies
+    // of 2 * n_splits dependent loads are what this kernel would take
+    constexpr int NB = 4;
     float M = EN_NEG_INF;
-    for (int sp = 0; sp < a.n_splits; ++sp)
-        M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
+    for (int sp0 = g; sp0 < a.n_splits; sp0 += NB * G) {
+        float mm[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            mm[j] = sp0 + j * G < a.n_splits ? a.ws_ml[((size_t)(sp0 + j * G) * rows + row) * 2] : EN_NEG_INF;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            M = fmaxf(M, mm[j]);
+    }
+    if constexpr (G > 1) {
+#pragma unroll
+        for (int o = 1; o < G; o <<= 1)
+            M = fmaxf(M, __shfl_xor(M, o, 64));
+    }
     float l = 0.f;
     fvec acc = 0.f;
-    for (int sp = 0; sp < a.n_splits; ++sp) {
-        const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
-        if (ml[0] == EN_NEG_INF)
-            continue;
-        const float w = ml[1] * exp2f(ml[0] - M);
-        l += w;
-        const tvec v = *reinterpret_cast<const tvec *>((const T *)a.ws_opart + ((size_t)sp * rows + row) * D + d0);
-        acc += __builtin_convertvector(v, fvec) * w;
+    for (int sp0 = g; sp0 < a.n_splits; sp0 += NB * G) {
+        f32x2 ml[NB];
+        tvec v[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const bool on = sp0 + j * G < a.n_splits;
+            const size_t r = (size_t)(on ? sp0 + j * G : 0) * rows + row;
+            ml[j] = *reinterpret_cast<const f32x2 *>(a.ws_ml + r * 2);
+            v[j] = *reinterpret_cast<const tvec *>((const T *)a.ws_opart + r * D + d0);
+            if (!on)
+                ml[j][0] = EN_NEG_INF;
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            // a split that saw no key of this row left (-inf, 0) and an output that is not to be used
+            const float w = ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * exp2f(ml[j][0] - M);
+            l += w;
+            acc += w == 0.f ? (fvec)0.f : __builtin_convertvector(v[j], fvec) * w;
+        }
+    }
+    if constexpr (G > 1) {
+#pragma unroll
+        for (int o = 1; o < G; o <<= 1) {
+            l += __shfl_xor(l, o, 64);
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                acc[e] += __shfl_xor(acc[e], o, 64);
+        }
+        if (g != 0)
+            return;
     }
     const float inv = 1.f / l;
     if (d0 == 0 && a.ws_mlfin) {
@@ -1429,20 +1474,50 @@ __device__ __forceinline__ void row_final_ml(const EnMassArgs &a, size_t rows, s
     L = p[1];
 }
 
+// The row's reference maximum and sum merged from the splits' pairs (what the combine kernel
+// writes to ws_mlfin, for code that runs beside it). Independent loads in batches of four.
+__device__ __forceinline__ void merged_ml(const EnMassArgs &a, size_t rows, size_t row, float &M, float &L)
+{
+    constexpr int NB = 4;
+    M = EN_NEG_INF;
+    L = 0.f;
+    for (int sp0 = 0; sp0 < a.n_splits; sp0 += NB) {
+        f32x2 ml[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            ml[j] = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)(sp0 + j < a.n_splits ? sp0 + j : 0) * rows + row) * 2);
+            if (sp0 + j >= a.n_splits)
+                ml[j][0] = EN_NEG_INF;
+        }
+        float Mb = M;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            Mb = fmaxf(Mb, ml[j][0]);
+        if (Mb == EN_NEG_INF)
+            continue;
+        L *= M == EN_NEG_INF ? 0.f : exp2f(M - Mb);
+        M = Mb;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            L += ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * exp2f(ml[j][0] - M);
+    }
+}
+
 // Splits whose key range meets bucket [blo, bhi): a contiguous range [lo, hi].
 __device__ __forceinline__ void bucket_splits(int n_splits, int ntiles, int Ltot, int blo, int bhi,
                                               int &lo, int &hi)
 {
-    lo = n_splits;
-    hi = -1;
-    for (int sp = 0; sp < n_splits; ++sp) {
-        const int kb = (sp * ntiles / n_splits) * EN_KEY_TILE;
-        const int ke = min(((sp + 1) * ntiles / n_splits) * EN_KEY_TILE, Ltot);
-        if (max(kb, blo) < min(ke, bhi)) {
-            lo = min(lo, sp);
-            hi = max(hi, sp);
-        }
+    // split sp covers tiles [sp * ntiles / n_splits, (sp + 1) * ntiles / n_splits): the split that
+    // holds tile t is the largest sp whose first tile is <= t, i.e. ((t + 1) * n_splits - 1) / ntiles
+    bhi = min(bhi, Ltot);          // a decode step's rows see less than the plan's whole new block
+    if (bhi <= blo) {
+        lo = n_splits;
+        hi = -1;
+        return;
     }
+    const int t_lo = blo / EN_KEY_TILE, t_hi = (bhi - 1) / EN_KEY_TILE;
+    lo = (int)(((long)(t_lo + 1) * n_splits - 1) / ntiles);
+    hi = (int)(((long)(t_hi + 1) * n_splits - 1) / ntiles);
 }
 
 __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int hq, int i, int bucket,
@@ -1521,14 +1596,8 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, i
         bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
         for (int i = threadIdx.x; i < a.Nq; i += 256) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
-            float M = EN_NEG_INF, L = 0.f;
-            for (int sp = 0; sp < a.n_splits; ++sp)
-                M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
-            for (int sp = 0; sp < a.n_splits; ++sp) {
-                const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
-                if (ml[0] != EN_NEG_INF)
-                    L += ml[1] * exp2f(ml[0] - M);
-            }
+            float M, L;
+            merged_ml(a, rows, row, M, L);
             acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
         }
     }
@@ -1541,7 +1610,9 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, i
 }
 
 // The same for few query rows per head (decode steps): one THREAD per (agent, bucket, head) walks
-// the rows, so that a step of one token does not launch a workgroup per (bucket, head).
+// the rows, so that a step of one token does not launch a workgroup per (bucket, head). This form
+// is a launch of its own in the mass call, whatever the number of splits: a decode step that asks
+// for no masses then does no work for them.
 __device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_t pair)
 {
     if (pair >= (size_t)a.B * (a.Smax + 1) * a.Hq)
@@ -1560,14 +1631,8 @@ __device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_
         bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
         for (int i = 0; i < a.Nq; ++i) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
-            float M = EN_NEG_INF, L = 0.f;
-            for (int sp = 0; sp < a.n_splits; ++sp)
-                M = fmaxf(M, a.ws_ml[((size_t)sp * rows + row) * 2]);
-            for (int sp = 0; sp < a.n_splits; ++sp) {
-                const f32x2 ml = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)sp * rows + row) * 2);
-                if (ml[0] != EN_NEG_INF)
-                    L += ml[1] * exp2f(ml[0] - M);
-            }
+            float M, L;
+            row_final_ml(a, rows, row, M, L);      // runs after the combine launch: the merged pair is there
             acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
         }
     }
@@ -1819,22 +1884,30 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     hipStream_t st = (hipStream_t)stream;
     const int D = pool->d.head_dim;
     const int vec = pool->d.dtype == EN_F32 ? 4 : 8;      // elements in 16 bytes
-    const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec);
+    const int G = a.n_splits > 8 ? 4 : 1;                 // lanes that share a (row, chunk)
+    const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec) * G;
     const int n_comb = (int)((n + 255) / 256);
-    const int n_part = m.Nq < EN_MASS_FEW_ROWS ? ((m.Smax + 1) * m.Hq * m.B + 255) / 256
-                                               : (m.Smax + 1) * m.Hq * m.B;
+    const int n_part = m.Nq < EN_MASS_FEW_ROWS ? 0 : (m.Smax + 1) * m.Hq * m.B;
     const dim3 grid((unsigned)(n_comb + n_part)), blk(256);
+#define EN_COMBINE(T, DD)                                                                             \
+    do {                                                                                              \
+        if (G == 1)                                                                                   \
+            hipLaunchKernelGGL((combine_kernel<T, DD, 1>), grid, blk, 0, st, a, m, n_comb);           \
+        else                                                                                          \
+            hipLaunchKernelGGL((combine_kernel<T, DD, 4>), grid, blk, 0, st, a, m, n_comb);           \
+    } while (0)
     if (pool->d.dtype == EN_F32) {
         if (D == 64)
-            hipLaunchKernelGGL((combine_kernel<float, 64>), grid, blk, 0, st, a, m, n_comb);
+            EN_COMBINE(float, 64);
         else
-            hipLaunchKernelGGL((combine_kernel<float, 128>), grid, blk, 0, st, a, m, n_comb);
+            EN_COMBINE(float, 128);
     } else {
         if (D == 64)
-            hipLaunchKernelGGL((combine_kernel<bf16_t, 64>), grid, blk, 0, st, a, m, n_comb);
+            EN_COMBINE(bf16_t, 64);
         else
-            hipLaunchKernelGGL((combine_kernel<bf16_t, 128>), grid, blk, 0, st, a, m, n_comb);
+            EN_COMBINE(bf16_t, 128);
     }
+#undef EN_COMBINE
     return (int)hipGetLastError();
 }
 
@@ -1894,11 +1967,11 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         const dim3 grid((a.Nq + 63) / 64, a.Hq, a.B), blk(256);
         hipLaunchKernelGGL(mass_rows_kernel, grid, blk, 0, st, a);
     } else {
-        // with several splits stage 1 has already run in the combine launch
+        // with several splits and many rows stage 1 has already run in the combine launch
         const dim3 blk(256);
         const dim3 grid = a.Nq < EN_MASS_FEW_ROWS ? dim3(((a.Smax + 1) * a.Hq * a.B + 255) / 256)
                                                   : dim3(a.Smax + 1, a.Hq, a.B);
-        if (a.n_splits == 1)
+        if (a.n_splits == 1 || a.Nq < EN_MASS_FEW_ROWS)
             hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
         const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
         hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
