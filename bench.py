@@ -210,6 +210,67 @@ def main():
         plan_d.close()
         pool_d.close()
 
+    if not hbm_bound:
+        # The decode phase that follows the prefill (Section 3.2: about 40 tokens per plan, over the KV that was
+        # loaded once): the context holds the cached segments and the prompt tokens; each step appends its
+        # key/value and attends (segmented_decode_step), eagerly and as one HIP graph of the 40 steps.
+        n_dec = 40
+        n_all = cfg.n_new + n_dec
+        pool_d = B.kv_pool_create(st.k_pool, st.v_pool, w.lens, cfg.n_q_heads, cfg.rope_base,
+                                  int(info.max_ctx_len) + n_dec)
+        plan_d = B.segment_select(pool_d, w.sel, w.sel_ptr, n_all)
+        kc_d, vt_d = B.alloc_context(pool_d, plan_d)
+        dt = torch.bfloat16
+        gen = torch.Generator(device="cuda:0").manual_seed(5)
+        shp = (cfg.n_agents, n_dec, cfg.n_kv_heads, cfg.head_dim)
+        qd = torch.randn((cfg.n_agents, n_dec, cfg.n_q_heads, cfg.head_dim), generator=gen, device="cuda:0").to(dt)
+        kd = torch.randn(shp, generator=gen, device="cuda:0").to(dt)
+        vd = torch.randn(shp, generator=gen, device="cuda:0").to(dt)
+        B.gather_rope(pool_d, plan_d, torch.cat([st.k_new, torch.zeros_like(kd)], 1).contiguous(),
+                      torch.cat([st.v_new, torch.zeros_like(vd)], 1).contiguous(), kc_d, vt_d)
+        qs = [qd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        ks = [kd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        vs = [vd[:, i:i + 1].contiguous() for i in range(n_dec)]
+        od = [torch.empty_like(q) for q in qs]
+        ws_d = torch.empty(max(B.decode_workspace_bytes(pool_d, plan_d, 1), 256), dtype=torch.uint8, device="cuda:0")
+
+        def decode_all():
+            for i in range(n_dec):
+                B.segmented_decode_step(pool_d, plan_d, cfg.n_new + i, qs[i], ks[i], vs[i], kc_d, vt_d, od[i], ws_d)
+        decode_all()
+        torch.cuda.synchronize()
+        B.timing_enable(n_dec)
+        d0 = time.perf_counter()
+        decode_all()
+        torch.cuda.synchronize()
+        d1 = time.perf_counter()
+        dec_kern_ms = B.timing_collect(n_dec)
+        B.timing_enable(0)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                decode_all()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(5):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        res["decode_after_prefill"] = {
+            "tokens_decoded": n_dec, "context_tokens": int(info.max_ctx_len),
+            "us_per_decode_step_eager": (d1 - d0) / n_dec * 1e6,
+            "us_per_decode_step_graph": (g1 - g0) / 5 / n_dec * 1e6,
+            "attention_kernel_us": float(np.mean(dec_kern_ms)) * 1e3,
+            "us_prefill_step_plus_40_decode_steps": sec_per_step * 1e6 + (g1 - g0) / 5 * 1e6,
+        }
+        del graph
+        plan_d.close()
+        pool_d.close()
+
     if not hbm_bound and cfg.n_agents == 1 and not args.no_residency:
         # Residency tier (Section 3.2, Section 4 "cache hit rate"): every group's K/V lives in a pinned host
         # store, the device holds a budget of slots, a step loads only the selected groups that are not

@@ -955,9 +955,20 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const int i_row = row_valid ? col % a.Nq : 0;
     const int hq = kvh * r + hl;
 
-    const int S = a.nseg[b];
-    const en_table_ptr bnd = as_table(a.bnd + (size_t)b * (a.Smax + 2));
-    const int Lc = bnd[S] + a.q_first;       // rows are new tokens q_first .. q_first+Nq-1
+    // the agent's header {S, L_c, ..} in one scalar load and, when they fit the wave, all bucket
+    // bounds at once, one per lane: no chain of dependent trips to memory before the first tile
+    const int32_t *bnd_g = a.bnd + (size_t)b * (a.Smax + 2);
+    const bool bnd_in_lanes = a.Smax + 2 <= 64;
+    int my_bnd = 0x7fffffff;
+    if (bnd_in_lanes && lane <= a.Smax + 1)
+        my_bnd = bnd_g[lane];
+    const en_table_ptr hdr = as_table(a.hdr + 4 * (size_t)b);
+    const int S = hdr[0];
+    const en_table_ptr bnd = as_table(bnd_g);
+    auto bound_at = [&](int s) {          // s is wave-uniform
+        return bnd_in_lanes ? __builtin_amdgcn_readlane(my_bnd, s) : bnd[s];
+    };
+    const int Lc = hdr[1] + a.q_first;       // rows are new tokens q_first .. q_first+Nq-1
     const int Ltot = Lc + a.Nq;
     const int ntiles64 = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     // split boundaries are whole 64-key tiles, as everywhere else
@@ -998,6 +1009,10 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 
     const int klane = col * KSTR + half * 16;
     const int vlane = KBYTES + col * VSTR + half * 16;
+
+    // the first tile is on its way while the queries are prepared
+    if (t_begin < t_end)
+        issue(lt_begin, 0);
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -1049,10 +1064,11 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         negm[e] = 0.f;
     float l_part = 0.f, seg_part = 0.f;
 
-    int cur = find_bucket(bnd, S, min(split_key_begin, Ltot - 1));
-    int cur_begin = bnd[cur];
-    int cur_end = bnd[cur + 1];
-    int nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+    const int tok0 = min(split_key_begin, Ltot - 1);
+    int cur = bnd_in_lanes ? (int)__popcll(__ballot(lane <= S && my_bnd <= tok0)) - 1 : find_bucket(bnd, S, tok0);
+    int cur_begin = bound_at(cur);
+    int cur_end = bound_at(cur + 1);
+    int nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     const size_t row_hq = (size_t)b * a.Hq + hq;
     float *seg_base = a.ws_seg
                           ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
@@ -1069,11 +1085,9 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         ++cur;
         cur_begin = cur_end;
         cur_end = (cur <= S) ? nxt_end : 0x7fffffff;
-        nxt_end = (cur + 1 <= S) ? bnd[cur + 2] : 0x7fffffff;
+        nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     };
 
-    if (t_begin < t_end)
-        issue(lt_begin, 0);
     int stage = 0;                               // of tile lt
     for (int lt = lt_begin; lt < lt_end; ++lt) {
         const char *stg = smem + stage * STAGE;
