@@ -1409,25 +1409,11 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
         return;
     const size_t row = idx / (D / V);
     const int d0 = (int)(idx % (D / V)) * V;
-    // the splits are read in batches of independent loads: one after the other, the latencies
-    // of 2 * n_splits dependent loads are what this kernel would take
-    constexpr int NB = 4;
-    float M = EN_NEG_INF;
-    for (int sp0 = g; sp0 < a.n_splits; sp0 += NB * G) {
-        float mm[NB];
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-            mm[j] = sp0 + j * G < a.n_splits ? a.ws_ml[((size_t)(sp0 + j * G) * rows + row) * 2] : EN_NEG_INF;
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-            M = fmaxf(M, mm[j]);
-    }
-    if constexpr (G > 1) {
-#pragma unroll
-        for (int o = 1; o < G; o <<= 1)
-            M = fmaxf(M, __shfl_xor(M, o, 64));
-    }
-    float l = 0.f;
+    // The splits are read in batches of independent loads, (reference, sum) pairs and outputs
+    // together, and merged batch by batch with a running reference: read one after the other,
+    // the latencies of 2 * n_splits dependent loads are what this kernel would take.
+    constexpr int NB = G == 1 ? 4 : 8;
+    float M = EN_NEG_INF, l = 0.f;
     fvec acc = 0.f;
     for (int sp0 = g; sp0 < a.n_splits; sp0 += NB * G) {
         f32x2 ml[NB];
@@ -1441,6 +1427,16 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
             if (!on)
                 ml[j][0] = EN_NEG_INF;
         }
+        float Mb = M;
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            Mb = fmaxf(Mb, ml[j][0]);
+        if (Mb == EN_NEG_INF)
+            continue;
+        const float keep = M == EN_NEG_INF ? 0.f : exp2f(M - Mb);
+        l *= keep;
+        acc *= keep;
+        M = Mb;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             // a split that saw no key of this row left (-inf, 0) and an output that is not to be used
@@ -1450,6 +1446,14 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
         }
     }
     if constexpr (G > 1) {
+        float Mall = M;
+#pragma unroll
+        for (int o = 1; o < G; o <<= 1)
+            Mall = fmaxf(Mall, __shfl_xor(Mall, o, 64));
+        const float keep = M == EN_NEG_INF ? 0.f : exp2f(M - Mall);
+        l *= keep;
+        acc *= keep;
+        M = Mall;
 #pragma unroll
         for (int o = 1; o < G; o <<= 1) {
             l += __shfl_xor(l, o, 64);
