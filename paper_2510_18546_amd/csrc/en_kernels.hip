@@ -545,6 +545,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     float m_ref = 0.f;
     bool has_ref = false;
     bool pending = row_valid && Lc + i_row >= split_key_begin;   // the row will see a key in this split
+    // the same as a wave mask, kept beside it: the test at the end of every phase is then one
+    // vector compare, one scalar OR and one branch
+    unsigned long long pend_mask = __builtin_amdgcn_ballot_w64(pending);
     f32x16 negm;
 #pragma unroll
     for (int e = 0; e < 16; ++e)
@@ -562,6 +565,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     // Blocks whose first key is at most `calm` need neither the causal mask on
     // the block after them nor any bucket bookkeeping.
     auto calm_limit = [&]() {
+        if (pend_mask != 0)           // rows without a reference yet: every block is looked at
+            return -1;
         int m = Lc + i_lo - 2 * KB + 1;
         if (cur_end <= split_key_end)
             m = min(m, cur_end - KB - 1);
@@ -707,12 +712,15 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         // came near overflow (any magnitude below that is harmless: P keeps its
         // relative precision in bf16 and the accumulators are fp32).
         constexpr float BIG = 1.0e18f;            // 2^60
-        const bool odd_row = __any(pending || !(rs < BIG));     // wave-uniform
-        if (kb <= calm && !odd_row) {
-            l_part += rs;
-            seg_part += rs;               // the whole block lies inside bucket `cur`
-            return;
+        const bool overflow = __builtin_amdgcn_ballot_w64(!(rs < BIG)) != 0;     // wave-uniform
+        if (kb <= calm) {                 // also says that no row lacks a reference
+            if (!overflow) {
+                l_part += rs;
+                seg_part += rs;           // the whole block lies inside bucket `cur`
+                return;
+            }
         }
+        const bool odd_row = overflow || pend_mask != 0;
         const int ke = min(kb + KB, split_key_end);
         mask_block(kb + KB, s_nxt);
         // ---- reference check: the wave recomputes the scores of the block,
@@ -742,6 +750,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             m_ref += delta;
             has_ref = has_ref || fix;
             pending = pending && !fix;
+            pend_mask = __builtin_amdgcn_ballot_w64(pending);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 negm[e] = -m_ref;
