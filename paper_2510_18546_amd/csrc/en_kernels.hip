@@ -775,7 +775,17 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
                 close_bucket();
         } else if (kb < split_key_end) {
             // buckets end inside the block: every bucket but the last one met takes the sum
-            // of its keys, the last one what is left of the block's sum
+            // of its keys, the last one what is left of the block's sum. The keys' sums can only
+            // be taken from the rounded probabilities, so for this block the row sum is taken
+            // from them too: a block must give the same total to the row and to its buckets
+            // (with a dominant key the difference, up to 2^-9 of it, would otherwise land in
+            // whatever bucket comes next, or be lost at the end of a split).
+            float rs_hat = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                rs_hat += (float)pbuf[PAR][e / 8][e % 8];
+            l_part += rs_hat - rs;
+            rs = rs_hat;
             float rest = rs;
             while (true) {
                 const int hi = min(cur_end, ke);
@@ -1548,10 +1558,14 @@ __device__ __forceinline__ void bucket_splits(int n_splits, int ntiles, int Ltot
 }
 
 __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int hq, int i, int bucket,
-                                                 int sp_lo, int sp_hi, float M, float L)
+                                                 int sp_lo, int sp_hi, float M, float L, int ntiles)
 {
     float acc = 0.f;
     for (int sp = sp_lo; sp <= sp_hi; ++sp) {
+        // an agent with fewer key tiles than the plan has splits leaves some splits without
+        // keys: nothing was written for them
+        if (sp * ntiles / a.n_splits == (sp + 1) * ntiles / a.n_splits)
+            continue;
         const f32x2 v = *reinterpret_cast<const f32x2 *>(
             a.ws_seg + (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
         if (v[1] != EN_NEG_INF)
@@ -1588,7 +1602,7 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
             if (valid && s <= S && bnd[s + 1] > bnd[s]) {
                 int lo, hi;
                 bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
-                v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+                v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
             }
             tile[lane][c] = v;
         }
@@ -1625,7 +1639,7 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, i
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
             float M, L;
             merged_ml(a, rows, row, M, L);
-            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
         }
     }
     acc = wave_sum(acc);
@@ -1660,7 +1674,7 @@ __device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
             float M, L;
             row_final_ml(a, rows, row, M, L);      // runs after the combine launch: the merged pair is there
-            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L);
+            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
         }
     }
     a.ws_red[pair] = acc;              // [b][s][hq]
@@ -1756,7 +1770,7 @@ __global__ __launch_bounds__(256) void cluster_score_kernel(EnClusterArgs a)
             const size_t row = ((size_t)b * m.Hq + hq) * m.Nq + i;
             float M, L;
             row_final_ml(m, rows, row, M, L);
-            acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L);
+            acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L, ntiles);
         }
     }
     acc = wave_sum(acc);

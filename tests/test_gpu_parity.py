@@ -81,7 +81,10 @@ def run_case(step_mod, O, cfg, n_splits=None, sel_lists=None, rows=None, name=""
         check_mass(cfg, sel_mass, ref_mass)
         ref_red = None
     # properties that hold at any size
-    np.testing.assert_allclose(mass.sum(-1), 1.0, atol=2e-3 if cfg.dtype == I.BF16 else 2e-5)
+    # every block of keys gives the same total to the row's sum and to its buckets, whatever the
+    # rounding of the probabilities: the masses of a row add up to 1 to fp32 rounding, none is negative
+    np.testing.assert_allclose(mass.sum(-1), 1.0, atol=1e-4 if cfg.dtype == I.BF16 else 2e-5)
+    assert mass.min() >= -1e-6, f"negative mass {mass.min():.3e}"
     np.testing.assert_allclose(red, mass.sum(axis=(1, 2)), rtol=1e-4, atol=1e-3)
     if ref_red is not None:
         tol = 1e-2 * cfg.n_new * cfg.n_q_heads if cfg.dtype == I.BF16 else 1e-4 * cfg.n_new * cfg.n_q_heads
@@ -264,6 +267,39 @@ def test_more_segments_than_lanes(step_mod, oracle, dtype, n_agents):
                 n_groups=120, n_sel=90, n_new=70, n_agents=n_agents, head_dim=128 if dtype == I.BF16 else 64)
     run_case(step_mod, oracle, cfg)
     run_case(step_mod, oracle, cfg, n_splits=3)
+
+
+@pytest.mark.parametrize("dtype,n_new", [(I.BF16, 40), (I.BF16, 2), (I.F32, 5)])
+def test_agent_with_fewer_tiles_than_splits(step_mod, oracle, dtype, n_new):
+    """The split count follows the longest context; an agent with a short one leaves some splits
+    without keys. Nothing is written for those, and nothing may be read from them (the scratch is
+    filled with a NaN pattern first)."""
+    import torch
+    cfg = small(f"short-agent-{dtype}-{n_new}", 940 + n_new, dtype=dtype, n_agents=3, n_groups=14, capacity=128,
+                len_lo=100, len_hi=128, n_sel=0, n_new=n_new, head_dim=128 if dtype == I.BF16 else 64)
+    sel_lists = [[0, 1, 2, 3, 4, 5, 6, 7, 8, 9], [11], [12, 13]]
+    w = I.make_workload(cfg, sel_lists=sel_lists)
+    st = step_mod.PlanningStep(w, n_splits=13)
+    st.ws.fill_(0xFF)
+    st.run()
+    torch.cuda.synchronize()
+    ref_out, ref_mass = oracle_full(oracle, w)
+    check_out(cfg, st.out_host(), ref_out)
+    check_mass(cfg, st.mass_host(), ref_mass)
+    red = st.mass_red_host()
+    assert np.isfinite(red).all()
+    np.testing.assert_allclose(red, oracle.reduce_mass(ref_mass), atol=1e-2 * cfg.n_new * cfg.n_q_heads)
+
+
+@pytest.mark.parametrize("splits", [None, 1, 3])
+def test_bf16_dominant_key_among_tiny_segments(step_mod, oracle, splits):
+    """A key that carries almost all of a row's weight, inside a 32-key block in which several
+    segments end, one of them exactly at the end of a KV split: the rounding of that key's
+    probability must not leak into a neighbouring bucket (a negative mass) or get lost."""
+    cfg = I.Config(name="tiny-planted", seed=1772, dtype=I.BF16, n_agents=3, n_q_heads=12, n_kv_heads=4,
+                   head_dim=64, n_groups=26, capacity=33, len_lo=4, len_hi=5, n_sel=16, n_new=64,
+                   rope_base=10000.0, planted=True)
+    run_case(step_mod, oracle, cfg, n_splits=splits)
 
 
 # ---------------------------------------------------------------------------
