@@ -338,7 +338,8 @@ int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n
  * gather_rope: the attention kernels read the gathered context, not the
  * slots); loads then wait only for that point and run beside the kernels
  * enqueued after it. Without a fence a fetch that has to load waits for
- * everything enqueued on `stream` so far.
+ * everything enqueued on `stream` so far, which then counts as a fence covering
+ * every earlier fetch.
  * kv_tier_prefetch loads groups that a later fetch is expected to ask for
  * (e.g. the same selection for the next layer) into slots whose readers the
  * last fence covers, least recently used first, and never waits for anything

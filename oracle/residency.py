@@ -18,6 +18,9 @@ Rules, in the order a step applies them
                     2. in list order, every other asked-for group takes the slot
                        whose last use is oldest; a slot never used is older than
                        any used one; among equally old slots the lowest number;
+                       Before the first load of a step, if the last fence is older
+                       than the previous step, the step fences for itself: everything
+                       up to the previous step counts as fenced from then on;
                     3. returns the slot of every group, and per group one of
                        "hit" (resident from an earlier fetch), "prefetched"
                        (resident because of a prefetch, first time asked for),
@@ -90,6 +93,8 @@ class Residency:
         for g in groups:
             if g in kind:
                 continue
+            if self.step > 1 and self.fenced < self.step - 1:
+                self.fenced = self.step - 1         # a fetch that has to load fences for itself
             s = self._oldest([s for s in range(self.n_slots) if self.age[s] < self.step])
             assert s >= 0
             self._load(g, s)

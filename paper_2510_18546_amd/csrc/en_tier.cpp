@@ -429,19 +429,21 @@ extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, 
         const int s = pick_victim(t, keep, t->tick - 1);
         if (s < 0)
             return tfail(EN_ERR_CAPACITY, "kv_tier_fetch: no slot left");      // cannot happen: n <= slots
-        if (!t->dry && !waited) {
+        if (!waited) {
             // Kernels of the caller that read the slots handed out earlier must
             // be done before a slot is overwritten. A fence the caller set after
-            // enqueuing them covers fetches up to fence_tick; otherwise everything
-            // queued on the caller's stream so far is waited for.
+            // enqueuing them covers fetches up to fence_tick; otherwise the fetch
+            // fences for itself: everything queued on the caller's stream so far
+            // is waited for, which covers every earlier fetch. (The books are kept
+            // the same way by a tier without device memory.)
             hipError_t e;
             if (t->tick > 1 && t->fence_tick < t->tick - 1) {
-                if ((e = hipEventRecord(t->ev_fence, st)) != hipSuccess)
+                if (!t->dry && (e = hipEventRecord(t->ev_fence, st)) != hipSuccess)
                     return thip(e, "kv_tier_fetch: hipEventRecord");
                 t->fence_tick = t->tick - 1;
                 t->have_fence = true;
             }
-            if (t->have_fence && (e = hipStreamWaitEvent(t->copy, t->ev_fence, 0)) != hipSuccess)
+            if (!t->dry && t->have_fence && (e = hipStreamWaitEvent(t->copy, t->ev_fence, 0)) != hipSuccess)
                 return thip(e, "kv_tier_fetch: hipStreamWaitEvent");
             waited = true;
         }

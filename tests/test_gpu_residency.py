@@ -233,3 +233,59 @@ def test_append_reaches_the_store_and_the_resident_copy(mods, base):
                          torch.zeros((cfg.capacity, cfg.n_kv_heads, cfg.head_dim), dtype=dt).cuda())
     assert e.value.code == 4
     tier.close()
+
+
+def test_random_tier_traces_keep_the_data_right(mods):
+    """Random traces of fetch / prefetch / fence / put / append on tiers of random sizes: the slots a fetch
+    hands out equal the bookkeeping oracle's, and what they hold equals what was put and appended."""
+    import torch
+    B, _ = mods
+    rng = np.random.default_rng(5)
+    for case in range(40):
+        base = "c1" if rng.random() < 0.6 else "c0"
+        G = int(rng.integers(3, 14))
+        n_slots = int(rng.integers(1, G + 1))
+        capc = I.CONFIGS[base].capacity
+        cfg = I.variant(I.CONFIGS[base], n_groups=G, seed=7000 + case, n_sel=1, fixed_sel=None, len_lo=0,
+                        len_hi=capc - 12)
+        w = I.make_workload(cfg)
+        announce(f"tier trace {case}: {base} G={G} slots={n_slots}")
+        tier, blocks = make_tier(B, cfg, w, n_slots, 4096)
+        dt = blocks[0][0].dtype
+        cur = {g: [blocks[g][0].clone(), blocks[g][1].clone()] for g in range(G)}
+        ref = Residency(n_slots)
+        for step in range(40):
+            op = rng.choice(["fetch", "fetch", "fetch", "prefetch", "fence", "put", "append"])
+            if op in ("fetch", "prefetch"):
+                groups = rng.permutation(G)[:int(rng.integers(0, n_slots + 1))]
+                if op == "prefetch":
+                    assert B.kv_tier_prefetch(tier, groups) == ref.prefetch(groups.tolist())
+                    continue
+                slots = B.kv_tier_fetch(tier, groups)
+                assert slots.tolist() == ref.fetch(groups.tolist())[0]
+                torch.cuda.synchronize()
+                for g, s in zip(groups, slots):
+                    n = cur[g][0].shape[1]
+                    assert np.array_equal(bits(tier.pool.k[s, :, :n, :]), bits(cur[g][0])), (case, step, g)
+                    assert np.array_equal(bits(tier.pool.v[s, :, :n, :]), bits(cur[g][1])), (case, step, g)
+            elif op == "fence":
+                B.kv_tier_fence(tier)
+                ref.fence()
+            elif op == "put":
+                g, n = int(rng.integers(0, G)), int(rng.integers(0, capc - 12))
+                k = torch.randn((cfg.n_kv_heads, n, cfg.head_dim)).to(dt)
+                v = torch.randn((cfg.n_kv_heads, n, cfg.head_dim)).to(dt)
+                B.kv_tier_put(tier, g, k, v)
+                ref.put(g)
+                cur[g] = [k, v]
+            else:
+                g = int(rng.integers(0, G))
+                n = int(rng.integers(0, min(capc - cur[g][0].shape[1], 5) + 1))
+                k = torch.randn((n, cfg.n_kv_heads, cfg.head_dim)).to(dt)
+                v = torch.randn((n, cfg.n_kv_heads, cfg.head_dim)).to(dt)
+                B.kv_tier_append(tier, g, k.cuda(), v.cuda(), n_tokens=n)
+                cur[g] = [torch.cat([cur[g][0], k.permute(1, 0, 2)], 1).contiguous(),
+                          torch.cat([cur[g][1], v.permute(1, 0, 2)], 1).contiguous()]
+            assert tier.residency().tolist() == [ref.slot_of(g) for g in range(G)], (case, step, op)
+        torch.cuda.synchronize()
+        tier.close()
