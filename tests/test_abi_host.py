@@ -256,3 +256,42 @@ def test_product_and_oracle_do_not_import_each_other():
     for path in glob.glob(os.path.join(root, "paper_2510_18546_amd", "csrc", "*")):
         assert "oracle" not in open(path).read().lower(), path
     assert "efficientnav.h" not in open(os.path.join(root, "oracle", "en_oracle.c")).read()
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 (and as C++), and a C program that links
+    the library can build a plan with host calls only."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    src = tmp_path / "abi.c"
+    src.write_text('''
+#include <stdio.h>
+#include <stdint.h>
+#include "efficientnav.h"
+int main(void) {
+    en_pool_desc d = {0};
+    int32_t len[3] = {3, 4, 5}, sel[2] = {2, 0}, ptr[2] = {0, 2}, off[3] = {0, 0, 0}, n = 0;
+    en_pool *pool = NULL; en_plan *plan = NULL; en_plan_info info;
+    d.n_groups = 3; d.capacity = 8; d.n_kv_heads = 1; d.n_q_heads = 4; d.head_dim = 64; d.dtype = EN_F32;
+    d.max_ctx = 64; d.rope_base = 10000.0;
+    if (kv_pool_create(&d, (void *)8, (void *)8, len, &pool) != EN_OK) return 1;
+    if (segment_select(pool, 1, sel, ptr, 4, &plan) != EN_OK) return 2;
+    if (en_plan_query(plan, 0, off, &n) != EN_OK || n != 2 || off[1] != 5 || off[2] != 8) return 3;
+    if (en_plan_get_info(plan, &info) != EN_OK || info.total_cached != 8) return 4;
+    if (segment_select(pool, 1, sel, ptr, 100, &plan) != EN_ERR_CAPACITY) return 5;
+    printf("%s\\n", en_last_error());
+    en_plan_destroy(plan); kv_pool_destroy(pool);
+    return 0;
+}
+''')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc,
+                           "-fsyntax-only", str(src)])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-I", inc, "-fsyntax-only", "-x", "c++", str(src)])
+    exe = tmp_path / "abi"
+    subprocess.check_call(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), B._build.LIB_PATH,
+                           "-Wl,-rpath," + os.path.dirname(B._build.LIB_PATH)])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    assert "max_ctx" in out.stdout
