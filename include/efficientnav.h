@@ -305,6 +305,16 @@ int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n
                            float scale, float threshold, float *score_dev, int32_t *assign_dev,
                            void *stream);
 
+/* The same from the scratch that segmented_decode_step(q_first, n_rows) left:
+ * for a plan that reserves rows for tokens still to be decoded, the prompt
+ * tokens are such a step (q_first = 0). Spans count from the step's first row:
+ * 0 <= span_ptr[o] < span_ptr[o+1] <= n_rows.
+ * Errors: as above, OUT_OF_RANGE (q_first + n_rows > N_q). */
+int segment_cluster_assign_rows(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                void *ws_dev, int32_t n_obj, const int32_t *span_ptr_host,
+                                int32_t per_key, int32_t accumulate, float scale, float threshold,
+                                float *score_dev, int32_t *assign_dev, void *stream);
+
 /* ------------------------------------------------------------------------
  * Residency tier (Section 3.2: the KV cache of all groups is kept in a large,
  * slow store and only the selected groups are loaded into device memory, once

@@ -25,6 +25,7 @@ EXPORTS = [
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
     "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
+    "segment_cluster_assign_rows",
     "en_decode_workspace_bytes", "segmented_decode_step", "en_timing_enable",
     "en_timing_collect", "en_last_error",
     "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_append",
@@ -90,6 +91,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
     lib.segment_cluster_assign.argtypes = [vp, vp, vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_float,
                                            C.c_float, vp, vp, vp]
+    lib.segment_cluster_assign_rows.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, C.c_int32, i32p, C.c_int32,
+                                                C.c_int32, C.c_float, C.c_float, vp, vp, vp]
     lib.en_decode_workspace_bytes.argtypes = [vp, vp, C.c_int32]
     lib.en_decode_workspace_bytes.restype = C.c_size_t
     lib.segmented_decode_step.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -311,6 +314,19 @@ def segment_cluster_assign(pool: Pool, plan: Plan, ws, spans, score, assign=None
         pool.handle, plan.handle, ptr(ws), len(spans) - 1, _ip(spans), int(per_key), int(accumulate),
         C.c_float(scale), C.c_float(threshold), ptr(score), ptr(assign) if assign is not None else None,
         _stream(stream) if hasattr(ws, "data_ptr") else C.c_void_p(0)))
+    return score, assign
+
+
+def segment_cluster_assign_rows(pool: Pool, plan: Plan, q_first: int, n_rows: int, ws, spans, score, assign=None,
+                                per_key: bool = False, accumulate: bool = False, scale: float = 1.0,
+                                threshold: float = 0.0, stream=None):
+    """As segment_cluster_assign, from the scratch that segmented_decode_step(q_first, n_rows) left."""
+    spans = _i32(spans)
+    ptr = lambda t: C.c_void_p(t.data_ptr() if hasattr(t, "data_ptr") else t)
+    _check(load().segment_cluster_assign_rows(
+        pool.handle, plan.handle, int(q_first), int(n_rows), ptr(ws), len(spans) - 1, _ip(spans), int(per_key),
+        int(accumulate), C.c_float(scale), C.c_float(threshold), ptr(score),
+        ptr(assign) if assign is not None else None, _stream(stream) if hasattr(ws, "data_ptr") else C.c_void_p(0)))
     return score, assign
 
 

@@ -734,6 +734,11 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
 }
 
 // KV splits for a step of n_rows query rows (same rule as for a whole plan).
+static int cluster_assign(en_pool *pool, en_plan *plan, int q_first, int n_rows, int n_splits, void *ws_dev,
+                          int32_t n_obj, const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                          float scale, float threshold, float *score_dev, int32_t *assign_dev, void *stream,
+                          const char *who);
+
 static int step_splits(const en_pool *pool, const en_plan *plan, int n_rows)
 {
     en_plan tmp;
@@ -805,6 +810,21 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
     return EN_OK;
 }
 
+extern "C" int segment_cluster_assign_rows(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                           void *ws_dev, int32_t n_obj, const int32_t *span_ptr_host,
+                                           int32_t per_key, int32_t accumulate, float scale, float threshold,
+                                           float *score_dev, int32_t *assign_dev, void *stream)
+{
+    if (!pool || !plan)
+        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign_rows: null argument");
+    if (q_first < 0 || n_rows <= 0 || long(q_first) + n_rows > plan->Nq)
+        return fail(EN_ERR_OUT_OF_RANGE, "segment_cluster_assign_rows: rows %d .. %d of %d new tokens", q_first,
+                    q_first + n_rows - 1, plan->Nq);
+    return cluster_assign(pool, plan, q_first, n_rows, step_splits(pool, plan, n_rows), ws_dev, n_obj, span_ptr_host,
+                          per_key, accumulate, scale, threshold, score_dev, assign_dev, stream,
+                          "segment_cluster_assign_rows");
+}
+
 extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
                                       float *mass_out_dev, void *stream)
 {
@@ -825,29 +845,33 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
     return EN_OK;
 }
 
-extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
-                                      const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
-                                      float scale, float threshold, float *score_dev, int32_t *assign_dev,
-                                      void *stream)
+// Shared by the two entry points below: the scratch is the one an attention call over rows
+// q_first .. q_first + n_rows - 1 with n_splits splits left behind.
+static int cluster_assign(en_pool *pool, en_plan *plan, int q_first, int n_rows, int n_splits, void *ws_dev,
+                          int32_t n_obj, const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                          float scale, float threshold, float *score_dev, int32_t *assign_dev, void *stream,
+                          const char *who)
 {
     if (!pool || !plan || !ws_dev || !span_ptr_host || !score_dev || n_obj <= 0 ||
         (per_key != 0 && per_key != 1) || (accumulate != 0 && accumulate != 1))
-        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: null argument, no objects or bad flag");
+        return fail(EN_ERR_INVALID_ARG, "%s: null argument, no objects or bad flag", who);
     if (plan->pool != pool)
-        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: plan belongs to another pool");
+        return fail(EN_ERR_INVALID_ARG, "%s: plan belongs to another pool", who);
     if (n_obj > EN_MAX_OBJECTS)
-        return fail(EN_ERR_UNSUPPORTED, "segment_cluster_assign: %d objects, at most %d per call", n_obj,
-                    EN_MAX_OBJECTS);
+        return fail(EN_ERR_UNSUPPORTED, "%s: %d objects, at most %d per call", who, n_obj, EN_MAX_OBJECTS);
     for (int o = 0; o < n_obj; ++o)
-        if (span_ptr_host[o] < 0 || span_ptr_host[o] >= span_ptr_host[o + 1] || span_ptr_host[o + 1] > plan->Nq)
-            return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: object %d spans [%d, %d) of %d new tokens", o,
-                        span_ptr_host[o], span_ptr_host[o + 1], plan->Nq);
+        if (span_ptr_host[o] < 0 || span_ptr_host[o] >= span_ptr_host[o + 1] || span_ptr_host[o + 1] > n_rows)
+            return fail(EN_ERR_INVALID_ARG, "%s: object %d spans [%d, %d) of %d new tokens", who, o, span_ptr_host[o],
+                        span_ptr_host[o + 1], n_rows);
     int rc;
     if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
         return rc;
-    const EnWsLayout L = en_ws_layout(pool, plan);
+    const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
     EnClusterArgs a;
     a.m = mass_args(pool, plan, static_cast<char *>(ws_dev), L);
+    a.m.Nq = n_rows;
+    a.m.n_splits = n_splits;
+    a.m.q_first = q_first;
     a.score = score_dev;
     a.assign = assign_dev;
     a.n_obj = n_obj;
@@ -858,6 +882,17 @@ extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev
     std::memcpy(a.spans, span_ptr_host, size_t(n_obj + 1) * sizeof(int32_t));
     const int e = en_launch_cluster(pool, a, stream);
     if (e != 0)
-        return hip_fail((hipError_t)e, "segment_cluster_assign launch");
+        return hip_fail((hipError_t)e, who);
     return EN_OK;
+}
+
+extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
+                                      const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                                      float scale, float threshold, float *score_dev, int32_t *assign_dev,
+                                      void *stream)
+{
+    if (!plan)
+        return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: null plan");
+    return cluster_assign(pool, plan, 0, plan->Nq, plan->n_splits, ws_dev, n_obj, span_ptr_host, per_key, accumulate,
+                          scale, threshold, score_dev, assign_dev, stream, "segment_cluster_assign");
 }

@@ -1,0 +1,124 @@
+"""The pieces composed the way a planner uses them, through the C ABI, against the oracle layer by layer:
+L layers, each with its own K/V of every group in a residency tier; one selection (Eq. (1) over relevance
+scores) per planning step; per layer: fetch (next layer's groups prefetched beside the attention), gather,
+attention, clustering scores accumulated over the first layers (Section 3.3), then the decision; then a few
+decoded tokens over the contexts gathered once (Section 3.2); then the new objects' K/V appended to the
+group they joined. Two planning steps, so that the second finds most groups resident."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle.residency import Residency
+from paper_2510_18546_amd import inputs as I
+from test_gpu_residency import announce, make_tier, bits  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def test_two_planning_steps_over_four_layers(oracle):
+    import torch
+    from paper_2510_18546_amd import binding as B
+    from paper_2510_18546_amd import step as S
+    L, n_dec, n_slots = 4, 3, 9
+    base = I.variant(I.CONFIGS["c1"], n_groups=14, capacity=96, len_lo=20, len_hi=80, n_sel=1, n_new=24,
+                     n_q_heads=8, n_kv_heads=2)
+    announce(f"planner flow: {L} layers, G={base.n_groups}, slots={n_slots}, Nq={base.n_new}, {n_dec} decoded tokens")
+    layers = [I.make_workload(I.variant(base, seed=400 + l), poison=False) for l in range(L)]
+    lens = layers[0].lens.copy()
+    for w in layers:                     # one map: every layer's block of a group has the same length
+        w.lens = lens.copy()
+    max_ctx = 8 * base.capacity + base.n_new + n_dec
+    tiers = [make_tier(B, base, w, n_slots, max_ctx)[0] for w in layers]
+    books = [Residency(n_slots) for _ in range(L)]
+    dev = [{k: S._to_device(getattr(w, k)[:1], True, "cuda:0") for k in ("q", "k_new", "v_new")} for w in layers]
+    spans = np.array([0, 6, 24], np.int32)           # two new objects
+    rng = np.random.default_rng(12)
+    scores = I.drifting_scores(77, base.n_groups, 2, rho=0.9)
+    n_all = base.n_new + n_dec
+    for step in range(2):
+        groups = B.kv_tier_select_scored(tiers[0], scores[step], 0.0, 6 * 64)
+        want = oracle.knapsack(scores[step], lens, 0.0, 6 * 64)
+        assert groups.tolist() == want and len(groups) >= 2
+        S1 = len(groups) + 1
+        score_acc = torch.zeros((1, 2, S1), dtype=torch.float32, device="cuda:0")
+        assign = torch.full((1, 2), -7, dtype=torch.int32, device="cuda:0")
+        ref_scores = np.zeros((2, S1))
+        ctx = []
+        for l, (w, tier) in enumerate(zip(layers, tiers)):
+            slots = B.kv_tier_fetch(tier, groups)
+            assert slots.tolist() == books[l].fetch(groups.tolist())[0]
+            plan = B.segment_select(tier.pool, slots, [0, len(slots)], n_all)
+            kc, vt = B.alloc_context(tier.pool, plan)
+            ws = torch.empty(max(B.decode_workspace_bytes(tier.pool, plan, base.n_new), 256), dtype=torch.uint8,
+                             device="cuda:0")
+            pad = lambda t: torch.cat([t, torch.zeros((1, n_dec) + tuple(t.shape[2:]), dtype=t.dtype,
+                                                     device=t.device)], 1).contiguous()
+            B.gather_rope(tier.pool, plan, pad(dev[l]["k_new"]), pad(dev[l]["v_new"]), kc, vt)
+            B.kv_tier_fence(tier)
+            out = torch.empty_like(dev[l]["q"])
+            mass = torch.empty((1, base.n_new, base.n_q_heads, S1), dtype=torch.float32, device="cuda:0")
+            # the prompt tokens: rows 0 .. n_new-1 of a plan that also has room for the decoded ones
+            B.segmented_decode_step(tier.pool, plan, 0, dev[l]["q"], dev[l]["k_new"], dev[l]["v_new"], kc, vt, out,
+                                    ws, mass_out=mass)
+            B.segment_cluster_assign_rows(tier.pool, plan, 0, base.n_new, ws, spans, score_acc,
+                                          assign if l == L - 1 else None, accumulate=True, scale=1.0 / L,
+                                          threshold=0.05)
+            torch.cuda.synchronize()
+            ref_out, ref_mass = oracle.attention(w.k_pool, w.v_pool, lens, groups.astype(np.int32),
+                                                 np.array([0, len(groups)], np.int32), w.q[:1], w.k_new[:1],
+                                                 w.v_new[:1], base.rope_base)
+            assert np.abs(S._to_host(out).astype(np.float64) - ref_out).max() <= 2e-2
+            assert np.abs(mass.cpu().numpy() - ref_mass).max() <= 1e-2
+            ref_scores += oracle.cluster_scores(ref_mass[0], [int(lens[g]) for g in groups], spans, False)
+            ctx.append((plan, kc, vt, ws))
+        got = score_acc.cpu().numpy()[0]
+        assert np.abs(got - ref_scores).max() <= 1e-2 * L
+        mine = oracle.cluster_assign(got / np.float32(L), [int(lens[g]) for g in groups], np.float32(0.05))
+        assert np.array_equal(assign.cpu().numpy()[0], mine)
+        # a few decoded tokens over the contexts gathered once, every layer
+        gen = torch.Generator(device="cuda:0").manual_seed(step)
+        dec = [[] for _ in range(L)]
+        for t in range(n_dec):
+            for l, (plan, kc, vt, ws) in enumerate(ctx):
+                q = torch.randn((1, 1, base.n_q_heads, base.head_dim), generator=gen, device="cuda:0").to(torch.bfloat16)
+                k = torch.randn((1, 1, base.n_kv_heads, base.head_dim), generator=gen, device="cuda:0").to(torch.bfloat16)
+                v = torch.randn((1, 1, base.n_kv_heads, base.head_dim), generator=gen, device="cuda:0").to(torch.bfloat16)
+                o = torch.empty_like(q)
+                B.segmented_decode_step(tiers[l].pool, plan, base.n_new + t, q, k, v, kc, vt, o, ws)
+                dec[l].append((q, k, v, o))
+        torch.cuda.synchronize()
+        # a decoded token is the next row of a prefill over [segments || prompt tokens || decoded tokens]
+        for l, w in enumerate(layers):
+            host = lambda j: np.concatenate([S._to_host(x[j]) for x in dec[l]], axis=1)
+            q_all = np.concatenate([w.q[:1], host(0)], axis=1)
+            k_all = np.concatenate([w.k_new[:1], host(1)], axis=1)
+            v_all = np.concatenate([w.v_new[:1], host(2)], axis=1)
+            rows = np.array([(0, base.n_new + t, h) for t in range(n_dec) for h in range(base.n_q_heads)], np.int32)
+            ref, _ = oracle.attention(w.k_pool, w.v_pool, lens, groups.astype(np.int32),
+                                      np.array([0, len(groups)], np.int32), q_all, k_all, v_all, base.rope_base,
+                                      rows=rows)
+            got = host(3)[0].reshape(n_dec * base.n_q_heads, base.head_dim).astype(np.float64)
+            assert np.abs(got - ref).max() <= 2e-2, (step, l)
+        # the first new object joins the group it was assigned to, in every layer: its K/V are appended
+        pos = int(assign.cpu().numpy()[0, 0])
+        if pos >= 0:
+            g = int(groups[pos])
+            n_obj_tokens = int(spans[1] - spans[0])
+            if lens[g] + n_obj_tokens <= base.capacity:
+                for l, tier in enumerate(tiers):
+                    k_rows = dev[l]["k_new"][0, :n_obj_tokens].contiguous()
+                    v_rows = dev[l]["v_new"][0, :n_obj_tokens].contiguous()
+                    B.kv_tier_append(tier, g, k_rows, v_rows)
+                    for arr, new in ((layers[l].k_pool, layers[l].k_new), (layers[l].v_pool, layers[l].v_new)):
+                        arr[g, :, lens[g]:lens[g] + n_obj_tokens, :] = np.transpose(new[0, :n_obj_tokens], (1, 0, 2))
+                lens[g] += n_obj_tokens
+                for w in layers:
+                    w.lens = lens.copy()
+        for plan, *_ in ctx:
+            plan.close()
+    # the second step found most of its groups in device memory
+    st = tiers[0].stats
+    assert st.hits > 0 and st.hits + st.misses + st.prefetched == st.requested
+    for tier in tiers:
+        tier.close()
