@@ -368,6 +368,42 @@ def main():
         tier.close()
         del k_slots, v_slots
 
+    if hbm_bound:
+        # 8-bit pool (an option beside the paper's method): the same gather from int8 codes and per-row scales,
+        # quantised by the library's own append; the context it writes is the same bf16 one.
+        G, Hkv, Cap, D = st.k_pool.shape
+        kq = torch.zeros((G, Hkv, Cap, D), dtype=torch.int8, device="cuda:0")
+        vq = torch.zeros_like(kq)
+        ks = torch.zeros((G, Hkv, Cap), dtype=torch.float32, device="cuda:0")
+        vs = torch.zeros_like(ks)
+        pool_q = B.kv_pool_create(kq, vq, np.zeros(G, np.int32), cfg.n_q_heads, cfg.rope_base,
+                                  cfg.n_sel * cfg.capacity + cfg.n_new)
+        B.kv_pool_set_scales(pool_q, ks, vs)
+        for g in range(G):
+            n = int(w.lens[g])
+            B.kv_pool_append(pool_q, g, st.k_pool[g, :, :n].permute(1, 0, 2).contiguous(),
+                             st.v_pool[g, :, :n].permute(1, 0, 2).contiguous())
+        plan_q = B.segment_select(pool_q, w.sel, w.sel_ptr, cfg.n_new)
+        torch.cuda.synchronize()
+
+        def time_gather(pool, plan, reps=5):
+            B.gather_rope(pool, plan, st.k_new, st.v_new, st.kc, st.vt)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.gather_rope(pool, plan, st.k_new, st.v_new, st.kc, st.vt)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+        t_bf16 = time_gather(st.pool, st.plan)
+        t_q8 = time_gather(pool_q, plan_q)
+        res["q8_pool"] = {"gather_us_bf16_pool": t_bf16, "gather_us_int8_pool": t_q8,
+                          "pool_bytes_ratio": (kq.numel() + ks.numel() * 4) / (st.k_pool.numel() * 2)}
+        plan_q.close()
+        pool_q.close()
+        del kq, vq, ks, vs
+
     if not args.no_ceilings:
         # Two measured ceilings of this machine beside the nominal peaks: a large bf16 GEMM of the vendor
         # library on the same kind of data (N(0,1) rounded to bf16), and a plain device copy.

@@ -65,7 +65,12 @@ typedef enum en_status {
     EN_ERR_DEVICE = 6         /* a HIP call failed; see en_last_error()       */
 } en_status;
 
-typedef enum en_dtype { EN_F32 = 0, EN_BF16 = 1 } en_dtype;
+typedef enum en_dtype {
+    EN_F32 = 0,
+    EN_BF16 = 1,
+    EN_I8 = 2   /* pool of 8-bit codes with one float scale per (group, head, token),
+                   see kv_pool_set_scales; contexts, queries, outputs are bf16 */
+} en_dtype;
 
 typedef struct en_pool en_pool; /* opaque */
 typedef struct en_plan en_plan; /* opaque */
@@ -109,6 +114,21 @@ typedef struct en_plan_info {
  */
 int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
                    const int32_t *len_host, en_pool **out);
+
+/* 8-bit pools (an option beside the paper's method, which names quantisation as
+ * compatible with it, Section 2): with desc->dtype = EN_I8, k_dev / v_dev hold
+ * int8 codes [G, Hkv, C, D] and every (group, head, token) row has a scale:
+ * value = code * scale. Scales: device float [G, Hkv, C] for keys and for
+ * values, owned by the caller like the pool arrays; set them before the first
+ * gather_rope. gather_rope turns the selected rows into the same bf16 contexts
+ * as for an EN_BF16 pool (keys: code * scale in float32, rotated, rounded once;
+ * values: code * scale rounded to bf16); new tokens, queries, outputs and the
+ * attention itself are bf16. kv_pool_append takes bf16 rows and stores codes and
+ * scales: scale = max|x| / 127 over the row, code = x / scale rounded to the
+ * nearest integer (ties to even), all in float32; a zero row gets scale 0.
+ * Residency tiers do not take EN_I8 pools.
+ * Errors: INVALID_ARG (null; pool is not EN_I8). */
+int kv_pool_set_scales(en_pool *pool, float *k_scale_dev, float *v_scale_dev);
 
 /* Record that group `group` now holds `len` tokens (the caller has written the
  * rows; Section 3.2: new objects are appended at the end of their group).

@@ -152,6 +152,27 @@ def append(k_pool, v_pool, lens, group: int, k_rows, v_rows):
     return k_pool, v_pool, lens
 
 
+def quantize_rows(x) -> Tuple[np.ndarray, np.ndarray]:
+    """KV rows as 8-bit codes with one scale per (token, head) row: an option beside the paper's
+    method, which names quantisation as compatible with it (Section 2). x: [..., D].
+    scale = max|x| / 127, code = x / scale rounded to the nearest integer, ties to even, in
+    [-127, 127]; a row of zeros has scale 0 and codes 0. The divisions and the rounding are taken
+    in float32: that is the precision in which the library decides the codes."""
+    x = np.asarray(x, dtype=np.float32)
+    amax = np.max(np.abs(x), axis=-1).astype(np.float32)
+    scale = (amax / np.float32(127.0)).astype(np.float32)
+    safe = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    q = np.rint((x / safe[..., None]).astype(np.float32))
+    q = np.clip(q, -127, 127).astype(np.int8)
+    q[scale == 0] = 0
+    return q, scale
+
+
+def dequantize_rows(codes, scale) -> np.ndarray:
+    """code * scale in float32, what the gather computes before it rotates and rounds to bf16."""
+    return (np.asarray(codes).astype(np.float32) * np.asarray(scale, dtype=np.float32)[..., None]).astype(np.float32)
+
+
 def cluster_scores(mass: np.ndarray, seg_lens: Sequence[int], spans: Sequence[int], per_key: bool) -> np.ndarray:
     """Section 3.3: attention between a newly detected object and an existing
     group. mass: [N_q, Hq, S+1] of ONE agent; an object o is the new tokens

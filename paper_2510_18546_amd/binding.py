@@ -16,12 +16,12 @@ import numpy as np
 
 from . import build as _build
 
-EN_F32, EN_BF16 = 0, 1
+EN_F32, EN_BF16, EN_I8 = 0, 1, 2
 STATUS = {0: "EN_OK", 1: "EN_ERR_INVALID_ARG", 2: "EN_ERR_OUT_OF_RANGE", 3: "EN_ERR_DUPLICATE",
           4: "EN_ERR_CAPACITY", 5: "EN_ERR_UNSUPPORTED", 6: "EN_ERR_DEVICE"}
 
 EXPORTS = [
-    "kv_pool_create", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
+    "kv_pool_create", "kv_pool_set_scales", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
     "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
@@ -72,6 +72,7 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib = C.CDLL(path)
     vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
     lib.kv_pool_create.argtypes = [C.POINTER(PoolDesc), vp, vp, i32p, C.POINTER(vp)]
+    lib.kv_pool_set_scales.argtypes = [vp, vp, vp]
     lib.kv_pool_set_len.argtypes = [vp, C.c_int32, C.c_int32]
     lib.kv_pool_append.argtypes = [vp, C.c_int32, vp, vp, C.c_int32, vp]
     lib.kv_pool_destroy.argtypes = [vp]
@@ -214,7 +215,7 @@ def kv_pool_create(k_pool, v_pool, lens, n_q_heads: int, rope_base: float, max_c
         import torch
         assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.shape == v_pool.shape
         shape = tuple(k_pool.shape)
-        dtype = EN_BF16 if k_pool.dtype == torch.bfloat16 else EN_F32
+        dtype = EN_BF16 if k_pool.dtype == torch.bfloat16 else EN_I8 if k_pool.dtype == torch.int8 else EN_F32
         k_ptr, v_ptr = k_pool.data_ptr(), v_pool.data_ptr()
     G, Hkv, Cap, D = shape
     desc = PoolDesc(G, Cap, Hkv, n_q_heads, D, dtype, max_ctx, 0, rope_base)
@@ -223,6 +224,18 @@ def kv_pool_create(k_pool, v_pool, lens, n_q_heads: int, rope_base: float, max_c
     _check(load().kv_pool_create(C.byref(desc), C.c_void_p(k_ptr), C.c_void_p(v_ptr), _ip(lens),
                                  C.byref(h)))
     return Pool(h, k_pool, v_pool, desc)
+
+
+def kv_pool_set_scales(pool: Pool, k_scale, v_scale):
+    """k_scale, v_scale: float32 tensors [G, Hkv, C] on the GPU (kept alive by the pool), or integers as
+    opaque pointers for host-only tests."""
+    if hasattr(k_scale, "data_ptr"):
+        assert k_scale.is_contiguous() and v_scale.is_contiguous()
+        pool.k_scale, pool.v_scale = k_scale, v_scale
+        kp, vp_ = k_scale.data_ptr(), v_scale.data_ptr()
+    else:
+        kp, vp_ = k_scale, v_scale
+    _check(load().kv_pool_set_scales(pool.handle, C.c_void_p(kp), C.c_void_p(vp_)))
 
 
 def kv_pool_set_len(pool: Pool, group: int, length: int):

@@ -44,7 +44,12 @@ static int hip_fail(hipError_t e, const char *what)
 
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 static inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
-static inline size_t elem_size(int dtype) { return dtype == EN_BF16 ? 2 : 4; }
+// bytes of an element of the contexts, the queries and the outputs (an EN_I8 pool computes in bf16)
+static inline size_t elem_size(int dtype) { return dtype == EN_F32 ? 4 : 2; }
+// bytes of an element of the pool arrays
+static inline size_t pool_elem_size(int dtype) { return dtype == EN_F32 ? 4 : dtype == EN_BF16 ? 2 : 1; }
+// the bf16 kernels serve EN_BF16 and EN_I8 pools
+static inline bool computes_bf16(int dtype) { return dtype != EN_F32; }
 
 // ---------------------------------------------------------------------------
 // pool
@@ -59,7 +64,7 @@ extern "C" int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev
         desc->n_q_heads <= 0 || desc->max_ctx <= 0 || desc->reserved != 0 ||
         !(desc->rope_base > 0.0))
         return fail(EN_ERR_INVALID_ARG, "kv_pool_create: non-positive size, reserved != 0 or bad rope_base");
-    if (desc->dtype != EN_F32 && desc->dtype != EN_BF16)
+    if (desc->dtype != EN_F32 && desc->dtype != EN_BF16 && desc->dtype != EN_I8)
         return fail(EN_ERR_UNSUPPORTED, "kv_pool_create: dtype %d", desc->dtype);
     if (desc->head_dim != 64 && desc->head_dim != 128)
         return fail(EN_ERR_UNSUPPORTED, "kv_pool_create: head_dim %d (64 or 128)", desc->head_dim);
@@ -91,6 +96,17 @@ extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
     return EN_OK;
 }
 
+extern "C" int kv_pool_set_scales(en_pool *pool, float *k_scale_dev, float *v_scale_dev)
+{
+    if (!pool || !k_scale_dev || !v_scale_dev)
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_set_scales: null argument");
+    if (pool->d.dtype != EN_I8)
+        return fail(EN_ERR_INVALID_ARG, "kv_pool_set_scales: the pool does not hold 8-bit codes");
+    pool->k_scale = k_scale_dev;
+    pool->v_scale = v_scale_dev;
+    return EN_OK;
+}
+
 extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
                               int32_t n_tokens, void *stream)
 {
@@ -104,6 +120,27 @@ extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_d
                     group, len, n_tokens, pool->d.capacity);
     if (n_tokens == 0)
         return EN_OK;
+    if (pool->d.dtype == EN_I8) {
+        if (!pool->k_scale || !pool->v_scale)
+            return fail(EN_ERR_INVALID_ARG, "kv_pool_append: an 8-bit pool needs kv_pool_set_scales first");
+        EnAppendQ8Args q;
+        q.k_rows = k_rows_dev;
+        q.v_rows = v_rows_dev;
+        q.k_pool = static_cast<int8_t *>(pool->k_dev);
+        q.v_pool = static_cast<int8_t *>(pool->v_dev);
+        q.k_scale = pool->k_scale;
+        q.v_scale = pool->v_scale;
+        q.n = n_tokens;
+        q.Hkv = pool->d.n_kv_heads;
+        q.C = pool->d.capacity;
+        q.group = group;
+        q.first = len;
+        const int eq = en_launch_append_q8(pool, q, stream);
+        if (eq != 0)
+            return hip_fail((hipError_t)eq, "kv_pool_append launch");
+        pool->len[group] = len + n_tokens;
+        return EN_OK;
+    }
     EnAppendArgs a;
     a.k_rows = k_rows_dev;
     a.v_rows = v_rows_dev;
@@ -114,7 +151,7 @@ extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_d
     a.C = pool->d.capacity;
     a.group = group;
     a.first = len;
-    a.row_chunks = pool->d.head_dim * int(elem_size(pool->d.dtype)) / 16;
+    a.row_chunks = pool->d.head_dim * int(pool_elem_size(pool->d.dtype)) / 16;
     const int e = en_launch_append(pool, a, stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "kv_pool_append launch");
@@ -184,7 +221,7 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
     // workgroup (its key tiles plus a start-up and wind-down worth about six
     // tiles), is shortest; at least four key tiles per split.
     const int r = pool->r;
-    if (pool->d.dtype == EN_BF16 && r * pl->Nq <= EN_ROWS_PER_WAVE) {
+    if (computes_bf16(pool->d.dtype) && r * pl->Nq <= EN_ROWS_PER_WAVE) {
         // decode path: one wave per (agent, KV head, split); the two LDS stages
         // of a wave let two waves share a compute unit, and a wave takes about
         // 2 us per 64-key tile whatever the load: as many splits as give every
@@ -592,6 +629,8 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
         return fail(EN_ERR_INVALID_ARG, "gather_rope: null argument");
     if (plan->pool != pool)
         return fail(EN_ERR_INVALID_ARG, "gather_rope: plan belongs to another pool");
+    if (pool->d.dtype == EN_I8 && (!pool->k_scale || !pool->v_scale))
+        return fail(EN_ERR_INVALID_ARG, "gather_rope: an 8-bit pool needs kv_pool_set_scales first");
     int rc;
     bool inlined = false;
     if ((rc = pool_ensure_device(pool)) != EN_OK ||
@@ -607,6 +646,8 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
     a.vt = vt_dev;
     a.cos_tab = pool->d_cos;
     a.sin_tab = pool->d_sin;
+    a.k_scale = pool->k_scale;
+    a.v_scale = pool->v_scale;
     a.nseg = d_nseg(plan);
     a.sel = d_sel(plan);
     a.bnd = d_bnd(plan);
@@ -695,7 +736,7 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     a.n_splits = n_splits;
     const int nqb = (n_rows + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
-    a.decode = (pool->d.dtype == EN_BF16 && pool->r * n_rows <= EN_ROWS_PER_WAVE) ? 1 : 0;
+    a.decode = (computes_bf16(pool->d.dtype) && pool->r * n_rows <= EN_ROWS_PER_WAVE) ? 1 : 0;
     if (a.decode)
         a.n_ptiles = 1;
     a.total_wgs = plan->B * pool->d.n_kv_heads * n_splits * a.n_ptiles;

@@ -17,6 +17,8 @@ struct en_pool {
     en_pool_desc d;
     void *k_dev = nullptr;
     void *v_dev = nullptr;
+    float *k_scale = nullptr;     // EN_I8 pools: one scale per (group, head, token)
+    float *v_scale = nullptr;
     std::vector<int32_t> len;     // current lengths [G]
     int r = 1;                    // Hq / Hkv
     // device side, created on first GPU use
@@ -54,6 +56,7 @@ struct EnGatherArgs {
     const float *cos_tab, *sin_tab;
     const int32_t *nseg, *sel, *bnd;
     int B, Hkv, C, Nq, Smax, T;
+    const float *k_scale, *v_scale;    // EN_I8 pools only
 };
 
 // The gather launch can carry a small plan's descriptor block inside its kernel
@@ -102,6 +105,13 @@ struct EnAppendArgs {
     int n, Hkv, C, group, first;   // rows go to tokens first .. first+n-1 of the group
     int row_chunks;                // 16-byte chunks per (token, head) row
 };
+struct EnAppendQ8Args {
+    const void *k_rows, *v_rows;   // bf16 [n, Hkv, D]
+    int8_t *k_pool, *v_pool;       // [G, Hkv, C, D]
+    float *k_scale, *v_scale;      // [G, Hkv, C]
+    int n, Hkv, C, group, first;
+};
+
 
 constexpr int EN_MAX_OBJECTS = 255;    // per segment_cluster_assign call (spans travel in the kernel arguments)
 struct EnClusterArgs {
@@ -145,6 +155,7 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
 int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
 int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
 int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
+int en_launch_append_q8(const en_pool *pool, const EnAppendQ8Args &a, void *stream);
 int en_launch_cluster(const en_pool *pool, const EnClusterArgs &a, void *stream);
 int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *stream);
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);

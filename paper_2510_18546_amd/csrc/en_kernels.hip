@@ -233,6 +233,166 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
 }
 
 // ---------------------------------------------------------------------------
+// gather from an 8-bit pool: the same bf16 contexts as above from rows of int8
+// codes with one float scale per (group, head, token): value = code * scale in
+// float32, keys rotated, everything rounded to bf16 once. New tokens arrive in
+// bf16 as ever. grid as for the bf16 gather.
+// ---------------------------------------------------------------------------
+struct EnCtxLoc {
+    int kind;        // 0 padding, 1 row of the pool, 2 row of the new tokens
+    size_t row;      // index of the row, in rows of D elements
+};
+__device__ __forceinline__ EnCtxLoc context_loc(const EnGatherArgs &a, int b, int kvh, int tok)
+{
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Lc = bnd[S];
+    const int Ltot = bnd[S + 1];
+    if (tok >= Ltot)
+        return {0, 0};
+    if (tok >= Lc)
+        return {2, ((size_t)b * a.Nq + (tok - Lc)) * a.Hkv + kvh};
+    const int s = find_bucket(bnd, S, tok);
+    const int sstr = a.Smax > 0 ? a.Smax : 1;
+    const int g = a.sel[(size_t)b * sstr + s];
+    return {1, ((size_t)g * a.Hkv + kvh) * a.C + (tok - bnd[s])};
+}
+
+template <int D>
+__device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx)
+{
+    constexpr int E = D / 16;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int tok = bx * 32 + threadIdx.x / 8;
+    const int c = threadIdx.x % 8;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
+    if (tok >= Lpad)
+        return;
+    bf16_t *dst = (bf16_t *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
+    typedef bf16_t tvec __attribute__((ext_vector_type(E)));
+    typedef float fvec __attribute__((ext_vector_type(E)));
+    const EnCtxLoc loc = context_loc(a, b, kvh, tok);
+    fvec x1 = 0.f, x2 = 0.f;
+    if (loc.kind == 1) {
+        const int8_t *src = (const int8_t *)a.k_pool + loc.row * D;
+        const float sc = a.k_scale[loc.row];
+        int8_t c1[E], c2[E];
+        __builtin_memcpy(c1, src + c * E, E);
+        __builtin_memcpy(c2, src + D / 2 + c * E, E);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            x1[e] = (float)c1[e] * sc;
+            x2[e] = (float)c2[e] * sc;
+        }
+    } else if (loc.kind == 2) {
+        const bf16_t *src = (const bf16_t *)a.k_new + loc.row * D;
+        x1 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + c * E), fvec);
+        x2 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + D / 2 + c * E), fvec);
+    }
+    fvec y1 = 0.f, y2 = 0.f;
+    if (loc.kind != 0) {
+        const fvec cs = *reinterpret_cast<const fvec *>(a.cos_tab + (size_t)tok * (D / 2) + c * E);
+        const fvec sn = *reinterpret_cast<const fvec *>(a.sin_tab + (size_t)tok * (D / 2) + c * E);
+        y1 = x1 * cs - x2 * sn;
+        y2 = x2 * cs + x1 * sn;
+    }
+    *reinterpret_cast<tvec *>(dst + c * E) = __builtin_convertvector(y1, tvec);
+    *reinterpret_cast<tvec *>(dst + D / 2 + c * E) = __builtin_convertvector(y2, tvec);
+}
+
+template <int D>
+__device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx)
+{
+    constexpr int STR = D + 2;                 // LDS row stride in elements
+    __shared__ uint16_t tile[EN_KEY_TILE * STR];
+    __shared__ size_t rows[EN_KEY_TILE];
+    __shared__ int kinds[EN_KEY_TILE];
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int t0 = bx * EN_KEY_TILE;
+    const int S = a.nseg[b];
+    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int Ltot = bnd[S + 1];
+    if (t0 >= Ltot)
+        return;
+    if (threadIdx.x < EN_KEY_TILE) {
+        const EnCtxLoc loc = context_loc(a, b, kvh, t0 + threadIdx.x);
+        rows[threadIdx.x] = loc.row;
+        kinds[threadIdx.x] = loc.kind;
+    }
+    __syncthreads();
+    typedef bf16_t bvec __attribute__((ext_vector_type(8)));
+    typedef float fvec8 __attribute__((ext_vector_type(8)));
+    constexpr int CH = D / 8;                  // chunks of 8 elements per token
+    for (int idx = threadIdx.x; idx < EN_KEY_TILE * CH; idx += 256) {
+        const int tk = idx / CH, ch = idx % CH;
+        bvec v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (kinds[tk] == 1) {
+            const int8_t *src = (const int8_t *)a.v_pool + rows[tk] * D + ch * 8;
+            const float sc = a.v_scale[rows[tk]];
+            int8_t cd[8];
+            __builtin_memcpy(cd, src, 8);
+            fvec8 f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                f[e] = (float)cd[e] * sc;
+            v = __builtin_convertvector(f, bvec);
+        } else if (kinds[tk] == 2) {
+            v = *reinterpret_cast<const bvec *>((const bf16_t *)a.v_new + rows[tk] * D + ch * 8);
+        }
+        uint4 raw;
+        __builtin_memcpy(&raw, &v, 16);
+        uint16_t *d = &tile[tk * STR + ch * 8];
+        // STR is even but not a multiple of 8: store as 4 dwords
+        reinterpret_cast<uint32_t *>(d)[0] = raw.x;
+        reinterpret_cast<uint32_t *>(d)[1] = raw.y;
+        reinterpret_cast<uint32_t *>(d)[2] = raw.z;
+        reinterpret_cast<uint32_t *>(d)[3] = raw.w;
+    }
+    __syncthreads();
+    // store: for every d, 8 chunks of 8 columns (the same order as the bf16 gather)
+    uint16_t *vt = (uint16_t *)a.vt + ((size_t)b * a.Hkv + kvh) * D * (size_t)a.T + t0;
+    for (int idx = threadIdx.x; idx < D * 8; idx += 256) {
+        const int d = idx / 8, ch = idx % 8;      // columns ch*8 .. ch*8+7
+        const int g16 = ch / 2, hf = ch % 2;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int tk = 16 * g16 + 8 * (e >> 2) + 4 * hf + (e & 3);
+            v[e] = tile[tk * STR + d];
+        }
+        uint4 o;
+        o.x = v[0] | ((uint32_t)v[1] << 16);
+        o.y = v[2] | ((uint32_t)v[3] << 16);
+        o.z = v[4] | ((uint32_t)v[5] << 16);
+        o.w = v[6] | ((uint32_t)v[7] << 16);
+        *reinterpret_cast<uint4 *>(vt + (size_t)d * a.T + ch * 8) = o;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
+{
+    EnGatherArgs a = g.a;
+    if (g.n_inline > 0) {
+        const int32_t *img = reinterpret_cast<const int32_t *>(
+            reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + offsetof(EnGatherLaunch, desc));
+        a.nseg = img + g.off_nseg;
+        a.sel = img + g.off_sel;
+        a.bnd = img + g.off_bnd;
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+            for (int i = threadIdx.x; i < g.n_inline; i += 256)
+                g.desc_out[i] = img[i];
+    }
+    if ((int)blockIdx.x < g.nk)
+        gather_q8_k_block<D>(a, blockIdx.x);
+    else
+        gather_q8_vt_block<D>(a, blockIdx.x - g.nk);
+}
+
+// ---------------------------------------------------------------------------
 // attn_bf16: matrix-core attention.
 //
 // Work unit: one workgroup of 8 waves = 8 (query head, 32-query block) pairs of
@@ -1866,6 +2026,39 @@ __global__ __launch_bounds__(256) void append_kernel(EnAppendArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// append to an 8-bit pool: one wave per (token, head) row and array. The row's
+// largest magnitude fixes the scale (max|x| / 127), the codes are x / scale
+// rounded to the nearest integer, ties to even, all in float32; a zero row has
+// scale 0. grid: (n, Hkv, 2), 64 threads.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void append_q8_kernel(EnAppendQ8Args a)
+{
+    constexpr int EPL = D / 64;               // elements per lane
+    const int tok = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const bf16_t *src = (const bf16_t *)(blockIdx.z == 0 ? a.k_rows : a.v_rows) + ((size_t)tok * a.Hkv + h) * D;
+    float x[EPL];
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        x[e] = (float)src[lane * EPL + e];
+        amax = fmaxf(amax, fabsf(x[e]));
+    }
+    amax = wave_max(amax);
+    const float scale = amax / 127.0f;
+    const size_t row = ((size_t)a.group * a.Hkv + h) * a.C + a.first + tok;
+    int8_t *dst = (blockIdx.z == 0 ? a.k_pool : a.v_pool) + row * D;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        float q = scale > 0.f ? rintf(x[e] / scale) : 0.f;
+        q = fminf(fmaxf(q, -127.f), 127.f);
+        dst[lane * EPL + e] = (int8_t)(int)q;
+    }
+    if (lane == 0)
+        (blockIdx.z == 0 ? a.k_scale : a.v_scale)[row] = scale;
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream)
@@ -1883,6 +2076,12 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
             hipLaunchKernelGGL((gather_kernel<float, 64>), grid, blk, 0, st, g);
         else
             hipLaunchKernelGGL((gather_kernel<float, 128>), grid, blk, 0, st, g);
+    } else if (pool->d.dtype == EN_I8) {
+        const dim3 grid(nk + nv, a.Hkv, a.B);
+        if (D == 64)
+            hipLaunchKernelGGL((gather_q8_kernel<64>), grid, blk, 0, st, g);
+        else
+            hipLaunchKernelGGL((gather_q8_kernel<128>), grid, blk, 0, st, g);
     } else {
         const dim3 grid(nk + nv, a.Hkv, a.B);
         if (D == 64)
@@ -1988,6 +2187,16 @@ int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream)
     const int units = max_tokens * (a.row_bytes / 16);
     const dim3 grid((units + 1023) / 1024, 2 * a.Hkv, a.n), blk(256);
     hipLaunchKernelGGL(tier_load_kernel, grid, blk, 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+int en_launch_append_q8(const en_pool *pool, const EnAppendQ8Args &a, void *stream)
+{
+    const dim3 grid(a.n, a.Hkv, 2), blk(64);
+    if (pool->d.head_dim == 64)
+        hipLaunchKernelGGL((append_q8_kernel<64>), grid, blk, 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((append_q8_kernel<128>), grid, blk, 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

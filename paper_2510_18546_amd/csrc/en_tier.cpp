@@ -105,6 +105,8 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: k_dev and v_dev must both be given or both be null");
     if (n_groups_total <= 0 || desc->n_groups <= 0)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: non-positive group or slot count");
+    if (desc->dtype == EN_I8)
+        return tfail(EN_ERR_UNSUPPORTED, "kv_tier_create: 8-bit pools are not served by a tier");
     en_tier *t = new (std::nothrow) en_tier;
     if (!t)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: out of host memory");

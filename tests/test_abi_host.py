@@ -295,3 +295,26 @@ int main(void) {
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
     assert "max_ctx" in out.stdout
+
+
+def test_q8_pool_checks_without_device():
+    pool = B.kv_pool_create(None, None, [3, 4], 4, 1e4, 64, dtype=B.EN_I8, k_ptr=8, v_ptr=8, shape=(2, 1, 8, 64))
+    plan = B.segment_select(pool, [1, 0], [0, 2], 4)
+    assert plan.offsets(0).tolist() == [0, 4, 7]
+    # contexts of an 8-bit pool are bf16: 2 bytes per element, 64 rows of padding granularity
+    assert B.context_bytes(pool, plan) == 1 * 1 * plan.info.ctx_stride * 64 * 2
+    with pytest.raises(B.EnError) as e:      # no scales yet
+        B.load().gather_rope.restype = C.c_int
+        rc = B.load().gather_rope(pool.handle, plan.handle, C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), None)
+        B._check(rc)
+    assert e.value.code == 1 and "kv_pool_set_scales" in str(e.value)
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_append(pool, 0, 8, 8, n_tokens=1)
+    assert e.value.code == 1
+    f32 = B.kv_pool_create(None, None, [3, 4], 4, 1e4, 64, dtype=B.EN_F32, k_ptr=8, v_ptr=8, shape=(2, 1, 8, 64))
+    with pytest.raises(B.EnError) as e:
+        B.kv_pool_set_scales(f32, 8, 8)
+    assert e.value.code == 1
+    with pytest.raises(B.EnError) as e:
+        B.kv_tier_create(None, None, 4, 4, 1e4, 64, dtype=B.EN_I8, shape=(2, 1, 8, 64))
+    assert e.value.code == 5

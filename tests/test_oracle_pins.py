@@ -401,3 +401,35 @@ def test_knapsack_dp_matches_bruteforce(oracle):
         budget = int(rng.integers(0, 25))
         assert oracle.knapsack_dp(p, lens, 0.375, budget) == \
             oracle.knapsack_bruteforce(p, lens, 0.375, budget)
+
+
+# ---------------------------------------------------------------------------
+# 8-bit KV rows (an option beside the paper's method)
+# ---------------------------------------------------------------------------
+def test_quantised_rows_error_bound_grid_and_zero_rows(oracle):
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal((50, 3, 64)).astype(np.float32) * rng.uniform(1e-3, 30, size=(50, 3, 1)).astype(np.float32)
+    x[7, 1] = 0.0
+    q, s = oracle.quantize_rows(x)
+    assert q.dtype == np.int8 and s.dtype == np.float32 and q.shape == x.shape and s.shape == x.shape[:-1]
+    assert np.abs(q.astype(np.int32)).max() <= 127
+    # the largest element of every row maps to +-127, the scale is max|x| / 127
+    amax = np.abs(x).max(-1)
+    assert np.array_equal(np.abs(q.astype(np.int32)).max(-1)[amax > 0], np.full((amax > 0).sum(), 127))
+    np.testing.assert_allclose(s, amax / 127.0, rtol=1e-6)
+    assert s[7, 1] == 0 and (q[7, 1] == 0).all()
+    # rounding to nearest: the error is at most half a step (plus float32 rounding of the division)
+    d = oracle.dequantize_rows(q, s)
+    assert (np.abs(d - x) <= 0.5 * s[..., None] * (1 + 1e-5) + 1e-12).all()
+    # values on the grid come back exactly, codes and all: steps of 2^-5, largest element 127 steps
+    k = rng.integers(-127, 128, size=(20, 2, 64)).astype(np.float32)
+    k[..., 0] = 127
+    q2, s2 = oracle.quantize_rows(k * np.float32(2.0 ** -5))
+    assert np.array_equal(q2.astype(np.float32), k) and (s2 == np.float32(2.0 ** -5)).all()
+    assert np.array_equal(oracle.dequantize_rows(q2, s2), k * np.float32(2.0 ** -5))
+    # ties go to even: 0.5 and 1.5 steps
+    t = np.zeros((1, 1, 64), np.float32)
+    t[0, 0, 0] = 127.0
+    t[0, 0, 1:5] = [0.5, 1.5, 2.5, -0.5]
+    qt, st = oracle.quantize_rows(t)
+    assert st[0, 0] == 1.0 and qt[0, 0, 1:5].tolist() == [0, 2, 2, 0]
