@@ -193,7 +193,7 @@ int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
                   int32_t *n_seg_out);
 
 /* Override the number of KV splits chosen by segment_select (>= 1, clamped to
- * the number of 64-key tiles). Must precede en_workspace_bytes. */
+ * the number of 64-key tiles and to 64). Must precede en_workspace_bytes. */
 int en_plan_set_splits(en_plan *plan, int32_t n_splits);
 
 /* May be called while work that uses the plan is still queued on a stream,

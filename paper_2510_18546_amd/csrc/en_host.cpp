@@ -236,13 +236,13 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
         if (want < 2 && tiles >= 64)
             want = 2;
         want = std::min<long>(want, std::max(1, tiles / 4));
-        return int(std::max<long>(1, std::min<long>(want, 64)));
+        return int(std::max<long>(1, std::min<long>(want, EN_MAX_SPLITS)));
     }
     const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     const int n_ptiles = (r * nqb + EN_WAVES - 1) / EN_WAVES;
     const long base = long(pl->B) * pool->d.n_kv_heads * n_ptiles;
     const int tiles = std::max(1, (pl->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
-    const int n_max = std::max(1, std::min(64, tiles / 4));
+    const int n_max = std::max(1, std::min(EN_MAX_SPLITS, tiles / 4));
     int best = 1;
     long best_cost = -1;
     for (int n = 1; n <= n_max; ++n) {
@@ -461,7 +461,7 @@ extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
     if (!plan || n_splits < 1)
         return fail(EN_ERR_INVALID_ARG, "en_plan_set_splits: null plan or n_splits < 1");
     const int tiles = std::max(1, (plan->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
-    plan->n_splits = std::min(n_splits, tiles);
+    plan->n_splits = std::min(std::min(n_splits, tiles), EN_MAX_SPLITS);
     return EN_OK;
 }
 
@@ -685,6 +685,7 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
     a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
     a.nseg = d_nseg(plan);
     a.bnd = d_bnd(plan);
+    a.hdr = d_hdr(plan);
     a.out = nullptr;
     a.B = plan->B;
     a.Hq = pool->d.n_q_heads;

@@ -94,6 +94,7 @@ struct EnMassArgs {
     const float *ws_ml, *ws_seg, *ws_mlfin;
     float *ws_red;          // [B, Smax+1, Hq] per-head partial sums of the reduced masses
     const int32_t *nseg, *bnd;
+    const int32_t *hdr;     // as in EnAttnArgs
     float *out;
     int B, Hq, Nq, Smax, n_splits;
     int q_first;            // as in EnAttnArgs
@@ -113,6 +114,7 @@ struct EnAppendQ8Args {
 };
 
 
+constexpr int EN_MAX_SPLITS = 64;       // KV splits of a plan: the mass kernels hold one split per lane
 constexpr int EN_MAX_OBJECTS = 255;    // per segment_cluster_assign call (spans travel in the kernel arguments)
 struct EnClusterArgs {
     EnMassArgs m;                  // the scratch of the attention call (m.out unused)

@@ -476,6 +476,13 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+__device__ __forceinline__ size_t readlane64(size_t v, int l)
+{
+    const unsigned lo = __builtin_amdgcn_readlane((int)(unsigned)v, l);
+    const unsigned hi = __builtin_amdgcn_readlane((int)(unsigned)(v >> 32), l);
+    return ((size_t)hi << 32) | lo;
+}
+
 __device__ __forceinline__ float pair_max(float v)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -1559,8 +1566,19 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
 // softmax output and w_sp = l_sp 2^(m_sp - m). One thread per 16 bytes of an
 // output row. grid: ceil(rows * D / V / 256), V = elements in 16 bytes.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red);
+__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk, float *red);
 constexpr int EN_MASS_FEW_ROWS = 64;      // below this many query rows per head the partial sums go thread-wise
+// Stage 1 of the reduced masses: a workgroup takes EN_MASS_BG consecutive buckets of one
+// (agent, head) over all query rows (see mass_partial_block).
+constexpr int EN_MASS_BG = 8;
+__host__ __device__ inline int mass_bucket_groups(const EnMassArgs &m)
+{
+    return (m.Smax + 1 + EN_MASS_BG - 1) / EN_MASS_BG;
+}
+__host__ inline int mass_partial_blocks(const EnMassArgs &m)
+{
+    return mass_bucket_groups(m) * m.Hq * m.B;
+}
 
 // With many splits (decode over a long context by few agents) G = 4 neighbouring lanes share a
 // (row, 16-byte chunk): lane g takes the splits g, g + 4, ... and the four partial results are
@@ -1570,11 +1588,8 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
 {
     // tail of the grid: per-head partial sums of the segment masses
     if ((int)blockIdx.x >= n_comb) {
-        __shared__ float red[4];
-        int t = blockIdx.x - n_comb;
-        const int s = t % (m.Smax + 1);
-        t /= (m.Smax + 1);
-        mass_partial_block(m, s, t % m.Hq, t / m.Hq, red);
+        __shared__ float red[4 * EN_MASS_BG];
+        mass_partial_block(m, blockIdx.x - n_comb, red);
         return;
     }
     constexpr int V = 16 / sizeof(T);
@@ -1700,31 +1715,69 @@ __device__ __forceinline__ void merged_ml(const EnMassArgs &a, size_t rows, size
     }
 }
 
-// Splits whose key range meets bucket [blo, bhi): a contiguous range [lo, hi].
-__device__ __forceinline__ void bucket_splits(int n_splits, int ntiles, int Ltot, int blo, int bhi,
+// Tiles of the KV splits, one split per lane (a plan has at most 64 splits): the attention
+// kernels give split sp the tiles [sp * ntiles / n_splits, (sp + 1) * ntiles / n_splits). Code that
+// has to know which splits cover a bucket asks this map with two wave votes instead of doing
+// integer divisions per bucket (a division by a run-time value is some thirty instructions, and
+// these kernels are bound by their instruction count).
+struct EnSplitMap {
+    int end_tile;                  // first tile after this lane's split; lanes >= n_splits: INT_MAX
+    unsigned long long keys;       // bit sp: split sp holds at least one tile
+};
+// whole wave, uniform arguments
+__device__ __forceinline__ EnSplitMap split_map(int n_splits, int ntiles)
+{
+    const unsigned q = threadIdx.x % 64;
+    const unsigned bgn = q * (unsigned)ntiles / (unsigned)n_splits;
+    const unsigned end = (q + 1) * (unsigned)ntiles / (unsigned)n_splits;
+    EnSplitMap m;
+    m.end_tile = (int)q < n_splits ? (int)end : 0x7fffffff;
+    m.keys = __ballot((int)q < n_splits && end != bgn);
+    return m;
+}
+// Splits whose key range meets bucket [blo, bhi): a contiguous range [lo, hi]. Whole wave, uniform
+// arguments: the split that holds tile t is the number of splits that end at or before t.
+__device__ __forceinline__ void bucket_splits(const EnSplitMap &m, int n_splits, int Ltot, int blo, int bhi,
                                               int &lo, int &hi)
 {
-    // split sp covers tiles [sp * ntiles / n_splits, (sp + 1) * ntiles / n_splits): the split that
-    // holds tile t is the largest sp whose first tile is <= t, i.e. ((t + 1) * n_splits - 1) / ntiles
     bhi = min(bhi, Ltot);          // a decode step's rows see less than the plan's whole new block
+    const int t_lo = blo / EN_KEY_TILE, t_hi = (bhi - 1) / EN_KEY_TILE;
+    const int l = (int)__popcll(__ballot(m.end_tile <= t_lo));
+    const int h = (int)__popcll(__ballot(m.end_tile <= t_hi));
+    lo = bhi <= blo ? n_splits : l;
+    hi = bhi <= blo ? -1 : h;
+}
+// The same for one thread on its own (32-bit arithmetic: (t + 1) * n_splits <= Ltot + 64): the split
+// that holds tile t is the largest sp whose first tile is <= t, ((t + 1) * n_splits - 1) / ntiles.
+// Also returns the mask of the splits in [lo, hi] that hold keys.
+__device__ __forceinline__ void bucket_splits_thread(int n_splits, int ntiles, int Ltot, int blo, int bhi,
+                                                     int &lo, int &hi, unsigned long long &keys)
+{
+    bhi = min(bhi, Ltot);
+    keys = 0;
     if (bhi <= blo) {
         lo = n_splits;
         hi = -1;
         return;
     }
-    const int t_lo = blo / EN_KEY_TILE, t_hi = (bhi - 1) / EN_KEY_TILE;
-    lo = (int)(((long)(t_lo + 1) * n_splits - 1) / ntiles);
-    hi = (int)(((long)(t_hi + 1) * n_splits - 1) / ntiles);
+    const unsigned t_lo = blo / EN_KEY_TILE, t_hi = (bhi - 1) / EN_KEY_TILE;
+    lo = (int)(((t_lo + 1) * (unsigned)n_splits - 1) / (unsigned)ntiles);
+    hi = (int)(((t_hi + 1) * (unsigned)n_splits - 1) / (unsigned)ntiles);
+    for (int sp = lo; sp <= hi; ++sp)
+        if ((unsigned)sp * (unsigned)ntiles / (unsigned)n_splits !=
+            (unsigned)(sp + 1) * (unsigned)ntiles / (unsigned)n_splits)
+            keys |= 1ull << sp;
 }
 
 __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int hq, int i, int bucket,
-                                                 int sp_lo, int sp_hi, float M, float L, int ntiles)
+                                                 int sp_lo, int sp_hi, float M, float L,
+                                                 unsigned long long keys)
 {
     float acc = 0.f;
     for (int sp = sp_lo; sp <= sp_hi; ++sp) {
         // an agent with fewer key tiles than the plan has splits leaves some splits without
         // keys: nothing was written for them
-        if (sp * ntiles / a.n_splits == (sp + 1) * ntiles / a.n_splits)
+        if (!((keys >> sp) & 1))
             continue;
         const f32x2 v = *reinterpret_cast<const f32x2 *>(
             a.ws_seg + (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
@@ -1752,17 +1805,19 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
     const int Ltot = bnd[S] + a.q_first + a.Nq;     // end of what the rows could see
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+    const EnSplitMap map = split_map(a.n_splits, ntiles);
     float M, L;
     row_final_ml(a, rows, row, M, L);
     for (int s0 = 0; s0 <= a.Smax; s0 += SB) {
         const int n = min(SB, a.Smax + 1 - s0);
         for (int c = wave; c < n; c += 4) {
-            const int s = s0 + c;
+            const int s = s0 + c;                 // the same for the whole wave
             float v = 0.f;
-            if (valid && s <= S && bnd[s + 1] > bnd[s]) {
+            if (s <= S && bnd[s + 1] > bnd[s]) {
                 int lo, hi;
-                bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
-                v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
+                bucket_splits(map, a.n_splits, Ltot, bnd[s], bnd[s + 1], lo, hi);
+                if (valid)
+                    v = row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, map.keys);
             }
             tile[lane][c] = v;
         }
@@ -1776,38 +1831,135 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
     }
 }
 
-// reduce = 1, stage 1: block (s, hq, b) sums bucket s of one head over the
-// queries into partial[b][s][hq]. With several KV splits this runs as the tail
-// of the combine launch (the partial sums are a by-product of the attention
-// call, whatever the caller asks of the mass call later) and merges the
-// splits' (reference, sum) pairs itself; with one split it is a launch of its
-// own. (One launch that lets the last workgroup finish needs a device-scope
-// release per workgroup, which writes the L2 back: measured 25 us; one
-// workgroup per bucket is bound by a single compute unit: 14 us.)
-__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int s, int hq, int b, float *red)
+// reduce = 1, stage 1: workgroup blk = (b * Hq + hq) * n_groups + group sums EN_MASS_BG buckets
+// of one head over the queries into partial[b][s][hq]. With several KV splits this runs as the
+// tail of the combine launch (the partial sums are a by-product of the attention call, whatever
+// the caller asks of the mass call later) and merges the splits' (reference, sum) pairs itself;
+// with one split it is a launch of its own.
+//
+// What this costs is instructions per (row, bucket) and dependent trips to memory (about a
+// microsecond each), not bytes. So lanes are rows: a row's merged (reference, sum) pair is made
+// once for the group's buckets; everything that is the same for all rows (which splits cover a
+// bucket, whether they hold keys) is decided from the agent's header and bounds in scalar
+// registers before the rows start; and a row's loads for all buckets go out together: a bucket
+// is covered by one split or by two neighbours unless it is longer than a split, so two entries
+// per bucket are fetched whether or not the second one counts (it lies inside the scratch either
+// way). A group with a bucket over more than two splits takes them one after the other.
+// (Other forms, measured on 16 agents x 25 buckets x 32 heads x 128 rows and on the tail of the
+// 8K-context merge: one workgroup per (bucket, head), all of the above per row: 23 us / 6 us;
+// the same buckets in one workgroup with loads as they are needed: 27 us / 13 us; one launch that
+// lets the last workgroup finish (a device-scope release per workgroup, which writes the L2
+// back): 25 us; one workgroup per bucket: 14 us.)
+__device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk, float *red)
 {
-    const size_t rows = (size_t)a.B * a.Hq * a.Nq;
-    const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S] + a.q_first + a.Nq;     // end of what the rows could see
-    const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
-    float acc = 0.f;
-    if (s <= S && bnd[s + 1] > bnd[s]) {
-        int lo, hi;
-        bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
-        for (int i = threadIdx.x; i < a.Nq; i += 256) {
-            const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
-            float M, L;
-            merged_ml(a, rows, row, M, L);
-            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
+    constexpr int BG = EN_MASS_BG;
+    const int ng = mass_bucket_groups(a);
+    const int s0 = (blk % ng) * BG;
+    const int hq = (blk / ng) % a.Hq;
+    const int b = blk / (ng * a.Hq);
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    float acc[BG];
+#pragma unroll
+    for (int j = 0; j < BG; ++j)
+        acc[j] = 0.f;
+    if (wave * 64 < a.Nq) {                        // a wave without rows has nothing to set up
+        const size_t rows = (size_t)a.B * a.Hq * a.Nq;
+        const en_table_ptr hdr = as_table(a.hdr + 4 * (size_t)b);
+        const int S = hdr[0];
+        const int Ltot = hdr[1] + a.q_first + a.Nq;     // end of what the rows could see
+        const unsigned ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
+        const unsigned n = a.n_splits;
+        // Bucket s0 + j is worked out by the lanes j, j + BG, ... (all of them alike), every bucket
+        // of the group at once: the first split that covers it and whether that split and the one
+        // after it count. Done bucket by bucket in scalar registers, this set-up was most of the
+        // kernel's time: the scalar unit is shared by all waves of a compute unit.
+        int lo_v, hi_v;
+        bool live_v, use0_v, use1_v, next_v;
+        size_t off0_v, off1_v;                          // byte offsets of the bucket's two entries of row 0
+        const size_t per_split = (size_t)a.B * a.Hq * (a.Smax + 1) * a.Nq * 8;      // bytes
+        {
+            const int jl = lane % BG;
+            const int s = min(s0 + jl, a.Smax);
+            const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+            const int blo = bnd[s];
+            const int bhi = min(bnd[s + 1], Ltot);      // a decode step's rows see less than the whole new block
+            live_v = s0 + jl <= S && bhi > blo;
+            const unsigned t_lo = live_v ? blo / EN_KEY_TILE : 0, t_hi = live_v ? (bhi - 1) / EN_KEY_TILE : 0;
+            // the split that holds tile t is the largest sp whose first tile is <= t
+            const unsigned l = ((t_lo + 1) * n - 1) / ntiles, h = ((t_hi + 1) * n - 1) / ntiles;
+            const unsigned e0 = l * ntiles / n, e1 = (l + 1) * ntiles / n, e2 = (l + 2) * ntiles / n;
+            next_v = l + 1 < n;
+            use0_v = live_v && e0 != e1;                // an agent with fewer tiles than splits leaves some empty
+            use1_v = live_v && h > l && next_v && e1 != e2;
+            lo_v = (int)l;
+            hi_v = (int)h;
+            off0_v = l * per_split + (((size_t)b * a.Hq + hq) * (a.Smax + 1) + s) * a.Nq * 8;
+            off1_v = off0_v + (next_v ? per_split : 0);
+        }
+        const unsigned use0 = (unsigned)__ballot(use0_v), use1 = (unsigned)__ballot(use1_v);
+        const unsigned live = (unsigned)__ballot(live_v);
+        const bool simple = __ballot(live_v && hi_v - lo_v > 1) == 0;
+        int lo[BG];
+#pragma unroll
+        for (int j = 0; j < BG; ++j)
+            lo[j] = __builtin_amdgcn_readlane(lo_v, j);
+        if (simple) {
+            const char *p0[BG], *p1[BG];
+#pragma unroll
+            for (int j = 0; j < BG; ++j) {
+                p0[j] = (const char *)a.ws_seg + readlane64(off0_v, j);
+                p1[j] = (const char *)a.ws_seg + readlane64(off1_v, j);
+            }
+            for (int i = threadIdx.x; i < a.Nq; i += 256) {
+                const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+                f32x2 v0[BG], v1[BG];
+#pragma unroll
+                for (int j = 0; j < BG; ++j) {
+                    v0[j] = *reinterpret_cast<const f32x2 *>(p0[j] + (unsigned)i * 8u);
+                    v1[j] = *reinterpret_cast<const f32x2 *>(p1[j] + (unsigned)i * 8u);
+                }
+                float M, L;
+                merged_ml(a, rows, row, M, L);
+                const float inv = 1.f / L;
+#pragma unroll
+                for (int j = 0; j < BG; ++j) {
+                    float part = 0.f;
+                    if (((use0 >> j) & 1) && v0[j][1] != EN_NEG_INF)
+                        part += v0[j][0] * fast_exp2(v0[j][1] - M);
+                    if (((use1 >> j) & 1) && v1[j][1] != EN_NEG_INF)
+                        part += v1[j][0] * fast_exp2(v1[j][1] - M);
+                    acc[j] += part * inv;
+                }
+            }
+        } else {
+            const EnSplitMap map = split_map(a.n_splits, (int)ntiles);
+            int hi[BG];
+#pragma unroll
+            for (int j = 0; j < BG; ++j)
+                hi[j] = __builtin_amdgcn_readlane(hi_v, j);
+            for (int i = threadIdx.x; i < a.Nq; i += 256) {
+                const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
+                float M, L;
+                merged_ml(a, rows, row, M, L);
+#pragma unroll
+                for (int j = 0; j < BG; ++j)
+                    if ((live >> j) & 1)
+                        acc[j] += row_bucket_mass(a, b, hq, i, s0 + j, lo[j], hi[j], M, L, map.keys);
+            }
         }
     }
-    acc = wave_sum(acc);
-    if (threadIdx.x % 64 == 0)
-        red[threadIdx.x / 64] = acc;
+#pragma unroll
+    for (int j = 0; j < BG; ++j) {
+        const float t = wave_sum(acc[j]);
+        if (lane == 0)
+            red[wave * BG + j] = t;
+    }
     __syncthreads();
-    if (threadIdx.x == 0)
-        a.ws_red[((size_t)b * (a.Smax + 1) + s) * a.Hq + hq] = red[0] + red[1] + red[2] + red[3];
+    if (threadIdx.x < BG && s0 + (int)threadIdx.x <= a.Smax) {
+        const int j = threadIdx.x;
+        a.ws_red[((size_t)b * (a.Smax + 1) + s0 + j) * a.Hq + hq] =
+            red[j] + red[BG + j] + red[2 * BG + j] + red[3 * BG + j];
+    }
 }
 
 // The same for few query rows per head (decode steps): one THREAD per (agent, bucket, head) walks
@@ -1829,25 +1981,26 @@ __device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_
     float acc = 0.f;
     if (s <= S && bnd[s + 1] > bnd[s]) {
         int lo, hi;
-        bucket_splits(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi);
+        unsigned long long keys;
+        bucket_splits_thread(a.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], lo, hi, keys);
         for (int i = 0; i < a.Nq; ++i) {
             const size_t row = ((size_t)b * a.Hq + hq) * a.Nq + i;
             float M, L;
             row_final_ml(a, rows, row, M, L);      // runs after the combine launch: the merged pair is there
-            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, ntiles);
+            acc += row_bucket_mass(a, b, hq, i, s, lo, hi, M, L, keys);
         }
     }
     a.ws_red[pair] = acc;              // [b][s][hq]
 }
 
-// grid: (Smax+1, Hq, B), or ceil(B (Smax+1) Hq / 256) blocks when Nq < EN_MASS_FEW_ROWS
+// grid: mass_partial_blocks(a), or ceil(B (Smax+1) Hq / 256) blocks when Nq < EN_MASS_FEW_ROWS
 __global__ __launch_bounds__(256) void mass_partial_kernel(EnMassArgs a)
 {
-    __shared__ float red[4];
+    __shared__ float red[4 * EN_MASS_BG];
     if (a.Nq < EN_MASS_FEW_ROWS)
         mass_partial_few_rows(a, (size_t)blockIdx.x * 256 + threadIdx.x);
     else
-        mass_partial_block(a, blockIdx.x, blockIdx.y, blockIdx.z, red);
+        mass_partial_block(a, blockIdx.x, red);
 }
 
 // reduce = 1, stage 2. One wave per (agent, bucket) adds up the heads.
@@ -1921,16 +2074,17 @@ __global__ __launch_bounds__(256) void cluster_score_kernel(EnClusterArgs a)
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     const int len = s <= S ? bnd[s + 1] - bnd[s] : 0;
     float acc = 0.f;
+    const EnSplitMap map = split_map(m.n_splits, ntiles);
     if (len > 0) {
         int slo, shi;
-        bucket_splits(m.n_splits, ntiles, Ltot, bnd[s], bnd[s + 1], slo, shi);
+        bucket_splits(map, m.n_splits, Ltot, bnd[s], bnd[s + 1], slo, shi);
         for (int idx = threadIdx.x; idx < n_pairs; idx += 256) {
             // token fastest: neighbouring lanes read neighbouring scratch entries
             const int hq = idx / (hi - lo), i = lo + idx % (hi - lo);
             const size_t row = ((size_t)b * m.Hq + hq) * m.Nq + i;
             float M, L;
             row_final_ml(m, rows, row, M, L);
-            acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L, ntiles);
+            acc += row_bucket_mass(m, b, hq, i, s, slo, shi, M, L, map.keys);
         }
     }
     acc = wave_sum(acc);
@@ -2127,7 +2281,7 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     const int G = a.n_splits > 8 ? 4 : 1;                 // lanes that share a (row, chunk)
     const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec) * G;
     const int n_comb = (int)((n + 255) / 256);
-    const int n_part = m.Nq < EN_MASS_FEW_ROWS ? 0 : (m.Smax + 1) * m.Hq * m.B;
+    const int n_part = m.Nq < EN_MASS_FEW_ROWS ? 0 : mass_partial_blocks(m);
     const dim3 grid((unsigned)(n_comb + n_part)), blk(256);
 #define EN_COMBINE(T, DD)                                                                             \
     do {                                                                                              \
@@ -2220,7 +2374,7 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         // with several splits and many rows stage 1 has already run in the combine launch
         const dim3 blk(256);
         const dim3 grid = a.Nq < EN_MASS_FEW_ROWS ? dim3(((a.Smax + 1) * a.Hq * a.B + 255) / 256)
-                                                  : dim3(a.Smax + 1, a.Hq, a.B);
+                                                  : dim3(mass_partial_blocks(a));
         if (a.n_splits == 1 || a.Nq < EN_MASS_FEW_ROWS)
             hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
         const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);

@@ -134,6 +134,10 @@ def test_set_splits_clamps():
     assert plan.info.n_splits == 3
     plan.set_splits(1)
     assert plan.info.n_splits == 1
+    long_pool = host_pool(np.full(40, 250, np.int32), cap=256, max_ctx=16384)
+    long_plan = B.segment_select(long_pool, np.arange(40), [0, 40], 1)  # 10001 keys -> 157 tiles
+    long_plan.set_splits(100)
+    assert long_plan.info.n_splits == 64
 
 
 def test_scored_selection_matches_oracle(oracle):
