@@ -61,7 +61,7 @@ typedef enum en_status {
     EN_ERR_OUT_OF_RANGE = 2,  /* group id outside [0,G) or len outside [0,C]  */
     EN_ERR_DUPLICATE = 3,     /* a group twice in one agent's selection       */
     EN_ERR_CAPACITY = 4,      /* L_c + N_q exceeds max_ctx / buffer too small */
-    EN_ERR_UNSUPPORTED = 5,   /* head_dim, head ratio or dtype not supported  */
+    EN_ERR_UNSUPPORTED = 5,   /* head_dim, head ratio, dtype or size not supported */
     EN_ERR_DEVICE = 6         /* a HIP call failed; see en_last_error()       */
 } en_status;
 

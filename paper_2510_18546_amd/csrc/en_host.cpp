@@ -703,6 +703,9 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
                          int q_first, int n_rows, int n_splits, const char *who)
 {
     const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
+    // the merge kernel splits a row number into (agent, head, token) in 32-bit arithmetic
+    if (size_t(plan->B) * pool->d.n_q_heads * size_t(n_rows) > 0x7fffffffu)
+        return fail(EN_ERR_UNSUPPORTED, "%s: more than 2^31 - 1 (agent, head, token) rows", who);
     if (!ws_dev && n_splits > 1)
         return fail(EN_ERR_INVALID_ARG, "%s: workspace required with %d splits", who, n_splits);
     if (ws_dev && ws_bytes < L.total)

@@ -1663,9 +1663,12 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
         f32x2 ml = {M, l};
         *reinterpret_cast<f32x2 *>(a.ws_mlfin + row * 2) = ml;
     }
-    const int i = (int)(row % a.Nq);
-    const int hq = (int)((row / a.Nq) % a.Hq);
-    const int b = (int)(row / ((size_t)a.Nq * a.Hq));
+    // 32-bit divisions (the host refuses more rows than that): a 64-bit division by a run-time
+    // value is some hundred instructions, a third of this kernel
+    const unsigned bh = (unsigned)row / (unsigned)a.Nq;
+    const unsigned i = (unsigned)row - bh * (unsigned)a.Nq;
+    const unsigned b = bh / (unsigned)a.Hq;
+    const unsigned hq = bh - b * (unsigned)a.Hq;
     T *op = (T *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D + d0;
     *reinterpret_cast<tvec *>(op) = __builtin_convertvector(acc * inv, tvec);
 }
@@ -2165,18 +2168,19 @@ __global__ __launch_bounds__(256) void tier_load_kernel(EnTierLoadArgs a)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void append_kernel(EnAppendArgs a)
 {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t total = (size_t)a.n * a.Hkv * a.row_chunks;
+    // n rows of one group: n <= C, so the chunk count fits 32 bits with room to spare
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    const unsigned total = (unsigned)a.n * a.Hkv * a.row_chunks;
     if (idx >= total)
         return;
-    const int c = (int)(idx % a.row_chunks);
-    const size_t rowi = idx / a.row_chunks;          // tok * Hkv + h
-    const int h = (int)(rowi % a.Hkv);
-    const int tok = (int)(rowi / a.Hkv);
+    const unsigned rowi = idx / (unsigned)a.row_chunks;          // tok * Hkv + h
+    const unsigned c = idx - rowi * (unsigned)a.row_chunks;
+    const unsigned tok = rowi / (unsigned)a.Hkv;
+    const unsigned h = rowi - tok * (unsigned)a.Hkv;
     const uint4 *src = reinterpret_cast<const uint4 *>(blockIdx.y == 0 ? a.k_rows : a.v_rows);
     uint4 *dst = reinterpret_cast<uint4 *>(blockIdx.y == 0 ? a.k_pool : a.v_pool);
     const size_t drow = ((size_t)a.group * a.Hkv + h) * a.C + a.first + tok;
-    dst[drow * a.row_chunks + c] = src[rowi * a.row_chunks + c];
+    dst[drow * a.row_chunks + c] = src[(size_t)rowi * a.row_chunks + c];
 }
 
 // ---------------------------------------------------------------------------
