@@ -696,11 +696,18 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
     return a;
 }
 
+// All r * n_rows query rows of a KV head fit one wave: the decode attention kernel takes the step.
+static bool decode_kernel_fits(const en_pool *pool, int n_rows)
+{
+    return computes_bf16(pool->d.dtype) && pool->r * n_rows <= EN_ROWS_PER_WAVE;
+}
+
 // Attention of n_rows query rows per agent (new tokens q_first .. q_first+n_rows-1 of the plan)
 // with n_splits KV splits; the scratch is laid out for exactly these.
 static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const void *kc_dev,
                          const void *vt_dev, void *out_dev, void *ws_dev, size_t ws_bytes, void *stream,
-                         int q_first, int n_rows, int n_splits, const char *who)
+                         int q_first, int n_rows, int n_splits, const char *who,
+                         const void *app_k_dev = nullptr, const void *app_v_dev = nullptr)
 {
     const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
     // the merge kernel splits a row number into (agent, head, token) in 32-bit arithmetic
@@ -740,11 +747,13 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     a.n_splits = n_splits;
     const int nqb = (n_rows + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
-    a.decode = (computes_bf16(pool->d.dtype) && pool->r * n_rows <= EN_ROWS_PER_WAVE) ? 1 : 0;
+    a.decode = decode_kernel_fits(pool, n_rows) ? 1 : 0;
     if (a.decode)
         a.n_ptiles = 1;
     a.total_wgs = plan->B * pool->d.n_kv_heads * n_splits * a.n_ptiles;
     a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
+    a.app_k = a.decode ? app_k_dev : nullptr;
+    a.app_v = a.decode ? app_v_dev : nullptr;
     const bool timed = g_ev_used < (int)g_ev_start.size();
     if (timed)
         (void)hipEventRecord(g_ev_start[g_ev_used], (hipStream_t)stream);
@@ -818,7 +827,11 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
     int rc;
     if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
         return rc;
-    // 1. the step's keys (rotated at their positions) and values join the gathered context
+    // 1. the step's keys (rotated at their positions) and values join the gathered context. When
+    // the step's rows fit the decode attention kernel, that kernel does it itself (the wave whose
+    // key range holds a new token writes it before it loads that range): a launch of its own for
+    // a few rows costs as much as a quarter of such a step.
+    const bool fused = decode_kernel_fits(pool, n_rows);
     EnCtxAppendArgs c;
     c.k_rows = k_rows_dev;
     c.v_rows = v_rows_dev;
@@ -832,13 +845,14 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
     c.n = n_rows;
     c.T = plan->ctx_stride;
     c.q_first = q_first;
-    int e = en_launch_ctx_append(pool, c, stream);
+    int e = fused ? 0 : en_launch_ctx_append(pool, c, stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "segmented_decode_step context append");
     // 2. attention of the step's rows over everything before and including them
     const int n_splits = step_splits(pool, plan, n_rows);
     if ((rc = run_attention(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream, q_first, n_rows,
-                            n_splits, "segmented_decode_step")) != EN_OK)
+                            n_splits, "segmented_decode_step", fused ? k_rows_dev : nullptr,
+                            fused ? v_rows_dev : nullptr)) != EN_OK)
         return rc;
     // 3. per-row masses, if wanted
     if (mass_out_dev) {

@@ -88,6 +88,9 @@ struct EnAttnArgs {
     int n_splits, n_ptiles, total_wgs;
     int decode;        // 1: all r*Nq query rows of a KV head fit one wave (attn_decode kernel)
     float scale_log2e;
+    // decode kernel only, or null: the rows' own keys / values [B, Nq, Hkv, D], which the kernel
+    // writes into the context (kc, vt) at positions L_c + q_first + t before it reads them
+    const void *app_k, *app_v;
 };
 
 struct EnMassArgs {

@@ -1196,35 +1196,106 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const int klane = col * KSTR + half * 16;
     const int vlane = KBYTES + col * VSTR + half * 16;
 
-    // the first tile is on its way while the queries are prepared
-    if (t_begin < t_end)
+    // ---- the step's own keys and values join the context (decode steps): new token t sits at
+    // position L_c + t, and the one wave whose key range holds that position writes it: the key
+    // rotated there, the value as a column of V^T, exactly as ctx_append_kernel does. Nobody else
+    // reads those lines in this launch (a 64-key tile belongs to one split, a KV head to one wave),
+    // and the wave itself waits for its stores to be acknowledged before it loads a tile that
+    // holds a new token. The first tile is on its way meanwhile if it holds none. ----
+    const int first_new = max(Lc, split_key_begin);
+    const bool owns_new = a.app_k != nullptr && first_new < split_key_end;
+    const bool first_tile_old = first_new >= (lt_begin + 1) * LB;
+    if (t_begin < t_end && !(owns_new && !first_tile_old))
         issue(lt_begin, 0);
+    // Lane c owns the rotary pairs (c, c + D/2), c + 64, ... of a token. The first new token's
+    // row is fetched here, together with the queries below; the stores follow the queries.
+    constexpr int APP_J = (D / 2 + 63) / 64;
+    float app_x1[APP_J], app_x2[APP_J], app_cs[APP_J], app_sn[APP_J];
+    bf16_t app_v1[APP_J], app_v2[APP_J];
+    auto app_load = [&](int t) {
+        const int pos = Lc + t;
+        const bf16_t *kr = (const bf16_t *)a.app_k + (((size_t)b * a.Nq + t) * a.Hkv + kvh) * D;
+        const bf16_t *vr = (const bf16_t *)a.app_v + (((size_t)b * a.Nq + t) * a.Hkv + kvh) * D;
+#pragma unroll
+        for (int j = 0; j < APP_J; ++j) {
+            const int c = min(lane + 64 * j, D / 2 - 1);
+            app_cs[j] = a.cos_tab[(size_t)pos * (D / 2) + c];
+            app_sn[j] = a.sin_tab[(size_t)pos * (D / 2) + c];
+            app_x1[j] = (float)kr[c];
+            app_x2[j] = (float)kr[c + D / 2];
+            app_v1[j] = vr[c];
+            app_v2[j] = vr[c + D / 2];
+        }
+    };
+    auto app_store = [&](int t) {
+        const int pos = Lc + t;
+        bf16_t *kd = (bf16_t *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + pos) * D;
+        // token j in column j with bits 2 and 3 exchanged
+        const int vcol = (pos & ~0xC) | ((pos & 4) << 1) | ((pos & 8) >> 1);
+        bf16_t *vd = (bf16_t *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T + vcol;
+#pragma unroll
+        for (int j = 0; j < APP_J; ++j) {
+            const int c = lane + 64 * j;
+            if (c < D / 2) {
+                kd[c] = (bf16_t)(app_x1[j] * app_cs[j] - app_x2[j] * app_sn[j]);
+                kd[c + D / 2] = (bf16_t)(app_x2[j] * app_cs[j] + app_x1[j] * app_sn[j]);
+                vd[(size_t)c * a.T] = app_v1[j];
+                vd[(size_t)(c + D / 2) * a.T] = app_v2[j];
+            }
+        }
+    };
+    if (owns_new)
+        app_load(first_new - Lc);
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
     {
-        float qx[NKS][8];
+        bf16x8 qraw[NKS];
         const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            qraw[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
             if (row_valid)
-                v = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                qx[ks][j] = (float)v[j];
+                qraw[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
         }
         const int pos = row_valid ? Lc + i_row : 0;
         const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
         const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+        float cs[NKS / 2][8], sn[NKS / 2][8];
+#pragma unroll
+        for (int ks = 0; ks < NKS / 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                cs[ks][j] = ct[16 * ks + j];
+                sn[ks][j] = st[16 * ks + j];
+            }
+        // the new tokens' stores go out between the loads of the queries and the arithmetic on
+        // them, so that their acknowledgement is under way while the queries are rotated
+        if (owns_new) {
+            int t = first_new - Lc;
+            app_store(t);
+            for (++t; t < a.Nq && Lc + t < split_key_end; ++t) {
+                app_load(t);
+                app_store(t);
+            }
+            if (!first_tile_old) {
+                wait_all_memory();                   // stores included
+                issue(lt_begin, 0);
+            }
+        }
+        float qx[NKS][8];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qx[ks][j] = (float)qraw[ks][j];
 #pragma unroll
         for (int ks = 0; ks < NKS / 2; ++ks) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float cs = ct[16 * ks + j], sn = st[16 * ks + j];
                 const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
-                qx[ks][j] = (x1 * cs - x2 * sn) * a.scale_log2e;
-                qx[ks + NKS / 2][j] = (x2 * cs + x1 * sn) * a.scale_log2e;
+                qx[ks][j] = (x1 * cs[ks][j] - x2 * sn[ks][j]) * a.scale_log2e;
+                qx[ks + NKS / 2][j] = (x2 * cs[ks][j] + x1 * sn[ks][j]) * a.scale_log2e;
             }
         }
 #pragma unroll
@@ -1274,6 +1345,10 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     };
 
+    // the stores of new tokens are acknowledged before the loop loads the tile that holds them
+    // (the loads of the queries went out in the meantime)
+    if (owns_new && first_tile_old)
+        wait_all_memory();
     int stage = 0;                               // of tile lt
     for (int lt = lt_begin; lt < lt_end; ++lt) {
         const char *stg = smem + stage * STAGE;
