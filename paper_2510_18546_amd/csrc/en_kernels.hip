@@ -1655,9 +1655,11 @@ __host__ inline int mass_partial_blocks(const EnMassArgs &m)
     return mass_bucket_groups(m) * m.Hq * m.B;
 }
 
-// With many splits (decode over a long context by few agents) G = 4 neighbouring lanes share a
-// (row, 16-byte chunk): lane g takes the splits g, g + 4, ... and the four partial results are
-// merged with lane shuffles, so that the chain of dependent loads is a quarter as long.
+// With many splits (decode over a long context by few agents) G = 4 or 16 neighbouring lanes
+// share a (row, 16-byte chunk): lane g takes the splits g, g + G, ... and the G partial results
+// are merged with lane shuffles, so that the chain of dependent loads is 1/G as long (with 16
+// lanes, up to 64 splits are one batch of loads) and the few rows of such a step make G times
+// as many workgroups.
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m, int n_comb)
 {
@@ -1681,7 +1683,7 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
     // The splits are read in batches of independent loads, (reference, sum) pairs and outputs
     // together, and merged batch by batch with a running reference: read one after the other,
     // the latencies of 2 * n_splits dependent loads are what this kernel would take.
-    constexpr int NB = G == 1 ? 4 : 8;
+    constexpr int NB = G == 4 ? 8 : 4;
     float M = EN_NEG_INF, l = 0.f;
     fvec acc = 0.f;
     for (int sp0 = g; sp0 < a.n_splits; sp0 += NB * G) {
@@ -2357,7 +2359,7 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     hipStream_t st = (hipStream_t)stream;
     const int D = pool->d.head_dim;
     const int vec = pool->d.dtype == EN_F32 ? 4 : 8;      // elements in 16 bytes
-    const int G = a.n_splits > 8 ? 4 : 1;                 // lanes that share a (row, chunk)
+    const int G = a.n_splits > 32 ? 16 : (a.n_splits > 8 ? 4 : 1);     // lanes that share a (row, chunk)
     const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec) * G;
     const int n_comb = (int)((n + 255) / 256);
     const int n_part = m.Nq < EN_MASS_FEW_ROWS ? 0 : mass_partial_blocks(m);
@@ -2366,8 +2368,10 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     do {                                                                                              \
         if (G == 1)                                                                                   \
             hipLaunchKernelGGL((combine_kernel<T, DD, 1>), grid, blk, 0, st, a, m, n_comb);           \
-        else                                                                                          \
+        else if (G == 4)                                                                              \
             hipLaunchKernelGGL((combine_kernel<T, DD, 4>), grid, blk, 0, st, a, m, n_comb);           \
+        else                                                                                          \
+            hipLaunchKernelGGL((combine_kernel<T, DD, 16>), grid, blk, 0, st, a, m, n_comb);          \
     } while (0)
     if (pool->d.dtype == EN_F32) {
         if (D == 64)

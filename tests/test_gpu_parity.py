@@ -232,10 +232,11 @@ def test_bf16_few_query_rows_decode_kernel(step_mod, oracle, nq, hq, hkv, d):
     run_case(step_mod, oracle, cfg, n_splits=3)
 
 
-@pytest.mark.parametrize("dtype,splits", [(I.BF16, 9), (I.BF16, 30), (I.BF16, None), (I.F32, 11)])
+@pytest.mark.parametrize("dtype,splits", [(I.BF16, 9), (I.BF16, 30), (I.BF16, None), (I.F32, 11),
+                                          (I.BF16, 33), (I.BF16, 61), (I.F32, 45)])
 def test_many_splits_are_merged_by_lane_groups(step_mod, oracle, dtype, splits):
     """More than eight KV splits (one agent decoding over a long context): the merge of the splits
-    is shared by four lanes per output chunk."""
+    is shared by four lanes per output chunk, more than 32 by sixteen."""
     cfg = small(f"many-splits-{dtype}-{splits}", 520 + (splits or 0), dtype=dtype, n_groups=40, capacity=128,
                 len_lo=90, len_hi=128, n_sel=36, n_new=3 if dtype == I.BF16 else 5,
                 head_dim=128 if dtype == I.BF16 else 64)
