@@ -226,8 +226,11 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
         // of a wave let two waves share a compute unit, and a wave takes about
         // 2 us per 64-key tile whatever the load: as many splits as give every
         // compute unit its two waves (measured on 1 and 4 agents x 8 K tokens:
-        // more waves than that only add start-up and merge work), at least four
-        // tiles per split. Long contexts of many agents are the exception: two
+        // more waves than that only add start-up and merge work), down to one
+        // tile per split (one agent over 1.7 K tokens: 18.9 us per step with at
+        // least four tiles per split, 15.0 with two, 12.8 with one: the waves run
+        // side by side and the merge costs the same launch either way).
+        // Long contexts of many agents are the exception: two
         // splits measured faster than one (0.73 against 0.78 ms on 64 agents x
         // 16 K tokens).
         const long base = long(pl->B) * pool->d.n_kv_heads;
@@ -235,7 +238,7 @@ static int choose_splits(const en_pool *pool, const en_plan *pl)
         long want = (2L * pool->n_cu + base - 1) / base;
         if (want < 2 && tiles >= 64)
             want = 2;
-        want = std::min<long>(want, std::max(1, tiles / 4));
+        want = std::min<long>(want, tiles);
         return int(std::max<long>(1, std::min<long>(want, EN_MAX_SPLITS)));
     }
     const int nqb = (pl->Nq + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
