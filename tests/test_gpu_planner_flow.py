@@ -50,7 +50,9 @@ def test_two_planning_steps_over_four_layers(oracle):
             assert slots.tolist() == books[l].fetch(groups.tolist())[0]
             plan = B.segment_select(tier.pool, slots, [0, len(slots)], n_all)
             kc, vt = B.alloc_context(tier.pool, plan)
-            ws = torch.empty(max(B.decode_workspace_bytes(tier.pool, plan, base.n_new), 256), dtype=torch.uint8,
+            # one scratch for the prompt rows and for the one-row steps: each row count has its own size
+            ws = torch.empty(max(B.decode_workspace_bytes(tier.pool, plan, base.n_new),
+                                 B.decode_workspace_bytes(tier.pool, plan, 1), 256), dtype=torch.uint8,
                              device="cuda:0")
             pad = lambda t: torch.cat([t, torch.zeros((1, n_dec) + tuple(t.shape[2:]), dtype=t.dtype,
                                                      device=t.device)], 1).contiguous()
