@@ -77,14 +77,41 @@ __device__ __forceinline__ int find_bucket(P bnd, int S, int tok)
     return lo;
 }
 
-// Source row of context token `tok` for (agent b, KV head kvh); nullptr for
-// padding rows at or beyond L_c + N_q.
-template <typename T, int D>
-__device__ __forceinline__ const T *context_src(const EnGatherArgs &a, const T *pool, const T *fresh,
-                                               int b, int kvh, int tok)
+// The bucket bounds and the selected groups of an agent, staged in LDS for the searches of a
+// gather block: a binary search over the table in global memory is six dependent trips to memory
+// per row, the group number a seventh (about 3 us before a block that moves 16 KB can issue its
+// first load); over LDS it is a few hundred cycles. All threads of the block call stage_tables;
+// staged = false: the tables do not fit and are read where they are.
+constexpr int EN_GATHER_TAB_LDS = 256;          // entries of either table
+struct EnGatherTables {
+    const int32_t *bnd, *sel;                   // the agent's bounds [Smax + 2] and groups [Smax]
+    bool staged;
+};
+__device__ __forceinline__ EnGatherTables stage_tables(const EnGatherArgs &a, int b, int32_t *lds)
 {
-    const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
+    const int nb = a.Smax + 2;
+    const int sstr = a.Smax > 0 ? a.Smax : 1;
+    EnGatherTables t;
+    t.bnd = a.bnd + (size_t)b * nb;
+    t.sel = a.sel + (size_t)b * sstr;
+    t.staged = nb <= EN_GATHER_TAB_LDS;
+    if (t.staged) {
+        for (int i = threadIdx.x; i < nb; i += 256)
+            lds[i] = t.bnd[i];
+        for (int i = threadIdx.x; i < a.Smax; i += 256)
+            lds[EN_GATHER_TAB_LDS + i] = t.sel[i];
+        __syncthreads();
+    }
+    return t;
+}
+
+// Source row of context token `tok` for (agent b, KV head kvh); nullptr for
+// padding rows at or beyond L_c + N_q. `bnd` and `sel` are the agent's tables
+// (global or staged), S its number of segments.
+template <typename T, int D, typename P>
+__device__ __forceinline__ const T *context_src(const EnGatherArgs &a, P bnd, P sel, int S, const T *pool,
+                                               const T *fresh, int b, int kvh, int tok)
+{
     const int Lc = bnd[S];
     const int Ltot = bnd[S + 1];
     if (tok >= Ltot)
@@ -92,8 +119,7 @@ __device__ __forceinline__ const T *context_src(const EnGatherArgs &a, const T *
     if (tok >= Lc)
         return fresh + (((size_t)b * a.Nq + (tok - Lc)) * a.Hkv + kvh) * D;
     const int s = find_bucket(bnd, S, tok);
-    const int sstr = a.Smax > 0 ? a.Smax : 1;
-    const int g = a.sel[(size_t)b * sstr + s];
+    const int g = sel[s];
     return pool + (((size_t)g * a.Hkv + kvh) * a.C + (tok - bnd[s])) * D;
 }
 
@@ -103,21 +129,19 @@ __device__ __forceinline__ const T *context_src(const EnGatherArgs &a, const T *
 // With COPY_V (fp32 path) the value row is copied alongside.
 // grid: (ceil(Lpad/32), Hkv, B), 256 threads.
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool COPY_V>
-__device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx)
+template <typename T, int D, bool COPY_V, typename P>
+__device__ __forceinline__ void gather_k_rows(const EnGatherArgs &a, int bx, P bnd, P sel, int S)
 {
     constexpr int E = D / 16;
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int tok = bx * 32 + threadIdx.x / 8;
     const int c = threadIdx.x % 8;
-    const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
     const int Ltot = bnd[S + 1];
     const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
     if (tok >= Lpad)
         return;
     T *dst = (T *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
-    const T *src = context_src<T, D>(a, (const T *)a.k_pool, (const T *)a.k_new, b, kvh, tok);
+    const T *src = context_src<T, D>(a, bnd, sel, S, (const T *)a.k_pool, (const T *)a.k_new, b, kvh, tok);
     typedef T tvec __attribute__((ext_vector_type(E)));
     typedef float fvec __attribute__((ext_vector_type(E)));
     fvec y1 = 0.f, y2 = 0.f;
@@ -133,7 +157,7 @@ __device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx)
     *reinterpret_cast<tvec *>(dst + D / 2 + c * E) = __builtin_convertvector(y2, tvec);
     if constexpr (COPY_V) {
         T *vdst = (T *)a.vt + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
-        const T *vsrc = context_src<T, D>(a, (const T *)a.v_pool, (const T *)a.v_new, b, kvh, tok);
+        const T *vsrc = context_src<T, D>(a, bnd, sel, S, (const T *)a.v_pool, (const T *)a.v_new, b, kvh, tok);
         tvec v1 = (T)0.f, v2 = (T)0.f;
         if (vsrc) {
             v1 = *reinterpret_cast<const tvec *>(vsrc + c * E);
@@ -144,13 +168,25 @@ __device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx)
     }
 }
 
+template <typename T, int D, bool COPY_V>
+__device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx, int32_t *lbnd)
+{
+    const int b = blockIdx.z;
+    const int S = a.nseg[b];
+    const EnGatherTables t = stage_tables(a, b, lbnd);
+    if (t.staged)
+        gather_k_rows<T, D, COPY_V>(a, bx, (const int32_t *)lbnd, (const int32_t *)lbnd + EN_GATHER_TAB_LDS, S);
+    else
+        gather_k_rows<T, D, COPY_V>(a, bx, t.bnd, t.sel, S);
+}
+
 // ---------------------------------------------------------------------------
 // gather_vt (bf16): values of a 64-token tile are staged in LDS and written
 // transposed, vt[d][column], where token j sits at column j with bits 2 and 3
 // exchanged. grid: (Lpad/64, Hkv, B), 256 threads.
 // ---------------------------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx)
+__device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx, int32_t *lbnd)
 {
     constexpr int STR = D + 2;                 // LDS row stride in elements
     __shared__ uint16_t tile[EN_KEY_TILE * STR];
@@ -158,14 +194,17 @@ __device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx)
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int t0 = bx * EN_KEY_TILE;
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S + 1];
-    if (t0 >= Ltot)
+    const EnGatherTables t = stage_tables(a, b, lbnd);
+    const int32_t *lsel = lbnd + EN_GATHER_TAB_LDS;
+    const int Ltot = t.staged ? lbnd[S + 1] : t.bnd[S + 1];
+    if (t0 >= Ltot)                            // the same for the whole block
         return;
-    if (threadIdx.x < EN_KEY_TILE)
-        srcs[threadIdx.x] = context_src<uint16_t, D>(a, (const uint16_t *)a.v_pool,
-                                                     (const uint16_t *)a.v_new, b, kvh,
-                                                     t0 + threadIdx.x);
+    if (threadIdx.x < EN_KEY_TILE) {
+        const uint16_t *vp = (const uint16_t *)a.v_pool, *vn = (const uint16_t *)a.v_new;
+        srcs[threadIdx.x] =
+            t.staged ? context_src<uint16_t, D>(a, (const int32_t *)lbnd, lsel, S, vp, vn, b, kvh, t0 + threadIdx.x)
+                     : context_src<uint16_t, D>(a, t.bnd, t.sel, S, vp, vn, b, kvh, t0 + threadIdx.x);
+    }
     __syncthreads();
     // load: D/8 chunks of 16 bytes per token
     constexpr int CH = D / 8;
@@ -222,13 +261,14 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
             for (int i = threadIdx.x; i < g.n_inline; i += 256)
                 g.desc_out[i] = img[i];
     }
+    __shared__ int32_t lbnd[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
     if constexpr (sizeof(T) == 4) {
-        gather_k_block<T, D, true>(a, blockIdx.x);
+        gather_k_block<T, D, true>(a, blockIdx.x, lbnd);
     } else {
         if ((int)blockIdx.x < g.nk)
-            gather_k_block<T, D, false>(a, blockIdx.x);
+            gather_k_block<T, D, false>(a, blockIdx.x, lbnd);
         else
-            gather_vt_block<D>(a, blockIdx.x - g.nk);
+            gather_vt_block<D>(a, blockIdx.x - g.nk, lbnd);
     }
 }
 

@@ -270,6 +270,15 @@ def test_more_segments_than_lanes(step_mod, oracle, dtype, n_agents):
     run_case(step_mod, oracle, cfg, n_splits=3)
 
 
+@pytest.mark.parametrize("dtype", [I.BF16, I.F32])
+def test_more_segments_than_the_gather_stages(step_mod, oracle, dtype):
+    """More than 254 selected segments: the gather no longer stages the agent's tables in LDS and
+    searches them where they are."""
+    cfg = small(f"very-many-seg-{dtype}", 297, dtype=dtype, capacity=5, len_lo=0, len_hi=5, n_groups=330,
+                n_sel=300, n_new=33, n_agents=2, head_dim=128 if dtype == I.BF16 else 64)
+    run_case(step_mod, oracle, cfg)
+
+
 @pytest.mark.parametrize("dtype,n_new", [(I.BF16, 40), (I.BF16, 2), (I.F32, 5)])
 def test_agent_with_fewer_tiles_than_splits(step_mod, oracle, dtype, n_new):
     """The split count follows the longest context; an agent with a short one leaves some splits
