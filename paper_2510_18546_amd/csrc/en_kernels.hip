@@ -282,10 +282,13 @@ struct EnCtxLoc {
     int kind;        // 0 padding, 1 row of the pool, 2 row of the new tokens
     size_t row;      // index of the row, in rows of D elements
 };
-__device__ __forceinline__ EnCtxLoc context_loc(const EnGatherArgs &a, int b, int kvh, int tok)
+// the tables staged in LDS (at lds and lds + EN_GATHER_TAB_LDS) or where they are, see stage_tables
+__device__ __forceinline__ EnCtxLoc context_loc(const EnGatherArgs &a, const EnGatherTables &t, const int32_t *lds,
+                                               int b, int kvh, int tok)
 {
+    const int32_t *bnd = t.staged ? lds : t.bnd;
+    const int32_t *sel = t.staged ? lds + EN_GATHER_TAB_LDS : t.sel;
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
     const int Lc = bnd[S];
     const int Ltot = bnd[S + 1];
     if (tok >= Ltot)
@@ -293,28 +296,27 @@ __device__ __forceinline__ EnCtxLoc context_loc(const EnGatherArgs &a, int b, in
     if (tok >= Lc)
         return {2, ((size_t)b * a.Nq + (tok - Lc)) * a.Hkv + kvh};
     const int s = find_bucket(bnd, S, tok);
-    const int sstr = a.Smax > 0 ? a.Smax : 1;
-    const int g = a.sel[(size_t)b * sstr + s];
+    const int g = sel[s];
     return {1, ((size_t)g * a.Hkv + kvh) * a.C + (tok - bnd[s])};
 }
 
 template <int D>
-__device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx)
+__device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx, int32_t *lds)
 {
     constexpr int E = D / 16;
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int tok = bx * 32 + threadIdx.x / 8;
     const int c = threadIdx.x % 8;
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S + 1];
+    const EnGatherTables tabs = stage_tables(a, b, lds);
+    const int Ltot = tabs.staged ? lds[S + 1] : tabs.bnd[S + 1];
     const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
     if (tok >= Lpad)
         return;
     bf16_t *dst = (bf16_t *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
     typedef bf16_t tvec __attribute__((ext_vector_type(E)));
     typedef float fvec __attribute__((ext_vector_type(E)));
-    const EnCtxLoc loc = context_loc(a, b, kvh, tok);
+    const EnCtxLoc loc = context_loc(a, tabs, lds, b, kvh, tok);
     fvec x1 = 0.f, x2 = 0.f;
     if (loc.kind == 1) {
         const int8_t *src = (const int8_t *)a.k_pool + loc.row * D;
@@ -344,7 +346,7 @@ __device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx)
 }
 
 template <int D>
-__device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx)
+__device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx, int32_t *lds)
 {
     constexpr int STR = D + 2;                 // LDS row stride in elements
     __shared__ uint16_t tile[EN_KEY_TILE * STR];
@@ -353,12 +355,12 @@ __device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int t0 = bx * EN_KEY_TILE;
     const int S = a.nseg[b];
-    const int32_t *bnd = a.bnd + (size_t)b * (a.Smax + 2);
-    const int Ltot = bnd[S + 1];
-    if (t0 >= Ltot)
+    const EnGatherTables tabs = stage_tables(a, b, lds);
+    const int Ltot = tabs.staged ? lds[S + 1] : tabs.bnd[S + 1];
+    if (t0 >= Ltot)                            // the same for the whole block
         return;
     if (threadIdx.x < EN_KEY_TILE) {
-        const EnCtxLoc loc = context_loc(a, b, kvh, t0 + threadIdx.x);
+        const EnCtxLoc loc = context_loc(a, tabs, lds, b, kvh, t0 + threadIdx.x);
         rows[threadIdx.x] = loc.row;
         kinds[threadIdx.x] = loc.kind;
     }
@@ -426,10 +428,11 @@ __global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
             for (int i = threadIdx.x; i < g.n_inline; i += 256)
                 g.desc_out[i] = img[i];
     }
+    __shared__ int32_t ltab[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
     if ((int)blockIdx.x < g.nk)
-        gather_q8_k_block<D>(a, blockIdx.x);
+        gather_q8_k_block<D>(a, blockIdx.x, ltab);
     else
-        gather_q8_vt_block<D>(a, blockIdx.x - g.nk);
+        gather_q8_vt_block<D>(a, blockIdx.x - g.nk, ltab);
 }
 
 // ---------------------------------------------------------------------------
