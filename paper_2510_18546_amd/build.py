@@ -8,16 +8,21 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libefficientnav.so")
-SOURCES = [os.path.join(_HERE, "csrc", "en_host.cpp"), os.path.join(_HERE, "csrc", "en_tier.cpp"),
-           os.path.join(_HERE, "csrc", "en_kernels.hip")]
-HEADERS = [os.path.join(_HERE, "csrc", "en_internal.h"), os.path.join(_ROOT, "include", "efficientnav.h")]
+_CSRC = os.path.join(_HERE, "csrc")
+SOURCES = [os.path.join(_CSRC, f) for f in
+           ("en_host.cpp", "en_tier.cpp", "en_gather.hip", "en_attn_prefill.hip", "en_attn_decode.hip",
+            "en_merge_mass.hip")]
+HEADERS = [os.path.join(_CSRC, "en_internal.h"), os.path.join(_CSRC, "en_device.h"),
+           os.path.join(_ROOT, "include", "efficientnav.h")]
+OBJ_DIR = os.path.join(_HERE, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # no NaN is ever produced (masked scores are -inf and guarded): lets the
     # compiler drop the canonicalising copies around every max
     "-fno-honor-nans",
@@ -40,18 +45,28 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile the library. With force=False an up-to-date library is kept."""
-    if not force and not is_stale():
-        return LIB_PATH
-    cmd = [hipcc()] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include"),
-                                     "-I", os.path.join(_HERE, "csrc")] + SOURCES + ["-o", LIB_PATH]
+def _run(cmd) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
+    return err
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    """Compile the library: every source to an object of its own, side by side, then one link.
+    With force=False an up-to-date library is kept."""
+    if not force and not is_stale():
+        return LIB_PATH
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
+    objs = [os.path.join(OBJ_DIR, os.path.basename(src) + ".o") for src in SOURCES]
+    jobs = [[hipcc()] + HIPCC_FLAGS + inc + ["-c", src, "-o", obj] for src, obj in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1)) as pool:
+        errs = list(pool.map(_run, jobs))
+    errs.append(_run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH]))
+    if verbose and any(e.strip() for e in errs):
+        print("\n".join(e for e in errs if e.strip()))
     return LIB_PATH
 
 

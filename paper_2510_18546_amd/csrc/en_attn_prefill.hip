@@ -1,0 +1,644 @@
+// attn_bf16: softmax(QK^T/sqrt(D))V of the new tokens over the gathered context
+// (Appendix A of arXiv 2510.18546) on the bf16 matrix cores, with an online
+// softmax and the per-segment partial sums of Section 3.3.
+#include "en_device.h"
+
+// ---------------------------------------------------------------------------
+// attn_bf16: matrix-core attention.
+//
+// Work unit: one workgroup of 8 waves = 8 (query head, 32-query block) pairs of
+// one KV head and one KV split, one workgroup per compute unit, two waves per
+// SIMD.
+//
+// Each wave keeps its 32 rotated, pre-scaled queries in registers and computes
+// S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that every lane owns ONE query
+// (column l%32) and 16 scores of a 32-key block; row reductions then need a
+// single exchange with lane l^32. P^T goes straight back into the matrix core
+// as the B operand of O^T += V^T P^T: no LDS round trip for P.
+//
+// The key loop is software-pipelined over 32-key blocks. Phase j issues, step
+// by step, the matrix instructions of S(j+1) = K(j+1) Q^T and of
+// O += V(j-1) P(j-1), and between them the vector work that turns S(j) into
+// P(j). Everything a phase reads was finished one phase earlier, so neither
+// unit waits for the other.
+//
+// What limits a wave here is the number of instructions it issues per matrix
+// instruction (a wave issues in order; scalar instructions cost it about seven
+// cycles each), so the loop is kept free of scalar address arithmetic: it is
+// unrolled over the three LDS stages, which turns every LDS address into a
+// per-lane base plus an immediate, the loader issues unconditionally (tiles
+// past the end are clamped to the last one and land in a dead stage), and the
+// common case of a block is decided by one scalar and one vector comparison.
+//
+// K tiles [64][D] and V^T tiles [D][64] go from global memory straight into
+// LDS (global_load_lds_dwordx4: 64 lanes x 16 bytes land contiguously), three
+// stages each, one workgroup barrier per 64-key tile; the loads of a tile are
+// spread over the steps of the two phases before it is needed. Inside a tile
+// the 16-byte chunks of a row are rotated by the number of the row's 256-byte
+// line (the loader does this through its per-lane source offsets), which
+// keeps the operand reads of 16 consecutive lanes on distinct banks without
+// padding.
+//
+// Element e of a 32x32 accumulator in lane l is row 8*(e/4) + 4*(l/32) + e%4,
+// column l%32.
+// ---------------------------------------------------------------------------
+
+constexpr int ATT_WAVES = EN_WAVES;
+
+template <int D>
+__global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
+{
+    constexpr int KT = EN_KEY_TILE;              // keys per LDS tile
+    constexpr int KB = 32;                       // keys per pipeline block
+    constexpr int NKS = D / 16;                  // k-steps of one block's QK^T product
+    constexpr int NDB = D / 32;                  // 32-row blocks of O^T
+    constexpr int NSTEP = 2 * NKS;               // matrix instructions per phase
+    constexpr int EPS = 16 / NKS;                // scores turned into P per pair of steps
+    constexpr int ROWB = 2 * D;                  // bytes per K row
+    constexpr int KCPR = ROWB / 16;              // 16-byte chunks per K row
+    constexpr int KRPL = 256 / ROWB;             // K rows per 256-byte line
+    constexpr int KBYTES = KT * ROWB;
+    constexpr int VROWB = KT * 2;                // bytes per V^T row of a tile
+    constexpr int VBYTES = D * VROWB;
+    constexpr int NST = 3;                       // LDS stages of K and of V^T
+    constexpr int VBASE = NST * KBYTES;
+    constexpr int NBK = KBYTES / 1024, NBV = VBYTES / 1024;   // 1 KB loader blocks per tile
+    constexpr int KJ = NBK / ATT_WAVES, VJ = NBV / ATT_WAVES; // blocks per wave
+    static_assert(NBK % ATT_WAVES == 0 && NBV % ATT_WAVES == 0 && KJ <= 2 && VJ <= 2, "loader blocks");
+    static_assert(KRPL == 1 || KRPL == 2, "row rotation");
+    __shared__ __attribute__((aligned(1024))) char smem[NST * (KBYTES + VBYTES)];
+
+    // ---- work decode: consecutive logical ids share K/V and map to one XCD ----
+    const int per_xcd = gridDim.x / 8;
+    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= a.total_wgs)
+        return;
+    int t = logical;
+    const int ptile = t % a.n_ptiles;
+    t /= a.n_ptiles;
+    const int sp = t % a.n_splits;
+    t /= a.n_splits;
+    const int kvh = t % a.Hkv;
+    const int b = t / a.Hkv;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int lane = tid % 64;
+    const int col = lane % 32, half = lane / 32;
+    const int r = a.Hq / a.Hkv;
+    const int nqb = (a.Nq + 31) / 32;
+    const int pair = ptile * ATT_WAVES + wave;
+    // A wave without a valid (head, query block) pair computes on zero queries
+    // and writes nothing.
+    const bool wave_valid = pair < r * nqb;
+    const int hl = wave_valid ? pair % r : 0;
+    const int qb = wave_valid ? pair / r : 0;
+    const int hq = kvh * r + hl;
+    const int i_row = qb * 32 + col;
+    const bool row_valid = wave_valid && i_row < a.Nq;
+
+    // What the workgroup needs before it can start loading: the agent's header
+    // {S, L_c, L_c + N_q} in one scalar load and, when they fit one wave, all
+    // bucket bounds at once, one per lane (a binary search over the table would
+    // be six dependent trips to memory, about half of the start-up time).
+    const int32_t *bnd_g = a.bnd + (size_t)b * (a.Smax + 2);
+    const bool bnd_in_lanes = a.Smax + 2 <= 64;
+    int my_bnd = 0x7fffffff;
+    if (bnd_in_lanes && lane <= a.Smax + 1)
+        my_bnd = bnd_g[lane];
+    const en_table_ptr hdr = as_table(a.hdr + 4 * (size_t)b);
+    const int S = hdr[0];
+    // the rows are new tokens q_first .. q_first+Nq-1: everything before them counts as context
+    const int Lc = hdr[1] + a.q_first;
+    const int Ltot = Lc + a.Nq;
+    const en_table_ptr bnd = as_table(bnd_g);
+    auto bound_at = [&](int s) {          // s is wave-uniform
+        return bnd_in_lanes ? __builtin_amdgcn_readlane(my_bnd, s) : bnd[s];
+    };
+    const int ntiles = (Ltot + KT - 1) / KT;
+    const int t_begin = (int)((long)sp * ntiles / a.n_splits);
+    int t_end = (int)((long)(sp + 1) * ntiles / a.n_splits);
+    const int split_key_begin = t_begin * KT;
+    const int split_key_end = min(t_end * KT, Ltot);
+    {
+        // causal frontier of the workgroup: last key any of its rows may see.
+        // Every wave walks all tiles up to it; a wave whose own frontier is
+        // earlier sees only masked scores in the last ones.
+        const int qb_hi = min((ptile * ATT_WAVES + ATT_WAVES - 1) / r, nqb - 1);
+        const int last_key = Lc + min(a.Nq - 1, qb_hi * 32 + 31);
+        t_end = min(t_end, last_key / KT + 1);
+    }
+    const int nt = max(t_end - t_begin, 0);      // tiles of the workgroup
+    const int i_lo = qb * 32;
+
+    // ---- loader set-up. Block blk of a tile is LDS bytes [1024 blk, 1024 blk + 1024);
+    // lane L of it is chunk q = 64 blk + L of the tile: row q / CPR, position
+    // q % CPR in that row, which holds the row's chunk (position - line) mod CPR. ----
+    const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
+    const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
+    const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem + wave * 1024;
+    uint32_t koff[KJ], voff[VJ];
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+        const int q = (wave + ATT_WAVES * j) * 64 + lane;
+        const int row = q / KCPR, pos = q % KCPR;
+        koff[j] = (uint32_t)(row * ROWB + ((pos - row / KRPL) & (KCPR - 1)) * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < VJ; ++j) {
+        const int q = (wave + ATT_WAVES * j) * 64 + lane;
+        const int d = q / 8, pos = q % 8;
+        voff[j] = (uint32_t)((size_t)d * a.T * 2 + ((pos - d / 2) & 7) * 16);
+    }
+    // Loader job of the current phase: one tile of K or of V^T, issued block by
+    // block between the matrix instructions. A tile index past the end is
+    // clamped: the last tile is fetched once more, into a stage nobody reads.
+    uint32_t job_goff = 0;
+    auto job_k = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * KBYTES; };
+    auto job_v = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * (KT * 2); };
+    auto dma_k = [&](auto j_tag, auto stage_tag) {
+        constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
+        if constexpr (j < KJ)
+            dma16_imm<stage * KBYTES + j * ATT_WAVES * 1024>(kg, koff[j] + job_goff, lds_w);
+    };
+    auto dma_v = [&](auto j_tag, auto stage_tag) {
+        constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
+        if constexpr (j < VJ)
+            dma16_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vg, voff[j] + job_goff, lds_w);
+    };
+
+    // ---- first loads, issued before the queries are prepared so that both are in
+    // flight together. The loop is unrolled over the three stages; the nt % 3
+    // tiles that do not fill a round come first, so the first tile's stage s0
+    // is chosen such that the last tile always sits in stage 2. ----
+    const int rem = nt % NST;
+    const int s0 = (NST - rem) % NST;
+    const int s1 = (s0 + 1) % NST, s2 = (s0 + 2) % NST;
+    if (nt > 0) {
+        char *vz = smem + VBASE + s2 * VBYTES;     // the first product reads a zero V^T stage
+        for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
+            *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
+        job_k(t_begin);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma16(kg, koff[j] + job_goff, lds_w + s0 * KBYTES + j * ATT_WAVES * 1024);
+        job_k(t_begin + 1);
+#pragma unroll
+        for (int j = 0; j < KJ; ++j)
+            dma16(kg, koff[j] + job_goff, lds_w + s1 * KBYTES + j * ATT_WAVES * 1024);
+        job_v(t_begin);
+#pragma unroll
+        for (int j = 0; j < VJ; ++j)
+            dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
+    }
+
+    // ---- operand read addresses inside a stage (plus immediates per step) ----
+    uint32_t kaddr[NKS];          // K row `col` of a 32-key block, chunk 2 ks + half
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+        kaddr[ks] = (uint32_t)(col * ROWB + ((2 * ks + half + col / KRPL) & (KCPR - 1)) * 16);
+    uint32_t vaddr[2][2];         // V^T row `col` of a 32-row block, keys 32 h + 16 kk + 8 half ..
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+            vaddr[h][kk] = (uint32_t)(VBASE + col * VROWB + ((4 * h + 2 * kk + half + col / 2) & 7) * 16);
+
+    // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
+    bf16x8 qf[NKS];
+    {
+        float qx[NKS][8];
+        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row_valid)
+                v = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qx[ks][j] = (float)v[j];
+        }
+        const int pos = row_valid ? Lc + i_row : 0;
+        const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
+        const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS / 2; ++ks) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float cs = ct[16 * ks + j], sn = st[16 * ks + j];
+                const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
+                qx[ks][j] = (x1 * cs - x2 * sn) * a.scale_log2e;
+                qx[ks + NKS / 2][j] = (x2 * cs + x1 * sn) * a.scale_log2e;
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qf[ks][j] = (bf16_t)qx[ks][j];
+    }
+
+    // ---- state ----
+    f32x16 o[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            o[d][e] = 0.f;
+    f32x16 sbuf[2];               // scores: block j in sbuf[j%2]
+    bf16x8 pbuf[2][2];            // P^T: block j in pbuf[j%2][0..1] (16 keys each)
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            sbuf[p][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                pbuf[p][kk][j] = (bf16_t)0.f;
+    }
+    // Softmax reference of this row (log2 units). It is chosen at the first
+    // block in which the row sees a key and afterwards only moved when the
+    // exponentials of a block would overflow (see phase). Scores leave the
+    // matrix core already reduced by it: the accumulators start at -m_ref.
+    float m_ref = 0.f;
+    bool has_ref = false;
+    bool pending = row_valid && Lc + i_row >= split_key_begin;   // the row will see a key in this split
+    // the same as a wave mask, kept beside it: the test at the end of every phase is then one
+    // vector compare, one scalar OR and one branch
+    unsigned long long pend_mask = __builtin_amdgcn_ballot_w64(pending);
+    f32x16 negm;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        negm[e] = 0.f;
+    float l_part = 0.f;           // this lane's share of the row sum
+    float seg_part = 0.f;         // this lane's share of the current bucket's sum
+
+    // bucket tracking (wave-uniform): bucket `cur` covers [cur_begin, cur_end);
+    // the bound after that is fetched ahead of its use
+    const int tok0 = min(split_key_begin, Ltot - 1);
+    int cur = bnd_in_lanes ? (int)__popcll(__ballot(lane <= S && my_bnd <= tok0)) - 1 : find_bucket(bnd, S, tok0);
+    int cur_begin = bound_at(cur);
+    int cur_end = bound_at(cur + 1);
+    int nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
+    // Blocks whose first key is at most `calm` need neither the causal mask on
+    // the block after them nor any bucket bookkeeping.
+    auto calm_limit = [&]() {
+        if (pend_mask != 0)           // rows without a reference yet: every block is looked at
+            return -1;
+        int m = Lc + i_lo - 2 * KB + 1;
+        if (cur_end <= split_key_end)
+            m = min(m, cur_end - KB - 1);
+        return m;
+    };
+    int calm = calm_limit();
+    const size_t row_hq = (size_t)b * a.Hq + hq;
+    // this lane's row in the per-segment table of this split; bucket s is s * Nq rows further
+    float *seg_base = a.ws_seg
+                          ? a.ws_seg + ((((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq + i_row) * 2
+                          : nullptr;
+
+    // A closed bucket's (sum, reference) pair is written one tile later, right
+    // after the next barrier: a store issued just before a barrier would make
+    // that barrier's wait for the tile loads wait for the store as well.
+    float pend_tot = 0.f, pend_m = 0.f;
+    int pend_bucket = -1;
+    auto write_pending = [&]() {
+        if (pend_bucket >= 0) {
+            if (seg_base && row_valid && half == 0) {
+                f32x2 v = {pend_tot, pend_m};
+                *reinterpret_cast<f32x2 *>(seg_base + (size_t)(pend_bucket * a.Nq) * 2) = v;
+            }
+            pend_bucket = -1;
+        }
+    };
+    auto close_bucket = [&]() {
+        // the whole wave: bucket `cur` has been fully consumed (or is empty)
+        if (cur_end > cur_begin) {
+            write_pending();
+            pend_tot = seg_part + xor32(seg_part);
+            pend_m = has_ref ? m_ref : EN_NEG_INF;
+            pend_bucket = cur;
+        }
+        seg_part = 0.f;
+        ++cur;
+        cur_begin = cur_end;
+        cur_end = (cur <= S) ? nxt_end : 0x7fffffff;
+        nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
+    };
+
+    // Scores of the 32-key block at byte offset blk_off of the K stages,
+    // relative to m_ref, unpipelined (prologue and rare path).
+    auto block_scores = [&](int blk_off, f32x16 &sv) {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(smem + kaddr[ks] + blk_off);
+            if (ks == 0)
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[0], negm, 0, 0, 0);
+            else
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], sv, 0, 0, 0);
+        }
+    };
+    // causal / padding mask of a block starting at key kb
+    auto mask_block = [&](int kb, f32x16 &sv) {
+        if (kb + KB - 1 > Lc + i_lo) {
+            const int rel = Lc + i_row - kb - 4 * half;      // last visible key, block-relative
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (8 * (e / 4) + (e % 4) > rel)
+                    sv[e] = EN_NEG_INF;
+        }
+    };
+
+    // One phase for block jb = PAR of the tile in K stage ST (global block
+    // j = 2 tile + PAR):
+    //   S(j+1) = K(j+1) Q^T - m_ref      NKS matrix instructions (even steps)
+    //   P(j)   = exp2(S(j))              vector ALU, EPS scores per pair of steps
+    //   O     += V(j-1)^T-block P(j-1)   NKS matrix instructions (odd steps)
+    // plus the loader blocks of the phase's job. Operand reads run PD steps ahead.
+    constexpr int PD = 4;         // operand reads run PD steps ahead, across phases too
+    bf16x8 fr[PD];
+    auto operand = [&](auto par_tag, auto st_tag, auto k_tag) {
+        constexpr int par = decltype(par_tag)::value, st = decltype(st_tag)::value, k = decltype(k_tag)::value;
+        // operand of step k of the phase (par, st): even steps read K, odd steps V^T.
+        // K of block j+1: par 0 -> second half of this tile, par 1 -> first half of the next.
+        // V^T of block j-1: par 0 -> keys 32..63 of the previous tile, par 1 -> keys 0..31 of this one.
+        if constexpr (k % 2 == 0) {
+            constexpr int off = ((st + par) % NST) * KBYTES + (par ^ 1) * KB * ROWB;
+            return *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + off);
+        } else {
+            constexpr int i = k / 2, kk = i / NDB, d = i % NDB;
+            constexpr int off = ((st + NST - 1 + par) % NST) * VBYTES + d * 32 * VROWB;
+            return *reinterpret_cast<const bf16x8 *>(smem + vaddr[par ^ 1][kk] + off);
+        }
+    };
+    auto phase = [&](auto par_tag, auto st_tag, int tile) {
+        constexpr int PAR = decltype(par_tag)::value, ST = decltype(st_tag)::value;
+        f32x16 &s_cur = sbuf[PAR];
+        f32x16 &s_nxt = sbuf[PAR ^ 1];
+        float rs = 0.f;
+        bf16x2 pb_hold[EPS / 2];
+        static_for<NSTEP>([&](auto k_tag) {
+            constexpr int k = decltype(k_tag)::value;
+            constexpr int i = k / 2;
+            const bf16x8 cur_fr = fr[k % PD];
+            if constexpr (k + PD < NSTEP)
+                fr[k % PD] = operand(par_tag, st_tag, std::integral_constant<int, (k + PD) % NSTEP>{});
+            else                               // first operands of the next phase
+                fr[k % PD] = operand(std::integral_constant<int, PAR ^ 1>{},
+                                     std::integral_constant<int, (ST + PAR) % NST>{},
+                                     std::integral_constant<int, (k + PD) % NSTEP>{});
+            if constexpr (k % 2 == 0) {
+                if constexpr (i == 0)
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[0], negm, 0, 0, 0);
+                else
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, qf[i], s_nxt, 0, 0, 0);
+                // exponentials of scores e0 .. e0+EPS-1 of the current block
+#pragma unroll
+                for (int u = 0; u < EPS; u += 2) {
+                    const int e = i * EPS + u;
+                    const f32x2 pp = {fast_exp2(s_cur[e]), fast_exp2(s_cur[e + 1])};
+                    pb_hold[u / 2] = __builtin_convertvector(pp, bf16x2);
+                    // plain adds: the dot-product instructions would occupy the matrix pipeline
+                    rs += pp[0];
+                    rs += pp[1];
+                    // keep this work in this step (the optimiser would sink it below the loop)
+                    asm volatile("" : "+v"(pb_hold[u / 2]), "+v"(rs));
+                }
+            } else {
+                constexpr int kk = i / NDB, d = i % NDB;
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur_fr, pbuf[PAR ^ 1][kk], o[d], 0, 0, 0);
+                // file the probabilities made in the previous step
+#pragma unroll
+                for (int u = 0; u < EPS; u += 2) {
+                    const int e = i * EPS + u;
+                    pbuf[PAR][e / 8][e % 8] = pb_hold[u / 2][0];
+                    pbuf[PAR][e / 8][e % 8 + 1] = pb_hold[u / 2][1];
+                }
+            }
+            if constexpr (k == 2 || k == NSTEP / 2 + 1) {
+                using j_tag = std::integral_constant<int, (k == 2) ? 0 : 1>;
+                if constexpr (PAR == 0)
+                    dma_k(j_tag{}, std::integral_constant<int, (ST + 2) % NST>{});
+                else
+                    dma_v(j_tag{}, std::integral_constant<int, (ST + 1) % NST>{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const int kb = tile * KT + PAR * KB;          // first key of block j
+        // Rare cases, one branch for all of them: the next block needs the causal
+        // mask, a bucket ends inside this block, or a row lacks a reference /
+        // came near overflow (any magnitude below that is harmless: P keeps its
+        // relative precision in bf16 and the accumulators are fp32).
+        constexpr float BIG = 1.0e18f;            // 2^60
+        const bool overflow = __builtin_amdgcn_ballot_w64(!(rs < BIG)) != 0;     // wave-uniform
+        if (kb <= calm) {                 // also says that no row lacks a reference
+            if (!overflow) {
+                l_part += rs;
+                seg_part += rs;           // the whole block lies inside bucket `cur`
+                return;
+            }
+        }
+        const bool odd_row = overflow || pend_mask != 0;
+        const int ke = min(kb + KB, split_key_end);
+        mask_block(kb + KB, s_nxt);
+        // ---- reference check: the wave recomputes the scores of the block,
+        // moves the affected rows to their current maximum, rescales what
+        // they have accumulated and redoes the exponentials ----
+        if (odd_row) {
+            f32x16 sv;
+            block_scores(ST * KBYTES + PAR * KB * ROWB, sv);
+            mask_block(kb, sv);
+            float mx = sv[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e)
+                mx = fmaxf(mx, sv[e]);
+            mx = pair_max(mx);
+            // both lanes of a row must take the same decision
+            const float want = (pending || !(rs < BIG)) ? 1.f : 0.f;
+            const bool fix = pair_max(want) > 0.f && mx > EN_NEG_INF;
+            const float delta = fix ? mx : 0.f;
+            const float alpha = fix ? (has_ref ? fast_exp2(-delta) : 0.f) : 1.f;
+#pragma unroll
+            for (int d = 0; d < NDB; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    o[d][e] *= alpha;
+            l_part *= alpha;
+            seg_part *= alpha;
+            m_ref += delta;
+            has_ref = has_ref || fix;
+            pending = pending && !fix;
+            pend_mask = __builtin_amdgcn_ballot_w64(pending);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                negm[e] = -m_ref;
+                s_nxt[e] -= delta;            // the next block was taken against the old reference
+            }
+            rs = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const bf16_t pb = (bf16_t)fast_exp2(sv[e] - delta);
+                pbuf[PAR][e / 8][e % 8] = pb;
+                rs += (float)pb;
+            }
+        }
+        l_part += rs;
+        // ---- per-bucket partial sums ----
+        if (cur_end > ke) {
+            seg_part += rs;
+        } else if (cur_end == ke && cur_begin <= kb) {
+            // the bucket ends exactly with this block (segments aligned to 32 keys)
+            seg_part += rs;
+            while (cur <= S && cur_end <= ke)
+                close_bucket();
+        } else if (kb < split_key_end) {
+            // buckets end inside the block: every bucket but the last one met takes the sum
+            // of its keys, the last one what is left of the block's sum. The keys' sums can only
+            // be taken from the rounded probabilities, so for this block the row sum is taken
+            // from them too: a block must give the same total to the row and to its buckets
+            // (with a dominant key the difference, up to 2^-9 of it, would otherwise land in
+            // whatever bucket comes next, or be lost at the end of a split).
+            float rs_hat = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                rs_hat += (float)pbuf[PAR][e / 8][e % 8];
+            l_part += rs_hat - rs;
+            rs = rs_hat;
+            float rest = rs;
+            while (true) {
+                const int hi = min(cur_end, ke);
+                if (cur_end > ke || cur > S) {
+                    seg_part += rest;
+                    break;
+                }
+                float part = 0.f;
+                const int rhi = hi - kb - 4 * half;     // keys below `hi` not yet given away
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int kr = 8 * (e / 4) + (e % 4);
+                    part += (kr < rhi) ? (float)pbuf[PAR][e / 8][e % 8] : 0.f;
+                }
+                // `part` is the sum over keys kb .. hi-1; what earlier buckets took is in rs - rest
+                part -= rs - rest;
+                seg_part += part;
+                rest -= part;
+                close_bucket();
+            }
+        }
+        calm = calm_limit();
+    };
+
+    // ---- main loop: one barrier per tile. Tile t_begin + n lives in stage n % 3.
+    // At the barrier of tile t everything issued so far has landed: K up to
+    // tile t+1, V^T up to tile t. The two phases of tile t then issue K of tile
+    // t+2 and V^T of tile t+1 into stages whose last readers finished before the
+    // barrier. The first product uses a zero P^T with a zero-filled V^T stage. ----
+    auto tile_body = [&](auto st_tag, int tile) {
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        lds_data_ready();
+        write_pending();
+        job_k(tile + 2);
+        phase(std::integral_constant<int, 0>{}, st_tag, tile);
+        job_v(tile + 1);
+        phase(std::integral_constant<int, 1>{}, st_tag, tile);
+    };
+    using c0 = std::integral_constant<int, 0>;
+    using c1 = std::integral_constant<int, 1>;
+    using c2 = std::integral_constant<int, 2>;
+    if (nt > 0) {
+        wait_all_memory();
+        __builtin_amdgcn_s_barrier();
+        lds_data_ready();
+        // scores of the first block
+        block_scores(s0 * KBYTES, sbuf[0]);
+        mask_block(t_begin * KT, sbuf[0]);
+        // first operands of the first phase: K keys 32..63 of the first tile, the zero V^T stage
+#pragma unroll
+        for (int k = 0; k < PD; ++k) {
+            if (k % 2 == 0) {
+                fr[k] = *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + s0 * KBYTES + KB * ROWB);
+            } else {
+                const int i = k / 2, kk = i / NDB, d = i % NDB;
+                fr[k] = *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + s2 * VBYTES + d * 32 * VROWB);
+            }
+        }
+        int tile = t_begin;
+        if (rem == 2) {
+            tile_body(c1{}, tile);
+            ++tile;
+        }
+        if (rem >= 1) {
+            tile_body(c2{}, tile);
+            ++tile;
+        }
+        for (; tile < t_end; tile += NST) {
+            tile_body(c0{}, tile);
+            tile_body(c1{}, tile + 1);
+            tile_body(c2{}, tile + 2);
+        }
+        // the last pending product: keys 32..63 of the last tile (stage 2)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int d = 0; d < NDB; ++d) {
+                const bf16x8 av =
+                    *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + 2 * VBYTES + d * 32 * VROWB);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pbuf[1][kk], o[d], 0, 0, 0);
+            }
+        // loads of the clamped tiles may still be in flight
+        wait_all_memory();
+    }
+
+    if (!wave_valid)
+        return;
+    // Buckets of this split beyond the workgroup's causal frontier still get an
+    // entry (zero mass); the bucket the loop stopped in gets what is pending.
+    if (seg_base) {
+        while (cur <= S && cur_begin < split_key_end)
+            close_bucket();
+        write_pending();
+    }
+
+    // ---- epilogue ----
+    const float l_tot = l_part + xor32(l_part);
+    const size_t row = row_hq * a.Nq + i_row;
+    if (a.ws_ml && row_valid && half == 0) {
+        f32x2 v = {has_ref ? m_ref : EN_NEG_INF, l_tot};
+        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
+    }
+    if (!row_valid)
+        return;
+    // One split: the output row. Several: this split's own softmax output
+    // (normalised by its own sum), merged by the combine kernel.
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    bf16_t *op = (a.n_splits == 1)
+                     ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
+                     : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
+#pragma unroll
+    for (int d = 0; d < NDB; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = (bf16_t)(o[d][4 * g + e] * inv);
+            *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+        }
+}
+
+// ---------------------------------------------------------------------------
+// launcher
+// ---------------------------------------------------------------------------
+int en_launch_attention_prefill(const en_pool *pool, const EnAttnArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
+    if (pool->d.head_dim == 64)
+        hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, blk, 0, st, a);
+    else
+        hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, blk, 0, st, a);
+    return (int)hipGetLastError();
+}

@@ -155,9 +155,10 @@ struct EnWsLayout {
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *plan, int n_rows, int n_splits);
 
-// Kernel launchers (en_kernels.hip). Return hipError_t as int.
+// Kernel launchers (the .hip files). Return hipError_t as int.
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream);
 int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream);
+int en_launch_attention_prefill(const en_pool *pool, const EnAttnArgs &a, void *stream);   // called by the former
 int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs &m, void *stream);
 int en_launch_append(const en_pool *pool, const EnAppendArgs &a, void *stream);
 int en_launch_append_q8(const en_pool *pool, const EnAppendQ8Args &a, void *stream);
