@@ -29,17 +29,19 @@ __host__ inline int mass_partial_blocks(const EnMassArgs &m)
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m, int n_comb)
 {
-    // tail of the grid: per-head partial sums of the segment masses
-    if ((int)blockIdx.x >= n_comb) {
+    // head of the grid (these workgroups take longest: they start first): per-head partial sums
+    // of the segment masses
+    const int n_part = (int)gridDim.x - n_comb;
+    if ((int)blockIdx.x < n_part) {
         __shared__ float red[4 * EN_MASS_BG];
-        mass_partial_block(m, blockIdx.x - n_comb, red);
+        mass_partial_block(m, blockIdx.x, red);
         return;
     }
     constexpr int V = 16 / sizeof(T);
     typedef T tvec __attribute__((ext_vector_type(V)));
     typedef float fvec __attribute__((ext_vector_type(V)));
     const size_t rows = (size_t)a.B * a.Hq * a.Nq;
-    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t idx = (size_t)(blockIdx.x - n_part) * 256 + threadIdx.x;
     const int g = (int)(idx % G);
     idx /= G;
     if (idx >= rows * (D / V))
@@ -70,14 +72,14 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
             Mb = fmaxf(Mb, ml[j][0]);
         if (Mb == EN_NEG_INF)
             continue;
-        const float keep = M == EN_NEG_INF ? 0.f : exp2f(M - Mb);
+        const float keep = M == EN_NEG_INF ? 0.f : fast_exp2(M - Mb);
         l *= keep;
         acc *= keep;
         M = Mb;
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             // a split that saw no key of this row left (-inf, 0) and an output that is not to be used
-            const float w = ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * exp2f(ml[j][0] - M);
+            const float w = ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * fast_exp2(ml[j][0] - M);
             l += w;
             acc += w == 0.f ? (fvec)0.f : __builtin_convertvector(v[j], fvec) * w;
         }
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256) void combine_kernel(EnAttnArgs a, EnMassArgs m
 #pragma unroll
         for (int o = 1; o < G; o <<= 1)
             Mall = fmaxf(Mall, __shfl_xor(Mall, o, 64));
-        const float keep = M == EN_NEG_INF ? 0.f : exp2f(M - Mall);
+        const float keep = M == EN_NEG_INF ? 0.f : fast_exp2(M - Mall);
         l *= keep;
         acc *= keep;
         M = Mall;
@@ -153,11 +155,11 @@ __device__ __forceinline__ void merged_ml(const EnMassArgs &a, size_t rows, size
             Mb = fmaxf(Mb, ml[j][0]);
         if (Mb == EN_NEG_INF)
             continue;
-        L *= M == EN_NEG_INF ? 0.f : exp2f(M - Mb);
+        L *= M == EN_NEG_INF ? 0.f : fast_exp2(M - Mb);
         M = Mb;
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-            L += ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * exp2f(ml[j][0] - M);
+            L += ml[j][0] == EN_NEG_INF ? 0.f : ml[j][1] * fast_exp2(ml[j][0] - M);
     }
 }
 
@@ -228,7 +230,7 @@ __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int
         const f32x2 v = *reinterpret_cast<const f32x2 *>(
             a.ws_seg + (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
         if (v[1] != EN_NEG_INF)
-            acc += v[0] * exp2f(v[1] - M);
+            acc += v[0] * fast_exp2(v[1] - M);
     }
     return acc / L;
 }
@@ -278,8 +280,8 @@ __global__ __launch_bounds__(256) void mass_rows_kernel(EnMassArgs a)
 }
 
 // reduce = 1, stage 1: workgroup blk = (b * Hq + hq) * n_groups + group sums EN_MASS_BG buckets
-// of one head over the queries into partial[b][s][hq]. With several KV splits this runs as the
-// tail of the combine launch (the partial sums are a by-product of the attention call, whatever
+// of one head over the queries into partial[b][s][hq]. With several KV splits this runs in the
+// first workgroups of the combine launch (the partial sums are a by-product of the attention call, whatever
 // the caller asks of the mass call later) and merges the splits' (reference, sum) pairs itself;
 // with one split it is a launch of its own.
 //
