@@ -61,71 +61,101 @@ __device__ __forceinline__ const T *context_src(const EnGatherArgs &a, P bnd, P 
 // gather_k: 8 lanes per token row. Lane c owns elements [c*E, c*E+E) of the
 // first half and their rotary partners in the second half (E = D/16).
 // With COPY_V (fp32 path) the value row is copied alongside.
-// grid: (ceil(Lpad/32), Hkv, B), 256 threads.
+// A block takes 32 token rows of HPB consecutive KV heads, kv0 onwards: where a
+// row comes from and its cosines and sines (two fp32 table rows, twice the bytes
+// of a bf16 key row) are the same for every head, so they are fetched once for
+// the HPB heads (64 agents x 16 K tokens, keys only: 1.14 ms with the table read
+// per head, 0.73 ms without the table, which is what the value half takes).
+// 256 threads, 32 rows per pass.
 // ---------------------------------------------------------------------------
-template <typename T, int D, bool COPY_V, typename P>
-__device__ __forceinline__ void gather_k_rows(const EnGatherArgs &a, int bx, P bnd, P sel, int S)
+template <typename T, int D, bool COPY_V, int HPB, typename P>
+__device__ __forceinline__ void gather_k_rows(const EnGatherArgs &a, int tok, int kv0, P bnd, P sel, int S)
 {
     constexpr int E = D / 16;
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int tok = bx * 32 + threadIdx.x / 8;
+    const int b = blockIdx.z;
     const int c = threadIdx.x % 8;
     const int Ltot = bnd[S + 1];
     const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
     if (tok >= Lpad)
         return;
-    T *dst = (T *)a.kc + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
-    const T *src = context_src<T, D>(a, bnd, sel, S, (const T *)a.k_pool, (const T *)a.k_new, b, kvh, tok);
     typedef T tvec __attribute__((ext_vector_type(E)));
     typedef float fvec __attribute__((ext_vector_type(E)));
-    fvec y1 = 0.f, y2 = 0.f;
-    if (src) {
-        const fvec x1 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + c * E), fvec);
-        const fvec x2 = __builtin_convertvector(*reinterpret_cast<const tvec *>(src + D / 2 + c * E), fvec);
-        const fvec cs = *reinterpret_cast<const fvec *>(a.cos_tab + (size_t)tok * (D / 2) + c * E);
-        const fvec sn = *reinterpret_cast<const fvec *>(a.sin_tab + (size_t)tok * (D / 2) + c * E);
-        y1 = x1 * cs - x2 * sn;
-        y2 = x2 * cs + x1 * sn;
-    }
-    *reinterpret_cast<tvec *>(dst + c * E) = __builtin_convertvector(y1, tvec);
-    *reinterpret_cast<tvec *>(dst + D / 2 + c * E) = __builtin_convertvector(y2, tvec);
-    if constexpr (COPY_V) {
-        T *vdst = (T *)a.vt + (((size_t)b * a.Hkv + kvh) * a.T + tok) * D;
-        const T *vsrc = context_src<T, D>(a, bnd, sel, S, (const T *)a.v_pool, (const T *)a.v_new, b, kvh, tok);
-        tvec v1 = (T)0.f, v2 = (T)0.f;
-        if (vsrc) {
-            v1 = *reinterpret_cast<const tvec *>(vsrc + c * E);
-            v2 = *reinterpret_cast<const tvec *>(vsrc + D / 2 + c * E);
+    // the rows of head kv0; head kv0 + h is h * hstride elements further, keys and values alike
+    const T *ksrc = context_src<T, D>(a, bnd, sel, S, (const T *)a.k_pool, (const T *)a.k_new, b, kv0, tok);
+    const T *vsrc = nullptr;
+    if constexpr (COPY_V)
+        vsrc = context_src<T, D>(a, bnd, sel, S, (const T *)a.v_pool, (const T *)a.v_new, b, kv0, tok);
+    const size_t hstride = tok >= bnd[S] ? (size_t)D : (size_t)a.C * D;      // new tokens [.., Hkv, D], pool [.., Hkv, C, D]
+    tvec x1[HPB], x2[HPB];
+    fvec cs = 0.f, sn = 0.f;
+    if (ksrc) {
+#pragma unroll
+        for (int h = 0; h < HPB; ++h) {
+            x1[h] = *reinterpret_cast<const tvec *>(ksrc + h * hstride + c * E);
+            x2[h] = *reinterpret_cast<const tvec *>(ksrc + h * hstride + D / 2 + c * E);
         }
-        *reinterpret_cast<tvec *>(vdst + c * E) = v1;
-        *reinterpret_cast<tvec *>(vdst + D / 2 + c * E) = v2;
+        cs = *reinterpret_cast<const fvec *>(a.cos_tab + (size_t)tok * (D / 2) + c * E);
+        sn = *reinterpret_cast<const fvec *>(a.sin_tab + (size_t)tok * (D / 2) + c * E);
+    }
+#pragma unroll
+    for (int h = 0; h < HPB; ++h) {
+        T *dst = (T *)a.kc + (((size_t)b * a.Hkv + kv0 + h) * a.T + tok) * D;
+        fvec y1 = 0.f, y2 = 0.f;
+        if (ksrc) {
+            const fvec f1 = __builtin_convertvector(x1[h], fvec), f2 = __builtin_convertvector(x2[h], fvec);
+            y1 = f1 * cs - f2 * sn;
+            y2 = f2 * cs + f1 * sn;
+        }
+        *reinterpret_cast<tvec *>(dst + c * E) = __builtin_convertvector(y1, tvec);
+        *reinterpret_cast<tvec *>(dst + D / 2 + c * E) = __builtin_convertvector(y2, tvec);
+    }
+    if constexpr (COPY_V) {
+#pragma unroll
+        for (int h = 0; h < HPB; ++h) {
+            T *vdst = (T *)a.vt + (((size_t)b * a.Hkv + kv0 + h) * a.T + tok) * D;
+            tvec v1 = (T)0.f, v2 = (T)0.f;
+            if (vsrc) {
+                v1 = *reinterpret_cast<const tvec *>(vsrc + h * hstride + c * E);
+                v2 = *reinterpret_cast<const tvec *>(vsrc + h * hstride + D / 2 + c * E);
+            }
+            *reinterpret_cast<tvec *>(vdst + c * E) = v1;
+            *reinterpret_cast<tvec *>(vdst + D / 2 + c * E) = v2;
+        }
     }
 }
 
-template <typename T, int D, bool COPY_V>
-__device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int bx, int32_t *lbnd)
+// The key rows of 64-token tile `tile` for the heads kv0 .. kv0 + HPB - 1, 32 rows at a time:
+// the halves first .. last of the tile.
+template <typename T, int D, bool COPY_V, int HPB>
+__device__ __forceinline__ void gather_k_block(const EnGatherArgs &a, int tile, int first, int last, int kv0,
+                                               int32_t *lbnd)
 {
     const int b = blockIdx.z;
     const int S = a.nseg[b];
     const EnGatherTables t = stage_tables(a, b, lbnd);
-    if (t.staged)
-        gather_k_rows<T, D, COPY_V>(a, bx, (const int32_t *)lbnd, (const int32_t *)lbnd + EN_GATHER_TAB_LDS, S);
-    else
-        gather_k_rows<T, D, COPY_V>(a, bx, t.bnd, t.sel, S);
+#pragma unroll 1
+    for (int half = first; half <= last; ++half) {
+        const int tok = tile * EN_KEY_TILE + half * 32 + threadIdx.x / 8;
+        if (t.staged)
+            gather_k_rows<T, D, COPY_V, HPB>(a, tok, kv0, (const int32_t *)lbnd,
+                                             (const int32_t *)lbnd + EN_GATHER_TAB_LDS, S);
+        else
+            gather_k_rows<T, D, COPY_V, HPB>(a, tok, kv0, t.bnd, t.sel, S);
+    }
 }
 
 // ---------------------------------------------------------------------------
 // gather_vt (bf16): values of a 64-token tile are staged in LDS and written
 // transposed, vt[d][column], where token j sits at column j with bits 2 and 3
-// exchanged. grid: (Lpad/64, Hkv, B), 256 threads.
+// exchanged. 256 threads; bx = number of the 64-token tile.
 // ---------------------------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx, int32_t *lbnd)
+__device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx, int kvh, int32_t *lbnd)
 {
     constexpr int STR = D + 2;                 // LDS row stride in elements
     __shared__ uint16_t tile[EN_KEY_TILE * STR];
     __shared__ const uint16_t *srcs[EN_KEY_TILE];
-    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int b = blockIdx.z;
     const int t0 = bx * EN_KEY_TILE;
     const int S = a.nseg[b];
     const EnGatherTables t = stage_tables(a, b, lbnd);
@@ -176,12 +206,26 @@ __device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx, i
     }
 }
 
-// One launch for the whole gather: the first nk blocks of the grid's x
-// dimension rotate keys (and copy fp32 values), the rest transpose bf16 values.
+// One launch for the whole gather. Grid (64-token tiles, units, agents); the units, head group
+// by head group: the key units (the tile's key rows of HPB heads, which also copy fp32 values),
+// then, for bf16, HPB value units (one head's transposed tile each). Workgroups are dispatched
+// tile by tile along one unit, then the next unit: each unit is a sequential stream through
+// memory (with the units of one tile side by side instead, the 8K-context gather took 18.8 us
+// against 13.5), and key and value units of several heads are in flight together: they load
+// different parts of a compute unit (vector memory and ALU against LDS), and a launch that ran
+// all key units before all value units took the sum of the two instead of little more than the
+// larger.
 // When the launch carries the plan's descriptor block in its arguments, the
 // tables are read from the argument segment and the first workgroup stores the
 // block to device memory for the kernels that follow on the stream.
-template <typename T, int D>
+// Key units per head group: with one head per unit a 64-token tile is two units of 32 rows
+// (more, shorter workgroups: what a small gather wants), with several heads one unit of two passes.
+__host__ __device__ constexpr int en_gather_key_units(int hpb)
+{
+    return hpb == 1 ? 2 : 1;
+}
+
+template <typename T, int D, int HPB>
 __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
 {
     EnGatherArgs a = g.a;
@@ -196,14 +240,14 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
                 g.desc_out[i] = img[i];
     }
     __shared__ int32_t lbnd[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
-    if constexpr (sizeof(T) == 4) {
-        gather_k_block<T, D, true>(a, blockIdx.x, lbnd);
-    } else {
-        if ((int)blockIdx.x < g.nk)
-            gather_k_block<T, D, false>(a, blockIdx.x, lbnd);
-        else
-            gather_vt_block<D>(a, blockIdx.x - g.nk, lbnd);
-    }
+    const int tile = blockIdx.x;
+    constexpr int KU = en_gather_key_units(HPB);
+    constexpr int PER = KU + (sizeof(T) == 2 ? HPB : 0);      // units per head group
+    const int hg = blockIdx.y / PER, r = blockIdx.y % PER;
+    if (r < KU)
+        gather_k_block<T, D, sizeof(T) == 4, HPB>(a, tile, KU == 2 ? r : 0, KU == 2 ? r : 1, hg * HPB, lbnd);
+    else if constexpr (sizeof(T) == 2)
+        gather_vt_block<D>(a, tile, hg * HPB + r - KU, lbnd);
 }
 
 // ---------------------------------------------------------------------------
@@ -235,14 +279,13 @@ __device__ __forceinline__ EnCtxLoc context_loc(const EnGatherArgs &a, const EnG
 }
 
 template <int D>
-__device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx, int32_t *lds)
+__device__ __forceinline__ void gather_q8_k_rows(const EnGatherArgs &a, const EnGatherTables &tabs, int tok, int kvh,
+                                                 int32_t *lds)
 {
     constexpr int E = D / 16;
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int tok = bx * 32 + threadIdx.x / 8;
+    const int b = blockIdx.z;
     const int c = threadIdx.x % 8;
     const int S = a.nseg[b];
-    const EnGatherTables tabs = stage_tables(a, b, lds);
     const int Ltot = tabs.staged ? lds[S + 1] : tabs.bnd[S + 1];
     const int Lpad = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
     if (tok >= Lpad)
@@ -280,13 +323,22 @@ __device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int bx,
 }
 
 template <int D>
-__device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx, int32_t *lds)
+__device__ __forceinline__ void gather_q8_k_block(const EnGatherArgs &a, int tile, int kvh, int32_t *lds)
+{
+    const EnGatherTables tabs = stage_tables(a, blockIdx.z, lds);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half)
+        gather_q8_k_rows<D>(a, tabs, tile * EN_KEY_TILE + half * 32 + threadIdx.x / 8, kvh, lds);
+}
+
+template <int D>
+__device__ __forceinline__ void gather_q8_vt_block(const EnGatherArgs &a, int bx, int kvh, int32_t *lds)
 {
     constexpr int STR = D + 2;                 // LDS row stride in elements
     __shared__ uint16_t tile[EN_KEY_TILE * STR];
     __shared__ size_t rows[EN_KEY_TILE];
     __shared__ int kinds[EN_KEY_TILE];
-    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int b = blockIdx.z;
     const int t0 = bx * EN_KEY_TILE;
     const int S = a.nseg[b];
     const EnGatherTables tabs = stage_tables(a, b, lds);
@@ -363,10 +415,12 @@ __global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
                 g.desc_out[i] = img[i];
     }
     __shared__ int32_t ltab[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
-    if ((int)blockIdx.x < g.nk)
-        gather_q8_k_block<D>(a, blockIdx.x, ltab);
+    // the grid of gather_kernel with one head per key unit
+    const int tile = blockIdx.x, kvh = blockIdx.y / 2;
+    if (blockIdx.y % 2 == 0)
+        gather_q8_k_block<D>(a, tile, kvh, ltab);
     else
-        gather_q8_vt_block<D>(a, blockIdx.x - g.nk, ltab);
+        gather_q8_vt_block<D>(a, tile, kvh, ltab);
 }
 
 // ---------------------------------------------------------------------------
@@ -493,33 +547,58 @@ __global__ __launch_bounds__(64) void append_q8_kernel(EnAppendQ8Args a)
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+// Heads per key unit: as many (8, 4, 2 that divide Hkv) as still leave 32 workgroups per compute unit.
+static int gather_heads_per_unit(const en_pool *pool, const EnGatherArgs &a, int n_tiles, bool with_value_units)
+{
+    for (int hpb = 8; hpb > 1; hpb /= 2) {
+        const long units = (long)(a.Hkv / hpb) * (en_gather_key_units(hpb) + (with_value_units ? hpb : 0));
+        if (a.Hkv % hpb == 0 && units * n_tiles * a.B >= 32L * pool->n_cu)
+            return hpb;
+    }
+    return 1;
+}
+
+template <typename T, int D>
+static void launch_gather_kernel(int hpb, dim3 grid, hipStream_t st, const EnGatherLaunch &g)
+{
+    const dim3 blk(256);
+    if (hpb == 8)
+        hipLaunchKernelGGL((gather_kernel<T, D, 8>), grid, blk, 0, st, g);
+    else if (hpb == 4)
+        hipLaunchKernelGGL((gather_kernel<T, D, 4>), grid, blk, 0, st, g);
+    else if (hpb == 2)
+        hipLaunchKernelGGL((gather_kernel<T, D, 2>), grid, blk, 0, st, g);
+    else
+        hipLaunchKernelGGL((gather_kernel<T, D, 1>), grid, blk, 0, st, g);
+}
+
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream)
 {
     const EnGatherArgs &a = g.a;
     hipStream_t st = (hipStream_t)stream;
-    const int Lpad = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE * EN_KEY_TILE;
-    const int nk = (Lpad + 31) / 32, nv = Lpad / EN_KEY_TILE;
-    g.nk = nk;
-    const dim3 blk(256);
+    const int n_tiles = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE;
     const int D = pool->d.head_dim;
-    if (pool->d.dtype == EN_F32) {
-        const dim3 grid(nk, a.Hkv, a.B);
-        if (D == 64)
-            hipLaunchKernelGGL((gather_kernel<float, 64>), grid, blk, 0, st, g);
-        else
-            hipLaunchKernelGGL((gather_kernel<float, 128>), grid, blk, 0, st, g);
-    } else if (pool->d.dtype == EN_I8) {
-        const dim3 grid(nk + nv, a.Hkv, a.B);
+    if (pool->d.dtype == EN_I8) {
+        const dim3 grid(n_tiles, 2 * a.Hkv, a.B), blk(256);
         if (D == 64)
             hipLaunchKernelGGL((gather_q8_kernel<64>), grid, blk, 0, st, g);
         else
             hipLaunchKernelGGL((gather_q8_kernel<128>), grid, blk, 0, st, g);
-    } else {
-        const dim3 grid(nk + nv, a.Hkv, a.B);
+        return (int)hipGetLastError();
+    }
+    const bool bf16 = pool->d.dtype != EN_F32;
+    const int hpb = gather_heads_per_unit(pool, a, n_tiles, bf16);
+    const dim3 grid(n_tiles, (a.Hkv / hpb) * (en_gather_key_units(hpb) + (bf16 ? hpb : 0)), a.B);
+    if (!bf16) {
         if (D == 64)
-            hipLaunchKernelGGL((gather_kernel<bf16_t, 64>), grid, blk, 0, st, g);
+            launch_gather_kernel<float, 64>(hpb, grid, st, g);
         else
-            hipLaunchKernelGGL((gather_kernel<bf16_t, 128>), grid, blk, 0, st, g);
+            launch_gather_kernel<float, 128>(hpb, grid, st, g);
+    } else {
+        if (D == 64)
+            launch_gather_kernel<bf16_t, 64>(hpb, grid, st, g);
+        else
+            launch_gather_kernel<bf16_t, 128>(hpb, grid, st, g);
     }
     return (int)hipGetLastError();
 }

@@ -660,7 +660,6 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
     a.Nq = plan->Nq;
     a.Smax = plan->Smax;
     a.T = plan->ctx_stride;
-    g.nk = 0;
     g.n_inline = 0;
     g.off_nseg = 0;
     g.off_sel = g.off_nseg + int(plan->nseg.size());

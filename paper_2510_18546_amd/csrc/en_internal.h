@@ -66,7 +66,6 @@ struct EnGatherArgs {
 constexpr int EN_INLINE_DESC_MAX = 960;      // ints; keeps the argument block under 4 KB
 struct EnGatherLaunch {
     EnGatherArgs a;
-    int nk;                 // blocks of the grid's x dimension that rotate keys
     int n_inline;           // ints of `desc` in use, 0: read the device block
     int off_nseg, off_sel, off_bnd;   // int offsets of the three tables in the block
     int32_t *desc_out;      // device block to fill when n_inline > 0
