@@ -650,6 +650,34 @@ def test_decode_steps_equal_prefill_rows(step_mod, oracle, dtype):
     assert e.value.code == 2
 
 
+@pytest.mark.parametrize("name,n_new", [("c2", 6), ("c3", 3)])
+def test_full_size_decode_steps(step_mod, oracle, name, n_new):
+    """One-token steps over full-size contexts (c2: one agent, 8192 cached tokens, as many KV splits as
+    the plan allows, the step's K/V written by the attention kernel itself; c3: 16 agents, ragged
+    segments): every step's output and masses against the oracle's rows of the same prefill."""
+    import torch
+    from paper_2510_18546_amd import binding as B
+    cfg = I.variant(I.CONFIGS[name], name=f"{name}-decode", n_new=n_new)
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w)
+    announce(f"full-size decode steps {name}: {n_new} tokens")
+    ref_out, ref_mass = oracle_full(oracle, w)
+    B.gather_rope(st.pool, st.plan, torch.zeros_like(st.k_new), torch.zeros_like(st.v_new), st.kc, st.vt)
+    S1 = st.info.max_segments + 1
+    ws = torch.empty(max(B.decode_workspace_bytes(st.pool, st.plan, 1), 256), dtype=torch.uint8, device=st.device)
+    ws.fill_(0xFF)
+    for i in range(n_new):
+        q, k, v = (t[:, i:i + 1].contiguous() for t in (st.q, st.k_new, st.v_new))
+        out = torch.empty_like(q)
+        mass = torch.empty((cfg.n_agents, 1, cfg.n_q_heads, S1), dtype=torch.float32, device=st.device)
+        B.segmented_decode_step(st.pool, st.plan, i, q, k, v, st.kc, st.vt, out, ws, mass_out=mass)
+        torch.cuda.synchronize()
+        check_out(cfg, step_mod._to_host(out).astype(np.float64), ref_out[:, i:i + 1])
+        got_mass = mass.cpu().numpy().astype(np.float64)
+        check_mass(cfg, got_mass, ref_mass[:, i:i + 1])
+        np.testing.assert_allclose(got_mass.sum(-1), 1.0, atol=1e-4)
+
+
 def test_decode_steps_in_a_graph(step_mod, oracle):
     """Eight one-token steps captured into one HIP graph (the steps allocate nothing and only launch
     kernels); three replays, each after an eager re-gather, reproduce the eager results bit for bit."""
