@@ -218,17 +218,65 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             for (int j = 0; j < 8; ++j)
                 qx[ks][j] = (float)v[j];
         }
-        const int pos = row_valid ? Lc + i_row : 0;
-        const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
-        const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+        // The rotary rows (cosines and sines of position L_c + i, D/2 floats each) are the same for
+        // the waves that share a query block, and they are twice the bytes of the queries
+        // themselves: loaded per wave they are two thirds of what the compute unit's vector
+        // memory path moves before the first tile (3 us of the launch). When the workgroup's
+        // waves share at most two query blocks (Hq / Hkv >= 4, mostly), their 64 rows are
+        // fetched once, into the K stage and the V^T stage that no tile load has touched yet
+        // (64 rows of D/2 floats are exactly one stage), the 16-byte chunks of a row rotated by
+        // the row number like those of a K tile, and every wave reads its rows from there.
+        constexpr int TCPR = D / 8;                  // 16-byte chunks per table row
+        const int qb_first = (ptile * ATT_WAVES) / r;
+        const int qb_last = min((ptile * ATT_WAVES + ATT_WAVES - 1) / r, nqb - 1);
+        const bool shared_tab = nt > 0 && qb_last - qb_first <= 1;
+        float cs[NKS / 2][8], sn[NKS / 2][8];
+        if (shared_tab) {
+            char *ctab = smem + s2 * KBYTES, *stab = smem + VBASE + s1 * VBYTES;
+            const int pos0 = Lc + qb_first * 32;
+            for (int q = tid; q < 64 * TCPR; q += 64 * ATT_WAVES) {
+                const int row = q / TCPR, c = q % TCPR;
+                const size_t src = (size_t)min(pos0 + row, Ltot - 1) * (D / 2) + 4 * c;
+                const int dst = row * (2 * D) + ((c + row) % TCPR) * 16;
+                *reinterpret_cast<f32x4 *>(ctab + dst) = *reinterpret_cast<const f32x4 *>(a.cos_tab + src);
+                *reinterpret_cast<f32x4 *>(stab + dst) = *reinterpret_cast<const f32x4 *>(a.sin_tab + src);
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0): this wave's rows are in LDS
+            __builtin_amdgcn_s_barrier();
+            lds_data_ready();
+            const int row = (wave_valid ? qb - qb_first : 0) * 32 + col;
+#pragma unroll
+            for (int ks = 0; ks < NKS / 2; ++ks)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int off = row * (2 * D) + ((4 * ks + 2 * half + jj + row) % TCPR) * 16;
+                    const f32x4 c4 = *reinterpret_cast<const f32x4 *>(ctab + off);
+                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(stab + off);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        cs[ks][4 * jj + e] = c4[e];
+                        sn[ks][4 * jj + e] = s4[e];
+                    }
+                }
+        } else {
+            const int pos = row_valid ? Lc + i_row : 0;
+            const float *ct = a.cos_tab + (size_t)pos * (D / 2) + 8 * half;
+            const float *st = a.sin_tab + (size_t)pos * (D / 2) + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < NKS / 2; ++ks)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    cs[ks][j] = ct[16 * ks + j];
+                    sn[ks][j] = st[16 * ks + j];
+                }
+        }
 #pragma unroll
         for (int ks = 0; ks < NKS / 2; ++ks) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float cs = ct[16 * ks + j], sn = st[16 * ks + j];
                 const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
-                qx[ks][j] = (x1 * cs - x2 * sn) * a.scale_log2e;
-                qx[ks + NKS / 2][j] = (x2 * cs + x1 * sn) * a.scale_log2e;
+                qx[ks][j] = (x1 * cs[ks][j] - x2 * sn[ks][j]) * a.scale_log2e;
+                qx[ks + NKS / 2][j] = (x2 * cs[ks][j] + x1 * sn[ks][j]) * a.scale_log2e;
             }
         }
 #pragma unroll
