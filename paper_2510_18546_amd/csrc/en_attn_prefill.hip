@@ -639,6 +639,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         // loads of the clamped tiles may still be in flight
         wait_all_memory();
     }
+    // every wave is done with the tiles: their stages become the waves' staging areas for the
+    // output rows (see the epilogue)
+    __builtin_amdgcn_s_barrier();
 
     if (!wave_valid)
         return;
@@ -657,14 +660,17 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         f32x2 v = {has_ref ? m_ref : EN_NEG_INF, l_tot};
         *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
     }
-    if (!row_valid)
-        return;
     // One split: the output row. Several: this split's own softmax output
     // (normalised by its own sum), merged by the combine kernel.
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    bf16_t *op = (a.n_splits == 1)
-                     ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
-                     : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
+    // A lane holds its row in pieces of 8 bytes, 32 rows per store instruction: written as they
+    // are, a wave's 8 KB go out as 512 pieces of 16 bytes (2 - 3.5 us at the end of the launch,
+    // when every wave does it at once). Staged through LDS, each store instruction writes whole
+    // rows: 64 lanes x 16 bytes = four rows of 256 bytes.
+    const float inv = (row_valid && l_tot > 0.f) ? 1.f / l_tot : 0.f;
+    constexpr int OSTR = 2 * D + 16;             // bytes per staged row (padded: bank spread, 16-byte aligned)
+    constexpr int OCPR = D / 8;                  // 16-byte chunks per row
+    static_assert(ATT_WAVES * 32 * OSTR <= NST * (KBYTES + VBYTES), "staging areas must fit the tile stages");
+    char *stage_o = smem + wave * (32 * OSTR);
 #pragma unroll
     for (int d = 0; d < NDB; ++d)
 #pragma unroll
@@ -673,8 +679,22 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 v[e] = (bf16_t)(o[d][4 * g + e] * inv);
-            *reinterpret_cast<bf16x4 *>(op + 32 * d + 8 * g + 4 * half) = v;
+            *reinterpret_cast<bf16x4 *>(stage_o + col * OSTR + (32 * d + 8 * g + 4 * half) * 2) = v;
         }
+    // the area is this wave's own: its writes only have to be complete (the compiler waits for them)
+#pragma unroll
+    for (int k = 0; k < 32 * OCPR / 64; ++k) {
+        const int idx = k * 64 + lane;
+        const int rr = idx / OCPR, c = idx % OCPR;
+        const int i = i_lo + rr;
+        if (i < a.Nq) {
+            const uint4 val = *reinterpret_cast<const uint4 *>(stage_o + rr * OSTR + c * 16);
+            bf16_t *op = (a.n_splits == 1)
+                             ? (bf16_t *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D
+                             : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row_hq * a.Nq + i) * D;
+            *reinterpret_cast<uint4 *>(op + c * 8) = val;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
