@@ -207,17 +207,6 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
     {
-        float qx[NKS][8];
-        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row_valid)
-                v = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                qx[ks][j] = (float)v[j];
-        }
         // The rotary rows (cosines and sines of position L_c + i, D/2 floats each) are the same for
         // the waves that share a query block, and they are twice the bytes of the queries
         // themselves: loaded per wave they are two thirds of what the compute unit's vector
@@ -230,16 +219,40 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         const int qb_first = (ptile * ATT_WAVES) / r;
         const int qb_last = min((ptile * ATT_WAVES + ATT_WAVES - 1) / r, nqb - 1);
         const bool shared_tab = nt > 0 && qb_last - qb_first <= 1;
-        float cs[NKS / 2][8], sn[NKS / 2][8];
+        // Order of the loads: the shared rotary rows first, then the wave's queries, so that the
+        // rows go to LDS (and the workgroup meets at the barrier) while the queries are on their way.
+        constexpr int TIT = TCPR / ATT_WAVES;        // chunks of either table per thread
+        static_assert(TCPR % ATT_WAVES == 0, "rotary rows per thread");
+        char *ctab = smem + s2 * KBYTES, *stab = smem + VBASE + s1 * VBYTES;
+        f32x4 tc[TIT], tsn[TIT];
         if (shared_tab) {
-            char *ctab = smem + s2 * KBYTES, *stab = smem + VBASE + s1 * VBYTES;
             const int pos0 = Lc + qb_first * 32;
-            for (int q = tid; q < 64 * TCPR; q += 64 * ATT_WAVES) {
+#pragma unroll
+            for (int it = 0; it < TIT; ++it) {
+                const int q = tid + it * 64 * ATT_WAVES;
                 const int row = q / TCPR, c = q % TCPR;
                 const size_t src = (size_t)min(pos0 + row, Ltot - 1) * (D / 2) + 4 * c;
+                tc[it] = *reinterpret_cast<const f32x4 *>(a.cos_tab + src);
+                tsn[it] = *reinterpret_cast<const f32x4 *>(a.sin_tab + src);
+            }
+        }
+        bf16x8 qraw[NKS];
+        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            qraw[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (row_valid)
+                qraw[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+        }
+        float cs[NKS / 2][8], sn[NKS / 2][8];
+        if (shared_tab) {
+#pragma unroll
+            for (int it = 0; it < TIT; ++it) {
+                const int q = tid + it * 64 * ATT_WAVES;
+                const int row = q / TCPR, c = q % TCPR;
                 const int dst = row * (2 * D) + ((c + row) % TCPR) * 16;
-                *reinterpret_cast<f32x4 *>(ctab + dst) = *reinterpret_cast<const f32x4 *>(a.cos_tab + src);
-                *reinterpret_cast<f32x4 *>(stab + dst) = *reinterpret_cast<const f32x4 *>(a.sin_tab + src);
+                *reinterpret_cast<f32x4 *>(ctab + dst) = tc[it];
+                *reinterpret_cast<f32x4 *>(stab + dst) = tsn[it];
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);          // lgkmcnt(0): this wave's rows are in LDS
             __builtin_amdgcn_s_barrier();
@@ -270,6 +283,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
                     sn[ks][j] = st[16 * ks + j];
                 }
         }
+        float qx[NKS][8];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                qx[ks][j] = (float)qraw[ks][j];
 #pragma unroll
         for (int ks = 0; ks < NKS / 2; ++ks) {
 #pragma unroll
