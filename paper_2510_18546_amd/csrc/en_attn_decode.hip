@@ -21,9 +21,15 @@
 // S^T = K Q^T, the exponentials and O^T += V^T P^T as in the prefill kernel. Partial results of the splits are merged by the same combine
 // and mass kernels.
 // ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
+template <int D, int SUB>
+__global__ __launch_bounds__(64 * SUB) void attn_decode_kernel(EnAttnArgs a)
 {
+    // SUB = 2: two waves share the unit's tiles (each issues half of a tile's loads and takes one
+    // of its two 32-key blocks, with softmax state, partial output and segment sums of its own,
+    // stored at partial-result index sp * 2 + wave). For steps that leave compute units idle: a
+    // wave alone on its SIMD takes about 2 us per tile, and the tiles' LDS stages allow two
+    // workgroups per compute unit, so this puts all four SIMDs to work.
+    static_assert(SUB == 1 || SUB == 2, "one or two waves per unit");
     // two LDS stages; a third (two tiles in flight per wave) was tried for grids of at most one
     // wave per compute unit and changed nothing: a lone wave is bound by issuing its own
     // instructions (about 2 us per tile), not by waiting for its loads
@@ -60,7 +66,9 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const int kvh = t % a.Hkv;
     const int b = t / a.Hkv;
 
-    const int lane = threadIdx.x;
+    const int wave = SUB == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int lane = threadIdx.x % 64;
+    const int spw = sp * SUB + wave;             // index of this wave's partial results
     const int col = lane % 32, half = lane / 32;
     const int r = a.Hq / a.Hkv;
     const bool row_valid = col < r * a.Nq;
@@ -95,29 +103,35 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const char *kg = (const char *)a.kc + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * ROWB;
     const char *vg = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)D * a.T * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
-    uint32_t koff[NBK], voff[NBV];
+    // the waves take the loader blocks in turn; a wave that would run out repeats the last one
+    constexpr int NKW = (NBK + SUB - 1) / SUB, NVW = (NBV + SUB - 1) / SUB;
+    uint32_t koff[NKW], voff[NVW], kblk[NKW], vblk[NVW];
 #pragma unroll
-    for (int j = 0; j < NBK; ++j) {
+    for (int jj = 0; jj < NKW; ++jj) {
+        const int j = min(wave + SUB * jj, NBK - 1);
         const int q = j * 64 + lane;
         const int row = q / KCPR, c = q % KCPR;
-        koff[j] = (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16);      // the pad chunk re-reads chunk 0
+        koff[jj] = (uint32_t)(row * ROWB + (c < KCPR - 1 ? c : 0) * 16);      // the pad chunk re-reads chunk 0
+        kblk[jj] = (uint32_t)j * 1024;
     }
 #pragma unroll
-    for (int j = 0; j < NBV; ++j) {
+    for (int jj = 0; jj < NVW; ++jj) {
+        const int j = min(wave + SUB * jj, NBV - 1);
         const int q = j * 64 + lane;
         const int d = q / VCPR, c = q % VCPR;
-        voff[j] = (uint32_t)((size_t)d * a.T * 2 + (c < VCPR - 1 ? c : 0) * 16);
+        voff[jj] = (uint32_t)((size_t)d * a.T * 2 + (c < VCPR - 1 ? c : 0) * 16);
+        vblk[jj] = (uint32_t)(KBYTES + j * 1024);
     }
     auto issue = [&](int tile, int stage) {
         const char *kt = kg + (size_t)tile * (LB * ROWB);
         const char *vtile = vg + (size_t)tile * (LB * 2);
         const uint32_t dst = lds0 + stage * STAGE;
 #pragma unroll
-        for (int j = 0; j < NBK; ++j)
-            dma16(kt, koff[j], dst + j * 1024);
+        for (int jj = 0; jj < NKW; ++jj)
+            dma16(kt, koff[jj], dst + kblk[jj]);
 #pragma unroll
-        for (int j = 0; j < NBV; ++j)
-            dma16(vtile, voff[j], dst + KBYTES + j * 1024);
+        for (int jj = 0; jj < NVW; ++jj)
+            dma16(vtile, voff[jj], dst + vblk[jj]);
     };
 
     const int klane = col * KSTR + half * 16;
@@ -171,7 +185,8 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
             }
         }
     };
-    if (owns_new)
+    const bool appends = owns_new && wave == 0;          // one wave writes, all wait for it
+    if (appends)
         app_load(first_new - Lc);
 
     // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
@@ -198,17 +213,20 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
             }
         // the new tokens' stores go out between the loads of the queries and the arithmetic on
         // them, so that their acknowledgement is under way while the queries are rotated
-        if (owns_new) {
+        if (appends) {
             int t = first_new - Lc;
             app_store(t);
             for (++t; t < a.Nq && Lc + t < split_key_end; ++t) {
                 app_load(t);
                 app_store(t);
             }
-            if (!first_tile_old) {
+        }
+        if (owns_new && !first_tile_old) {
+            if (appends)
                 wait_all_memory();                   // stores included
-                issue(lt_begin, 0);
-            }
+            if (SUB > 1)
+                __syncthreads();
+            issue(lt_begin, 0);
         }
         float qx[NKS][8];
 #pragma unroll
@@ -255,7 +273,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     int nxt_end = (cur + 1 <= S) ? bound_at(cur + 2) : 0x7fffffff;
     const size_t row_hq = (size_t)b * a.Hq + hq;
     float *seg_base = a.ws_seg
-                          ? a.ws_seg + (((size_t)sp * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
+                          ? a.ws_seg + (((size_t)spw * a.B * a.Hq + row_hq) * (a.Smax + 1)) * a.Nq * 2
                           : nullptr;
     auto close_bucket = [&]() {
         if (cur_end > cur_begin) {
@@ -274,39 +292,56 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
 
     // the stores of new tokens are acknowledged before the loop loads the tile that holds them
     // (the loads of the queries went out in the meantime)
-    if (owns_new && first_tile_old)
-        wait_all_memory();
+    if (owns_new && first_tile_old) {
+        if (appends)
+            wait_all_memory();
+        if (SUB > 1)
+            __syncthreads();
+    }
+    constexpr int NUW = NU / SUB;                // 32-key blocks of a tile per wave
+    const int u0 = wave * NUW;                   // this wave's first
     int stage = 0;                               // of tile lt
     for (int lt = lt_begin; lt < lt_end; ++lt) {
         const char *stg = smem + stage * STAGE;
         // every LDS read of the previous tile has returned (its matrix
         // instructions consumed them), so its stage may be overwritten
         __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0)
-        constexpr int PER_TILE = NBK + NBV;
-        if (lt + 1 < lt_end) {
-            issue(lt + 1, stage ^ 1);
-            // this tile's loads have landed when at most the next tile's are outstanding
-            __builtin_amdgcn_s_waitcnt((PER_TILE & 15) | ((PER_TILE >> 4) << 14) | 0x0f70);
+        if (SUB == 1) {
+            constexpr int PER_TILE = NBK + NBV;
+            if (lt + 1 < lt_end) {
+                issue(lt + 1, stage ^ 1);
+                // this tile's loads have landed when at most the next tile's are outstanding
+                __builtin_amdgcn_s_waitcnt((PER_TILE & 15) | ((PER_TILE >> 4) << 14) | 0x0f70);
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+            }
         } else {
-            __builtin_amdgcn_s_waitcnt(0x0f70);              // vmcnt(0)
+            // this wave's share of the tile has landed, and past the barrier the other's too, and
+            // nobody reads the previous tile any more: the next one may overwrite it. It was a
+            // whole tile's arithmetic ahead of its wait, as with one wave.
+            __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            if (lt + 1 < lt_end)
+                issue(lt + 1, stage ^ 1);
         }
         lds_data_ready();
         const int kb = lt * LB;
+        const int kbw = kb + KB * u0;                // this wave's keys of the tile: [kbw, kbw + KB * NUW)
         // ---- S^T = K Q^T - m_ref, the two 32-key blocks as independent chains ----
-        f32x16 sv[NU];
+        f32x16 sv[NUW];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(stg + u * (KB * KSTR) + klane + ks * 32);
+            for (int u = 0; u < NUW; ++u) {
+                const bf16x8 fr = *reinterpret_cast<const bf16x8 *>(stg + (u0 + u) * (KB * KSTR) + klane + ks * 32);
                 sv[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr, qf[ks], ks == 0 ? negm : sv[u], 0, 0, 0);
             }
         // causal / padding mask; columns differ in i, so every tile that reaches
-        // past L_c is checked. Element e of block u is key 32 u + 8 (e / 4) + e % 4 + 4 half of the tile.
-        if (kb + LB - 1 > Lc) {
-            const int rel = Lc + i_row - kb - 4 * half;
+        // past L_c is checked. Element e of block u is key 32 u + 8 (e / 4) + e % 4 + 4 half, counted from kbw.
+        if (kbw + KB * NUW - 1 > Lc) {
+            const int rel = Lc + i_row - kbw - 4 * half;
 #pragma unroll
-            for (int u = 0; u < NU; ++u)
+            for (int u = 0; u < NUW; ++u)
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     if (KB * u + 8 * (e / 4) + (e % 4) > rel)
@@ -314,12 +349,12 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         }
         // ---- reference (first visible tile, or near overflow) ----
         constexpr float BIG = 1.0e18f;
-        bf16x8 pf[NU][2];
+        bf16x8 pf[NUW][2];
         float rs = 0.f;
         {
-            float p[NU][16];
+            float p[NUW][16];
 #pragma unroll
-            for (int u = 0; u < NU; ++u)
+            for (int u = 0; u < NUW; ++u)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     p[u][e] = fast_exp2(sv[u][e]);
@@ -328,7 +363,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
             if (__any(pending || !(rs < BIG))) {
                 float mx = sv[0][0];
 #pragma unroll
-                for (int u = 0; u < NU; ++u)
+                for (int u = 0; u < NUW; ++u)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         mx = fmaxf(mx, sv[u][e]);
@@ -351,7 +386,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
                 for (int e = 0; e < 16; ++e)
                     negm[e] = -m_ref;
 #pragma unroll
-                for (int u = 0; u < NU; ++u)
+                for (int u = 0; u < NUW; ++u)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         p[u][e] = fast_exp2(sv[u][e] - delta);
@@ -359,7 +394,7 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
             // the sums use the rounded probabilities, like the products
             rs = 0.f;
 #pragma unroll
-            for (int u = 0; u < NU; ++u)
+            for (int u = 0; u < NUW; ++u)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const bf16_t pb = (bf16_t)p[u][e];
@@ -369,17 +404,19 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         }
         l_part += rs;
         // ---- per-bucket partial sums ----
-        const int ke = min(kb + LB, split_key_end);
+        // (a wave that takes every other block closes the buckets that lie between its blocks
+        // with what it had of them, possibly nothing: ranges below kbw select no element)
+        const int ke = min(kbw + KB * NUW, split_key_end);
         if (cur_end > ke) {
             seg_part += rs;
-        } else if (kb < split_key_end) {
-            int lo = kb;
+        } else if (kbw < split_key_end) {
+            int lo = kbw;
             while (true) {
                 const int hi = min(cur_end, ke);
                 float part = 0.f;
-                const int rlo = lo - kb - 4 * half, rhi = hi - kb - 4 * half;
+                const int rlo = lo - kbw - 4 * half, rhi = hi - kbw - 4 * half;
 #pragma unroll
-                for (int u = 0; u < NU; ++u)
+                for (int u = 0; u < NUW; ++u)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int kr = KB * u + 8 * (e / 4) + (e % 4);
@@ -394,12 +431,12 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
         }
         // ---- O^T += V^T P^T ----
 #pragma unroll
-        for (int u = 0; u < NU; ++u)
+        for (int u = 0; u < NUW; ++u)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                 for (int d = 0; d < NDB; ++d) {
-                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(stg + u * (KB * 2) + vlane + kk * 32 + d * 32 * VSTR);
+                    const bf16x8 av = *reinterpret_cast<const bf16x8 *>(stg + (u0 + u) * (KB * 2) + vlane + kk * 32 + d * 32 * VSTR);
                     o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[u][kk], o[d], 0, 0, 0);
                 }
         stage ^= 1;
@@ -413,14 +450,14 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(EnAttnArgs a)
     const size_t row = row_hq * a.Nq + i_row;
     if (a.ws_ml && row_valid && half == 0) {
         f32x2 v = {has_ref ? m_ref : EN_NEG_INF, l_tot};
-        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)sp * a.B * a.Hq * a.Nq + row) * 2) = v;
+        *reinterpret_cast<f32x2 *>(a.ws_ml + ((size_t)spw * a.B * a.Hq * a.Nq + row) * 2) = v;
     }
     if (!row_valid)
         return;
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    bf16_t *op = (a.n_splits == 1)
+    bf16_t *op = (a.n_splits * SUB == 1)
                      ? (bf16_t *)a.out + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D
-                     : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row) * D;
+                     : (bf16_t *)a.ws_opart + ((size_t)spw * a.B * a.Hq * a.Nq + row) * D;
 #pragma unroll
     for (int d = 0; d < NDB; ++d)
 #pragma unroll
@@ -563,11 +600,20 @@ int en_launch_attention(const en_pool *pool, const EnAttnArgs &a, void *stream)
         else
             hipLaunchKernelGGL((attn_f32_kernel<128>), grid, blk, 0, st, a);
     } else if (a.decode) {
-        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64);
-        if (D == 64)
-            hipLaunchKernelGGL((attn_decode_kernel<64>), grid, blk, 0, st, a);
-        else
-            hipLaunchKernelGGL((attn_decode_kernel<128>), grid, blk, 0, st, a);
+        const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * a.sub);
+        if (a.sub != 1 && a.sub != 2)
+            return (int)hipErrorInvalidValue;
+        if (D == 64) {
+            if (a.sub == 1)
+                hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, blk, 0, st, a);
+            else
+                hipLaunchKernelGGL((attn_decode_kernel<64, 2>), grid, blk, 0, st, a);
+        } else {
+            if (a.sub == 1)
+                hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, blk, 0, st, a);
+            else
+                hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, blk, 0, st, a);
+        }
     } else {
         return en_launch_attention_prefill(pool, a, stream);
     }

@@ -549,9 +549,28 @@ extern "C" size_t en_context_bytes(const en_pool *pool, const en_plan *plan)
            elem_size(pool->d.dtype);
 }
 
-// Scratch layout for n_rows query rows per agent and n_splits KV splits.
-EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *pl, int n_rows, int n_splits)
+// All r * n_rows query rows of a KV head fit one wave: the decode attention kernel takes the step.
+static bool decode_kernel_fits(const en_pool *pool, int n_rows)
 {
+    return computes_bf16(pool->d.dtype) && pool->r * n_rows <= EN_ROWS_PER_WAVE;
+}
+
+// Waves per (agent, KV head, split) in the decode attention kernel. One wave alone on its SIMD
+// takes about 2 us per 64-key tile whatever the load, and the kernel's LDS stages leave room for
+// two workgroups per compute unit: when a step has no more units than that, two waves share each
+// unit's tiles, each takes every other 32-key block and leaves partial results of its own (the
+// scratch then holds n_splits * 2 of them per row; the units' key ranges stay whole tiles).
+int en_attn_sub(const en_pool *pool, const en_plan *pl, int n_rows, int n_splits)
+{
+    if (!decode_kernel_fits(pool, n_rows))
+        return 1;
+    return long(pl->B) * pool->d.n_kv_heads * n_splits <= 2L * pool->n_cu ? 2 : 1;
+}
+
+// Scratch layout for n_rows query rows per agent and n_splits KV splits.
+EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *pl, int n_rows, int n_splits_plan)
+{
+    const int n_splits = n_splits_plan * en_attn_sub(pool, pl, n_rows, n_splits_plan);     // partial results per row
     EnWsLayout L;
     const size_t rows = size_t(pl->B) * pool->d.n_q_heads * n_rows;
     L.ml_off = 0;
@@ -678,7 +697,9 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
     return EN_OK;
 }
 
-static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, const EnWsLayout &L)
+// For the rows q_first .. q_first + n_rows - 1 of the plan's new tokens, attended with n_splits KV splits.
+static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, const EnWsLayout &L, int n_rows,
+                            int n_splits, int q_first)
 {
     EnMassArgs a;
     a.ws_ml = reinterpret_cast<const float *>(ws + L.ml_off);
@@ -691,17 +712,12 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
     a.out = nullptr;
     a.B = plan->B;
     a.Hq = pool->d.n_q_heads;
-    a.Nq = plan->Nq;
+    a.Nq = n_rows;
     a.Smax = plan->Smax;
-    a.n_splits = plan->n_splits;
-    a.q_first = 0;
+    a.n_splits = n_splits;
+    a.sub = en_attn_sub(pool, plan, n_rows, n_splits);
+    a.q_first = q_first;
     return a;
-}
-
-// All r * n_rows query rows of a KV head fit one wave: the decode attention kernel takes the step.
-static bool decode_kernel_fits(const en_pool *pool, int n_rows)
-{
-    return computes_bf16(pool->d.dtype) && pool->r * n_rows <= EN_ROWS_PER_WAVE;
 }
 
 // Attention of n_rows query rows per agent (new tokens q_first .. q_first+n_rows-1 of the plan)
@@ -715,8 +731,11 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     // the merge kernel splits a row number into (agent, head, token) in 32-bit arithmetic
     if (size_t(plan->B) * pool->d.n_q_heads * size_t(n_rows) > 0x7fffffffu)
         return fail(EN_ERR_UNSUPPORTED, "%s: more than 2^31 - 1 (agent, head, token) rows", who);
-    if (!ws_dev && n_splits > 1)
-        return fail(EN_ERR_INVALID_ARG, "%s: workspace required with %d splits", who, n_splits);
+    // (without scratch there is nowhere to leave partial results: one wave per unit then)
+    const int sub = ws_dev ? en_attn_sub(pool, plan, n_rows, n_splits) : 1;
+    const int n_partials = n_splits * sub;
+    if (!ws_dev && n_partials > 1)
+        return fail(EN_ERR_INVALID_ARG, "%s: workspace required with %d partial results per row", who, n_partials);
     if (ws_dev && ws_bytes < L.total)
         return fail(EN_ERR_CAPACITY, "%s: workspace %zu < %zu bytes", who, ws_bytes, L.total);
     if (ws_dev && (reinterpret_cast<uintptr_t>(ws_dev) & 15))
@@ -737,8 +756,8 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     char *ws = static_cast<char *>(ws_dev);
     a.ws_ml = ws ? reinterpret_cast<float *>(ws + L.ml_off) : nullptr;
     a.ws_seg = ws ? reinterpret_cast<float *>(ws + L.seg_off) : nullptr;
-    a.ws_opart = (ws && n_splits > 1) ? static_cast<void *>(ws + L.opart_off) : nullptr;
-    a.ws_mlfin = (ws && n_splits > 1) ? reinterpret_cast<float *>(ws + L.mlfin_off) : nullptr;
+    a.ws_opart = (ws && n_partials > 1) ? static_cast<void *>(ws + L.opart_off) : nullptr;
+    a.ws_mlfin = (ws && n_partials > 1) ? reinterpret_cast<float *>(ws + L.mlfin_off) : nullptr;
     a.B = plan->B;
     a.Hq = pool->d.n_q_heads;
     a.Hkv = pool->d.n_kv_heads;
@@ -747,6 +766,7 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     a.T = plan->ctx_stride;
     a.q_first = q_first;
     a.n_splits = n_splits;
+    a.sub = sub;
     const int nqb = (n_rows + EN_ROWS_PER_WAVE - 1) / EN_ROWS_PER_WAVE;
     a.n_ptiles = (pool->r * nqb + EN_WAVES - 1) / EN_WAVES;
     a.decode = decode_kernel_fits(pool, n_rows) ? 1 : 0;
@@ -764,13 +784,12 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
         (void)hipEventRecord(g_ev_stop[g_ev_used++], (hipStream_t)stream);
     if (e != 0)
         return hip_fail((hipError_t)e, who);
-    if (n_splits > 1) {
+    if (n_partials > 1) {
         // the same launch also leaves the per-head partial sums of the segment masses
-        EnMassArgs m = mass_args(pool, plan, ws, L);
-        m.Nq = n_rows;
-        m.n_splits = n_splits;
-        m.q_first = q_first;
-        e = en_launch_combine(pool, a, m, stream);
+        const EnMassArgs m = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first);
+        EnAttnArgs c = a;
+        c.n_splits = n_partials;              // the merge only counts partial results
+        e = en_launch_combine(pool, c, m, stream);
         if (e != 0)
             return hip_fail((hipError_t)e, "split combine launch");
     }
@@ -859,10 +878,7 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
     // 3. per-row masses, if wanted
     if (mass_out_dev) {
         const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
-        EnMassArgs m = mass_args(pool, plan, static_cast<char *>(ws_dev), L);
-        m.Nq = n_rows;
-        m.n_splits = n_splits;
-        m.q_first = q_first;
+        EnMassArgs m = mass_args(pool, plan, static_cast<char *>(ws_dev), L, n_rows, n_splits, q_first);
         m.out = mass_out_dev;
         e = en_launch_mass(pool, m, 0, stream);
         if (e != 0)
@@ -898,7 +914,7 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
         return rc;
     const EnWsLayout L = en_ws_layout(pool, plan);
     char *ws = static_cast<char *>(ws_dev);
-    EnMassArgs a = mass_args(pool, plan, ws, L);
+    EnMassArgs a = mass_args(pool, plan, ws, L, plan->Nq, plan->n_splits, 0);
     a.out = mass_out_dev;
     const int e = en_launch_mass(pool, a, reduce, stream);
     if (e != 0)
@@ -929,10 +945,7 @@ static int cluster_assign(en_pool *pool, en_plan *plan, int q_first, int n_rows,
         return rc;
     const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
     EnClusterArgs a;
-    a.m = mass_args(pool, plan, static_cast<char *>(ws_dev), L);
-    a.m.Nq = n_rows;
-    a.m.n_splits = n_splits;
-    a.m.q_first = q_first;
+    a.m = mass_args(pool, plan, static_cast<char *>(ws_dev), L, n_rows, n_splits, q_first);
     a.score = score_dev;
     a.assign = assign_dev;
     a.n_obj = n_obj;

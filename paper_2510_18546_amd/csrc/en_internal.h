@@ -86,6 +86,9 @@ struct EnAttnArgs {
                        // before L_c + q_first is visible to all of them (0 for a whole prefill)
     int n_splits, n_ptiles, total_wgs;
     int decode;        // 1: all r*Nq query rows of a KV head fit one wave (attn_decode kernel)
+    int sub;           // decode kernel: waves per (agent, KV head, split); wave w takes every sub-th 32-key
+                       // block of the split's tiles and leaves its own partial results at index
+                       // sp * sub + w of n_splits * sub
     float scale_log2e;
     // decode kernel only, or null: the rows' own keys / values [B, Nq, Hkv, D], which the kernel
     // writes into the context (kc, vt) at positions L_c + q_first + t before it reads them
@@ -99,6 +102,7 @@ struct EnMassArgs {
     const int32_t *hdr;     // as in EnAttnArgs
     float *out;
     int B, Hq, Nq, Smax, n_splits;
+    int sub;                // as in EnAttnArgs: n_splits * sub partial results per row, the sub of a split side by side
     int q_first;            // as in EnAttnArgs
 };
 
@@ -153,6 +157,7 @@ struct EnWsLayout {
 };
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *plan, int n_rows, int n_splits);
+int en_attn_sub(const en_pool *pool, const en_plan *plan, int n_rows, int n_splits);
 
 // Kernel launchers (the .hip files). Return hipError_t as int.
 int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, void *stream);

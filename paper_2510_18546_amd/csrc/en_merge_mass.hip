@@ -128,7 +128,7 @@ __device__ __forceinline__ void row_final_ml(const EnMassArgs &a, size_t rows, s
                                              float &L)
 {
     // one split: its own (reference, sum); several: the pair the combine kernel merged
-    const float *p = (a.n_splits > 1 ? a.ws_mlfin : a.ws_ml) + row * 2;
+    const float *p = (a.n_splits * a.sub > 1 ? a.ws_mlfin : a.ws_ml) + row * 2;
     (void)rows;
     M = p[0];
     L = p[1];
@@ -141,12 +141,13 @@ __device__ __forceinline__ void merged_ml(const EnMassArgs &a, size_t rows, size
     constexpr int NB = 4;
     M = EN_NEG_INF;
     L = 0.f;
-    for (int sp0 = 0; sp0 < a.n_splits; sp0 += NB) {
+    const int n_part = a.n_splits * a.sub;      // partial results per row
+    for (int sp0 = 0; sp0 < n_part; sp0 += NB) {
         f32x2 ml[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            ml[j] = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)(sp0 + j < a.n_splits ? sp0 + j : 0) * rows + row) * 2);
-            if (sp0 + j >= a.n_splits)
+            ml[j] = *reinterpret_cast<const f32x2 *>(a.ws_ml + ((size_t)(sp0 + j < n_part ? sp0 + j : 0) * rows + row) * 2);
+            if (sp0 + j >= n_part)
                 ml[j][0] = EN_NEG_INF;
         }
         float Mb = M;
@@ -227,10 +228,14 @@ __device__ __forceinline__ float row_bucket_mass(const EnMassArgs &a, int b, int
         // keys: nothing was written for them
         if (!((keys >> sp) & 1))
             continue;
-        const f32x2 v = *reinterpret_cast<const f32x2 *>(
-            a.ws_seg + (((((size_t)sp * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
-        if (v[1] != EN_NEG_INF)
-            acc += v[0] * fast_exp2(v[1] - M);
+        // the waves that shared the split's tiles each left a pair of their own
+        for (int w = 0; w < a.sub; ++w) {
+            const f32x2 v = *reinterpret_cast<const f32x2 *>(
+                a.ws_seg +
+                (((((size_t)(sp * a.sub + w) * a.B + b) * a.Hq + hq) * (a.Smax + 1) + bucket) * a.Nq + i) * 2);
+            if (v[1] != EN_NEG_INF)
+                acc += v[0] * fast_exp2(v[1] - M);
+        }
     }
     return acc / L;
 }
@@ -346,7 +351,7 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk,
         }
         const unsigned use0 = (unsigned)__ballot(use0_v), use1 = (unsigned)__ballot(use1_v);
         const unsigned live = (unsigned)__ballot(live_v);
-        const bool simple = __ballot(live_v && hi_v - lo_v > 1) == 0;
+        const bool simple = a.sub == 1 && __ballot(live_v && hi_v - lo_v > 1) == 0;
         int lo[BG];
 #pragma unroll
         for (int j = 0; j < BG; ++j)
@@ -601,7 +606,7 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
         const dim3 blk(256);
         const dim3 grid = a.Nq < EN_MASS_FEW_ROWS ? dim3(((a.Smax + 1) * a.Hq * a.B + 255) / 256)
                                                   : dim3(mass_partial_blocks(a));
-        if (a.n_splits == 1 || a.Nq < EN_MASS_FEW_ROWS)
+        if (a.n_splits * a.sub == 1 || a.Nq < EN_MASS_FEW_ROWS)
             hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
         const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
         hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
