@@ -93,8 +93,8 @@ __global__ __launch_bounds__(64 * SUB) void attn_decode_kernel(EnAttnArgs a)
     const int Ltot = Lc + a.Nq;
     const int ntiles64 = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
     // split boundaries are whole 64-key tiles, as everywhere else
-    const int split_key_begin = (int)((long)sp * ntiles64 / a.n_splits) * EN_KEY_TILE;
-    const int split_key_end = min((int)((long)(sp + 1) * ntiles64 / a.n_splits) * EN_KEY_TILE, Ltot);
+    const int split_key_begin = (int)split_first_tile(sp, ntiles64, a.n_splits) * EN_KEY_TILE;
+    const int split_key_end = min((int)split_first_tile(sp + 1, ntiles64, a.n_splits) * EN_KEY_TILE, Ltot);
     const int t_begin = split_key_begin, t_end = split_key_end;
     const int lt_begin = split_key_begin / LB;           // load tiles; splits begin on them
     const int lt_end = (split_key_end + LB - 1) / LB;    // context rows are zero up to a multiple of 64
@@ -496,8 +496,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(EnAttnArgs a)
     const int Lc = bnd[S] + a.q_first;       // rows are new tokens q_first .. q_first+Nq-1
     const int Ltot = Lc + a.Nq;
     const int ntiles = (Ltot + EN_KEY_TILE - 1) / EN_KEY_TILE;
-    const int kbeg = (int)((long)sp * ntiles / a.n_splits) * EN_KEY_TILE;
-    const int kend_split = min((int)((long)(sp + 1) * ntiles / a.n_splits) * EN_KEY_TILE, Ltot);
+    const int kbeg = (int)split_first_tile(sp, ntiles, a.n_splits) * EN_KEY_TILE;
+    const int kend_split = min((int)split_first_tile(sp + 1, ntiles, a.n_splits) * EN_KEY_TILE, Ltot);
     const int kend = min(kend_split, Lc + i + 1);       // causal limit
 
     // rotated, scaled query in LDS

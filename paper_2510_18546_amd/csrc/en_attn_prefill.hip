@@ -116,8 +116,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         return bnd_in_lanes ? __builtin_amdgcn_readlane(my_bnd, s) : bnd[s];
     };
     const int ntiles = (Ltot + KT - 1) / KT;
-    const int t_begin = (int)((long)sp * ntiles / a.n_splits);
-    int t_end = (int)((long)(sp + 1) * ntiles / a.n_splits);
+    const int t_begin = (int)split_first_tile(sp, ntiles, a.n_splits);
+    int t_end = (int)split_first_tile(sp + 1, ntiles, a.n_splits);
     const int split_key_begin = t_begin * KT;
     const int split_key_end = min(t_end * KT, Ltot);
     {

@@ -55,6 +55,16 @@ __device__ __forceinline__ en_table_ptr as_table(const int32_t *p)
     return (en_table_ptr)(uintptr_t)p;
 }
 
+// KV split sp of n_splits takes the 64-key tiles [split_first_tile(sp), split_first_tile(sp + 1))
+// of an agent's ntiles. The boundaries are rounded up: when the tiles do not divide evenly it is
+// the last splits that get one fewer, and the last split is the one with extra work (the causal
+// edge; in a decode step, the step's own keys, written before they can be loaded). Tile t lies in
+// split t * n_splits / ntiles. 32-bit arithmetic: n_splits <= 64 and ntiles < 2^25.
+__device__ __forceinline__ unsigned split_first_tile(unsigned sp, unsigned ntiles, unsigned n_splits)
+{
+    return (sp * ntiles + n_splits - 1) / n_splits;
+}
+
 template <typename P>
 __device__ __forceinline__ int find_bucket(P bnd, int S, int tok)
 {

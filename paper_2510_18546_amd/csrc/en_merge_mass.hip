@@ -165,7 +165,7 @@ __device__ __forceinline__ void merged_ml(const EnMassArgs &a, size_t rows, size
 }
 
 // Tiles of the KV splits, one split per lane (a plan has at most 64 splits): the attention
-// kernels give split sp the tiles [sp * ntiles / n_splits, (sp + 1) * ntiles / n_splits). Code that
+// kernels give split sp the tiles [split_first_tile(sp), split_first_tile(sp + 1)). Code that
 // has to know which splits cover a bucket asks this map with two wave votes instead of doing
 // integer divisions per bucket (a division by a run-time value is some thirty instructions, and
 // these kernels are bound by their instruction count).
@@ -177,8 +177,8 @@ struct EnSplitMap {
 __device__ __forceinline__ EnSplitMap split_map(int n_splits, int ntiles)
 {
     const unsigned q = threadIdx.x % 64;
-    const unsigned bgn = q * (unsigned)ntiles / (unsigned)n_splits;
-    const unsigned end = (q + 1) * (unsigned)ntiles / (unsigned)n_splits;
+    const unsigned bgn = split_first_tile(q, ntiles, n_splits);
+    const unsigned end = split_first_tile(q + 1, ntiles, n_splits);
     EnSplitMap m;
     m.end_tile = (int)q < n_splits ? (int)end : 0x7fffffff;
     m.keys = __ballot((int)q < n_splits && end != bgn);
@@ -196,8 +196,8 @@ __device__ __forceinline__ void bucket_splits(const EnSplitMap &m, int n_splits,
     lo = bhi <= blo ? n_splits : l;
     hi = bhi <= blo ? -1 : h;
 }
-// The same for one thread on its own (32-bit arithmetic: (t + 1) * n_splits <= Ltot + 64): the split
-// that holds tile t is the largest sp whose first tile is <= t, ((t + 1) * n_splits - 1) / ntiles.
+// The same for one thread on its own (32-bit arithmetic: t * n_splits <= Ltot): the split
+// that holds tile t is the largest sp whose first tile is <= t, t * n_splits / ntiles.
 // Also returns the mask of the splits in [lo, hi] that hold keys.
 __device__ __forceinline__ void bucket_splits_thread(int n_splits, int ntiles, int Ltot, int blo, int bhi,
                                                      int &lo, int &hi, unsigned long long &keys)
@@ -210,11 +210,10 @@ __device__ __forceinline__ void bucket_splits_thread(int n_splits, int ntiles, i
         return;
     }
     const unsigned t_lo = blo / EN_KEY_TILE, t_hi = (bhi - 1) / EN_KEY_TILE;
-    lo = (int)(((t_lo + 1) * (unsigned)n_splits - 1) / (unsigned)ntiles);
-    hi = (int)(((t_hi + 1) * (unsigned)n_splits - 1) / (unsigned)ntiles);
+    lo = (int)(t_lo * (unsigned)n_splits / (unsigned)ntiles);
+    hi = (int)(t_hi * (unsigned)n_splits / (unsigned)ntiles);
     for (int sp = lo; sp <= hi; ++sp)
-        if ((unsigned)sp * (unsigned)ntiles / (unsigned)n_splits !=
-            (unsigned)(sp + 1) * (unsigned)ntiles / (unsigned)n_splits)
+        if (split_first_tile(sp, ntiles, n_splits) != split_first_tile(sp + 1, ntiles, n_splits))
             keys |= 1ull << sp;
 }
 
@@ -339,8 +338,9 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk,
             live_v = s0 + jl <= S && bhi > blo;
             const unsigned t_lo = live_v ? blo / EN_KEY_TILE : 0, t_hi = live_v ? (bhi - 1) / EN_KEY_TILE : 0;
             // the split that holds tile t is the largest sp whose first tile is <= t
-            const unsigned l = ((t_lo + 1) * n - 1) / ntiles, h = ((t_hi + 1) * n - 1) / ntiles;
-            const unsigned e0 = l * ntiles / n, e1 = (l + 1) * ntiles / n, e2 = (l + 2) * ntiles / n;
+            const unsigned l = t_lo * n / ntiles, h = t_hi * n / ntiles;
+            const unsigned e0 = split_first_tile(l, ntiles, n), e1 = split_first_tile(l + 1, ntiles, n),
+                           e2 = split_first_tile(l + 2, ntiles, n);
             next_v = l + 1 < n;
             use0_v = live_v && e0 != e1;                // an agent with fewer tiles than splits leaves some empty
             use1_v = live_v && h > l && next_v && e1 != e2;
