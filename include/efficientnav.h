@@ -227,7 +227,8 @@ int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void 
 
 /* Bytes of scratch the attention call needs for this plan: per-split running
  * (max, sum), per-(row, segment) partial sums, and, when n_splits > 1, partial
- * outputs. */
+ * outputs (a step of few rows and few agents keeps two partial results per
+ * split: the size accounts for it). */
 size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan);
 
 /* softmax(Q K^T / sqrt(D)) V (Appendix A) of the N_q new tokens over the
