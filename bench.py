@@ -271,7 +271,9 @@ def main():
         plan_d.close()
         pool_d.close()
 
-    if not hbm_bound and cfg.n_agents == 1 and not args.no_residency:
+    # (on workloads whose groups all have the slot's length: with ragged groups the token budget of
+    # Eq. (1) selects more groups than the workload's own plan, scratch and slots are sized for)
+    if not hbm_bound and cfg.n_agents == 1 and cfg.len_lo == cfg.len_hi and not args.no_residency:
         # Residency tier (Section 3.2, Section 4 "cache hit rate"): every group's K/V lives in a pinned host
         # store, the device holds a budget of slots, a step loads only the selected groups that are not
         # there. Selections: Eq. (1) over relevance scores that drift slowly from step to step.

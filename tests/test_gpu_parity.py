@@ -260,6 +260,17 @@ def test_bf16_tiny_segments(step_mod, oracle):
     run_case(step_mod, oracle, cfg)
 
 
+@pytest.mark.parametrize("nq,splits,len_hi", [(1, 1, 9), (4, 2, 9), (2, 5, 40), (3, None, 9)])
+def test_bf16_two_waves_share_a_unit(step_mod, oracle, nq, splits, len_hi):
+    """A step with so few (agent, KV head, split) units that two waves share each unit's tiles, each
+    taking every other 32-key block and leaving partial results of its own. Segments shorter than a
+    block, some empty: buckets lie wholly inside the other wave's blocks, or straddle two waves'
+    blocks and two splits. Outputs, per-row masses and per-head sums against the oracle."""
+    cfg = small(f"bf16-two-waves-nq{nq}-{splits}", 530 + nq, capacity=max(len_hi, 9), len_lo=0, len_hi=len_hi,
+                n_groups=48, n_sel=44, n_new=nq)
+    run_case(step_mod, oracle, cfg, n_splits=splits)
+
+
 @pytest.mark.parametrize("dtype,n_agents", [(I.BF16, 1), (I.BF16, 9), (I.F32, 2)])
 def test_more_segments_than_lanes(step_mod, oracle, dtype, n_agents):
     """More than 62 selected segments per agent: the bucket bounds no longer fit one per lane, and
