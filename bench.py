@@ -131,7 +131,7 @@ def main():
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(args.workload)
-    roof["kernel"] = "attn_decode_kernel<128>" if hbm_bound else "attn_bf16_kernel<128>"
+    roof["kernel"] = "attn_decode_kernel<128, 1>" if hbm_bound else "attn_bf16_kernel<128>"
     roof["kernel_us"] = kern_s * 1e6
     roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
 
