@@ -560,17 +560,16 @@ static bool decode_kernel_fits(const en_pool *pool, int n_rows)
 // two workgroups per compute unit: when a step has no more units than that, two waves share each
 // unit's tiles, each takes every other 32-key block and leaves partial results of its own (the
 // scratch then holds n_splits * 2 of them per row; the units' key ranges stay whole tiles).
-// Only up to 64 partial results per row: measured per decoded token with 8 KV heads, two waves
-// against one took 10.9 / 12.4 us (1 agent, 25 splits), 11.4 / 12.5 (2 agents, 17 splits),
-// 12.9 / 14.0 (2 agents, 32 splits), 14.2 / 14.0 (4 agents, 16 splits), but 12.3 / 12.1 (1 agent,
-// 37 splits) and 13.9 / 13.0 (1 agent, 64 splits), whether the merge read its 128 partial
-// results in one round of loads or in two.
+// Measured per decoded token with 8 KV heads, two waves against one: 10.9 / 12.4 us (1 agent,
+// 25 splits), 11.3 / 12.5 (2 agents, 17 splits), 12.6 / 13.9 (2 agents, 32 splits), 13.1 / 14.0
+// (4 agents, 16 splits), 12.9 / 13.0 (1 agent, 4K tokens, 64 splits), 17.5 / 18.0 (1 agent, 8.7K
+// tokens, 64 splits); the attention launch itself 9.6 / 10.0 us in the last but one case. (The
+// merge of twice as many partial results must not eat the gain: see its lane groups.)
 int en_attn_sub(const en_pool *pool, const en_plan *pl, int n_rows, int n_splits)
 {
     if (!decode_kernel_fits(pool, n_rows))
         return 1;
-    const bool idle_units = long(pl->B) * pool->d.n_kv_heads * n_splits <= 2L * pool->n_cu;
-    return idle_units && 2 * n_splits <= EN_MAX_SPLITS ? 2 : 1;
+    return long(pl->B) * pool->d.n_kv_heads * n_splits <= 2L * pool->n_cu ? 2 : 1;
 }
 
 // Scratch layout for n_rows query rows per agent and n_splits KV splits.

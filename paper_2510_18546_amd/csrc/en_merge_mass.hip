@@ -21,7 +21,7 @@ __host__ inline int mass_partial_blocks(const EnMassArgs &m)
     return mass_bucket_groups(m) * m.Hq * m.B;
 }
 
-// With many splits (decode over a long context by few agents) G = 4 or 16 neighbouring lanes
+// With many splits (decode over a long context by few agents) G = 4, 16 or 32 neighbouring lanes
 // share a (row, 16-byte chunk): lane g takes the splits g, g + G, ... and the G partial results
 // are merged with lane shuffles, so that the chain of dependent loads is 1/G as long (with 16
 // lanes, up to 64 splits are one batch of loads) and the few rows of such a step make G times
@@ -553,7 +553,14 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
     hipStream_t st = (hipStream_t)stream;
     const int D = pool->d.head_dim;
     const int vec = pool->d.dtype == EN_F32 ? 4 : 8;      // elements in 16 bytes
-    const int G = a.n_splits > 32 ? 16 : (a.n_splits > 8 ? 4 : 1);     // lanes that share a (row, chunk)
+    // Lanes that share a (row, chunk). What the merge of a step of few rows costs is the partial
+    // results per lane (each a dependent step of the running merge), not the number of workgroups:
+    // about four per lane is best. Per decoded token, same box: 128 partial results by 16 / 32 / 64
+    // lanes 18.0 / 17.5 / 17.9 us; 74 by 16 / 32 / 64 lanes 12.1 / 11.5 / 11.6; 32 (four agents) by
+    // 4 / 16 lanes 14.0 / 13.1. A prefill's many rows fill the chip without that.
+    int G = a.n_splits > 32 ? 16 : (a.n_splits > 8 ? 4 : 1);
+    if ((size_t)a.B * a.Hq * a.Nq * (D / vec) <= 16384)
+        G = a.n_splits > 64 ? 32 : (a.n_splits > 16 ? 16 : (a.n_splits > 4 ? 4 : 1));
     const size_t n = (size_t)a.B * a.Hq * a.Nq * (D / vec) * G;
     const int n_comb = (int)((n + 255) / 256);
     const int n_part = m.Nq < EN_MASS_FEW_ROWS ? 0 : mass_partial_blocks(m);
@@ -564,8 +571,10 @@ int en_launch_combine(const en_pool *pool, const EnAttnArgs &a, const EnMassArgs
             hipLaunchKernelGGL((combine_kernel<T, DD, 1>), grid, blk, 0, st, a, m, n_comb);           \
         else if (G == 4)                                                                              \
             hipLaunchKernelGGL((combine_kernel<T, DD, 4>), grid, blk, 0, st, a, m, n_comb);           \
-        else                                                                                          \
+        else if (G == 16)                                                                             \
             hipLaunchKernelGGL((combine_kernel<T, DD, 16>), grid, blk, 0, st, a, m, n_comb);          \
+        else                                                                                          \
+            hipLaunchKernelGGL((combine_kernel<T, DD, 32>), grid, blk, 0, st, a, m, n_comb);          \
     } while (0)
     if (pool->d.dtype == EN_F32) {
         if (D == 64)
