@@ -140,6 +140,19 @@ def test_set_splits_clamps():
     assert long_plan.info.n_splits == 64
 
 
+@pytest.mark.parametrize("n_groups,tiles,expect", [(7, 28, 28), (17, 67, 34), (25, 98, 49), (34, 133, 64),
+                                                   (41, 161, 54)])
+def test_split_choice_of_a_one_token_step(n_groups, tiles, expect):
+    """Host logic, 256 compute units assumed without a device, 2 KV heads, one agent: as many KV splits
+    as there are key tiles up to 64; then the fewest splits that keep the longest split as short (67
+    tiles: 2 per split either way, so 34 splits; 161 tiles: 54 x 3) unless fewer than an eighth of the
+    splits are three tiles or longer (133 tiles over 64 splits: five of them)."""
+    pool = host_pool(np.full(n_groups, 250, np.int32), cap=256, max_ctx=16384)
+    plan = B.segment_select(pool, np.arange(n_groups), [0, n_groups], 1)
+    assert (plan.info.max_ctx_len + 63) // 64 == tiles
+    assert plan.info.n_splits == expect
+
+
 def test_scored_selection_matches_oracle(oracle):
     rng = np.random.default_rng(5)
     for trial in range(120):
