@@ -112,9 +112,12 @@ def test_two_planning_steps_over_four_layers(oracle):
                     k_rows = dev[l]["k_new"][0, :n_obj_tokens].contiguous()
                     v_rows = dev[l]["v_new"][0, :n_obj_tokens].contiguous()
                     B.kv_tier_append(tier, g, k_rows, v_rows)
-                    for arr, new in ((layers[l].k_pool, layers[l].k_new), (layers[l].v_pool, layers[l].v_new)):
-                        arr[g, :, lens[g]:lens[g] + n_obj_tokens, :] = np.transpose(new[0, :n_obj_tokens], (1, 0, 2))
-                lens[g] += n_obj_tokens
+                    # the reference pool of this layer grows by the oracle's append (Section 3.2)
+                    layers[l].k_pool, layers[l].v_pool, new_lens = oracle.append(
+                        layers[l].k_pool, layers[l].v_pool, lens, g, layers[l].k_new[0, :n_obj_tokens],
+                        layers[l].v_new[0, :n_obj_tokens])
+                    assert new_lens[g] == lens[g] + n_obj_tokens
+                lens = new_lens.copy()
                 for w in layers:
                     w.lens = lens.copy()
         for plan, *_ in ctx:

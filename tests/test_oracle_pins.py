@@ -104,9 +104,67 @@ def test_plan_golden(oracle):
     off = oracle.plan(w.lens, w.sel)
     assert off.dtype == np.int32 and np.array_equal(off, want)
     assert off[-1] == first_new and off[-1] + w.cfg.n_new - 1 == last_new
-    kinds = [l.split()[1] for l in open(os.path.join(GOLD, "prompt_order.txt"))
-             if not l.startswith("#")]
-    assert kinds == sorted(kinds, key=lambda k: k != "group")   # groups precede new
+
+
+def test_prompt_order_golden(oracle):
+    """Appendix B, "Prompt for Planning": the selected groups come first, in their order, the
+    new tokens (instruction, then trajectory) last. The golden file lists the slots of that
+    example; the oracle must place each slot's tokens at the positions this order gives them:
+    cached tokens before L_c, new tokens from L_c on. Which row of the oracle's context a token
+    landed in, and at which position it was rotated, is read off its key: every token gets a
+    key of its own (a one-hot pair pattern times a token number), rotated here with complex
+    numbers."""
+    slots = [l.split() for l in open(os.path.join(GOLD, "prompt_order.txt")) if not l.startswith("#")]
+    assert [int(t[0]) for t in slots] == list(range(len(slots)))
+    groups = [int(t[2]) for t in slots if t[1] == "group"]
+    new_spans = [t[2] for t in slots if t[1] == "new"]
+    assert groups == [2, 3] and new_spans == ["instruction", "trajectory"]
+    lens = np.array([4, 1, 3, 5, 2], dtype=np.int32)           # five groups; 2 and 3 are selected
+    span_len = {"instruction": 2, "trajectory": 3}
+    Hkv, D, Cap, base = 1, 4, 5, 100.0
+    G = len(lens)
+    tag = lambda n: np.array([1.0 + n, 0.5, -0.25 * n, 2.0])   # token number n -> a key of its own
+    k_pool = np.full((G, Hkv, Cap, D), np.nan, dtype=np.float32)
+    for g in range(G):
+        for t in range(lens[g]):
+            k_pool[g, 0, t] = tag(10 * g + t)
+    n_new = sum(span_len[n] for n in new_spans)
+    k_new = np.stack([tag(100 + i) for i in range(n_new)])[:, None, :].astype(np.float32)
+    off = oracle.plan(lens, groups)
+    assert list(off) == [0, 3, 8]
+    Lc = int(off[-1])
+    kc, vc = oracle.gather_rope(k_pool, np.nan_to_num(k_pool), lens, groups, k_new, k_new, base)
+    assert kc.shape == (Hkv, Lc + n_new, D)
+    # expected order of token numbers, written out from the golden slots
+    order = []
+    for t in slots:
+        if t[1] == "group":
+            order += [10 * int(t[2]) + j for j in range(lens[int(t[2])])]
+    order += [100 + i for i in range(n_new)]
+    assert order == [20, 21, 22, 30, 31, 32, 33, 34, 100, 101, 102, 103, 104]
+    for pos, n in enumerate(order):
+        np.testing.assert_allclose(kc[0, pos], rope_complex(tag(n), pos, base), atol=1e-12)
+        assert (pos < Lc) == (n < 100)                          # cached before L_c, new from L_c on
+    # values are copied, not rotated, in the same order
+    np.testing.assert_array_equal(vc[0, :, 0], [1.0 + n for n in order])
+
+
+def test_reduce_mass_explicit_loops(oracle):
+    """reduce_mass sums over query tokens and heads, per agent and bucket: against a double loop
+    on a small tensor whose axes all differ in length (a sum over the wrong axes changes the shape
+    or the values, not only the grand total)."""
+    rng = np.random.default_rng(12)
+    B, Nq, Hq, S1 = 2, 3, 4, 5
+    mass = rng.random((B, Nq, Hq, S1))
+    want = np.zeros((B, S1))
+    for b in range(B):
+        for s in range(S1):
+            for i in range(Nq):
+                for h in range(Hq):
+                    want[b, s] += mass[b, i, h, s]
+    got = oracle.reduce_mass(mass)
+    assert got.shape == (B, S1)
+    np.testing.assert_allclose(got, want, atol=1e-13)
 
 
 def test_plan_rejects_bad_id(oracle):

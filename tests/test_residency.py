@@ -116,6 +116,47 @@ def test_oracle_prefetch_and_fence():
 SHAPE = (8, 16, 64)     # Hkv, C, D of a block; irrelevant to the bookkeeping
 
 
+def test_oracle_unfenced_fetch_fences_for_itself_hand_worked():
+    """Four steps worked by hand, no library involved. Three slots, no explicit fence anywhere.
+    The rule under test: a fetch that has to load while the last fence is older than the previous
+    step first waits for everything queued so far (there is nothing else it could wait for), and
+    that wait covers every reader of the slots handed out in earlier steps, so from then on those
+    slots count as fenced, exactly as after fence(). Slots used by the CURRENT step are not covered.
+
+      step 1  fetch A B C   all miss                        slots [A B C]  ages [1 1 1]  fenced never
+      step 2  fetch A D     A hit (age 2); D must load: fences for itself -> fenced = 1;
+                            D takes the oldest slot not used in step 2: slots 1 and 2 are both age 1,
+                            the lower number wins            slots [A D C]  ages [2 2 1]
+              prefetch E    may take slots with age <= fenced = 1 only: slot 2 (C) -> E, 1 loaded;
+                            without the rule nothing would be fenced and 0 would be loaded
+                                                            slots [A D E]  ages [2 2 1]
+              prefetch F    slot 2 now holds a prefetched group as old as the fence: it is the only
+                            candidate again, F displaces E   slots [A D F]
+      step 3  fetch F A     F was prefetched, A hit          ages [3 2 3]
+      step 4  fetch C       miss; fences for itself -> fenced = 3; oldest slot is 1 (D, age 2)
+                                                            slots [A C F]  ages [3 4 3]
+    """
+    A, B_, C, D, E, F = range(6)
+    r = Residency(3)
+    assert r.fetch([A, B_, C]) == ([0, 1, 2], ["miss", "miss", "miss"])
+    assert r.fenced == -1
+    assert r.fetch([A, D]) == ([0, 1], ["hit", "miss"])
+    assert r.fenced == 1
+    assert r.prefetch([E]) == 1 and r.slot_of(E) == 2 and r.slot_of(C) == -1
+    assert r.prefetch([F]) == 1 and r.slot_of(F) == 2 and r.slot_of(E) == -1
+    assert r.fetch([F, A]) == ([2, 0], ["prefetched", "hit"])
+    assert r.fetch([C]) == ([1], ["miss"])
+    assert r.fenced == 3
+    assert [r.group_in[s] for s in range(3)] == [A, C, F]
+    assert (r.hits, r.prefetched, r.misses, r.loads, r.evictions, r.requested) == (2, 1, 5, 7, 4, 8)
+    # and with an explicit fence in its place the same trace gives the same slots
+    q = Residency(3)
+    q.fetch([A, B_, C])
+    q.fence()
+    q.fetch([A, D])
+    assert q.prefetch([E]) == 1 and q.slot_of(E) == 2
+
+
 def _tier(n_slots, G):
     t = B.kv_tier_create(None, None, G, 32, 1e4, 4096, dtype=B.EN_BF16, shape=(n_slots,) + SHAPE)
     for g in range(G):
