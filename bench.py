@@ -109,15 +109,15 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
-    B.timing_enable(args.steps)
+    B.timing_enable(st.pool, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kern_ms = B.timing_collect(args.steps)
-    B.timing_enable(0)
+    kern_ms = B.timing_collect(st.pool, args.steps)
+    B.timing_enable(st.pool, 0)
 
     sec_per_step = (t1 - t0) / args.steps
     kern_s = float(np.mean(kern_ms)) * 1e-3
@@ -179,13 +179,13 @@ def main():
                 B.segmented_decode_step(pool_d, plan_d, i, qs[i], ks[i], vs[i], kc_d, vt_d, od[i], ws_d)
         decode_all()
         torch.cuda.synchronize()
-        B.timing_enable(n_dec)
+        B.timing_enable(pool_d, n_dec)
         d0 = time.perf_counter()
         decode_all()
         torch.cuda.synchronize()
         d1 = time.perf_counter()
-        dec_kern_ms = B.timing_collect(n_dec)
-        B.timing_enable(0)
+        dec_kern_ms = B.timing_collect(pool_d, n_dec)
+        B.timing_enable(pool_d, 0)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
@@ -239,13 +239,13 @@ def main():
                 B.segmented_decode_step(pool_d, plan_d, cfg.n_new + i, qs[i], ks[i], vs[i], kc_d, vt_d, od[i], ws_d)
         decode_all()
         torch.cuda.synchronize()
-        B.timing_enable(n_dec)
+        B.timing_enable(pool_d, n_dec)
         d0 = time.perf_counter()
         decode_all()
         torch.cuda.synchronize()
         d1 = time.perf_counter()
-        dec_kern_ms = B.timing_collect(n_dec)
-        B.timing_enable(0)
+        dec_kern_ms = B.timing_collect(pool_d, n_dec)
+        B.timing_enable(pool_d, 0)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()

@@ -433,16 +433,18 @@ int kv_tier_destroy(en_tier *tier);
 /* ------------------------------------------------------------------------
  * Measurement aid for callers that need the duration of the attention kernel
  * itself (the kernel the roofline is quoted on), not of the whole call.
- * en_timing_enable(n > 0) creates n pairs of HIP events; from then on every
- * segmented_prefill_attention call records one pair around its main kernel
- * launch, on the stream it launches on, until n pairs are used.
- * en_timing_enable(0) frees them. en_timing_collect waits for the recorded
- * pairs, writes their durations in milliseconds to ms_out_host (at most cap)
- * and resets the record count. Process-wide, not thread-safe.
- * Errors: INVALID_ARG, DEVICE.
+ * en_timing_enable(pool, n > 0) creates n pairs of HIP events in the pool; from
+ * then on every segmented_prefill_attention / segmented_decode_step call on that
+ * pool records one pair around its main kernel launch, on the stream it launches
+ * on, until n pairs are used. en_timing_enable(pool, 0) frees them (so does
+ * kv_pool_destroy). en_timing_collect waits for the recorded pairs, writes their
+ * durations in milliseconds to ms_out_host (at most cap) and resets the record
+ * count. The state belongs to the pool: calls on one pool are serialised by the
+ * caller as for every other call. Not for streams under graph capture.
+ * Errors: INVALID_ARG, CAPACITY (host memory), DEVICE.
  */
-int en_timing_enable(int32_t max_records);
-int en_timing_collect(float *ms_out_host, int32_t cap, int32_t *n_out);
+int en_timing_enable(en_pool *pool, int32_t max_records);
+int en_timing_collect(en_pool *pool, float *ms_out_host, int32_t cap, int32_t *n_out);
 
 const char *en_last_error(void);
 

@@ -98,8 +98,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_decode_workspace_bytes.restype = C.c_size_t
     lib.segmented_decode_step.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
                                           C.c_size_t, vp]
-    lib.en_timing_enable.argtypes = [C.c_int32]
-    lib.en_timing_collect.argtypes = [C.POINTER(C.c_float), C.c_int32, i32p]
+    lib.en_timing_enable.argtypes = [vp, C.c_int32]
+    lib.en_timing_collect.argtypes = [vp, C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
     lib.kv_tier_slot_bytes.argtypes = [C.POINTER(PoolDesc)]
     lib.kv_tier_slot_bytes.restype = C.c_int64
@@ -476,14 +476,14 @@ def kv_tier_prefetch(tier: Tier, groups) -> int:
     return n.value
 
 
-def timing_enable(n: int):
-    _check(load().en_timing_enable(int(n)))
+def timing_enable(pool: Pool, n: int):
+    _check(load().en_timing_enable(pool.handle, int(n)))
 
 
-def timing_collect(cap: int) -> np.ndarray:
-    """Durations (ms) of the attention kernel launches recorded since the last
-    collect."""
+def timing_collect(pool: Pool, cap: int) -> np.ndarray:
+    """Durations (ms) of the attention kernel launches on this pool recorded since
+    the last collect."""
     ms = np.zeros(cap, dtype=np.float32)
     n = C.c_int32()
-    _check(load().en_timing_collect(ms.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)))
+    _check(load().en_timing_collect(pool.handle, ms.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)))
     return ms[:n.value].copy()

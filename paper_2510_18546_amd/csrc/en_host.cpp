@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 
@@ -37,6 +38,12 @@ static int fail(int code, const char *fmt, ...)
     return code;
 }
 
+int en_fail_exception(const char *who, bool out_of_memory)
+{
+    return out_of_memory ? fail(EN_ERR_CAPACITY, "%s: out of host memory", who)
+                         : fail(EN_ERR_INVALID_ARG, "%s: unexpected C++ exception", who);
+}
+
 static int hip_fail(hipError_t e, const char *what)
 {
     return fail(EN_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
@@ -54,7 +61,7 @@ static inline bool computes_bf16(int dtype) { return dtype != EN_F32; }
 // ---------------------------------------------------------------------------
 // pool
 // ---------------------------------------------------------------------------
-extern "C" int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
+static int kv_pool_create_impl(const en_pool_desc *desc, void *k_dev, void *v_dev,
                               const int32_t *len_host, en_pool **out)
 {
     if (!desc || !k_dev || !v_dev || !len_host || !out)
@@ -76,17 +83,27 @@ extern "C" int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev
                         len_host[g], desc->capacity);
     en_pool *p = new (std::nothrow) en_pool;
     if (!p)
-        return fail(EN_ERR_INVALID_ARG, "kv_pool_create: out of host memory");
+        return fail(EN_ERR_CAPACITY, "kv_pool_create: out of host memory");
     p->d = *desc;
     p->k_dev = k_dev;
     p->v_dev = v_dev;
-    p->len.assign(len_host, len_host + desc->n_groups);
+    try {
+        p->len.assign(len_host, len_host + desc->n_groups);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(EN_ERR_CAPACITY, "kv_pool_create: out of host memory for %d group lengths", desc->n_groups);
+    }
     p->r = desc->n_q_heads / desc->n_kv_heads;
     *out = p;
     return EN_OK;
 }
+extern "C" int kv_pool_create(const en_pool_desc *desc, void *k_dev, void *v_dev,
+                              const int32_t *len_host, en_pool **out)
+{
+    EN_GUARDED("kv_pool_create", kv_pool_create_impl(desc, k_dev, v_dev, len_host, out));
+}
 
-extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
+static int kv_pool_set_len_impl(en_pool *pool, int32_t group, int32_t len)
 {
     if (!pool)
         return fail(EN_ERR_INVALID_ARG, "kv_pool_set_len: null pool");
@@ -95,8 +112,12 @@ extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
     pool->len[group] = len;
     return EN_OK;
 }
+extern "C" int kv_pool_set_len(en_pool *pool, int32_t group, int32_t len)
+{
+    EN_GUARDED("kv_pool_set_len", kv_pool_set_len_impl(pool, group, len));
+}
 
-extern "C" int kv_pool_set_scales(en_pool *pool, float *k_scale_dev, float *v_scale_dev)
+static int kv_pool_set_scales_impl(en_pool *pool, float *k_scale_dev, float *v_scale_dev)
 {
     if (!pool || !k_scale_dev || !v_scale_dev)
         return fail(EN_ERR_INVALID_ARG, "kv_pool_set_scales: null argument");
@@ -106,8 +127,12 @@ extern "C" int kv_pool_set_scales(en_pool *pool, float *k_scale_dev, float *v_sc
     pool->v_scale = v_scale_dev;
     return EN_OK;
 }
+extern "C" int kv_pool_set_scales(en_pool *pool, float *k_scale_dev, float *v_scale_dev)
+{
+    EN_GUARDED("kv_pool_set_scales", kv_pool_set_scales_impl(pool, k_scale_dev, v_scale_dev));
+}
 
-extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+static int kv_pool_append_impl(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
                               int32_t n_tokens, void *stream)
 {
     if (!pool || n_tokens < 0 || (n_tokens > 0 && (!k_rows_dev || !v_rows_dev)))
@@ -158,11 +183,19 @@ extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_d
     pool->len[group] = len + n_tokens;
     return EN_OK;
 }
+extern "C" int kv_pool_append(en_pool *pool, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                              int32_t n_tokens, void *stream)
+{
+    EN_GUARDED("kv_pool_append", kv_pool_append_impl(pool, group, k_rows_dev, v_rows_dev, n_tokens, stream));
+}
 
-extern "C" int kv_pool_destroy(en_pool *pool)
+static void timing_release(en_pool *pool);
+
+static int kv_pool_destroy_impl(en_pool *pool)
 {
     if (!pool)
         return EN_OK;
+    timing_release(pool);
     if (pool->d_cos)
         (void)hipFree(pool->d_cos);
     if (pool->d_sin)
@@ -173,6 +206,10 @@ extern "C" int kv_pool_destroy(en_pool *pool)
         pl->pool = nullptr;               // only en_plan_destroy may still be called on these
     delete pool;
     return EN_OK;
+}
+extern "C" int kv_pool_destroy(en_pool *pool)
+{
+    EN_GUARDED("kv_pool_destroy", kv_pool_destroy_impl(pool));
 }
 
 // Rotary table: cos/sin(pos * base^(-2k/D)) evaluated in double, stored as
@@ -286,9 +323,10 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
         Smax = std::max(Smax, sel_ptr[b + 1] - sel_ptr[b]);
     }
     const int G = pool->d.n_groups;
-    en_plan *pl = new (std::nothrow) en_plan;
+    std::unique_ptr<en_plan> holder(new (std::nothrow) en_plan);     // released to the caller at the end
+    en_plan *pl = holder.get();
     if (!pl)
-        return fail(EN_ERR_INVALID_ARG, "segment_select: out of host memory");
+        return fail(EN_ERR_CAPACITY, "segment_select: out of host memory");
     pl->pool = pool;
     pl->B = B;
     pl->Nq = n_new;
@@ -307,12 +345,10 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
         for (int s = 0; s < S; ++s) {
             const int g = sel[sel_ptr[b] + s];
             if (g < 0 || g >= G) {
-                delete pl;
                 return fail(EN_ERR_OUT_OF_RANGE, "segment_select: agent %d entry %d: group %d outside [0,%d)",
                             b, s, g, G);
             }
             if (seen[g] == b) {
-                delete pl;
                 return fail(EN_ERR_DUPLICATE, "segment_select: agent %d selects group %d twice", b, g);
             }
             seen[g] = b;
@@ -320,13 +356,11 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
             bnd[s] = int32_t(acc);
             acc += pool->len[g];
             if (acc + n_new > pool->d.max_ctx) {
-                delete pl;
                 return fail(EN_ERR_CAPACITY, "segment_select: agent %d: L_c + N_q exceeds max_ctx %d", b,
                             pool->d.max_ctx);
             }
         }
         if (acc + n_new > pool->d.max_ctx) {
-            delete pl;
             return fail(EN_ERR_CAPACITY, "segment_select: agent %d: L_c + N_q = %lld exceeds max_ctx %d", b,
                         (long long)(acc + n_new), pool->d.max_ctx);
         }
@@ -343,27 +377,46 @@ static int build_plan(const en_pool *pool, int32_t B, const int32_t *sel, const 
     pl->ctx_stride = round_up(pl->max_ctx_len, EN_KEY_TILE);
     pl->n_splits = choose_splits(pool, pl);
     pool->plans.push_back(pl);
-    *out = pl;
+    *out = holder.release();
     return EN_OK;
 }
 
-extern "C" int segment_select(const en_pool *pool, int32_t n_agents, const int32_t *sel_host,
+static int segment_select_impl(const en_pool *pool, int32_t n_agents, const int32_t *sel_host,
                               const int32_t *sel_ptr_host, int32_t n_new, en_plan **out)
 {
     return build_plan(pool, n_agents, sel_host, sel_ptr_host, n_new, out);
+}
+extern "C" int segment_select(const en_pool *pool, int32_t n_agents, const int32_t *sel_host,
+                              const int32_t *sel_ptr_host, int32_t n_new, en_plan **out)
+{
+    EN_GUARDED("segment_select", segment_select_impl(pool, n_agents, sel_host, sel_ptr_host, n_new, out));
 }
 
 // Eq. (1) as an exact 0/1 knapsack over token capacity: the groups with
 // p > threshold whose lengths fit the budget and whose summed (p - threshold) is
 // largest; among those the fewest tokens, then the lowest ids.
-void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
-                 std::vector<int32_t> &chosen)
+// (the file is compiled without NaN semantics: finiteness is read from the bits)
+static inline bool finite_bits(float x)
+{
+    uint32_t u;
+    std::memcpy(&u, &x, sizeof u);
+    return (u & 0x7f800000u) != 0x7f800000u;
+}
+
+int en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
+                std::vector<int32_t> &chosen)
 {
     chosen.clear();
+    if (!finite_bits(threshold))
+        return fail(EN_ERR_INVALID_ARG, "retrieval knapsack: the threshold is not finite");
     struct Item { int id; int64_t v; int w; };
     std::vector<Item> items;
     int64_t wsum = 0;
     for (int g = 0; g < G; ++g) {
+        if (len[g] < 0)
+            continue;                       // not a candidate (a store group never put)
+        if (!finite_bits(p_host[g]))
+            return fail(EN_ERR_INVALID_ARG, "retrieval knapsack: score of group %d is not finite", g);
         const double d = double(p_host[g]) - double(threshold);
         const int64_t v = (int64_t)std::nearbyint(d * 4294967296.0);   // ties to even
         if (v > 0) {
@@ -376,13 +429,20 @@ void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold
     if (wsum <= budget_tokens) {
         for (auto &it : items)
             chosen.push_back(it.id);
-        return;
+        return EN_OK;
     }
     // best[a][w] over items a.. with capacity w: maximal value, then minimal
     // tokens (two rolling rows). take[a][w] records whether taking item a is
     // optimal at that state, ties included, so that the walk from item 0
     // prefers the lowest ids (lexicographically smallest sorted list).
     const size_t cols = size_t(W) + 1;
+    {
+        // one bit per (item, capacity) plus four rows of the capacity: refused beyond a stated size
+        const size_t need = size_t(m) * ((cols + 63) / 64) * 8 + cols * 24;
+        if (need > EN_KNAPSACK_MAX_BYTES)
+            return fail(EN_ERR_CAPACITY, "retrieval knapsack: %d candidates x %lld tokens of budget need a table of "
+                        "%zu bytes (limit %zu)", m, (long long)W, need, EN_KNAPSACK_MAX_BYTES);
+    }
     std::vector<int64_t> vcur(cols, 0), vnext(cols, 0);
     std::vector<int32_t> tcur(cols, 0), tnext(cols, 0);
     const size_t words = (cols + 63) / 64;
@@ -416,9 +476,10 @@ void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold
             w -= items[a].w;
         }
     }
+    return EN_OK;
 }
 
-extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, float threshold,
+static int segment_select_scored_impl(const en_pool *pool, const float *p_host, float threshold,
                                      int64_t budget_tokens, int32_t n_new, int32_t *sel_out_host,
                                      int32_t *n_sel_out, en_plan **out)
 {
@@ -429,7 +490,9 @@ extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, f
     if (out)
         *out = nullptr;
     std::vector<int32_t> chosen;
-    en_knapsack(p_host, pool->len.data(), pool->d.n_groups, threshold, budget_tokens, chosen);
+    const int krc = en_knapsack(p_host, pool->len.data(), pool->d.n_groups, threshold, budget_tokens, chosen);
+    if (krc != EN_OK)
+        return krc;
     *n_sel_out = int32_t(chosen.size());
     std::copy(chosen.begin(), chosen.end(), sel_out_host);
     if (!out)
@@ -437,8 +500,14 @@ extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, f
     const int32_t ptr[2] = {0, int32_t(chosen.size())};
     return build_plan(pool, 1, chosen.data(), ptr, n_new, out);
 }
+extern "C" int segment_select_scored(const en_pool *pool, const float *p_host, float threshold,
+                                     int64_t budget_tokens, int32_t n_new, int32_t *sel_out_host,
+                                     int32_t *n_sel_out, en_plan **out)
+{
+    EN_GUARDED("segment_select_scored", segment_select_scored_impl(pool, p_host, threshold, budget_tokens, n_new, sel_out_host, n_sel_out, out));
+}
 
-extern "C" int en_plan_get_info(const en_plan *plan, en_plan_info *info)
+static int en_plan_get_info_impl(const en_plan *plan, en_plan_info *info)
 {
     if (!plan || !info)
         return fail(EN_ERR_INVALID_ARG, "en_plan_get_info: null argument");
@@ -452,8 +521,12 @@ extern "C" int en_plan_get_info(const en_plan *plan, en_plan_info *info)
     info->total_cached = plan->total_cached;
     return EN_OK;
 }
+extern "C" int en_plan_get_info(const en_plan *plan, en_plan_info *info)
+{
+    EN_GUARDED("en_plan_get_info", en_plan_get_info_impl(plan, info));
+}
 
-extern "C" int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
+static int en_plan_query_impl(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
                              int32_t *n_seg_out)
 {
     if (!plan)
@@ -468,8 +541,13 @@ extern "C" int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offset
                     sizeof(int32_t) * size_t(S + 1));
     return EN_OK;
 }
+extern "C" int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
+                             int32_t *n_seg_out)
+{
+    EN_GUARDED("en_plan_query", en_plan_query_impl(plan, agent, offsets_out_host, n_seg_out));
+}
 
-extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
+static int en_plan_set_splits_impl(en_plan *plan, int32_t n_splits)
 {
     if (!plan || n_splits < 1)
         return fail(EN_ERR_INVALID_ARG, "en_plan_set_splits: null plan or n_splits < 1");
@@ -477,8 +555,12 @@ extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
     plan->n_splits = std::min(std::min(n_splits, tiles), EN_MAX_SPLITS);
     return EN_OK;
 }
+extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
+{
+    EN_GUARDED("en_plan_set_splits", en_plan_set_splits_impl(plan, n_splits));
+}
 
-extern "C" int en_plan_destroy(en_plan *plan)
+static int en_plan_destroy_impl(en_plan *plan)
 {
     if (!plan)
         return EN_OK;
@@ -495,6 +577,10 @@ extern "C" int en_plan_destroy(en_plan *plan)
     }
     delete plan;
     return EN_OK;
+}
+extern "C" int en_plan_destroy(en_plan *plan)
+{
+    EN_GUARDED("en_plan_destroy", en_plan_destroy_impl(plan));
 }
 
 // Device block of a plan (taken from the pool's cache of released blocks when
@@ -612,54 +698,74 @@ extern "C" size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan)
 }
 
 // ---------------------------------------------------------------------------
-// kernel timing with HIP events (measurement aid)
+// kernel timing with HIP events (measurement aid); the events live in the pool
 // ---------------------------------------------------------------------------
-static std::vector<hipEvent_t> g_ev_start, g_ev_stop;
-static int g_ev_used = 0;
-
-extern "C" int en_timing_enable(int32_t max_records)
+static void timing_release(en_pool *pool)
 {
-    if (max_records < 0)
-        return fail(EN_ERR_INVALID_ARG, "en_timing_enable: negative count");
-    for (auto e : g_ev_start)
+    for (auto e : pool->ev_start)
         (void)hipEventDestroy(e);
-    for (auto e : g_ev_stop)
+    for (auto e : pool->ev_stop)
         (void)hipEventDestroy(e);
-    g_ev_start.clear();
-    g_ev_stop.clear();
-    g_ev_used = 0;
+    pool->ev_start.clear();
+    pool->ev_stop.clear();
+    pool->ev_used = 0;
+}
+
+static int en_timing_enable_impl(en_pool *pool, int32_t max_records)
+{
+    if (!pool || max_records < 0)
+        return fail(EN_ERR_INVALID_ARG, "en_timing_enable: null pool or negative count");
+    timing_release(pool);
+    try {
+        pool->ev_start.reserve(size_t(max_records));
+        pool->ev_stop.reserve(size_t(max_records));
+    } catch (const std::bad_alloc &) {
+        return fail(EN_ERR_CAPACITY, "en_timing_enable: out of host memory for %d records", max_records);
+    }
     for (int i = 0; i < max_records; ++i) {
         hipEvent_t a, b;
         hipError_t e;
-        if ((e = hipEventCreate(&a)) != hipSuccess || (e = hipEventCreate(&b)) != hipSuccess)
+        if ((e = hipEventCreate(&a)) != hipSuccess)
             return hip_fail(e, "hipEventCreate");
-        g_ev_start.push_back(a);
-        g_ev_stop.push_back(b);
+        if ((e = hipEventCreate(&b)) != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return hip_fail(e, "hipEventCreate");
+        }
+        pool->ev_start.push_back(a);
+        pool->ev_stop.push_back(b);
     }
     return EN_OK;
 }
-
-extern "C" int en_timing_collect(float *ms_out_host, int32_t cap, int32_t *n_out)
+extern "C" int en_timing_enable(en_pool *pool, int32_t max_records)
 {
-    if (!ms_out_host || !n_out || cap < 0)
+    EN_GUARDED("en_timing_enable", en_timing_enable_impl(pool, max_records));
+}
+
+static int en_timing_collect_impl(en_pool *pool, float *ms_out_host, int32_t cap, int32_t *n_out)
+{
+    if (!pool || !ms_out_host || !n_out || cap < 0)
         return fail(EN_ERR_INVALID_ARG, "en_timing_collect: null argument");
-    const int n = std::min<int>(g_ev_used, cap);
+    const int n = std::min<int>(pool->ev_used, cap);
     for (int i = 0; i < n; ++i) {
         hipError_t e;
-        if ((e = hipEventSynchronize(g_ev_stop[i])) != hipSuccess)
+        if ((e = hipEventSynchronize(pool->ev_stop[i])) != hipSuccess)
             return hip_fail(e, "hipEventSynchronize");
-        if ((e = hipEventElapsedTime(&ms_out_host[i], g_ev_start[i], g_ev_stop[i])) != hipSuccess)
+        if ((e = hipEventElapsedTime(&ms_out_host[i], pool->ev_start[i], pool->ev_stop[i])) != hipSuccess)
             return hip_fail(e, "hipEventElapsedTime");
     }
     *n_out = n;
-    g_ev_used = 0;
+    pool->ev_used = 0;
     return EN_OK;
+}
+extern "C" int en_timing_collect(en_pool *pool, float *ms_out_host, int32_t cap, int32_t *n_out)
+{
+    EN_GUARDED("en_timing_collect", en_timing_collect_impl(pool, ms_out_host, cap, n_out));
 }
 
 // ---------------------------------------------------------------------------
 // GPU entry points
 // ---------------------------------------------------------------------------
-extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+static int gather_rope_impl(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
                            void *kc_dev, void *vt_dev, void *stream)
 {
     if (!pool || !plan || !k_new_dev || !v_new_dev || !kc_dev || !vt_dev)
@@ -710,6 +816,11 @@ extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, 
         return hip_fail((hipError_t)e, "gather_rope launch");
     }
     return EN_OK;
+}
+extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                           void *kc_dev, void *vt_dev, void *stream)
+{
+    EN_GUARDED("gather_rope", gather_rope_impl(pool, plan, k_new_dev, v_new_dev, kc_dev, vt_dev, stream));
 }
 
 // For the rows q_first .. q_first + n_rows - 1 of the plan's new tokens, attended with n_splits KV splits.
@@ -791,12 +902,12 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
     a.app_k = a.decode ? app_k_dev : nullptr;
     a.app_v = a.decode ? app_v_dev : nullptr;
-    const bool timed = g_ev_used < (int)g_ev_start.size();
+    const bool timed = pool->ev_used < (int)pool->ev_start.size();
     if (timed)
-        (void)hipEventRecord(g_ev_start[g_ev_used], (hipStream_t)stream);
+        (void)hipEventRecord(pool->ev_start[pool->ev_used], (hipStream_t)stream);
     int e = en_launch_attention(pool, a, stream);
     if (timed)
-        (void)hipEventRecord(g_ev_stop[g_ev_used++], (hipStream_t)stream);
+        (void)hipEventRecord(pool->ev_stop[pool->ev_used++], (hipStream_t)stream);
     if (e != 0)
         return hip_fail((hipError_t)e, who);
     if (n_partials > 1) {
@@ -811,7 +922,7 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     return EN_OK;
 }
 
-extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
+static int segmented_prefill_attention_impl(en_pool *pool, en_plan *plan, const void *q_dev,
                                            const void *kc_dev, const void *vt_dev, void *out_dev,
                                            void *ws_dev, size_t ws_bytes, void *stream)
 {
@@ -821,6 +932,12 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
         return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention: plan belongs to another pool");
     return run_attention(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream, 0, plan->Nq,
                          plan->n_splits, "segmented_prefill_attention");
+}
+extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
+                                           const void *kc_dev, const void *vt_dev, void *out_dev,
+                                           void *ws_dev, size_t ws_bytes, void *stream)
+{
+    EN_GUARDED("segmented_prefill_attention", segmented_prefill_attention_impl(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream));
 }
 
 // KV splits for a step of n_rows query rows (same rule as for a whole plan).
@@ -846,7 +963,7 @@ extern "C" size_t en_decode_workspace_bytes(const en_pool *pool, const en_plan *
     return en_ws_layout_for(pool, plan, n_rows, step_splits(pool, plan, n_rows)).total;
 }
 
-extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+static int segmented_decode_step_impl(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
                                      const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
                                      void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
                                      void *ws_dev, size_t ws_bytes, void *stream)
@@ -901,8 +1018,15 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
     }
     return EN_OK;
 }
+extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                     const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                                     void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                                     void *ws_dev, size_t ws_bytes, void *stream)
+{
+    EN_GUARDED("segmented_decode_step", segmented_decode_step_impl(pool, plan, q_first, n_rows, q_dev, k_rows_dev, v_rows_dev, kc_dev, vt_dev, out_dev, mass_out_dev, ws_dev, ws_bytes, stream));
+}
 
-extern "C" int segment_cluster_assign_rows(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+static int segment_cluster_assign_rows_impl(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
                                            void *ws_dev, int32_t n_obj, const int32_t *span_ptr_host,
                                            int32_t per_key, int32_t accumulate, float scale, float threshold,
                                            float *score_dev, int32_t *assign_dev, void *stream)
@@ -916,8 +1040,15 @@ extern "C" int segment_cluster_assign_rows(en_pool *pool, en_plan *plan, int32_t
                           per_key, accumulate, scale, threshold, score_dev, assign_dev, stream,
                           "segment_cluster_assign_rows");
 }
+extern "C" int segment_cluster_assign_rows(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                           void *ws_dev, int32_t n_obj, const int32_t *span_ptr_host,
+                                           int32_t per_key, int32_t accumulate, float scale, float threshold,
+                                           float *score_dev, int32_t *assign_dev, void *stream)
+{
+    EN_GUARDED("segment_cluster_assign_rows", segment_cluster_assign_rows_impl(pool, plan, q_first, n_rows, ws_dev, n_obj, span_ptr_host, per_key, accumulate, scale, threshold, score_dev, assign_dev, stream));
+}
 
-extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
+static int segment_attention_mass_impl(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
                                       float *mass_out_dev, void *stream)
 {
     if (!pool || !plan || !ws_dev || !mass_out_dev || (reduce != 0 && reduce != 1))
@@ -935,6 +1066,11 @@ extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev
     if (e != 0)
         return hip_fail((hipError_t)e, "segment_attention_mass launch");
     return EN_OK;
+}
+extern "C" int segment_attention_mass(en_pool *pool, en_plan *plan, void *ws_dev, int32_t reduce,
+                                      float *mass_out_dev, void *stream)
+{
+    EN_GUARDED("segment_attention_mass", segment_attention_mass_impl(pool, plan, ws_dev, reduce, mass_out_dev, stream));
 }
 
 // Shared by the two entry points below: the scratch is the one an attention call over rows
@@ -975,7 +1111,7 @@ static int cluster_assign(en_pool *pool, en_plan *plan, int q_first, int n_rows,
     return EN_OK;
 }
 
-extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
+static int segment_cluster_assign_impl(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
                                       const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
                                       float scale, float threshold, float *score_dev, int32_t *assign_dev,
                                       void *stream)
@@ -984,4 +1120,11 @@ extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev
         return fail(EN_ERR_INVALID_ARG, "segment_cluster_assign: null plan");
     return cluster_assign(pool, plan, 0, plan->Nq, plan->n_splits, ws_dev, n_obj, span_ptr_host, per_key, accumulate,
                           scale, threshold, score_dev, assign_dev, stream, "segment_cluster_assign");
+}
+extern "C" int segment_cluster_assign(en_pool *pool, en_plan *plan, void *ws_dev, int32_t n_obj,
+                                      const int32_t *span_ptr_host, int32_t per_key, int32_t accumulate,
+                                      float scale, float threshold, float *score_dev, int32_t *assign_dev,
+                                      void *stream)
+{
+    EN_GUARDED("segment_cluster_assign", segment_cluster_assign_impl(pool, plan, ws_dev, n_obj, span_ptr_host, per_key, accumulate, scale, threshold, score_dev, assign_dev, stream));
 }

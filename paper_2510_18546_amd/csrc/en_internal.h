@@ -4,8 +4,11 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <new>
 #include <utility>
 #include <vector>
+
+#include <hip/hip_runtime_api.h>
 
 #include "efficientnav.h"
 
@@ -30,6 +33,9 @@ struct en_pool {
     // plans made on this pool and not yet destroyed: a pool that is destroyed
     // first cuts them loose, so that destroying them later stays safe
     mutable std::vector<struct en_plan *> plans;
+    // measurement aid (en_timing_*): event pairs around the attention kernel of the calls on this pool
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    int ev_used = 0;
 };
 
 struct en_plan {
@@ -173,6 +179,21 @@ int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream);
 
 void en_set_error(const char *fmt, ...);
 
+// Every extern "C" entry point that returns a status runs its body through this: no C++
+// exception (std::bad_alloc from a container sized by caller input, above all) crosses the C ABI.
+int en_fail_exception(const char *who, bool out_of_memory);
+#define EN_GUARDED(who, call)                      \
+    try {                                          \
+        return (call);                             \
+    } catch (const std::bad_alloc &) {             \
+        return en_fail_exception(who, true);       \
+    } catch (...) {                                \
+        return en_fail_exception(who, false);      \
+    }
+
 // Retrieval knapsack of Eq. (1) over `G` candidates with lengths `len` (tokens); ids ascending.
-void en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
-                 std::vector<int32_t> &chosen);
+// Returns an en_status: INVALID_ARG for a score or threshold that is not finite, CAPACITY when the
+// table of the dynamic programme would exceed EN_KNAPSACK_MAX_BYTES.
+constexpr size_t EN_KNAPSACK_MAX_BYTES = size_t(1) << 30;
+int en_knapsack(const float *p_host, const int32_t *len, int G, float threshold, int64_t budget_tokens,
+                std::vector<int32_t> &chosen);

@@ -67,7 +67,7 @@ extern "C" int64_t kv_tier_slot_bytes(const en_pool_desc *desc)
     return int64_t(2) * desc->n_kv_heads * desc->capacity * desc->head_dim * int64_t(tier_elem(desc->dtype));
 }
 
-extern "C" int kv_tier_destroy(en_tier *t)
+static int kv_tier_destroy_impl(en_tier *t)
 {
     if (!t)
         return EN_OK;
@@ -94,8 +94,12 @@ extern "C" int kv_tier_destroy(en_tier *t)
     delete t;
     return EN_OK;
 }
+extern "C" int kv_tier_destroy(en_tier *t)
+{
+    EN_GUARDED("kv_tier_destroy", kv_tier_destroy_impl(t));
+}
 
-extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev, void *v_dev,
+static int kv_tier_create_impl(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev, void *v_dev,
                               en_tier **out)
 {
     if (!desc || !out)
@@ -109,16 +113,23 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
         return tfail(EN_ERR_UNSUPPORTED, "kv_tier_create: 8-bit pools are not served by a tier");
     en_tier *t = new (std::nothrow) en_tier;
     if (!t)
-        return tfail(EN_ERR_INVALID_ARG, "kv_tier_create: out of host memory");
+        return tfail(EN_ERR_CAPACITY, "kv_tier_create: out of host memory");
     t->d = *desc;
     t->G = n_groups_total;
     t->dry = (k_dev == nullptr);
     const int n_slots = desc->n_groups;
-    t->len.assign(size_t(n_groups_total), -1);
-    t->slot_of.assign(size_t(n_groups_total), -1);
-    t->group_in.assign(size_t(n_slots), -1);
-    t->last_use.assign(size_t(n_slots), -1);
-    t->ahead.assign(size_t(n_slots), 0);
+    std::vector<int32_t> zeros;
+    try {
+        t->len.assign(size_t(n_groups_total), -1);
+        t->slot_of.assign(size_t(n_groups_total), -1);
+        t->group_in.assign(size_t(n_slots), -1);
+        t->last_use.assign(size_t(n_slots), -1);
+        t->ahead.assign(size_t(n_slots), 0);
+        zeros.assign(size_t(n_slots), 0);
+    } catch (const std::bad_alloc &) {
+        delete t;
+        return tfail(EN_ERR_CAPACITY, "kv_tier_create: out of host memory for the books of the groups");
+    }
     if (t->dry) {
         if (desc->capacity <= 0) {
             delete t;
@@ -127,7 +138,6 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
         *out = t;
         return EN_OK;
     }
-    std::vector<int32_t> zeros(size_t(n_slots), 0);
     int rc = kv_pool_create(desc, k_dev, v_dev, zeros.data(), &t->pool);   // validates the description
     if (rc != EN_OK) {
         delete t;
@@ -163,6 +173,11 @@ extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, 
     *out = t;
     return EN_OK;
 }
+extern "C" int kv_tier_create(const en_pool_desc *desc, int32_t n_groups_total, void *k_dev, void *v_dev,
+                              en_tier **out)
+{
+    EN_GUARDED("kv_tier_create", kv_tier_create_impl(desc, n_groups_total, k_dev, v_dev, out));
+}
 
 extern "C" en_pool *kv_tier_pool(en_tier *t) { return t ? t->pool : nullptr; }
 
@@ -181,7 +196,7 @@ static void drop_resident(en_tier *t, int group)
         t->pool->len[s] = 0;
 }
 
-extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const void *v_host, int32_t len)
+static int kv_tier_put_impl(en_tier *t, int32_t group, const void *k_host, const void *v_host, int32_t len)
 {
     if (!t || len < 0)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_put: null tier or negative length");
@@ -213,8 +228,12 @@ extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const 
     drop_resident(t, group);      // the device copy, if any, is stale
     return EN_OK;
 }
+extern "C" int kv_tier_put(en_tier *t, int32_t group, const void *k_host, const void *v_host, int32_t len)
+{
+    EN_GUARDED("kv_tier_put", kv_tier_put_impl(t, group, k_host, v_host, len));
+}
 
-extern "C" int kv_tier_append(en_tier *t, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+static int kv_tier_append_impl(en_tier *t, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
                               int32_t n_tokens, void *stream)
 {
     if (!t || n_tokens < 0)
@@ -272,8 +291,13 @@ extern "C" int kv_tier_append(en_tier *t, int32_t group, const void *k_rows_dev,
         t->pool->len[slot] = len + n_tokens;
     return EN_OK;
 }
+extern "C" int kv_tier_append(en_tier *t, int32_t group, const void *k_rows_dev, const void *v_rows_dev,
+                              int32_t n_tokens, void *stream)
+{
+    EN_GUARDED("kv_tier_append", kv_tier_append_impl(t, group, k_rows_dev, v_rows_dev, n_tokens, stream));
+}
 
-extern "C" int kv_tier_select_scored(const en_tier *t, const float *p_host, float threshold,
+static int kv_tier_select_scored_impl(const en_tier *t, const float *p_host, float threshold,
                                      int64_t budget_tokens, int32_t *groups_out_host, int32_t *n_out)
 {
     if (!t || !p_host || !groups_out_host || !n_out)
@@ -289,10 +313,17 @@ extern "C" int kv_tier_select_scored(const en_tier *t, const float *p_host, floa
             p[g] = threshold;     // value 0: never taken
         }
     std::vector<int32_t> chosen;
-    en_knapsack(p.data(), len.data(), t->G, threshold, budget_tokens, chosen);
+    const int krc = en_knapsack(p.data(), len.data(), t->G, threshold, budget_tokens, chosen);
+    if (krc != EN_OK)
+        return krc;
     *n_out = int32_t(chosen.size());
     std::copy(chosen.begin(), chosen.end(), groups_out_host);
     return EN_OK;
+}
+extern "C" int kv_tier_select_scored(const en_tier *t, const float *p_host, float threshold,
+                                     int64_t budget_tokens, int32_t *groups_out_host, int32_t *n_out)
+{
+    EN_GUARDED("kv_tier_select_scored", kv_tier_select_scored_impl(t, p_host, threshold, budget_tokens, groups_out_host, n_out));
 }
 
 static int check_groups(const en_tier *t, const int32_t *groups, int n, const char *who)
@@ -393,7 +424,7 @@ static void place(en_tier *t, int group, int slot)
         t->pool->len[slot] = t->len[group];
 }
 
-extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,
+static int kv_tier_fetch_impl(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,
                              void *stream)
 {
     int rc = check_groups(t, groups_host, n, "kv_tier_fetch");
@@ -468,8 +499,13 @@ extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, 
     }
     return EN_OK;
 }
+extern "C" int kv_tier_fetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *slots_out_host,
+                             void *stream)
+{
+    EN_GUARDED("kv_tier_fetch", kv_tier_fetch_impl(t, groups_host, n, slots_out_host, stream));
+}
 
-extern "C" int kv_tier_fence(en_tier *t, void *stream)
+static int kv_tier_fence_impl(en_tier *t, void *stream)
 {
     if (!t)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_fence: null tier");
@@ -482,8 +518,12 @@ extern "C" int kv_tier_fence(en_tier *t, void *stream)
     t->fence_tick = t->tick;
     return EN_OK;
 }
+extern "C" int kv_tier_fence(en_tier *t, void *stream)
+{
+    EN_GUARDED("kv_tier_fence", kv_tier_fence_impl(t, stream));
+}
 
-extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *n_loaded_out)
+static int kv_tier_prefetch_impl(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *n_loaded_out)
 {
     int rc = check_groups(t, groups_host, n, "kv_tier_prefetch");
     if (rc != EN_OK)
@@ -528,19 +568,31 @@ extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t 
         *n_loaded_out = loaded;
     return EN_OK;
 }
+extern "C" int kv_tier_prefetch(en_tier *t, const int32_t *groups_host, int32_t n, int32_t *n_loaded_out)
+{
+    EN_GUARDED("kv_tier_prefetch", kv_tier_prefetch_impl(t, groups_host, n, n_loaded_out));
+}
 
-extern "C" int kv_tier_get_stats(const en_tier *t, en_tier_stats *out)
+static int kv_tier_get_stats_impl(const en_tier *t, en_tier_stats *out)
 {
     if (!t || !out)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_get_stats: null argument");
     *out = t->st;
     return EN_OK;
 }
+extern "C" int kv_tier_get_stats(const en_tier *t, en_tier_stats *out)
+{
+    EN_GUARDED("kv_tier_get_stats", kv_tier_get_stats_impl(t, out));
+}
 
-extern "C" int kv_tier_residency(const en_tier *t, int32_t *slot_of_group_out_host)
+static int kv_tier_residency_impl(const en_tier *t, int32_t *slot_of_group_out_host)
 {
     if (!t || !slot_of_group_out_host)
         return tfail(EN_ERR_INVALID_ARG, "kv_tier_residency: null argument");
     std::copy(t->slot_of.begin(), t->slot_of.end(), slot_of_group_out_host);
     return EN_OK;
+}
+extern "C" int kv_tier_residency(const en_tier *t, int32_t *slot_of_group_out_host)
+{
+    EN_GUARDED("kv_tier_residency", kv_tier_residency_impl(t, slot_of_group_out_host));
 }

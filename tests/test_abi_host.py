@@ -182,6 +182,40 @@ def test_scored_selection_edges():
     assert e.value.code == 1
 
 
+def test_scored_selection_refuses_what_it_cannot_hold_or_compare():
+    """Nothing crosses the C ABI as a C++ exception: a knapsack table beyond the stated limit is
+    refused with a status, and so is a score or threshold that is not a finite number."""
+    # 2000 candidates x a budget of 5e6 tokens: 2000 * 5e6 / 8 bytes = 1.25 GB of take bits > 1 GiB
+    G, cap = 2000, 5000
+    lens = np.full(G, cap, np.int32)
+    pool = host_pool(lens, cap=cap, max_ctx=2 ** 31 - 1)
+    p = np.linspace(0.6, 0.9, G).astype(np.float32)
+    with pytest.raises(B.EnError) as e:
+        B.segment_select_scored(pool, p, 0.5, 5_000_000, 1, want_plan=False)
+    assert e.value.code == 4 and "limit" in str(e.value)
+    # the same candidates under a budget that admits them all need no table
+    got = B.segment_select_scored(pool, p, 0.5, G * cap, 1, want_plan=False)[0]
+    assert got.tolist() == list(range(G))
+    small_pool = host_pool(np.array([4, 1, 3, 3], np.int32))
+    for bad in (np.nan, np.inf, -np.inf):
+        p4 = np.array([0.9, bad, 0.6, 0.55], np.float32)
+        with pytest.raises(B.EnError) as e:
+            B.segment_select_scored(small_pool, p4, 0.5, 5, 1, want_plan=False)
+        assert e.value.code == 1
+        with pytest.raises(B.EnError) as e:
+            B.segment_select_scored(small_pool, np.array([0.9, 0.2, 0.6, 0.55], np.float32), bad, 5, 1,
+                                    want_plan=False)
+        assert e.value.code == 1
+    # a tier's selection goes through the same checks
+    t = B.kv_tier_create(None, None, 4, 4, 1e4, 64, dtype=B.EN_BF16, shape=(2, 2, 8, 64))
+    for g in range(4):
+        B.kv_tier_put(t, g, None, None, 3)
+    with pytest.raises(B.EnError) as e:
+        B.kv_tier_select_scored(t, np.array([0.9, np.nan, 0.6, 0.55], np.float32), 0.5, 6)
+    assert e.value.code == 1
+    t.close()
+
+
 def test_append_checks_without_device():
     """Range and capacity checks of kv_pool_append come before any device work;
     a rejected append leaves the length as it was."""

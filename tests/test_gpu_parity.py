@@ -444,12 +444,16 @@ def test_device_side_errors_and_timing_aid(step_mod):
     with pytest.raises(B.EnError) as e:
         B.gather_rope(other.pool, st.plan, st.k_new, st.v_new, st.kc, st.vt)
     assert e.value.code == 1                                  # plan of another pool
-    B.timing_enable(3)
+    # the timing aid belongs to a pool: calls on another pool leave no record in this one
+    B.timing_enable(st.pool, 3)
+    other.gather()
+    other.attention()
     for _ in range(5):
         st.attention()
     torch.cuda.synchronize()
-    ms = B.timing_collect(8)
-    B.timing_enable(0)
+    ms = B.timing_collect(st.pool, 8)
+    assert len(B.timing_collect(other.pool, 8)) == 0
+    B.timing_enable(st.pool, 0)
     assert len(ms) == 3 and (ms > 0).all() and (ms < 50).all()
 
 
