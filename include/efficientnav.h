@@ -278,6 +278,32 @@ int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_first, int32_t
                           void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
                           void *ws_dev, size_t ws_bytes, void *stream);
 
+/* segmented_decode_step for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The same step, with the scratch taken from a static device array of
+ * EN_STATIC_SCRATCH_BYTES (8 MiB) that is part of the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends).
+ * This call allocates nothing and frees nothing, on the device or through any
+ * library: the pool and the plan must already have been through gather_rope
+ * (which is where the rotary table and the plan's descriptor block are created;
+ * a decode step follows a gather anyway), else INVALID_ARG.
+ * A step whose scratch (en_decode_workspace_bytes) exceeds the static array is
+ * refused with CAPACITY: one agent over 8.7 K tokens needs 1.6 MB, 64 agents over
+ * 16 K tokens 3.2 MB.
+ * All calls on one GPU share that GPU's array, which keeps what the last call
+ * left in it (the kernels write every entry they later read; nothing relies on
+ * zeroes): calls that overlap in time on one GPU race, so keep them on one
+ * stream or order them yourself. The step's masses come back through
+ * mass_out_dev; segment_cluster_assign_rows reads a caller's workspace and does
+ * not follow this call.
+ * Other arguments and errors as segmented_decode_step.
+ */
+#define EN_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+int segmented_decode_step_static(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                 const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                                 void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                                 void *stream);
+
 /* Per-segment attention mass (Section 3.3: the attention between newly
  * detected objects and an existing group) from the scratch left by the
  * attention call on the same plan and stream.

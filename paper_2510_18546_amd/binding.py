@@ -26,7 +26,7 @@ EXPORTS = [
     "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
     "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
     "segment_cluster_assign_rows",
-    "en_decode_workspace_bytes", "segmented_decode_step", "en_timing_enable",
+    "en_decode_workspace_bytes", "segmented_decode_step", "segmented_decode_step_static", "en_timing_enable",
     "en_timing_collect", "en_last_error",
     "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_append",
     "kv_tier_select_scored",
@@ -98,6 +98,7 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_decode_workspace_bytes.restype = C.c_size_t
     lib.segmented_decode_step.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
                                           C.c_size_t, vp]
+    lib.segmented_decode_step_static.argtypes = [vp, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.en_timing_enable.argtypes = [vp, C.c_int32]
     lib.en_timing_collect.argtypes = [vp, C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
@@ -355,6 +356,17 @@ def segmented_decode_step(pool: Pool, plan: Plan, q_first: int, q, k_rows, v_row
         pool.handle, plan.handle, int(q_first), n, q.data_ptr(), k_rows.data_ptr(), v_rows.data_ptr(),
         kc.data_ptr(), vt.data_ptr(), out.data_ptr(), mass_out.data_ptr() if mass_out is not None else None,
         ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream(stream)))
+    return out
+
+
+def segmented_decode_step_static(pool: Pool, plan: Plan, q_first: int, q, k_rows, v_rows, kc, vt, out,
+                                 mass_out=None, stream=None):
+    """segmented_decode_step on the library's static device scratch: the call allocates nothing."""
+    n = int(q.shape[1])
+    _check(load().segmented_decode_step_static(
+        pool.handle, plan.handle, int(q_first), n, q.data_ptr(), k_rows.data_ptr(), v_rows.data_ptr(),
+        kc.data_ptr(), vt.data_ptr(), out.data_ptr(), mass_out.data_ptr() if mass_out is not None else None,
         _stream(stream)))
     return out
 

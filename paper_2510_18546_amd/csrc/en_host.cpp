@@ -244,6 +244,11 @@ static int pool_ensure_device(en_pool *p)
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
         prop.multiProcessorCount > 0)
         p->n_cu = prop.multiProcessorCount;
+    // set-up is also where this device's address of the static scratch is looked up, so that
+    // segmented_decode_step_static finds it ready (it asks again by itself if this failed)
+    void *sp = nullptr;
+    size_t sb = 0;
+    (void)en_static_scratch(&sp, &sb);
     return EN_OK;
 }
 
@@ -1024,6 +1029,45 @@ extern "C" int segmented_decode_step(en_pool *pool, en_plan *plan, int32_t q_fir
                                      void *ws_dev, size_t ws_bytes, void *stream)
 {
     EN_GUARDED("segmented_decode_step", segmented_decode_step_impl(pool, plan, q_first, n_rows, q_dev, k_rows_dev, v_rows_dev, kc_dev, vt_dev, out_dev, mass_out_dev, ws_dev, ws_bytes, stream));
+}
+
+// The decode step for callers that cannot allocate: the scratch is the library's static device
+// array, and neither the rotary table nor the plan's descriptor block is created here.
+static int segmented_decode_step_static_impl(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                             const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                                             void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                                             void *stream)
+{
+    if (!pool || !plan)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step_static: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step_static: plan belongs to another pool");
+    if (n_rows <= 0)
+        return fail(EN_ERR_OUT_OF_RANGE, "segmented_decode_step_static: n_rows = %d", n_rows);
+    const size_t need = en_ws_layout_for(pool, plan, n_rows, step_splits(pool, plan, n_rows)).total;
+    if (need > EN_STATIC_SCRATCH_BYTES)
+        return fail(EN_ERR_CAPACITY, "segmented_decode_step_static: the step needs %zu bytes of scratch, the static "
+                    "scratch holds %zu; use segmented_decode_step with a workspace of the caller's", need,
+                    size_t(EN_STATIC_SCRATCH_BYTES));
+    if (!pool->d_cos || !plan->uploaded)
+        return fail(EN_ERR_INVALID_ARG, "segmented_decode_step_static: the plan has not been through gather_rope "
+                    "(which creates the pool's rotary table and the plan's descriptor block); this call creates nothing");
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    const int e = en_static_scratch(&ws, &ws_bytes);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "segmented_decode_step_static: address of the static scratch");
+    return segmented_decode_step_impl(pool, plan, q_first, n_rows, q_dev, k_rows_dev, v_rows_dev, kc_dev, vt_dev,
+                                      out_dev, mass_out_dev, ws, ws_bytes, stream);
+}
+extern "C" int segmented_decode_step_static(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,
+                                            const void *q_dev, const void *k_rows_dev, const void *v_rows_dev,
+                                            void *kc_dev, void *vt_dev, void *out_dev, float *mass_out_dev,
+                                            void *stream)
+{
+    EN_GUARDED("segmented_decode_step_static",
+               segmented_decode_step_static_impl(pool, plan, q_first, n_rows, q_dev, k_rows_dev, v_rows_dev, kc_dev,
+                                                 vt_dev, out_dev, mass_out_dev, stream));
 }
 
 static int segment_cluster_assign_rows_impl(en_pool *pool, en_plan *plan, int32_t q_first, int32_t n_rows,

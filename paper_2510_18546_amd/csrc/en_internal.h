@@ -177,6 +177,11 @@ int en_launch_ctx_append(const en_pool *pool, const EnCtxAppendArgs &a, void *st
 int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *stream);
 int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream);
 
+// The static device scratch of segmented_decode_step_static (en_static_scratch.hip,
+// EN_STATIC_SCRATCH_BYTES of the public header): the device address of the current device's copy
+// (returns 0 or a hipError_t).
+int en_static_scratch(void **ptr_out, size_t *bytes_out);
+
 void en_set_error(const char *fmt, ...);
 
 // Every extern "C" entry point that returns a status runs its body through this: no C++
