@@ -9,7 +9,7 @@
  *                               prefilled on its own (Section 3.2)
  *   segment_select[_scored]     which groups enter the prompt, in which order,
  *                               and where each lands (Section 3.4, Eq. (1))
- *   gather_rope                 load the selected blocks once per planning
+ *   gather_rope[_queries]       load the selected blocks once per planning
  *                               step and re-position them (Section 3.2)
  *   segmented_prefill_attention new prompt tokens attend over
  *                               [selected segments || themselves]
@@ -225,6 +225,18 @@ size_t en_context_bytes(const en_pool *pool, const en_plan *plan);
 int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
                 void *kc_dev, void *vt_dev, void *stream);
 
+/* gather_rope, and in the same launch the step's queries prepared for the
+ * attention kernel: rotated at L_c + i, scaled by log2(e)/sqrt(D) (the softmax
+ * runs in the log2 domain) and rounded to bf16 once, which
+ * segmented_prefill_attention otherwise does in every workgroup, once per KV
+ * split. For segmented_prefill_attention_prepared on the same plan.
+ *   q_dev      : device, [B, N_q, Hq, D] bf16, unrotated
+ *   q_prep_dev : device, [B, N_q, Hq, D] bf16, receives the prepared queries
+ * EN_BF16 and EN_I8 pools. Errors: as gather_rope, UNSUPPORTED (EN_F32 pool).
+ */
+int gather_rope_queries(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                        const void *q_dev, void *kc_dev, void *vt_dev, void *q_prep_dev, void *stream);
+
 /* Bytes of scratch the attention call needs for this plan: per-split running
  * (max, sum), per-(row, segment) partial sums, and, when n_splits > 1, partial
  * outputs (a step of few rows and few agents keeps two partial results per
@@ -245,6 +257,31 @@ size_t en_workspace_bytes(const en_pool *pool, const en_plan *plan);
 int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
                                 const void *kc_dev, const void *vt_dev, void *out_dev,
                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/* segmented_prefill_attention over queries that gather_rope_queries prepared
+ * (the arithmetic is the same, the results are bit for bit those of
+ * segmented_prefill_attention on the unprepared queries), optionally with the
+ * reduced masses in the same launches:
+ *   q_prep_dev       : device, [B, N_q, Hq, D] bf16, from gather_rope_queries
+ *   mass_red_out_dev : device float [B, Smax+1] or NULL: receives what
+ *                      segment_attention_mass(reduce = 1) would write, without a
+ *                      launch of its own. The heads' sums are added up as
+ *                      fixed-point integers (in the scratch), so the result
+ *                      does not depend on the order in which they arrive and is
+ *                      the same from run to run; it may differ from what
+ *                      segment_attention_mass(reduce = 1) gives (a float sum in
+ *                      a fixed order) in the last bits. That call may still
+ *                      follow, with either reduce mode. At most 1023 query
+ *                      heads.
+ * Plans whose steps have enough query rows for the matrix-core prefill kernel
+ * (more than 32 rows per KV head); EN_BF16 and EN_I8 pools.
+ * Errors: as segmented_prefill_attention, UNSUPPORTED (EN_F32 pool, or so few
+ * rows that the decode kernel takes the step).
+ */
+int segmented_prefill_attention_prepared(en_pool *pool, en_plan *plan, const void *q_prep_dev,
+                                         const void *kc_dev, const void *vt_dev, void *out_dev,
+                                         float *mass_red_out_dev, void *ws_dev, size_t ws_bytes,
+                                         void *stream);
 
 /* Decode-phase reuse of a gathered context (Section 3.2: the selected KV is
  * loaded once per planning step, then about 40 tokens are decoded over it).
@@ -471,6 +508,28 @@ int kv_tier_destroy(en_tier *tier);
  */
 int en_timing_enable(en_pool *pool, int32_t max_records);
 int en_timing_collect(en_pool *pool, float *ms_out_host, int32_t cap, int32_t *n_out);
+
+/* ------------------------------------------------------------------------
+ * Measured ceilings of the machine, for quoting beside the nominal peaks. They
+ * compute nothing of the method; the caller times them (events on `stream`).
+ *
+ * en_ceiling_mfma_bf16: n_workgroups workgroups of 8 waves (two per SIMD), each
+ *   wave `iters` rounds of 8 matrix instructions 32x32x16 bf16 and nothing else
+ *   (operands in registers, 4 accumulators, 4 A and 2 B fragments in turn).
+ *   constant_operands = 0: operand bits like normal-distributed data (random sign
+ *   and mantissa); 1: every operand 0.5 (the clock of the chip depends on how many
+ *   bits toggle). *flops_out receives the operations one launch performs.
+ *   sink_dev: device scratch of n_workgroups * 2048 bytes (never written in
+ *   practice).
+ * en_ceiling_read_stream: n_workgroups workgroups read `bytes` (a multiple of 16,
+ *   16-byte aligned) of device memory once, 16 bytes per lane and load, and keep
+ *   nothing. sink_dev: 1024 bytes of device scratch.
+ * Errors: INVALID_ARG, CAPACITY (sink too small), DEVICE.
+ */
+int en_ceiling_mfma_bf16(void *sink_dev, size_t sink_bytes, int32_t n_workgroups, int32_t iters,
+                         int32_t constant_operands, double *flops_out, void *stream);
+int en_ceiling_read_stream(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes,
+                           int32_t n_workgroups, void *stream);
 
 const char *en_last_error(void);
 

@@ -23,11 +23,12 @@ STATUS = {0: "EN_OK", 1: "EN_ERR_INVALID_ARG", 2: "EN_ERR_OUT_OF_RANGE", 3: "EN_
 EXPORTS = [
     "kv_pool_create", "kv_pool_set_scales", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
-    "en_plan_destroy", "en_context_bytes", "gather_rope", "en_workspace_bytes",
-    "segmented_prefill_attention", "segment_attention_mass", "segment_cluster_assign",
+    "en_plan_destroy", "en_context_bytes", "gather_rope", "gather_rope_queries", "en_workspace_bytes",
+    "segmented_prefill_attention", "segmented_prefill_attention_prepared", "segment_attention_mass",
+    "segment_cluster_assign",
     "segment_cluster_assign_rows",
     "en_decode_workspace_bytes", "segmented_decode_step", "segmented_decode_step_static", "en_timing_enable",
-    "en_timing_collect", "en_last_error",
+    "en_timing_collect", "en_last_error", "en_ceiling_mfma_bf16", "en_ceiling_read_stream",
     "kv_tier_slot_bytes", "kv_tier_create", "kv_tier_pool", "kv_tier_put", "kv_tier_append",
     "kv_tier_select_scored",
     "kv_tier_fetch", "kv_tier_fence", "kv_tier_prefetch", "kv_tier_get_stats", "kv_tier_residency",
@@ -89,6 +90,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_workspace_bytes.restype = C.c_size_t
     lib.gather_rope.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.segmented_prefill_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.gather_rope_queries.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.segmented_prefill_attention_prepared.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.segment_attention_mass.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
     lib.segment_cluster_assign.argtypes = [vp, vp, vp, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_float,
                                            C.c_float, vp, vp, vp]
@@ -102,6 +105,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_timing_enable.argtypes = [vp, C.c_int32]
     lib.en_timing_collect.argtypes = [vp, C.POINTER(C.c_float), C.c_int32, i32p]
     lib.en_last_error.restype = C.c_char_p
+    lib.en_ceiling_mfma_bf16.argtypes = [vp, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
+    lib.en_ceiling_read_stream.argtypes = [vp, C.c_size_t, vp, C.c_size_t, C.c_int32, vp]
     lib.kv_tier_slot_bytes.argtypes = [C.POINTER(PoolDesc)]
     lib.kv_tier_slot_bytes.restype = C.c_int64
     lib.kv_tier_create.argtypes = [C.POINTER(PoolDesc), C.c_int32, vp, vp, C.POINTER(vp)]
@@ -312,6 +317,22 @@ def segmented_prefill_attention(pool: Pool, plan: Plan, q, kc, vt, out, ws=None,
     return out
 
 
+def gather_rope_queries(pool: Pool, plan: Plan, k_new, v_new, q, kc, vt, q_prep, stream=None):
+    _check(load().gather_rope_queries(pool.handle, plan.handle, k_new.data_ptr(), v_new.data_ptr(), q.data_ptr(),
+                                      kc.data_ptr(), vt.data_ptr(), q_prep.data_ptr(), _stream(stream)))
+    return kc, vt, q_prep
+
+
+def segmented_prefill_attention_prepared(pool: Pool, plan: Plan, q_prep, kc, vt, out, ws=None, mass_red_out=None,
+                                         stream=None):
+    _check(load().segmented_prefill_attention_prepared(
+        pool.handle, plan.handle, q_prep.data_ptr(), kc.data_ptr(), vt.data_ptr(), out.data_ptr(),
+        mass_red_out.data_ptr() if mass_red_out is not None else None,
+        ws.data_ptr() if ws is not None else None, ws.numel() * ws.element_size() if ws is not None else 0,
+        _stream(stream)))
+    return out
+
+
 def segment_attention_mass(pool: Pool, plan: Plan, ws, reduce: int, mass_out, stream=None):
     _check(load().segment_attention_mass(pool.handle, plan.handle, ws.data_ptr(), int(reduce),
                                          mass_out.data_ptr(), _stream(stream)))
@@ -499,3 +520,19 @@ def timing_collect(pool: Pool, cap: int) -> np.ndarray:
     n = C.c_int32()
     _check(load().en_timing_collect(pool.handle, ms.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)))
     return ms[:n.value].copy()
+
+
+def ceiling_mfma_bf16(sink, n_workgroups: int, iters: int, constant_operands: bool, stream=None) -> float:
+    """Enqueue the matrix-instruction-only loop; returns the operations of the launch."""
+    flops = C.c_double()
+    _check(load().en_ceiling_mfma_bf16(sink.data_ptr(), sink.numel() * sink.element_size(), int(n_workgroups),
+                                       int(iters), int(bool(constant_operands)), C.byref(flops), _stream(stream)))
+    return flops.value
+
+
+def ceiling_read_stream(src, sink, n_workgroups: int, stream=None) -> int:
+    """Enqueue the read-only stream over `src`; returns the bytes one launch reads."""
+    nbytes = src.numel() * src.element_size()
+    _check(load().en_ceiling_read_stream(src.data_ptr(), nbytes, sink.data_ptr(), sink.numel() * sink.element_size(),
+                                         int(n_workgroups), _stream(stream)))
+    return nbytes

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libefficientnav.so")
 _CSRC = os.path.join(_HERE, "csrc")
 SOURCES = [os.path.join(_CSRC, f) for f in
            ("en_host.cpp", "en_tier.cpp", "en_gather.hip", "en_attn_prefill.hip", "en_attn_decode.hip",
-            "en_merge_mass.hip", "en_static_scratch.hip")]
+            "en_merge_mass.hip", "en_static_scratch.hip", "en_ceilings.hip")]
 HEADERS = [os.path.join(_CSRC, "en_internal.h"), os.path.join(_CSRC, "en_device.h"),
            os.path.join(_ROOT, "include", "efficientnav.h")]
 OBJ_DIR = os.path.join(_HERE, "_build")

@@ -45,7 +45,9 @@
 
 constexpr int ATT_WAVES = EN_WAVES;
 
-template <int D>
+// QPREP: the queries arrive prepared (rotated at L_c + i, scaled, bf16: the gather launch did it
+// once), else the wave prepares its own 32 from the caller's unrotated ones.
+template <int D, bool QPREP>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 {
     constexpr int KT = EN_KEY_TILE;              // keys per LDS tile
@@ -73,6 +75,9 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (logical >= a.total_wgs)
         return;
+    if (logical == 0 && a.red_zero)               // start of the reduced masses that later launches add up
+        for (int i = threadIdx.x; i < a.n_red_zero; i += 64 * ATT_WAVES)
+            a.red_zero[i] = 0ull;
     int t = logical;
     const int ptile = t % a.n_ptiles;
     t /= a.n_ptiles;
@@ -204,8 +209,17 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         for (int kk = 0; kk < 2; ++kk)
             vaddr[h][kk] = (uint32_t)(VBASE + col * VROWB + ((4 * h + 2 * kk + half + col / 2) & 7) * 16);
 
-    // ---- Q: load, rotate at L_c + i, scale, round to bf16 ----
+    // ---- Q: prepared queries are loaded as they are; else load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
+    if constexpr (QPREP) {
+        const bf16_t *qp = (const bf16_t *)a.q + (((size_t)b * a.Nq + i_row) * a.Hq + hq) * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            qf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (row_valid)
+                qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+        }
+    } else
     {
         // The rotary rows (cosines and sines of position L_c + i, D/2 floats each) are the same for
         // the waves that share a query block, and they are twice the bytes of the queries
@@ -294,8 +308,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float x1 = qx[ks][j], x2 = qx[ks + NKS / 2][j];
-                qx[ks][j] = (x1 * cs[ks][j] - x2 * sn[ks][j]) * a.scale_log2e;
-                qx[ks + NKS / 2][j] = (x2 * cs[ks][j] + x1 * sn[ks][j]) * a.scale_log2e;
+                rope_scale_pair(x1, x2, cs[ks][j], sn[ks][j], a.scale_log2e, qx[ks][j], qx[ks + NKS / 2][j]);
             }
         }
 #pragma unroll
@@ -723,9 +736,16 @@ int en_launch_attention_prefill(const en_pool *pool, const EnAttnArgs &a, void *
 {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
-    if (pool->d.head_dim == 64)
-        hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, blk, 0, st, a);
-    else
-        hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, blk, 0, st, a);
+    if (pool->d.head_dim == 64) {
+        if (a.q_prepared)
+            hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, blk, 0, st, a);
+    } else {
+        if (a.q_prepared)
+            hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, blk, 0, st, a);
+    }
     return (int)hipGetLastError();
 }

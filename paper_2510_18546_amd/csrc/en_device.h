@@ -29,6 +29,17 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// A query's rotary pair (k, k + D/2) turned by its position's angle and scaled for the softmax in
+// the log2 domain. One definition for every kernel that prepares queries, with the products and
+// sums kept as written (no fused multiply-add): the attention kernel and the gather launch then
+// produce the same bits.
+__device__ __forceinline__ void rope_scale_pair(float x1, float x2, float c, float s, float scale, float &y1, float &y2)
+{
+#pragma clang fp contract(off)
+    y1 = (x1 * c - x2 * s) * scale;
+    y2 = (x2 * c + x1 * s) * scale;
+}
+
 // Exchange a value with the lane 32 positions away.
 __device__ __forceinline__ float xor32(float v)
 {

@@ -225,6 +225,44 @@ __host__ __device__ constexpr int en_gather_key_units(int hpb)
     return hpb == 1 ? 2 : 1;
 }
 
+// Queries prepared for the attention kernel (rows i of agent b, every head): rotated at L_c + i,
+// scaled for the log2-domain softmax, rounded to bf16 once, exactly what a workgroup of the
+// attention kernel would otherwise do for its own rows, once per KV split. The rows of an agent are
+// dealt out over the gridDim.x workgroups of this unit; D/8 threads share a row, each takes four
+// rotary pairs (k .. k+3, k + D/2 ..).
+template <int D>
+__device__ __forceinline__ void prepare_queries(const EnGatherArgs &a, int part, int n_parts, int b)
+{
+    constexpr int TPR = D / 8;                     // threads per row
+    const int S = a.nseg[b];
+    const int Lc = a.bnd[(size_t)b * (a.Smax + 2) + S];
+    const int rows = a.Nq * a.Hq;
+    const int per = (rows + n_parts - 1) / n_parts;
+    const int r1 = min(rows, (part + 1) * per);
+    const int t = threadIdx.x % TPR;
+    for (int row = part * per + threadIdx.x / TPR; row < r1; row += 256 / TPR) {
+        const int i = row / a.Hq;
+        const size_t base = ((size_t)b * rows + row) * D;
+        const bf16_t *src = (const bf16_t *)a.q + base;
+        const bf16x4 x1 = *reinterpret_cast<const bf16x4 *>(src + 4 * t);
+        const bf16x4 x2 = *reinterpret_cast<const bf16x4 *>(src + D / 2 + 4 * t);
+        const size_t trow = (size_t)(Lc + i) * (D / 2) + 4 * t;
+        const f32x4 c = *reinterpret_cast<const f32x4 *>(a.cos_tab + trow);
+        const f32x4 sn = *reinterpret_cast<const f32x4 *>(a.sin_tab + trow);
+        bf16x4 y1, y2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float r1f, r2f;
+            rope_scale_pair((float)x1[e], (float)x2[e], c[e], sn[e], a.scale_log2e, r1f, r2f);
+            y1[e] = (bf16_t)r1f;
+            y2[e] = (bf16_t)r2f;
+        }
+        bf16_t *dst = (bf16_t *)a.q_prep + base;
+        *reinterpret_cast<bf16x4 *>(dst + 4 * t) = y1;
+        *reinterpret_cast<bf16x4 *>(dst + D / 2 + 4 * t) = y2;
+    }
+}
+
 template <typename T, int D, int HPB>
 __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
 {
@@ -243,7 +281,19 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
     const int tile = blockIdx.x;
     constexpr int KU = en_gather_key_units(HPB);
     constexpr int PER = KU + (sizeof(T) == 2 ? HPB : 0);      // units per head group
-    const int hg = blockIdx.y / PER, r = blockIdx.y % PER;
+    int unit = blockIdx.y;
+    if constexpr (sizeof(T) == 2) {
+        // one more unit along y, in front of the key and value units (dispatched first, so that its
+        // short chains of loads run beside the streams and not behind them): the queries to prepare
+        if (a.q) {
+            if (unit == 0) {
+                prepare_queries<D>(a, tile, gridDim.x, blockIdx.z);
+                return;
+            }
+            --unit;
+        }
+    }
+    const int hg = unit / PER, r = unit % PER;
     if (r < KU)
         gather_k_block<T, D, sizeof(T) == 4, HPB>(a, tile, KU == 2 ? r : 0, KU == 2 ? r : 1, hg * HPB, lbnd);
     else if constexpr (sizeof(T) == 2)
@@ -416,8 +466,16 @@ __global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
     }
     __shared__ int32_t ltab[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
     // the grid of gather_kernel with one head per key unit
-    const int tile = blockIdx.x, kvh = blockIdx.y / 2;
-    if (blockIdx.y % 2 == 0)
+    int unit = blockIdx.y;
+    if (a.q) {
+        if (unit == 0) {
+            prepare_queries<D>(a, blockIdx.x, gridDim.x, blockIdx.z);      // the unit in front: queries to prepare
+            return;
+        }
+        --unit;
+    }
+    const int tile = blockIdx.x, kvh = unit / 2;
+    if (unit % 2 == 0)
         gather_q8_k_block<D>(a, tile, kvh, ltab);
     else
         gather_q8_vt_block<D>(a, tile, kvh, ltab);
@@ -579,7 +637,7 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
     const int n_tiles = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE;
     const int D = pool->d.head_dim;
     if (pool->d.dtype == EN_I8) {
-        const dim3 grid(n_tiles, 2 * a.Hkv, a.B), blk(256);
+        const dim3 grid(n_tiles, 2 * a.Hkv + (a.q ? 1 : 0), a.B), blk(256);
         if (D == 64)
             hipLaunchKernelGGL((gather_q8_kernel<64>), grid, blk, 0, st, g);
         else
@@ -588,7 +646,8 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
     }
     const bool bf16 = pool->d.dtype != EN_F32;
     const int hpb = gather_heads_per_unit(pool, a, n_tiles, bf16);
-    const dim3 grid(n_tiles, (a.Hkv / hpb) * (en_gather_key_units(hpb) + (bf16 ? hpb : 0)), a.B);
+    // (one more unit along y when the launch also prepares the queries: bf16 contexts only)
+    const dim3 grid(n_tiles, (a.Hkv / hpb) * (en_gather_key_units(hpb) + (bf16 ? hpb : 0)) + (bf16 && a.q ? 1 : 0), a.B);
     if (!bf16) {
         if (D == 64)
             launch_gather_kernel<float, 64>(hpb, grid, st, g);

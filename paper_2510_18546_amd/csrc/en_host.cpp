@@ -58,6 +58,12 @@ static inline size_t pool_elem_size(int dtype) { return dtype == EN_F32 ? 4 : dt
 // the bf16 kernels serve EN_BF16 and EN_I8 pools
 static inline bool computes_bf16(int dtype) { return dtype != EN_F32; }
 
+// log2(e) / sqrt(D): scores are taken in the log2 domain
+static inline float softmax_scale_log2e(const en_pool *pool)
+{
+    return float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
+}
+
 // ---------------------------------------------------------------------------
 // pool
 // ---------------------------------------------------------------------------
@@ -682,7 +688,8 @@ EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *pl, int n_rows, 
     L.ml_off = 0;
     L.seg_off = align256(L.ml_off + size_t(n_splits) * rows * 2 * sizeof(float));
     L.red_off = align256(L.seg_off + size_t(n_splits) * rows * (pl->Smax + 1) * 2 * sizeof(float));
-    L.mlfin_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
+    L.redacc_off = align256(L.red_off + size_t(pl->B) * (pl->Smax + 1) * pool->d.n_q_heads * sizeof(float));
+    L.mlfin_off = align256(L.redacc_off + size_t(pl->B) * (pl->Smax + 1) * sizeof(unsigned long long));
     L.opart_off = align256(L.mlfin_off + (n_splits > 1 ? rows * 2 * sizeof(float) : 0));
     L.total = L.opart_off;
     if (n_splits > 1)
@@ -768,10 +775,54 @@ extern "C" int en_timing_collect(en_pool *pool, float *ms_out_host, int32_t cap,
 }
 
 // ---------------------------------------------------------------------------
+// measured ceilings (measurement aid): a loop of matrix instructions only, a read-only stream
+// ---------------------------------------------------------------------------
+static int en_ceiling_mfma_bf16_impl(void *sink_dev, size_t sink_bytes, int32_t n_workgroups, int32_t iters,
+                                     int32_t constant_operands, double *flops_out, void *stream)
+{
+    if (!sink_dev || !flops_out || n_workgroups <= 0 || iters <= 0 || (constant_operands != 0 && constant_operands != 1))
+        return fail(EN_ERR_INVALID_ARG, "en_ceiling_mfma_bf16: null argument, non-positive size or bad flag");
+    if (sink_bytes < size_t(n_workgroups) * 512 * sizeof(float))
+        return fail(EN_ERR_CAPACITY, "en_ceiling_mfma_bf16: sink of %zu bytes, %zu needed", sink_bytes,
+                    size_t(n_workgroups) * 512 * sizeof(float));
+    const int e = en_launch_ceiling_mfma(static_cast<float *>(sink_dev), n_workgroups, iters, constant_operands, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "en_ceiling_mfma_bf16 launch");
+    // 8 waves per workgroup, 8 instructions per round, 2 * 32 * 32 * 16 operations each
+    *flops_out = double(n_workgroups) * 8.0 * double(iters) * 8.0 * 32768.0;
+    return EN_OK;
+}
+extern "C" int en_ceiling_mfma_bf16(void *sink_dev, size_t sink_bytes, int32_t n_workgroups, int32_t iters,
+                                    int32_t constant_operands, double *flops_out, void *stream)
+{
+    EN_GUARDED("en_ceiling_mfma_bf16",
+               en_ceiling_mfma_bf16_impl(sink_dev, sink_bytes, n_workgroups, iters, constant_operands, flops_out, stream));
+}
+
+static int en_ceiling_read_stream_impl(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes,
+                                       int32_t n_workgroups, void *stream)
+{
+    if (!src_dev || !sink_dev || n_workgroups <= 0 || bytes < 16 || (bytes & 15) ||
+        (reinterpret_cast<uintptr_t>(src_dev) & 15))
+        return fail(EN_ERR_INVALID_ARG, "en_ceiling_read_stream: null argument, or size / address not a multiple of 16");
+    if (sink_bytes < 256 * sizeof(uint32_t))
+        return fail(EN_ERR_CAPACITY, "en_ceiling_read_stream: the sink needs 1024 bytes");
+    const int e = en_launch_ceiling_read(src_dev, bytes, sink_dev, n_workgroups, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "en_ceiling_read_stream launch");
+    return EN_OK;
+}
+extern "C" int en_ceiling_read_stream(const void *src_dev, size_t bytes, void *sink_dev, size_t sink_bytes,
+                                      int32_t n_workgroups, void *stream)
+{
+    EN_GUARDED("en_ceiling_read_stream", en_ceiling_read_stream_impl(src_dev, bytes, sink_dev, sink_bytes, n_workgroups, stream));
+}
+
+// ---------------------------------------------------------------------------
 // GPU entry points
 // ---------------------------------------------------------------------------
-static int gather_rope_impl(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
-                           void *kc_dev, void *vt_dev, void *stream)
+static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                         const void *q_dev, void *kc_dev, void *vt_dev, void *q_prep_dev, void *stream)
 {
     if (!pool || !plan || !k_new_dev || !v_new_dev || !kc_dev || !vt_dev)
         return fail(EN_ERR_INVALID_ARG, "gather_rope: null argument");
@@ -805,6 +856,10 @@ static int gather_rope_impl(en_pool *pool, en_plan *plan, const void *k_new_dev,
     a.Nq = plan->Nq;
     a.Smax = plan->Smax;
     a.T = plan->ctx_stride;
+    a.q = q_dev;
+    a.q_prep = q_prep_dev;
+    a.Hq = pool->d.n_q_heads;
+    a.scale_log2e = softmax_scale_log2e(pool);
     g.n_inline = 0;
     g.off_nseg = 0;
     g.off_sel = g.off_nseg + int(plan->nseg.size());
@@ -825,7 +880,24 @@ static int gather_rope_impl(en_pool *pool, en_plan *plan, const void *k_new_dev,
 extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
                            void *kc_dev, void *vt_dev, void *stream)
 {
-    EN_GUARDED("gather_rope", gather_rope_impl(pool, plan, k_new_dev, v_new_dev, kc_dev, vt_dev, stream));
+    EN_GUARDED("gather_rope", gather_common(pool, plan, k_new_dev, v_new_dev, nullptr, kc_dev, vt_dev, nullptr, stream));
+}
+
+static int gather_rope_queries_impl(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                                    const void *q_dev, void *kc_dev, void *vt_dev, void *q_prep_dev, void *stream)
+{
+    if (!q_dev || !q_prep_dev)
+        return fail(EN_ERR_INVALID_ARG, "gather_rope_queries: null argument");
+    if (pool && !computes_bf16(pool->d.dtype))
+        return fail(EN_ERR_UNSUPPORTED, "gather_rope_queries: prepared queries are bf16; a float32 pool keeps its "
+                    "queries as they are (gather_rope, segmented_prefill_attention)");
+    return gather_common(pool, plan, k_new_dev, v_new_dev, q_dev, kc_dev, vt_dev, q_prep_dev, stream);
+}
+extern "C" int gather_rope_queries(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
+                                   const void *q_dev, void *kc_dev, void *vt_dev, void *q_prep_dev, void *stream)
+{
+    EN_GUARDED("gather_rope_queries",
+               gather_rope_queries_impl(pool, plan, k_new_dev, v_new_dev, q_dev, kc_dev, vt_dev, q_prep_dev, stream));
 }
 
 // For the rows q_first .. q_first + n_rows - 1 of the plan's new tokens, attended with n_splits KV splits.
@@ -837,6 +909,15 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
     a.ws_seg = reinterpret_cast<const float *>(ws + L.seg_off);
     a.ws_mlfin = reinterpret_cast<const float *>(ws + L.mlfin_off);
     a.ws_red = reinterpret_cast<float *>(ws + L.red_off);
+    a.red_out = nullptr;
+    a.red_acc = reinterpret_cast<unsigned long long *>(ws + L.redacc_off);
+    {
+        // fixed point of the reduced masses: a sum is at most Hq * n_rows, and sum << (shift + 10) must fit 63 bits
+        int bits = 0;
+        while ((uint64_t(1) << bits) < uint64_t(pool->d.n_q_heads) * uint64_t(n_rows))
+            ++bits;
+        a.red_shift = std::max(0, std::min(30, 52 - bits));
+    }
     a.nseg = d_nseg(plan);
     a.bnd = d_bnd(plan);
     a.hdr = d_hdr(plan);
@@ -856,7 +937,8 @@ static EnMassArgs mass_args(const en_pool *pool, const en_plan *plan, char *ws, 
 static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const void *kc_dev,
                          const void *vt_dev, void *out_dev, void *ws_dev, size_t ws_bytes, void *stream,
                          int q_first, int n_rows, int n_splits, const char *who,
-                         const void *app_k_dev = nullptr, const void *app_v_dev = nullptr)
+                         const void *app_k_dev = nullptr, const void *app_v_dev = nullptr,
+                         bool q_prepared = false, float *mass_red_out_dev = nullptr)
 {
     const EnWsLayout L = en_ws_layout_for(pool, plan, n_rows, n_splits);
     // the merge kernel splits a row number into (agent, head, token) in 32-bit arithmetic
@@ -904,9 +986,12 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     if (a.decode)
         a.n_ptiles = 1;
     a.total_wgs = plan->B * pool->d.n_kv_heads * n_splits * a.n_ptiles;
-    a.scale_log2e = float(1.4426950408889634 / std::sqrt(double(pool->d.head_dim)));
+    a.scale_log2e = softmax_scale_log2e(pool);
     a.app_k = a.decode ? app_k_dev : nullptr;
     a.app_v = a.decode ? app_v_dev : nullptr;
+    a.q_prepared = q_prepared ? 1 : 0;
+    a.red_zero = (mass_red_out_dev && ws) ? reinterpret_cast<unsigned long long *>(ws + L.redacc_off) : nullptr;
+    a.n_red_zero = a.red_zero ? plan->B * (plan->Smax + 1) : 0;
     const bool timed = pool->ev_used < (int)pool->ev_start.size();
     if (timed)
         (void)hipEventRecord(pool->ev_start[pool->ev_used], (hipStream_t)stream);
@@ -917,12 +1002,22 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
         return hip_fail((hipError_t)e, who);
     if (n_partials > 1) {
         // the same launch also leaves the per-head partial sums of the segment masses
-        const EnMassArgs m = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first);
+        EnMassArgs m = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first);
+        m.red_out = mass_red_out_dev;
         EnAttnArgs c = a;
         c.n_splits = n_partials;              // the merge only counts partial results
         e = en_launch_combine(pool, c, m, stream);
         if (e != 0)
             return hip_fail((hipError_t)e, "split combine launch");
+    }
+    if (mass_red_out_dev) {
+        // stage 1 of the reduced masses as a launch of its own where no merge launch carried it (one
+        // partial result per row, or few rows per head): en_launch_mass launches nothing otherwise
+        EnMassArgs m = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first);
+        m.red_out = mass_red_out_dev;
+        e = en_launch_mass(pool, m, 2, stream);
+        if (e != 0)
+            return hip_fail((hipError_t)e, "reduced masses launch");
     }
     return EN_OK;
 }
@@ -943,6 +1038,40 @@ extern "C" int segmented_prefill_attention(en_pool *pool, en_plan *plan, const v
                                            void *ws_dev, size_t ws_bytes, void *stream)
 {
     EN_GUARDED("segmented_prefill_attention", segmented_prefill_attention_impl(pool, plan, q_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream));
+}
+
+static int segmented_prefill_attention_prepared_impl(en_pool *pool, en_plan *plan, const void *q_prep_dev,
+                                                     const void *kc_dev, const void *vt_dev, void *out_dev,
+                                                     float *mass_red_out_dev, void *ws_dev, size_t ws_bytes,
+                                                     void *stream)
+{
+    if (!pool || !plan || !q_prep_dev || !kc_dev || !vt_dev || !out_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention_prepared: null argument");
+    if (plan->pool != pool)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention_prepared: plan belongs to another pool");
+    if (!computes_bf16(pool->d.dtype))
+        return fail(EN_ERR_UNSUPPORTED, "segmented_prefill_attention_prepared: prepared queries are bf16");
+    if (decode_kernel_fits(pool, plan->Nq))
+        return fail(EN_ERR_UNSUPPORTED, "segmented_prefill_attention_prepared: a step of so few query rows "
+                    "(%d per KV head) goes through segmented_prefill_attention or segmented_decode_step",
+                    pool->r * plan->Nq);
+    if (mass_red_out_dev && !ws_dev)
+        return fail(EN_ERR_INVALID_ARG, "segmented_prefill_attention_prepared: masses need the workspace");
+    if (mass_red_out_dev && pool->d.n_q_heads > 1023)
+        return fail(EN_ERR_UNSUPPORTED, "segmented_prefill_attention_prepared: reduced masses in the attention call "
+                    "count at most 1023 query heads; use segment_attention_mass");
+    return run_attention(pool, plan, q_prep_dev, kc_dev, vt_dev, out_dev, ws_dev, ws_bytes, stream, 0, plan->Nq,
+                         plan->n_splits, "segmented_prefill_attention_prepared", nullptr, nullptr, true,
+                         mass_red_out_dev);
+}
+extern "C" int segmented_prefill_attention_prepared(en_pool *pool, en_plan *plan, const void *q_prep_dev,
+                                                    const void *kc_dev, const void *vt_dev, void *out_dev,
+                                                    float *mass_red_out_dev, void *ws_dev, size_t ws_bytes,
+                                                    void *stream)
+{
+    EN_GUARDED("segmented_prefill_attention_prepared",
+               segmented_prefill_attention_prepared_impl(pool, plan, q_prep_dev, kc_dev, vt_dev, out_dev,
+                                                         mass_red_out_dev, ws_dev, ws_bytes, stream));
 }
 
 // KV splits for a step of n_rows query rows (same rule as for a whole plan).

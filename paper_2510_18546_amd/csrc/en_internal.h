@@ -63,6 +63,12 @@ struct EnGatherArgs {
     const int32_t *nseg, *sel, *bnd;
     int B, Hkv, C, Nq, Smax, T;
     const float *k_scale, *v_scale;    // EN_I8 pools only
+    // queries to prepare in the same launch, or null: q [B, Nq, Hq, D] unrotated ->
+    // q_prep, rotated at L_c + i, scaled by scale_log2e, bf16
+    const void *q;
+    void *q_prep;
+    int Hq;
+    float scale_log2e;
 };
 
 // The gather launch can carry a small plan's descriptor block inside its kernel
@@ -96,6 +102,11 @@ struct EnAttnArgs {
                        // block of the split's tiles and leaves its own partial results at index
                        // sp * sub + w of n_splits * sub
     float scale_log2e;
+    int q_prepared;    // prefill kernel: q holds prepared queries (rotated, scaled, bf16: see EnGatherArgs)
+    // prefill kernel, or null: n_red_zero accumulator words that its first workgroup sets to zero
+    // (EnMassArgs::red_acc, which the launches after it add to)
+    unsigned long long *red_zero;
+    int n_red_zero;
     // decode kernel only, or null: the rows' own keys / values [B, Nq, Hkv, D], which the kernel
     // writes into the context (kc, vt) at positions L_c + q_first + t before it reads them
     const void *app_k, *app_v;
@@ -104,6 +115,13 @@ struct EnAttnArgs {
 struct EnMassArgs {
     const float *ws_ml, *ws_seg, *ws_mlfin;
     float *ws_red;          // [B, Smax+1, Hq] per-head partial sums of the reduced masses
+    // Reduced masses without a launch of their own, or null: every per-head partial sum is also added,
+    // as a fixed-point integer (2^-red_shift; integer sums do not depend on the order of the
+    // additions), to red_acc [B, Smax+1], whose low 10 bits count the heads that have arrived; the
+    // head that arrives last writes the sum to red_out [B, Smax+1].
+    float *red_out;
+    unsigned long long *red_acc;
+    int red_shift;
     const int32_t *nseg, *bnd;
     const int32_t *hdr;     // as in EnAttnArgs
     float *out;
@@ -159,7 +177,7 @@ struct EnCtxAppendArgs {
 
 // Workspace layout helper (bytes, every part 256-byte aligned).
 struct EnWsLayout {
-    size_t ml_off, seg_off, red_off, mlfin_off, opart_off, total;
+    size_t ml_off, seg_off, red_off, redacc_off, mlfin_off, opart_off, total;
 };
 EnWsLayout en_ws_layout(const en_pool *pool, const en_plan *plan);
 EnWsLayout en_ws_layout_for(const en_pool *pool, const en_plan *plan, int n_rows, int n_splits);
@@ -181,6 +199,9 @@ int en_launch_tier_load(const EnTierLoadArgs &a, int max_tokens, void *stream);
 // EN_STATIC_SCRATCH_BYTES of the public header): the device address of the current device's copy
 // (returns 0 or a hipError_t).
 int en_static_scratch(void **ptr_out, size_t *bytes_out);
+
+int en_launch_ceiling_mfma(float *sink_dev, int n_workgroups, int iters, int constant, void *stream);
+int en_launch_ceiling_read(const void *src_dev, size_t bytes, void *sink_dev, int n_workgroups, void *stream);
 
 void en_set_error(const char *fmt, ...);
 

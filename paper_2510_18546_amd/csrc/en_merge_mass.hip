@@ -8,6 +8,23 @@
 // output row. grid: ceil(rows * D / V / 256), V = elements in 16 bytes.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk, float *red);
+
+// The reduced masses without a launch of their own: a head's sum for (agent, bucket) `idx` joins the
+// others in ONE atomic addition on a 64-bit word that holds the sum in fixed point (so that it does
+// not depend on the order in which the heads arrive) above a 10-bit count of arrivals; whoever
+// arrives last (sees Hq in the count) has the complete sum in hand, from the atomic's own return
+// value, and writes it out. The word was set to zero by the attention launch before.
+__device__ __forceinline__ void add_reduced_mass(const EnMassArgs &a, size_t idx, float head_sum)
+{
+    if (!a.red_out)
+        return;
+    const long long q = __float2ll_rn(ldexpf(head_sum, a.red_shift));
+    const unsigned long long add = ((unsigned long long)q << 10) + 1ull;
+    const unsigned long long now = atomicAdd(a.red_acc + idx, add) + add;
+    if ((int)(now & 1023ull) == a.Hq)
+        a.red_out[idx] = ldexpf((float)((long long)(now - (unsigned long long)a.Hq) >> 10), -a.red_shift);
+}
+
 constexpr int EN_MASS_FEW_ROWS = 64;      // below this many query rows per head the partial sums go thread-wise
 // Stage 1 of the reduced masses: a workgroup takes EN_MASS_BG consecutive buckets of one
 // (agent, head) over all query rows (see mass_partial_block).
@@ -410,8 +427,9 @@ __device__ __forceinline__ void mass_partial_block(const EnMassArgs &a, int blk,
     __syncthreads();
     if (threadIdx.x < BG && s0 + (int)threadIdx.x <= a.Smax) {
         const int j = threadIdx.x;
-        a.ws_red[((size_t)b * (a.Smax + 1) + s0 + j) * a.Hq + hq] =
-            red[j] + red[BG + j] + red[2 * BG + j] + red[3 * BG + j];
+        const float tot = red[j] + red[BG + j] + red[2 * BG + j] + red[3 * BG + j];
+        a.ws_red[((size_t)b * (a.Smax + 1) + s0 + j) * a.Hq + hq] = tot;
+        add_reduced_mass(a, (size_t)b * (a.Smax + 1) + s0 + j, tot);
     }
 }
 
@@ -444,6 +462,7 @@ __device__ __forceinline__ void mass_partial_few_rows(const EnMassArgs &a, size_
         }
     }
     a.ws_red[pair] = acc;              // [b][s][hq]
+    add_reduced_mass(a, (size_t)b * (a.Smax + 1) + s, acc);
 }
 
 // grid: mass_partial_blocks(a), or ceil(B (Smax+1) Hq / 256) blocks when Nq < EN_MASS_FEW_ROWS
@@ -617,8 +636,10 @@ int en_launch_mass(const en_pool *pool, const EnMassArgs &a, int reduce, void *s
                                                   : dim3(mass_partial_blocks(a));
         if (a.n_splits * a.sub == 1 || a.Nq < EN_MASS_FEW_ROWS)
             hipLaunchKernelGGL(mass_partial_kernel, grid, blk, 0, st, a);
-        const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
-        hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
+        if (reduce == 1) {           // reduce == 2: stage 1 only, which adds into a.red_out
+            const dim3 grid2((a.B * (a.Smax + 1) + 3) / 4);
+            hipLaunchKernelGGL(mass_final_kernel, grid2, blk, 0, st, a);
+        }
     }
     return (int)hipGetLastError();
 }

@@ -30,7 +30,12 @@ class PlanningStep:
     """Device-resident state of one workload: pool, plan, inputs, buffers."""
 
     def __init__(self, w: I.Workload, device: str = "cuda:0", n_splits: Optional[int] = None,
-                 max_ctx: Optional[int] = None):
+                 max_ctx: Optional[int] = None, prepared: Optional[bool] = None):
+        """prepared: the queries are prepared in the gather launch and the reduced masses come out
+        of the attention call (gather_rope_queries + segmented_prefill_attention_prepared), where the
+        library offers that (bf16 contexts, steps of more than 32 query rows per KV head): the
+        default. False: the five calls gather_rope / segmented_prefill_attention /
+        segment_attention_mass."""
         import torch
         cfg = w.cfg
         self.w, self.cfg = w, cfg
@@ -47,6 +52,9 @@ class PlanningStep:
                 max_ctx = max(max_ctx, int(np.max(np.diff(w.sel_ptr))) * cfg.capacity + cfg.n_new)
         self.pool = B.kv_pool_create(self.k_pool, self.v_pool, w.lens, cfg.n_q_heads, cfg.rope_base,
                                      max_ctx)
+        can_prepare = self.bf16 and (cfg.n_q_heads // cfg.n_kv_heads) * cfg.n_new > 32
+        self.prepared = can_prepare if prepared is None else (prepared and can_prepare)
+        self.q_prep = torch.empty_like(self.q) if self.prepared else None
         self.plan = None
         self.select(n_splits)
         self.out = torch.empty((cfg.n_agents, cfg.n_new, cfg.n_q_heads, cfg.head_dim),
@@ -79,10 +87,19 @@ class PlanningStep:
         return self.plan
 
     def gather(self):
-        B.gather_rope(self.pool, self.plan, self.k_new, self.v_new, self.kc, self.vt)
+        if self.prepared:
+            B.gather_rope_queries(self.pool, self.plan, self.k_new, self.v_new, self.q, self.kc, self.vt, self.q_prep)
+        else:
+            B.gather_rope(self.pool, self.plan, self.k_new, self.v_new, self.kc, self.vt)
 
-    def attention(self):
-        B.segmented_prefill_attention(self.pool, self.plan, self.q, self.kc, self.vt, self.out, self.ws)
+    def attention(self, reduced_mass: bool = False):
+        """reduced_mass (prepared form only): the reduced masses come out of this call too."""
+        if self.prepared:
+            B.segmented_prefill_attention_prepared(self.pool, self.plan, self.q_prep, self.kc, self.vt, self.out,
+                                                   self.ws, self.mass_red if reduced_mass else None)
+        else:
+            assert not reduced_mass
+            B.segmented_prefill_attention(self.pool, self.plan, self.q, self.kc, self.vt, self.out, self.ws)
 
     def masses(self, reduce: int):
         B.segment_attention_mass(self.pool, self.plan, self.ws, reduce,
@@ -90,10 +107,10 @@ class PlanningStep:
 
     def run(self, full_mass: bool = True, reduced_mass: bool = True):
         self.gather()
-        self.attention()
+        self.attention(reduced_mass and self.prepared)
         if full_mass:
             self.masses(0)
-        if reduced_mass:
+        if reduced_mass and not self.prepared:
             self.masses(1)
 
     # -- read-back ------------------------------------------------------------

@@ -370,6 +370,66 @@ def test_gather_rope_layout(step_mod, oracle, dtype):
 
 
 # ---------------------------------------------------------------------------
+# the two forms of a step: queries prepared in the gather launch and reduced masses out of the
+# attention call (what run_case and the benchmark use where the library offers it), against the
+# five separate calls
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["ragged", "one-split", "d64", "c1"])
+def test_prepared_step_equals_the_five_calls(step_mod, oracle, case):
+    import torch
+    cfg = {"ragged": small("prep-ragged", 900, n_agents=2, len_lo=0, n_sel=7),
+           "one-split": small("prep-one-split", 901, n_agents=3, n_new=40),
+           "d64": small("prep-d64", 902, head_dim=64, n_q_heads=4, n_kv_heads=1, n_new=45),
+           "c1": I.CONFIGS["c1"]}[case]
+    splits = {"ragged": 3, "one-split": 1, "d64": 2, "c1": None}[case]
+    announce(f"prepared vs five calls: {cfg.name} splits={splits}")
+    w = I.make_workload(cfg)
+    a = step_mod.PlanningStep(w, n_splits=splits, prepared=True)
+    b = step_mod.PlanningStep(w, n_splits=splits, prepared=False)
+    assert a.prepared and not b.prepared
+    a.mass_red.fill_(float("nan"))            # the attention launch must start the sums at zero itself
+    a.run()
+    b.run()
+    torch.cuda.synchronize()
+    # same arithmetic on the queries, wherever it is done: the same bits
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+    assert torch.equal(a.mass.view(torch.int32), b.mass.view(torch.int32))
+    # reduced masses: an exact integer sum of the heads' sums against the float sum of the mass call
+    ra, rb = a.mass_red_host(), b.mass_red_host()
+    assert np.isfinite(ra).all()
+    np.testing.assert_allclose(ra, rb, rtol=2e-6, atol=1e-5)
+    # ... and a second run starts from zero again, not from the first run's sums, and gives the same
+    # bits: the heads' sums are added as integers, whatever order they arrive in
+    a.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(a.mass_red_host(), ra)
+    # the mass call after a prepared attention call gives the fixed-order sums
+    a.masses(1)
+    torch.cuda.synchronize()
+    assert np.array_equal(a.mass_red_host(), rb)
+    ref_out, ref_mass = oracle_full(oracle, w)
+    check_out(cfg, a.out_host(), ref_out)
+    check_mass(cfg, a.mass_host(), ref_mass)
+
+
+def test_prepared_form_refusals(step_mod):
+    from paper_2510_18546_amd import binding as B
+    w32 = I.make_workload(small("prep-f32", 903, dtype=I.F32, head_dim=64, n_new=40))
+    st = step_mod.PlanningStep(w32)
+    assert not st.prepared
+    with pytest.raises(B.EnError) as e:
+        B.gather_rope_queries(st.pool, st.plan, st.k_new, st.v_new, st.q, st.kc, st.vt, st.q)
+    assert e.value.code == 5
+    wd = I.make_workload(small("prep-decode", 904, n_new=2))       # 4 heads per KV head x 2 rows: the decode kernel's
+    sd = step_mod.PlanningStep(wd)
+    assert not sd.prepared
+    sd.gather()
+    with pytest.raises(B.EnError) as e:
+        B.segmented_prefill_attention_prepared(sd.pool, sd.plan, sd.q, sd.kc, sd.vt, sd.out, sd.ws)
+    assert e.value.code == 5
+
+
+# ---------------------------------------------------------------------------
 # full benchmark sizes, in the launch configuration the benchmark times
 # (default split choice): every output row, every mass and the reduced masses
 # against the oracle
