@@ -35,15 +35,26 @@ WORKLOAD_TEXT = {
     "c4": "c4: decode, 64 agents x 1 new token over 64 segments x 256 tokens (16384) from a 1024-group pool; 32q/8kv, D=128, bf16",
 }
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs, each scaled by what the same counter reads for a plain copy
-# of known size (profiles/attn_bf16_c2_hbm_traffic.md); null where not measured.
-MEASURED_TRAFFIC = {"c2": 64.6e6, "c4": 4.318e9}     # c4: profiles/attn_decode_c4_hbm_traffic.md
+# HBM bytes from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs, each scaled by what the same counter
+# reads for a plain copy of known size: per launch of the dominant kernel, and per whole planning step
+# (all its launches). Stored figures, re-measured when a kernel changes; the profile named holds the
+# commands and the counters.
+MEASURED_TRAFFIC = {
+    "c2": {"kernel": 64.6e6, "step": 172.0e6, "source": "profiles/attn_bf16_c2_hbm_traffic.md"},
+    "c4": {"kernel": 4.318e9, "step": None, "source": "profiles/attn_decode_c4_hbm_traffic.md"},
+}
 
 
 def algorithmic_flops(cfg, info) -> int:
     """4*Hq*D per visible (query, key) pair; causal triangle counted once."""
     return 4 * cfg.n_q_heads * cfg.head_dim * int(info.total_pairs)
+
+
+def step_traffic(name, cfg, info):
+    alg = algorithmic_bytes(cfg, info) + 2 * cfg.n_agents * cfg.n_new * cfg.n_kv_heads * cfg.head_dim * 2
+    t = MEASURED_TRAFFIC.get(name, {})
+    return {"algorithmic_bytes": alg, "measured_bytes": t.get("step"),
+            "ratio": (t["step"] / alg) if t.get("step") else None, "source": t.get("source")}
 
 
 def algorithmic_bytes(cfg, info) -> int:
@@ -113,6 +124,9 @@ def main():
     ap.add_argument("--no-residency", action="store_true",
                     help="skip the residency-tier figures (hit rate against the device budget, planning "
                          "steps whose groups are loaded from the host store) reported under 'residency'")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="with the default workload, skip the brief figures of c1, c3, c4 and c5 reported under "
+                         "'other_workloads'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -141,50 +155,57 @@ def main():
     if args.ceilings:
         print(json.dumps({"ceilings": measure_ceilings(torch, B)}))
         return
-    cfg = I.CONFIGS[args.workload]
-    w = I.make_workload(cfg)
-    st = step.PlanningStep(w)
-    info = st.info
-    flops = algorithmic_flops(cfg, info)
-    hbm_bound = cfg.n_new == 1
+    def time_workload(name, steps, warmup):
+        """K whole planning steps of one workload, inputs resident; the attention kernel's own
+        duration from HIP events around its launches, on the stream it is launched on."""
+        cfg = I.CONFIGS[name]
+        w = I.make_workload(cfg)
+        st = step.PlanningStep(w)
+        info = st.info
+        flops = algorithmic_flops(cfg, info)
+        hbm_bound = cfg.n_new == 1
 
-    def one_step():
-        st.select()
-        st.gather()                       # with the queries prepared in the same launch (prefill workloads)
-        if st.prepared:
-            st.attention(True)            # ... and the reduced masses out of the attention call
+        def one_step():
+            st.select()
+            st.gather()                       # with the queries prepared in the same launch (prefill workloads)
+            if st.prepared:
+                st.attention(True)            # ... and the reduced masses out of the attention call
+            else:
+                st.attention()
+                st.masses(1)
+
+        for _ in range(warmup):
+            one_step()
+        torch.cuda.synchronize()
+        B.timing_enable(st.pool, steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kern_ms = B.timing_collect(st.pool, steps)
+        B.timing_enable(st.pool, 0)
+        sec_per_step = (t1 - t0) / steps
+        kern_s = float(np.mean(kern_ms)) * 1e-3
+        if hbm_bound:
+            abytes = algorithmic_bytes(cfg, info)
+            roof = {"bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
         else:
-            st.attention()
-            st.masses(1)
+            roof = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        # HBM bytes per launch of this kernel: a stored figure from rocprofv3 --pmc runs (FETCH_SIZE and
+        # WRITE_SIZE, each scaled by what it reads for a plain copy), not something this run measures
+        roof["traffic"] = MEASURED_TRAFFIC.get(name, {}).get("kernel")
+        roof["traffic_source"] = MEASURED_TRAFFIC.get(name, {}).get("source")
+        roof["kernel"] = "attn_decode_kernel<128, 1>" if hbm_bound else "attn_bf16_kernel<128, true>"
+        roof["kernel_us"] = kern_s * 1e6
+        roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
+        return cfg, w, st, info, flops, hbm_bound, sec_per_step, roof
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    B.timing_enable(st.pool, args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    kern_ms = B.timing_collect(st.pool, args.steps)
-    B.timing_enable(st.pool, 0)
-
-    sec_per_step = (t1 - t0) / args.steps
-    kern_s = float(np.mean(kern_ms)) * 1e-3
+    cfg, w, st, info, flops, hbm_bound, sec_per_step, roof = time_workload(args.workload, args.steps, args.warmup)
     value = flops / sec_per_step / 1e12
-
-    if hbm_bound:
-        abytes = algorithmic_bytes(cfg, info)
-        roof = {"bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC.get(args.workload)
-    roof["kernel"] = "attn_decode_kernel<128, 1>" if hbm_bound else "attn_bf16_kernel<128>"
-    roof["kernel_us"] = kern_s * 1e6
-    roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
 
     res = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -197,6 +218,9 @@ def main():
                    "flops_per_step": flops, "cached_tokens": int(info.total_cached),
                    "new_tokens": cfg.n_new, "agents": cfg.n_agents},
         "roofline": roof,
+        # the whole step's HBM traffic (stored profile figure) against the bytes the method must move once:
+        # selected K+V read once, Q, O, new K/V (2-byte elements)
+        "step_traffic": step_traffic(args.workload, cfg, info),
         # the paper's own figures, other hardware, whole planner: context only, never a target
         "paper_context": "EfficientNav-11b (40-layer LLaMA-3.2-11b planner): 0.35 s planning latency per "
                          "navigation step on 1x RTX A6000 vs 3.07 s naive and 2.27 s vLLM (Table 3); prefill "
@@ -311,11 +335,20 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         g1 = time.perf_counter()
+        # bytes a decoded token must read once: K and V of the context (the prompt and, on average, half of
+        # the decoded tokens included), every KV head
+        dec_bytes = 2 * cfg.n_kv_heads * cfg.head_dim * 2 * cfg.n_agents * (int(info.max_ctx_len) + n_dec / 2)
+        us_graph = (g1 - g0) / 5 / n_dec * 1e6
+        us_attn = float(np.mean(dec_kern_ms)) * 1e3
         res["decode_after_prefill"] = {
             "tokens_decoded": n_dec, "context_tokens": int(info.max_ctx_len),
             "us_per_decode_step_eager": (d1 - d0) / n_dec * 1e6,
-            "us_per_decode_step_graph": (g1 - g0) / 5 / n_dec * 1e6,
-            "attention_kernel_us": float(np.mean(dec_kern_ms)) * 1e3,
+            "us_per_decode_step_graph": us_graph,
+            "attention_kernel_us": us_attn,
+            "context_bytes_per_step": dec_bytes,
+            "hbm_floor_us": dec_bytes / (PEAK_HBM_GBS * 1e9) * 1e6,
+            "frac_of_hbm_peak_step": dec_bytes / (us_graph * 1e-6) / (PEAK_HBM_GBS * 1e9),
+            "frac_of_hbm_peak_attention_kernel": dec_bytes / (us_attn * 1e-6) / (PEAK_HBM_GBS * 1e9),
             "us_prefill_step_plus_40_decode_steps": sec_per_step * 1e6 + (g1 - g0) / 5 * 1e6,
         }
         del graph
@@ -456,6 +489,21 @@ def main():
         plan_q.close()
         pool_q.close()
         del kq, vq, ks, vs
+
+    if args.workload == "c2" and not args.no_other_workloads:
+        # the other workloads in brief, from the same run (each has a full line of its own under --workload)
+        del st, w
+        other = {}
+        for name in ("c1", "c3", "c5", "c4"):
+            o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 40, 8)
+            other[name] = {"workload": WORKLOAD_TEXT[name], "us_per_planning_step": o_sec * 1e6,
+                           "value_tflops": o_flops / o_sec / 1e12, "n_splits": int(o_info.n_splits),
+                           "roofline": o_roof}
+            del o_w, o_st
+            torch.cuda.empty_cache()
+        res["other_workloads"] = other
+        cfg = I.CONFIGS[args.workload]
+        w = I.make_workload(cfg)
 
     if not args.no_ceilings:
         res["ceilings"] = measure_ceilings(torch, B)
