@@ -127,6 +127,11 @@ def main():
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="with the default workload, skip the brief figures of c1, c3, c4 and c5 reported under "
                          "'other_workloads'")
+    ap.add_argument("--five-calls", action="store_true",
+                    help="time the step as the five calls gather_rope / segmented_prefill_attention / "
+                         "segment_attention_mass (queries rotated inside the attention kernel, reduced masses "
+                         "by a launch of their own) instead of gather_rope_queries + "
+                         "segmented_prefill_attention_prepared: the before/after of those two changes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -160,7 +165,7 @@ def main():
         duration from HIP events around its launches, on the stream it is launched on."""
         cfg = I.CONFIGS[name]
         w = I.make_workload(cfg)
-        st = step.PlanningStep(w)
+        st = step.PlanningStep(w, prepared=False if args.five_calls else None)
         info = st.info
         flops = algorithmic_flops(cfg, info)
         hbm_bound = cfg.n_new == 1
@@ -199,7 +204,8 @@ def main():
         # WRITE_SIZE, each scaled by what it reads for a plain copy), not something this run measures
         roof["traffic"] = MEASURED_TRAFFIC.get(name, {}).get("kernel")
         roof["traffic_source"] = MEASURED_TRAFFIC.get(name, {}).get("source")
-        roof["kernel"] = "attn_decode_kernel<128, 1>" if hbm_bound else "attn_bf16_kernel<128, true>"
+        roof["kernel"] = ("attn_decode_kernel<128, 1>" if hbm_bound else
+                          "attn_bf16_kernel<128, true>" if st.prepared else "attn_bf16_kernel<128, false>")
         roof["kernel_us"] = kern_s * 1e6
         roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
         return cfg, w, st, info, flops, hbm_bound, sec_per_step, roof
@@ -216,7 +222,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "n_splits": int(info.n_splits),
                    "flops_per_step": flops, "cached_tokens": int(info.total_cached),
-                   "new_tokens": cfg.n_new, "agents": cfg.n_agents},
+                   "new_tokens": cfg.n_new, "agents": cfg.n_agents,
+                   "entry_points": ("segment_select, gather_rope_queries, segmented_prefill_attention_prepared"
+                                    if st.prepared else
+                                    "segment_select, gather_rope, segmented_prefill_attention, "
+                                    "segment_attention_mass")},
         "roofline": roof,
         # the whole step's HBM traffic (stored profile figure) against the bytes the method must move once:
         # selected K+V read once, Q, O, new K/V (2-byte elements)
