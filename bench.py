@@ -132,6 +132,10 @@ def main():
                          "segment_attention_mass (queries rotated inside the attention kernel, reduced masses "
                          "by a launch of their own) instead of gather_rope_queries + "
                          "segmented_prefill_attention_prepared: the before/after of those two changes")
+    ap.add_argument("--values-from-pool", action="store_true",
+                    help="prefill-only form of the step: the values are not gathered, the attention kernel fetches "
+                         "them from the pool's blocks (en_plan_values_from_pool); the decode phase that the line "
+                         "also reports gathers its own context either way")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (scales the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -160,12 +164,13 @@ def main():
     if args.ceilings:
         print(json.dumps({"ceilings": measure_ceilings(torch, B)}))
         return
-    def time_workload(name, steps, warmup):
+    def time_workload(name, steps, warmup, values_from_pool=args.values_from_pool):
         """K whole planning steps of one workload, inputs resident; the attention kernel's own
         duration from HIP events around its launches, on the stream it is launched on."""
         cfg = I.CONFIGS[name]
         w = I.make_workload(cfg)
-        st = step.PlanningStep(w, prepared=False if args.five_calls else None)
+        st = step.PlanningStep(w, prepared=False if args.five_calls else None,
+                               values_from_pool=values_from_pool and cfg.n_new > 1)
         info = st.info
         flops = algorithmic_flops(cfg, info)
         hbm_bound = cfg.n_new == 1
@@ -223,6 +228,7 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[args.workload], "n_splits": int(info.n_splits),
                    "flops_per_step": flops, "cached_tokens": int(info.total_cached),
                    "new_tokens": cfg.n_new, "agents": cfg.n_agents,
+                   "values": "left in the pool (en_plan_values_from_pool)" if st.values_from_pool else "gathered",
                    "entry_points": ("segment_select, gather_rope_queries, segmented_prefill_attention_prepared"
                                     if st.prepared else
                                     "segment_select, gather_rope, segmented_prefill_attention, "
@@ -512,6 +518,18 @@ def main():
             del o_w, o_st
             torch.cuda.empty_cache()
         res["other_workloads"] = other
+        if not args.values_from_pool:
+            # Steps that no decode phase follows (the clustering passes of Section 3.3) can leave the values
+            # where they are (en_plan_values_from_pool: the attention kernel fetches them from the pool's
+            # blocks, bit-identical results): the same steps in that form, same run.
+            vp = {}
+            for name in ("c2", "c3"):
+                o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 40, 8, True)
+                vp[name] = {"us_per_planning_step": o_sec * 1e6, "value_tflops": o_flops / o_sec / 1e12,
+                            "attention_kernel_us": o_roof["kernel_us"]}
+                del o_w, o_st
+                torch.cuda.empty_cache()
+            res["prefill_only_values_from_pool"] = vp
         cfg = I.CONFIGS[args.workload]
         w = I.make_workload(cfg)
 

@@ -196,6 +196,25 @@ int en_plan_query(const en_plan *plan, int32_t agent, int32_t *offsets_out_host,
  * the number of 64-key tiles and to 64). Must precede en_workspace_bytes. */
 int en_plan_set_splits(en_plan *plan, int32_t n_splits);
 
+/* Prefill-only steps: leave the values where they are (Section 3.2 asks for each
+ * selected group's KV to be loaded once; a step that no decode phase follows has no
+ * second reader for a gathered copy of the values). With on = 1, gather_rope and
+ * gather_rope_queries still write the rotated keys, but into vt_dev only, per
+ * (agent, KV head, context row), the device address of that row's values in the
+ * pool's block or in v_new_dev (8 bytes per row, [B, Hkv, T], then one row of
+ * zeros for the padding of the last tile; the buffer keeps its size,
+ * en_context_bytes), and segmented_prefill_attention[_prepared] fetch the rows
+ * from there. Results are bit-identical to those of the gathered form. The pool's
+ * values and v_new_dev must stay unchanged, and allocated, from the gather to the
+ * end of the attention call. Set it before the gather; a change after the gather
+ * makes the attention calls fail (INVALID_ARG) until the plan is gathered again.
+ * Errors: INVALID_ARG (null, flag not 0 / 1, values not 256-byte aligned: the
+ * pool's here, v_new_dev at the gather), UNSUPPORTED (not an EN_BF16 pool with
+ * head_dim 128; a plan of so few new tokens that its attention runs in the
+ * decode kernel). segmented_decode_step[_static] and any step over a part of the
+ * plan's rows return UNSUPPORTED on such a plan: they read gathered values. */
+int en_plan_values_from_pool(en_plan *plan, int32_t on);
+
 /* May be called while work that uses the plan is still queued on a stream,
  * provided later plans of the same pool are used on that same stream;
  * otherwise synchronise first. */

@@ -23,6 +23,7 @@ STATUS = {0: "EN_OK", 1: "EN_ERR_INVALID_ARG", 2: "EN_ERR_OUT_OF_RANGE", 3: "EN_
 EXPORTS = [
     "kv_pool_create", "kv_pool_set_scales", "kv_pool_set_len", "kv_pool_append", "kv_pool_destroy", "segment_select",
     "segment_select_scored", "en_plan_get_info", "en_plan_query", "en_plan_set_splits",
+    "en_plan_values_from_pool",
     "en_plan_destroy", "en_context_bytes", "gather_rope", "gather_rope_queries", "en_workspace_bytes",
     "segmented_prefill_attention", "segmented_prefill_attention_prepared", "segment_attention_mass",
     "segment_cluster_assign",
@@ -83,6 +84,7 @@ def load(path: Optional[str] = None) -> C.CDLL:
     lib.en_plan_get_info.argtypes = [vp, C.POINTER(PlanInfo)]
     lib.en_plan_query.argtypes = [vp, C.c_int32, i32p, i32p]
     lib.en_plan_set_splits.argtypes = [vp, C.c_int32]
+    lib.en_plan_values_from_pool.argtypes = [vp, C.c_int32]
     lib.en_plan_destroy.argtypes = [vp]
     lib.en_context_bytes.argtypes = [vp, vp]
     lib.en_context_bytes.restype = C.c_size_t
@@ -195,6 +197,9 @@ class Plan:
 
     def set_splits(self, n: int):
         _check(load().en_plan_set_splits(self.handle, int(n)))
+
+    def values_from_pool(self, on: bool):
+        _check(load().en_plan_values_from_pool(self.handle, 1 if on else 0))
 
     def close(self):
         if self.handle:

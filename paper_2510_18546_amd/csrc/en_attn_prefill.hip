@@ -47,9 +47,16 @@ constexpr int ATT_WAVES = EN_WAVES;
 
 // QPREP: the queries arrive prepared (rotated at L_c + i, scaled, bf16: the gather launch did it
 // once), else the wave prepares its own 32 from the caller's unrotated ones.
-template <int D, bool QPREP>
+// VPOOL: the values were not gathered. a.vt holds, per (agent, KV head, context row), the address of
+// that row's D values where they are (a block of the pool, the new tokens, a row of zeros for the
+// padding of the last tile). The loader fetches the 64 rows of a tile from there, so a V tile sits
+// in LDS row-major, [64 keys][D], and the operand reads transpose it (ds_read_b64_tr_b16). Inside
+// a tile the 16-byte chunks of a row are rotated by four times the row number: the 16 lanes of
+// one transposing read then touch 4 rows x 32 bytes on distinct banks.
+template <int D, bool QPREP, bool VPOOL>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 {
+    static_assert(!VPOOL || D == 128, "values from the pool: 256-byte rows");
     constexpr int KT = EN_KEY_TILE;              // keys per LDS tile
     constexpr int KB = 32;                       // keys per pipeline block
     constexpr int NKS = D / 16;                  // k-steps of one block's QK^T product
@@ -153,14 +160,49 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     for (int j = 0; j < VJ; ++j) {
         const int q = (wave + ATT_WAVES * j) * 64 + lane;
         const int d = q / 8, pos = q % 8;
-        voff[j] = (uint32_t)((size_t)d * a.T * 2 + ((pos - d / 2) & 7) * 16);
+        voff[j] = VPOOL ? 0u : (uint32_t)((size_t)d * a.T * 2 + ((pos - d / 2) & 7) * 16);
     }
+    // VPOOL: loader block blk = wave + 8 j of a tile is rows 4 blk .. 4 blk + 3, lane L of it position
+    // L % 16 of row 4 blk + L / 16, which holds chunk (L % 16 - 4 row) mod 16 of that row.
+    const char *vtab = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * 8;
+    const uint32_t vtab_lane = (uint32_t)(4 * wave + lane / 16) * 8;      // this lane's first row of a tile; the second: 32 rows on
+    const uint32_t vchunk = (uint32_t)((lane % 16 - 4 * (lane / 16)) & 15) * 16;
+    // Addresses of this lane's 16 bytes of the V tile to load next (vrow) and of the one after
+    // (vnext, on its way from the table). The table is read with ordinary loads, which the compiler
+    // waits for where it first uses the result: vrow_take is therefore called where everything in
+    // flight has just been waited for anyway (right after a tile's barrier), one whole tile after
+    // the request. (Between loader blocks, which the compiler does not see, it could only wait for
+    // all of them.)
+    unsigned long long vrow[VJ], vnext[VJ];
+#pragma unroll
+    for (int j = 0; j < VJ; ++j)
+        vrow[j] = vnext[j] = 0;
+    auto vrow_request = [&](int tile) {
+        if constexpr (VPOOL) {
+            const char *p = vtab + (size_t)min(tile, t_end - 1) * (KT * 8) + vtab_lane;
+#pragma unroll
+            for (int j = 0; j < VJ; ++j)
+                vnext[j] = *reinterpret_cast<const unsigned long long *>(p + j * 32 * 8);
+        }
+    };
+    auto vrow_take = [&]() {
+        if constexpr (VPOOL) {
+#pragma unroll
+            for (int j = 0; j < VJ; ++j) {
+                vrow[j] = vnext[j] | vchunk;
+                asm volatile("" : "+v"(vrow[j]));      // here, not later
+            }
+        }
+    };
     // Loader job of the current phase: one tile of K or of V^T, issued block by
     // block between the matrix instructions. A tile index past the end is
     // clamped: the last tile is fetched once more, into a stage nobody reads.
     uint32_t job_goff = 0;
     auto job_k = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * KBYTES; };
-    auto job_v = [&](int tile) { job_goff = (uint32_t)min(tile, t_end - 1) * (KT * 2); };
+    auto job_v = [&](int tile) {
+        if constexpr (!VPOOL)
+            job_goff = (uint32_t)min(tile, t_end - 1) * (KT * 2);
+    };
     auto dma_k = [&](auto j_tag, auto stage_tag) {
         constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
         if constexpr (j < KJ)
@@ -168,8 +210,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     };
     auto dma_v = [&](auto j_tag, auto stage_tag) {
         constexpr int j = decltype(j_tag)::value, stage = decltype(stage_tag)::value;
-        if constexpr (j < VJ)
-            dma16_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vg, voff[j] + job_goff, lds_w);
+        if constexpr (j < VJ) {
+            if constexpr (VPOOL)
+                dma16_addr_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vrow[j], lds_w);
+            else
+                dma16_imm<VBASE + stage * VBYTES + j * ATT_WAVES * 1024>(vg, voff[j] + job_goff, lds_w);
+        }
     };
 
     // ---- first loads, issued before the queries are prepared so that both are in
@@ -180,9 +226,16 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     const int s0 = (NST - rem) % NST;
     const int s1 = (s0 + 1) % NST, s2 = (s0 + 2) % NST;
     if (nt > 0) {
+        vrow_request(t_begin);       // (VPOOL) the first V tile waits for these: asked for first, loaded first
         char *vz = smem + VBASE + s2 * VBYTES;     // the first product reads a zero V^T stage
         for (int i = tid * 16; i < VBYTES; i += 64 * ATT_WAVES * 16)
             *reinterpret_cast<uint4 *>(vz + i) = make_uint4(0, 0, 0, 0);
+        if constexpr (VPOOL) {
+            vrow_take();
+#pragma unroll
+            for (int j = 0; j < VJ; ++j)
+                dma16_addr(vrow[j], lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
+        }
         job_k(t_begin);
 #pragma unroll
         for (int j = 0; j < KJ; ++j)
@@ -192,9 +245,13 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         for (int j = 0; j < KJ; ++j)
             dma16(kg, koff[j] + job_goff, lds_w + s1 * KBYTES + j * ATT_WAVES * 1024);
         job_v(t_begin);
+        if constexpr (VPOOL) {
+            vrow_request(t_begin + 1);
+        } else {
 #pragma unroll
-        for (int j = 0; j < VJ; ++j)
-            dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
+            for (int j = 0; j < VJ; ++j)
+                dma16(vg, voff[j] + job_goff, lds_w + VBASE + s0 * VBYTES + j * ATT_WAVES * 1024);
+        }
     }
 
     // ---- operand read addresses inside a stage (plus immediates per step) ----
@@ -208,6 +265,29 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
             vaddr[h][kk] = (uint32_t)(VBASE + col * VROWB + ((4 * h + 2 * kk + half + col / 2) & 7) * 16);
+    // VPOOL: the operand of a product is V^T[32 d + col][keys k0 + 4 half + {0..3}, k0 + 8 + 4 half + {0..3}]
+    // (k0 = 32 h + 16 kk: the keys whose probabilities the lane holds), two transposing reads. In
+    // one read the 16 lanes of a group point at 4 key rows x 16 values: lane j at row j / 4, values
+    // 4 (j % 4) .., and lane i receives value i of the four rows.
+    uint32_t vtaddr[NDB];
+#pragma unroll
+    for (int d = 0; d < NDB; ++d) {
+        const int j = lane % 16, grp = lane / 16;
+        const int row = 4 * half + j / 4;
+        const int chunk = 4 * d + 2 * (grp % 2) + (j % 4) / 2;
+        vtaddr[d] = (uint32_t)(VBASE + row * ROWB + ((chunk + 4 * row) & 15) * 16 + 8 * (j % 2));
+    }
+    // the operand of O^T block d from the keys k0 .. k0 + 15 of the V stage at byte offset stage_off
+    auto v_operand = [&](int d, int stage_off, int k0) -> bf16x8 {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        typedef __attribute__((address_space(3))) s16x4 *lds_s16x4;
+        char *p = smem + vtaddr[d] + stage_off + k0 * ROWB;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(p + 8 * ROWB));
+        const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, both);
+    };
 
     // ---- Q: prepared queries are loaded as they are; else load, rotate at L_c + i, scale, round to bf16 ----
     bf16x8 qf[NKS];
@@ -449,8 +529,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             return *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + off);
         } else {
             constexpr int i = k / 2, kk = i / NDB, d = i % NDB;
-            constexpr int off = ((st + NST - 1 + par) % NST) * VBYTES + d * 32 * VROWB;
-            return *reinterpret_cast<const bf16x8 *>(smem + vaddr[par ^ 1][kk] + off);
+            if constexpr (VPOOL) {
+                return v_operand(d, ((st + NST - 1 + par) % NST) * VBYTES, 32 * (par ^ 1) + 16 * kk);
+            } else {
+                constexpr int off = ((st + NST - 1 + par) % NST) * VBYTES + d * 32 * VROWB;
+                return *reinterpret_cast<const bf16x8 *>(smem + vaddr[par ^ 1][kk] + off);
+            }
         }
     };
     auto phase = [&](auto par_tag, auto st_tag, int tile) {
@@ -619,6 +703,8 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         wait_all_memory();
         __builtin_amdgcn_s_barrier();
         lds_data_ready();
+        vrow_take();                  // (VPOOL) rows of V tile + 1, asked for a tile ago
+        vrow_request(tile + 2);
         write_pending();
         job_k(tile + 2);
         phase(std::integral_constant<int, 0>{}, st_tag, tile);
@@ -642,7 +728,10 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
                 fr[k] = *reinterpret_cast<const bf16x8 *>(smem + kaddr[k / 2] + s0 * KBYTES + KB * ROWB);
             } else {
                 const int i = k / 2, kk = i / NDB, d = i % NDB;
-                fr[k] = *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + s2 * VBYTES + d * 32 * VROWB);
+                if constexpr (VPOOL)
+                    fr[k] = v_operand(d, s2 * VBYTES, 32 + 16 * kk);
+                else
+                    fr[k] = *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + s2 * VBYTES + d * 32 * VROWB);
             }
         }
         int tile = t_begin;
@@ -664,8 +753,11 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
             for (int d = 0; d < NDB; ++d) {
-                const bf16x8 av =
-                    *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + 2 * VBYTES + d * 32 * VROWB);
+                bf16x8 av;
+                if constexpr (VPOOL)
+                    av = v_operand(d, 2 * VBYTES, 32 + 16 * kk);
+                else
+                    av = *reinterpret_cast<const bf16x8 *>(smem + vaddr[1][kk] + 2 * VBYTES + d * 32 * VROWB);
                 o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pbuf[1][kk], o[d], 0, 0, 0);
             }
         // loads of the clamped tiles may still be in flight
@@ -737,15 +829,22 @@ int en_launch_attention_prefill(const en_pool *pool, const EnAttnArgs &a, void *
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
     if (pool->d.head_dim == 64) {
+        if (a.v_rows)
+            return (int)hipErrorInvalidValue;      // the host refuses this before it gets here
         if (a.q_prepared)
-            hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((attn_bf16_kernel<64, true, false>), grid, blk, 0, st, a);
         else
-            hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((attn_bf16_kernel<64, false, false>), grid, blk, 0, st, a);
+    } else if (a.v_rows) {
+        if (a.q_prepared)
+            hipLaunchKernelGGL((attn_bf16_kernel<128, true, true>), grid, blk, 0, st, a);
+        else
+            hipLaunchKernelGGL((attn_bf16_kernel<128, false, true>), grid, blk, 0, st, a);
     } else {
         if (a.q_prepared)
-            hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((attn_bf16_kernel<128, true, false>), grid, blk, 0, st, a);
         else
-            hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, blk, 0, st, a);
+            hipLaunchKernelGGL((attn_bf16_kernel<128, false, false>), grid, blk, 0, st, a);
     }
     return (int)hipGetLastError();
 }

@@ -112,6 +112,23 @@ __device__ __forceinline__ void dma16(const void *sbase, uint32_t voff, uint32_t
                  : "memory");
 }
 
+// The same from a full address per lane (rows that lie anywhere in memory).
+template <int IMM>
+__device__ __forceinline__ void dma16_addr_imm(unsigned long long addr, uint32_t lds_base)
+{
+    asm volatile("s_add_u32 m0, %0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(addr), "n"(IMM)
+                 : "memory", "scc");
+}
+__device__ __forceinline__ void dma16_addr(unsigned long long addr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(addr)
+                 : "memory");
+}
+
 __device__ __forceinline__ void wait_all_memory()
 {
     __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)

@@ -163,6 +163,21 @@ __device__ __forceinline__ void gather_vt_block(const EnGatherArgs &a, int bx, i
     const int Ltot = t.staged ? lbnd[S + 1] : t.bnd[S + 1];
     if (t0 >= Ltot)                            // the same for the whole block
         return;
+    if (a.v_rows) {
+        // the values stay where they are: the tile's 64 row addresses instead (padding rows: the row of zeros)
+        char *zero_row = (char *)a.vt + en_v_rows_table_bytes(a.B, a.Hkv, a.T);
+        if (threadIdx.x < EN_KEY_TILE) {
+            const uint16_t *vp = (const uint16_t *)a.v_pool, *vn = (const uint16_t *)a.v_new;
+            const uint16_t *src =
+                t.staged ? context_src<uint16_t, D>(a, (const int32_t *)lbnd, lsel, S, vp, vn, b, kvh, t0 + threadIdx.x)
+                         : context_src<uint16_t, D>(a, t.bnd, t.sel, S, vp, vn, b, kvh, t0 + threadIdx.x);
+            unsigned long long *tab = (unsigned long long *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)a.T + t0;
+            tab[threadIdx.x] = (unsigned long long)(uintptr_t)(src ? (const void *)src : (const void *)zero_row);
+        } else if (bx == 0 && kvh == 0 && b == 0 && threadIdx.x < EN_KEY_TILE + D * 2 / 16) {
+            reinterpret_cast<uint4 *>(zero_row)[threadIdx.x - EN_KEY_TILE] = make_uint4(0, 0, 0, 0);
+        }
+        return;
+    }
     if (threadIdx.x < EN_KEY_TILE) {
         const uint16_t *vp = (const uint16_t *)a.v_pool, *vn = (const uint16_t *)a.v_new;
         srcs[threadIdx.x] =

@@ -571,6 +571,32 @@ extern "C" int en_plan_set_splits(en_plan *plan, int32_t n_splits)
     EN_GUARDED("en_plan_set_splits", en_plan_set_splits_impl(plan, n_splits));
 }
 
+static bool decode_kernel_fits(const en_pool *pool, int n_rows);
+static int en_plan_values_from_pool_impl(en_plan *plan, int32_t on)
+{
+    if (!plan || (on != 0 && on != 1))
+        return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: null plan or a flag that is neither 0 nor 1");
+    const en_pool *pool = plan->pool;
+    if (on) {
+        if (!pool)
+            return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: the plan's pool has been destroyed");
+        if (pool->d.dtype != EN_BF16 || pool->d.head_dim != 128)
+            return fail(EN_ERR_UNSUPPORTED, "en_plan_values_from_pool: bf16 pools with head_dim 128 only (rows of 256 "
+                        "bytes that the attention kernel fetches as they are)");
+        if (decode_kernel_fits(pool, plan->Nq))
+            return fail(EN_ERR_UNSUPPORTED, "en_plan_values_from_pool: a step of so few query rows (%d per KV head) "
+                        "runs in the decode kernel, which reads gathered values", pool->r * plan->Nq);
+        if (reinterpret_cast<uintptr_t>(pool->v_dev) & 255)
+            return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: the pool's values must be 256-byte aligned");
+    }
+    plan->values_from_pool = on != 0;
+    return EN_OK;
+}
+extern "C" int en_plan_values_from_pool(en_plan *plan, int32_t on)
+{
+    EN_GUARDED("en_plan_values_from_pool", en_plan_values_from_pool_impl(plan, on));
+}
+
 static int en_plan_destroy_impl(en_plan *plan)
 {
     if (!plan)
@@ -860,6 +886,10 @@ static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, co
     a.q_prep = q_prep_dev;
     a.Hq = pool->d.n_q_heads;
     a.scale_log2e = softmax_scale_log2e(pool);
+    a.v_rows = plan->values_from_pool ? 1 : 0;
+    if (a.v_rows && (reinterpret_cast<uintptr_t>(v_new_dev) & 255))
+        return fail(EN_ERR_INVALID_ARG, "gather_rope: with the values taken from where they are "
+                    "(en_plan_values_from_pool) the new tokens' values must be 256-byte aligned");
     g.n_inline = 0;
     g.off_nseg = 0;
     g.off_sel = g.off_nseg + int(plan->nseg.size());
@@ -875,6 +905,7 @@ static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, co
             plan->uploaded = false;       // the block was to be filled by this launch
         return hip_fail((hipError_t)e, "gather_rope launch");
     }
+    plan->gathered_values_from_pool = a.v_rows;
     return EN_OK;
 }
 extern "C" int gather_rope(en_pool *pool, en_plan *plan, const void *k_new_dev, const void *v_new_dev,
@@ -990,6 +1021,13 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
     a.app_k = a.decode ? app_k_dev : nullptr;
     a.app_v = a.decode ? app_v_dev : nullptr;
     a.q_prepared = q_prepared ? 1 : 0;
+    a.v_rows = plan->values_from_pool ? 1 : 0;
+    if (a.v_rows && (a.decode || q_first != 0 || n_rows != plan->Nq))
+        return fail(EN_ERR_UNSUPPORTED, "%s: a plan whose values stay in the pool (en_plan_values_from_pool) has no "
+                    "gathered values for a step of its own rows; gather them (flag 0) first", who);
+    if (plan->gathered_values_from_pool >= 0 && plan->gathered_values_from_pool != a.v_rows)
+        return fail(EN_ERR_INVALID_ARG, "%s: en_plan_values_from_pool was changed after the plan's last gather; "
+                    "gather again", who);
     a.red_zero = (mass_red_out_dev && ws) ? reinterpret_cast<unsigned long long *>(ws + L.redacc_off) : nullptr;
     a.n_red_zero = a.red_zero ? plan->B * (plan->Smax + 1) : 0;
     const bool timed = pool->ev_used < (int)pool->ev_start.size();
@@ -1111,6 +1149,9 @@ static int segmented_decode_step_impl(en_pool *pool, en_plan *plan, int32_t q_fi
                     q_first, q_first + n_rows, plan->Nq);
     if (mass_out_dev && !ws_dev)
         return fail(EN_ERR_INVALID_ARG, "segmented_decode_step: masses need the workspace");
+    if (plan->values_from_pool)
+        return fail(EN_ERR_UNSUPPORTED, "segmented_decode_step: the plan's values stay in the pool "
+                    "(en_plan_values_from_pool); the decode steps read a gathered context");
     int rc;
     if ((rc = pool_ensure_device(pool)) != EN_OK || (rc = plan_ensure_device(plan, (hipStream_t)stream)) != EN_OK)
         return rc;

@@ -53,6 +53,9 @@ struct en_plan {
     size_t d_desc_bytes = 0;
     std::vector<int32_t> h_desc;  // staging copy, alive as long as the plan
     bool uploaded = false;
+    // en_plan_values_from_pool: the gather leaves the values where they are (EnGatherArgs::v_rows)
+    bool values_from_pool = false;
+    int gathered_values_from_pool = -1;      // mode of the last gather on this plan, -1: none yet
 };
 
 // Arguments of the device kernels (plain data, passed by value).
@@ -69,7 +72,18 @@ struct EnGatherArgs {
     void *q_prep;
     int Hq;
     float scale_log2e;
+    // 1 (bf16, D = 128): the values stay where they are. vt receives, per (agent, KV head, context
+    // row up to the end of the last 64-row tile), the 8-byte address of the row's values in the
+    // pool or the new tokens, [B, Hkv, T], and behind that table one row of zeros, which the
+    // padding rows of an agent's last tile point at.
+    int v_rows;
 };
+
+// Bytes of the row-address table of EnGatherArgs::v_rows (the row of zeros follows it).
+constexpr size_t en_v_rows_table_bytes(int B, int Hkv, int T)
+{
+    return ((size_t)B * Hkv * T * 8 + 255) / 256 * 256;
+}
 
 // The gather launch can carry a small plan's descriptor block inside its kernel
 // arguments: the kernel reads the descriptors from there and one workgroup
@@ -103,6 +117,8 @@ struct EnAttnArgs {
                        // sp * sub + w of n_splits * sub
     float scale_log2e;
     int q_prepared;    // prefill kernel: q holds prepared queries (rotated, scaled, bf16: see EnGatherArgs)
+    int v_rows;        // prefill kernel: vt holds no values but the address of every context row's values
+                       // (see EnGatherArgs::v_rows)
     // prefill kernel, or null: n_red_zero accumulator words that its first workgroup sets to zero
     // (EnMassArgs::red_acc, which the launches after it add to)
     unsigned long long *red_zero;

@@ -30,12 +30,14 @@ class PlanningStep:
     """Device-resident state of one workload: pool, plan, inputs, buffers."""
 
     def __init__(self, w: I.Workload, device: str = "cuda:0", n_splits: Optional[int] = None,
-                 max_ctx: Optional[int] = None, prepared: Optional[bool] = None):
+                 max_ctx: Optional[int] = None, prepared: Optional[bool] = None,
+                 values_from_pool: bool = False):
         """prepared: the queries are prepared in the gather launch and the reduced masses come out
         of the attention call (gather_rope_queries + segmented_prefill_attention_prepared), where the
         library offers that (bf16 contexts, steps of more than 32 query rows per KV head): the
         default. False: the five calls gather_rope / segmented_prefill_attention /
-        segment_attention_mass."""
+        segment_attention_mass.
+        values_from_pool: the plan leaves the values where they are (en_plan_values_from_pool)."""
         import torch
         cfg = w.cfg
         self.w, self.cfg = w, cfg
@@ -55,6 +57,7 @@ class PlanningStep:
         can_prepare = self.bf16 and (cfg.n_q_heads // cfg.n_kv_heads) * cfg.n_new > 32
         self.prepared = can_prepare if prepared is None else (prepared and can_prepare)
         self.q_prep = torch.empty_like(self.q) if self.prepared else None
+        self.values_from_pool = values_from_pool
         self.plan = None
         self.select(n_splits)
         self.out = torch.empty((cfg.n_agents, cfg.n_new, cfg.n_q_heads, cfg.head_dim),
@@ -69,6 +72,8 @@ class PlanningStep:
         self.plan = B.segment_select(self.pool, self.w.sel, self.w.sel_ptr, self.cfg.n_new)
         if n_splits is not None:
             self.plan.set_splits(n_splits)
+        if self.values_from_pool:
+            self.plan.values_from_pool(True)
         inf = self.plan.info
         self.info = inf
         if getattr(self, "_ctx_bytes", -1) != B.context_bytes(self.pool, self.plan):

@@ -430,6 +430,99 @@ def test_prepared_form_refusals(step_mod):
 
 
 # ---------------------------------------------------------------------------
+# values left where they are (en_plan_values_from_pool): the attention kernel fetches the value rows
+# from the pool's blocks and the new tokens through a table of row addresses. Same values into the
+# same products in the same order: the same bits as the gathered form.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("case", ["ragged", "one-split", "tail-1", "tail-37", "agents", "five-calls", "c1", "c2",
+                                  "c3"])
+def test_values_from_pool_equals_the_gathered_form(step_mod, oracle, case):
+    import torch
+    cfg = {"ragged": small("vp-ragged", 910, n_agents=2, len_lo=0, n_sel=7),
+           "one-split": small("vp-one-split", 911, n_agents=3, n_new=40),
+           "tail-1": small("vp-tail-1", 912, len_lo=64, len_hi=64, capacity=64, n_sel=4, n_new=65),
+           "tail-37": small("vp-tail-37", 913, len_lo=50, len_hi=50, capacity=64, n_sel=3, n_new=79),
+           "agents": small("vp-agents", 914, n_agents=5, n_groups=40, len_lo=1, len_hi=30, capacity=32, n_sel=11,
+                           n_new=33),
+           "five-calls": small("vp-five-calls", 915, n_agents=2),
+           "c1": I.CONFIGS["c1"], "c2": I.CONFIGS["c2"], "c3": I.CONFIGS["c3"]}[case]
+    splits = {"ragged": 3, "one-split": 1, "tail-1": 2, "tail-37": 1, "agents": 2}.get(case)
+    prepared = False if case == "five-calls" else None
+    announce(f"values from the pool vs gathered: {cfg.name} splits={splits} prepared={prepared}")
+    w = I.make_workload(cfg)             # rows of a group beyond its length hold NaN
+    a = step_mod.PlanningStep(w, n_splits=splits, prepared=prepared, values_from_pool=True)
+    b = step_mod.PlanningStep(w, n_splits=splits, prepared=prepared)
+    a.vt.view(torch.int16).fill_(0x7fc0)  # NaN where the gathered form would have values
+    a.run()
+    b.run()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+    assert torch.equal(a.mass.view(torch.int32), b.mass.view(torch.int32))
+    assert np.array_equal(a.mass_red_host(), b.mass_red_host())
+    # the keys are gathered as ever
+    for ag in range(cfg.n_agents):
+        assert np.array_equal(a.context_host(ag)[0], b.context_host(ag)[0])
+    # a second step on the same plan, and one after the plan goes back to gathered values
+    a.out.zero_()
+    a.run()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+    a.plan.values_from_pool(False)
+    a.out.zero_()
+    a.run()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+    for ag in range(cfg.n_agents):        # ... which gathers the values again
+        for x, y in zip(a.context_host(ag)[:2], b.context_host(ag)[:2]):      # keys and values of the context
+            assert np.array_equal(x, y)
+    if case not in ("c2", "c3"):          # (their gathered form has its own full-size comparison)
+        ref_out, ref_mass = oracle_full(oracle, w)
+        check_out(cfg, a.out_host(), ref_out)
+        check_mass(cfg, a.mass_host(), ref_mass)
+
+
+def test_values_from_pool_refusals(step_mod):
+    import torch
+    from paper_2510_18546_amd import binding as B
+
+    def code_of(fn):
+        with pytest.raises(B.EnError) as e:
+            fn()
+        return e.value.code
+
+    # fp32 pools and 64-wide heads keep their gathered values
+    s32 = step_mod.PlanningStep(I.make_workload(small("vp-f32", 916, dtype=I.F32, head_dim=64, n_new=40)))
+    assert code_of(lambda: s32.plan.values_from_pool(True)) == 5
+    s64 = step_mod.PlanningStep(I.make_workload(small("vp-d64", 917, head_dim=64, n_q_heads=4, n_kv_heads=1)))
+    assert code_of(lambda: s64.plan.values_from_pool(True)) == 5
+    # so few rows that the attention runs in the decode kernel
+    sd = step_mod.PlanningStep(I.make_workload(small("vp-decode", 918, n_new=2)))
+    assert code_of(lambda: sd.plan.values_from_pool(True)) == 5
+    # the flag is 0 or 1
+    st = step_mod.PlanningStep(I.make_workload(small("vp-flag", 919)))
+    with pytest.raises(B.EnError) as e:
+        B._check(B.load().en_plan_values_from_pool(st.plan.handle, 2))
+    assert e.value.code == 1
+    # a change between the gather and the attention call is caught; a new gather clears it
+    st.gather()
+    st.plan.values_from_pool(True)
+    assert code_of(lambda: st.attention()) == 1
+    st.gather()
+    st.attention()
+    # the decode steps read gathered values
+    ws = torch.empty(B.decode_workspace_bytes(st.pool, st.plan, 1), dtype=torch.uint8, device=st.device)
+    assert code_of(lambda: B.segmented_decode_step(st.pool, st.plan, 0, st.q[:, :1].contiguous(),
+                                                   st.k_new[:, :1].contiguous(), st.v_new[:, :1].contiguous(),
+                                                   st.kc, st.vt, st.out[:, :1].contiguous(), ws)) == 5
+    # the new tokens' value rows are fetched as 256-byte rows: aligned
+    raw = torch.empty(st.v_new.numel() + 64, dtype=st.v_new.dtype, device=st.device)
+    v_mis = raw[64:].view(st.v_new.shape)
+    v_mis.copy_(st.v_new)
+    assert code_of(lambda: B.gather_rope(st.pool, st.plan, st.k_new, v_mis, st.kc, st.vt)) == 1
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------
 # full benchmark sizes, in the launch configuration the benchmark times
 # (default split choice): every output row, every mass and the reduced masses
 # against the oracle
