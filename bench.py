@@ -210,7 +210,8 @@ def main():
         roof["traffic"] = MEASURED_TRAFFIC.get(name, {}).get("kernel")
         roof["traffic_source"] = MEASURED_TRAFFIC.get(name, {}).get("source")
         roof["kernel"] = ("attn_decode_kernel<128, 1>" if hbm_bound else
-                          "attn_bf16_kernel<128, true>" if st.prepared else "attn_bf16_kernel<128, false>")
+                          "attn_bf16_kernel<128, %s, %s>" % ("true" if st.prepared else "false",
+                                                             "true" if st.values_from_pool else "false"))
         roof["kernel_us"] = kern_s * 1e6
         roof["kernel_us_min"] = float(np.min(kern_ms)) * 1e3
         return cfg, w, st, info, flops, hbm_bound, sec_per_step, roof

@@ -767,8 +767,29 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     // output rows (see the epilogue)
     __builtin_amdgcn_s_barrier();
 
-    if (!wave_valid)
+    if (!wave_valid && !a.red_direct)
         return;
+    float inv = 0.f;
+    // (one split, reduced masses from this kernel: see below) the wave's pairs of 2 UB buckets
+    constexpr int UB = 8;
+    f32x2 pairs[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+        pairs[u] = f32x2{0.f, EN_NEG_INF};
+    const bool red_direct = a.red_direct && seg_base;        // the same for the whole workgroup
+    auto load_pairs = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int sa = s0 + 2 * u;                         // wave-uniform
+            const int nb = a.Smax + 1;
+            const int b0 = bound_at(min(sa, nb)), b1 = bound_at(min(sa + 1, nb)), b2 = bound_at(min(sa + 2, nb));
+            const bool live = half == 0 ? (sa <= S && b1 > b0) : (sa + 1 <= S && b2 > b1);
+            pairs[u] = f32x2{0.f, EN_NEG_INF};
+            if (live && row_valid)
+                pairs[u] = *reinterpret_cast<const f32x2 *>(seg_base + (size_t)((sa + half) * a.Nq) * 2);
+        }
+    };
+    if (wave_valid) {
     // Buckets of this split beyond the workgroup's causal frontier still get an
     // entry (zero mass); the bucket the loop stopped in gets what is pending.
     if (seg_base) {
@@ -790,7 +811,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
     // are, a wave's 8 KB go out as 512 pieces of 16 bytes (2 - 3.5 us at the end of the launch,
     // when every wave does it at once). Staged through LDS, each store instruction writes whole
     // rows: 64 lanes x 16 bytes = four rows of 256 bytes.
-    const float inv = (row_valid && l_tot > 0.f) ? 1.f / l_tot : 0.f;
+    inv = (row_valid && l_tot > 0.f) ? 1.f / l_tot : 0.f;
     constexpr int OSTR = 2 * D + 16;             // bytes per staged row (padded: bank spread, 16-byte aligned)
     constexpr int OCPR = D / 8;                  // 16-byte chunks per row
     static_assert(ATT_WAVES * 32 * OSTR <= NST * (KBYTES + VBYTES), "staging areas must fit the tile stages");
@@ -806,6 +827,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             *reinterpret_cast<bf16x4 *>(stage_o + col * OSTR + (32 * d + 8 * g + 4 * half) * 2) = v;
         }
     // the area is this wave's own: its writes only have to be complete (the compiler waits for them)
+    if (red_direct) {
+        // the pairs are read back here, behind the wave's last stores of them (waited for) and
+        // ahead of the output rows' stores, so that their way from memory overlaps those
+        wait_all_memory();
+        load_pairs(0);
+    }
 #pragma unroll
     for (int k = 0; k < 32 * OCPR / 64; ++k) {
         const int idx = k * 64 + lane;
@@ -817,6 +844,50 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
                              ? (bf16_t *)a.out + (((size_t)b * a.Nq + i) * a.Hq + hq) * D
                              : (bf16_t *)a.ws_opart + ((size_t)sp * a.B * a.Hq * a.Nq + row_hq * a.Nq + i) * D;
             *reinterpret_cast<uint4 *>(op + c * 8) = val;
+        }
+    }
+
+    }      // wave_valid
+
+    // ---- one split: the reduced masses [B, S+1] from here, without a further launch. The wave's
+    // (sum, reference) pairs of every bucket are in the scratch (its own stores: waited for, then
+    // read back, several buckets per batch of loads); with the rows' final references and sums in
+    // registers a bucket's masses of the wave's 32 rows are summed (the two halves of the wave take
+    // a bucket each), the workgroup's eight sums per bucket meet in LDS, and one thread per bucket
+    // adds the workgroup's sum, as a fixed-point integer, to the plan's accumulator of
+    // (agent, bucket): one arrival per workgroup (arrivals at one address take about 0.1 us each). ----
+    if (red_direct) {
+        constexpr int OAREA = ATT_WAVES * 32 * (2 * D + 16);      // the staging areas of the output rows
+        float *red_w = reinterpret_cast<float *>(smem + OAREA);   // [waves][Smax + 1]
+        static_assert(OAREA + ATT_WAVES * EN_RED_DIRECT_MAX_BUCKETS * 4 <= NST * (KBYTES + VBYTES), "sums of the buckets beside the staging areas");
+        const int nb = a.Smax + 1;
+        for (int s0 = 0; s0 < nb; s0 += 2 * UB) {
+            if (s0 > 0 && wave_valid)
+                load_pairs(s0);
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int s = s0 + 2 * u + half;
+                float v = pairs[u][1] != EN_NEG_INF ? pairs[u][0] * fast_exp2(pairs[u][1] - m_ref) * inv : 0.f;
+                v = half_sum(v);
+                if (col == 0 && s < nb)
+                    red_w[wave * nb + s] = v;
+            }
+        }
+        __syncthreads();
+        for (int s = tid; s < nb; s += 64 * ATT_WAVES) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < ATT_WAVES; ++w)
+                v += red_w[w * nb + s];
+            const size_t idx = (size_t)b * nb + s;
+            const long long q = __float2ll_rn(ldexpf(v, a.red_shift));
+            const unsigned long long add = ((unsigned long long)q << 10) + 1ull;
+            const unsigned long long now = atomicAdd(a.red_direct + idx, add) + add;
+            if ((int)(now & 1023ull) == a.red_target) {
+                a.red_direct_out[idx] =
+                    ldexpf((float)((long long)(now - (unsigned long long)a.red_target) >> 10), -a.red_shift);
+                a.red_direct[idx] = 0ull;           // nobody arrives after the last: ready for the next call
+            }
         }
     }
 }

@@ -165,6 +165,21 @@ __device__ __forceinline__ float pair_max(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Sum over the 32 lanes of each half of the wave, in every lane of the half: four steps inside the
+// rows of 16 lanes in the vector ALU (data-parallel primitives), one exchange between the two rows.
+__device__ __forceinline__ float half_sum(float v)
+{
+    auto dpp = [](float x, auto ctrl) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});      // quad_perm [1, 0, 3, 2]
+    v += dpp(v, std::integral_constant<int, 0x4E>{});      // quad_perm [2, 3, 0, 1]
+    v += dpp(v, std::integral_constant<int, 0x141>{});     // row_half_mirror
+    v += dpp(v, std::integral_constant<int, 0x140>{});     // row_mirror
+    v += __shfl_xor(v, 16, 64);
+    return v;
+}
+
 __device__ __forceinline__ float wave_max(float v)
 {
 #pragma unroll

@@ -289,8 +289,12 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
         a.sel = img + g.off_sel;
         a.bnd = img + g.off_bnd;
         if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+        {
             for (int i = threadIdx.x; i < g.n_inline; i += 256)
                 g.desc_out[i] = img[i];
+            for (int i = threadIdx.x; i < g.n_zero; i += 256)
+                g.desc_out[g.n_inline + i] = 0;
+        }
     }
     __shared__ int32_t lbnd[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
     const int tile = blockIdx.x;
@@ -476,8 +480,12 @@ __global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
         a.sel = img + g.off_sel;
         a.bnd = img + g.off_bnd;
         if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+        {
             for (int i = threadIdx.x; i < g.n_inline; i += 256)
                 g.desc_out[i] = img[i];
+            for (int i = threadIdx.x; i < g.n_zero; i += 256)
+                g.desc_out[g.n_inline + i] = 0;
+        }
     }
     __shared__ int32_t ltab[2 * EN_GATHER_TAB_LDS];       // bucket bounds, then selected groups
     // the grid of gather_kernel with one head per key unit

@@ -632,9 +632,11 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream, bool inline_ok = 
     if (pl->uploaded)
         return EN_OK;
     const size_t n = pl->nseg.size() + pl->sel.size() + pl->bnd.size() + pl->hdr.size();
-    const size_t bytes = n * sizeof(int32_t);
+    pl->acc_off = (n + 1) & ~size_t(1);                                   // 8-byte aligned
+    const size_t n_all = pl->acc_off + 2 * size_t(pl->B) * (pl->Smax + 1);    // tables, then the accumulators
+    const size_t bytes = n_all * sizeof(int32_t);
     pl->h_desc.clear();
-    pl->h_desc.reserve(n);
+    pl->h_desc.reserve(n_all);
     pl->h_desc.insert(pl->h_desc.end(), pl->nseg.begin(), pl->nseg.end());
     pl->h_desc.insert(pl->h_desc.end(), pl->sel.begin(), pl->sel.end());
     pl->h_desc.insert(pl->h_desc.end(), pl->bnd.begin(), pl->bnd.end());
@@ -655,8 +657,9 @@ static int plan_ensure_device(en_plan *pl, hipStream_t stream, bool inline_ok = 
         pl->d_desc_bytes = cap;
     }
     if (inline_ok && n <= size_t(EN_INLINE_DESC_MAX)) {
-        *inlined = true;
+        *inlined = true;              // (the launch also sets the accumulators to zero)
     } else {
+        pl->h_desc.resize(n_all, 0);
         // Stream-ordered copy; the staging vector lives as long as the plan.
         if ((e = hipMemcpyAsync(pl->d_desc, pl->h_desc.data(), bytes, hipMemcpyHostToDevice, stream)) !=
             hipSuccess)
@@ -895,8 +898,10 @@ static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, co
     g.off_sel = g.off_nseg + int(plan->nseg.size());
     g.off_bnd = g.off_sel + int(plan->sel.size());
     g.desc_out = plan->d_desc;
+    g.n_zero = 0;
     if (inlined) {
         g.n_inline = int(plan->h_desc.size());
+        g.n_zero = int(plan->acc_off + 2 * size_t(plan->B) * (plan->Smax + 1)) - g.n_inline;
         std::memcpy(g.desc, plan->h_desc.data(), plan->h_desc.size() * sizeof(int32_t));
     }
     const int e = en_launch_gather(pool, g, plan->max_ctx_len, stream);
@@ -1030,6 +1035,23 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
                     "gather again", who);
     a.red_zero = (mass_red_out_dev && ws) ? reinterpret_cast<unsigned long long *>(ws + L.redacc_off) : nullptr;
     a.n_red_zero = a.red_zero ? plan->B * (plan->Smax + 1) : 0;
+    // One partial result per row in the matrix-core kernel: its workgroups add the reduced masses up
+    // themselves, in the plan's own accumulators (every workgroup arrives once per bucket; the
+    // kernel keeps its eight waves' sums of the buckets in LDS).
+    a.red_direct = nullptr;
+    a.red_direct_out = nullptr;
+    a.red_shift = a.red_target = 0;
+    const int arrivals = pool->d.n_kv_heads * a.n_ptiles;        // workgroups per agent
+    const bool red_direct = mass_red_out_dev && ws && n_partials == 1 && !a.decode && computes_bf16(pool->d.dtype) &&
+                            q_first == 0 && n_rows == plan->Nq && arrivals <= 1023 && plan->Smax + 1 <= EN_RED_DIRECT_MAX_BUCKETS;
+    if (red_direct) {
+        a.red_direct = reinterpret_cast<unsigned long long *>(plan->d_desc + plan->acc_off);
+        a.red_direct_out = mass_red_out_dev;
+        a.red_shift = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first).red_shift;
+        a.red_target = arrivals;
+        a.red_zero = nullptr;
+        a.n_red_zero = 0;
+    }
     const bool timed = pool->ev_used < (int)pool->ev_start.size();
     if (timed)
         (void)hipEventRecord(pool->ev_start[pool->ev_used], (hipStream_t)stream);
@@ -1048,7 +1070,7 @@ static int run_attention(en_pool *pool, en_plan *plan, const void *q_dev, const 
         if (e != 0)
             return hip_fail((hipError_t)e, "split combine launch");
     }
-    if (mass_red_out_dev) {
+    if (mass_red_out_dev && !red_direct) {
         // stage 1 of the reduced masses as a launch of its own where no merge launch carried it (one
         // partial result per row, or few rows per head): en_launch_mass launches nothing otherwise
         EnMassArgs m = mass_args(pool, plan, ws, L, n_rows, n_splits, q_first);

@@ -53,6 +53,10 @@ struct en_plan {
     size_t d_desc_bytes = 0;
     std::vector<int32_t> h_desc;  // staging copy, alive as long as the plan
     bool uploaded = false;
+    // behind the tables in the device block: B * (Smax + 1) 64-bit accumulators of the reduced masses
+    // that the prefill attention kernel adds up itself (EnAttnArgs::red_direct). Zero when the block is
+    // filled; whoever completes a sum sets its word back to zero.
+    size_t acc_off = 0;           // in ints from d_desc
     // en_plan_values_from_pool: the gather leaves the values where they are (EnGatherArgs::v_rows)
     bool values_from_pool = false;
     int gathered_values_from_pool = -1;      // mode of the last gather on this plan, -1: none yet
@@ -93,6 +97,7 @@ constexpr int EN_INLINE_DESC_MAX = 960;      // ints; keeps the argument block u
 struct EnGatherLaunch {
     EnGatherArgs a;
     int n_inline;           // ints of `desc` in use, 0: read the device block
+    int n_zero;             // ints to set to zero behind them in the device block (the plan's accumulators)
     int off_nseg, off_sel, off_bnd;   // int offsets of the three tables in the block
     int32_t *desc_out;      // device block to fill when n_inline > 0
     int32_t desc[EN_INLINE_DESC_MAX];
@@ -123,6 +128,13 @@ struct EnAttnArgs {
     // (EnMassArgs::red_acc, which the launches after it add to)
     unsigned long long *red_zero;
     int n_red_zero;
+    // prefill kernel with one KV split, or null: the reduced masses [B, Smax+1] without any further
+    // launch. Every workgroup adds, per bucket, the masses of its rows to red_direct (fixed point,
+    // 2^-red_shift, above a 10-bit count of arrivals, as in EnMassArgs); the one that sees
+    // red_target arrivals writes the sum to red_direct_out and sets the word back to zero.
+    unsigned long long *red_direct;
+    float *red_direct_out;
+    int red_shift, red_target;
     // decode kernel only, or null: the rows' own keys / values [B, Nq, Hkv, D], which the kernel
     // writes into the context (kc, vt) at positions L_c + q_first + t before it reads them
     const void *app_k, *app_v;
@@ -160,6 +172,7 @@ struct EnAppendQ8Args {
 };
 
 
+constexpr int EN_RED_DIRECT_MAX_BUCKETS = 256;   // EnAttnArgs::red_direct: buckets whose sums a workgroup keeps in LDS
 constexpr int EN_MAX_SPLITS = 64;       // KV splits of a plan: the mass kernels hold one split per lane
 constexpr int EN_MAX_OBJECTS = 255;    // per segment_cluster_assign call (spans travel in the kernel arguments)
 struct EnClusterArgs {
