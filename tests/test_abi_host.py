@@ -369,3 +369,35 @@ def test_q8_pool_checks_without_device():
     with pytest.raises(B.EnError) as e:
         B.kv_tier_create(None, None, 4, 4, 1e4, 64, dtype=B.EN_I8, shape=(2, 1, 8, 64))
     assert e.value.code == 5
+
+
+def test_values_from_pool_checks_without_device():
+    """en_plan_values_from_pool is a host-side property of the plan: what it refuses needs no GPU."""
+    def code_of(fn):
+        with pytest.raises(B.EnError) as e:
+            fn()
+        return e.value.code
+
+    lens = [5, 6, 7]
+    ok = B.kv_pool_create(None, None, lens, 8, 1e4, 256, dtype=B.EN_BF16, k_ptr=0x1000, v_ptr=0x2000,
+                          shape=(3, 2, 8, 128))
+    plan = B.segment_select(ok, [2, 0], [0, 2], 40)
+    plan.values_from_pool(True)
+    plan.values_from_pool(False)
+    assert code_of(lambda: B._check(B.load().en_plan_values_from_pool(plan.handle, 2))) == 1
+    assert code_of(lambda: B._check(B.load().en_plan_values_from_pool(None, 1))) == 1
+    # so few new tokens that the step runs in the decode kernel (4 heads per KV head x 2 rows fit one wave)
+    few = B.segment_select(ok, [1], [0, 1], 2)
+    assert code_of(lambda: few.values_from_pool(True)) == 5
+    few.values_from_pool(False)             # switching it off is always allowed
+    # 64-wide heads, float32 and 8-bit pools keep their gathered values
+    for kw in (dict(dtype=B.EN_BF16, shape=(3, 2, 8, 64)), dict(dtype=B.EN_F32, shape=(3, 2, 8, 128)),
+               dict(dtype=B.EN_I8, shape=(3, 2, 8, 128))):
+        pool = B.kv_pool_create(None, None, lens, 8, 1e4, 256, k_ptr=0x1000, v_ptr=0x2000, **kw)
+        p = B.segment_select(pool, [2, 0], [0, 2], 40)
+        assert code_of(lambda: p.values_from_pool(True)) == 5
+    # value rows are fetched as 256-byte rows
+    odd = B.kv_pool_create(None, None, lens, 8, 1e4, 256, dtype=B.EN_BF16, k_ptr=0x1000, v_ptr=0x2080,
+                           shape=(3, 2, 8, 128))
+    p = B.segment_select(odd, [2, 0], [0, 2], 40)
+    assert code_of(lambda: p.values_from_pool(True)) == 1
