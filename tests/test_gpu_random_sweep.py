@@ -114,3 +114,46 @@ def test_random_decode_steps_and_clustering(step_mod, oracle, seed):
                 mine = oracle.cluster_assign(score[b].cpu().numpy(), lens, np.float32(thr))
                 assert np.array_equal(got_a[b], mine)
         del st
+
+
+@pytest.mark.parametrize("seed", [404])
+def test_random_steps_with_values_left_in_the_pool(step_mod, seed):
+    """en_plan_values_from_pool on random shapes: the same bits as the gathered form (which the sweeps
+    above hold against the oracle), whatever the segments' lengths, the tail of the last tile, the
+    number of agents and splits, and whether the queries were prepared in the gather launch."""
+    import torch
+    rng = np.random.default_rng(seed)
+    done = 0
+    while done < 100:
+        hkv = int(rng.choice([1, 2, 4]))
+        r = int(rng.choice([1, 2, 3, 4, 7]))
+        n_new = int(rng.choice([9, 17, 33, 64, 70, 129, 200]))
+        if r * n_new <= 32:
+            continue                  # such a step runs in the decode kernel, which reads gathered values
+        cap = int(rng.choice([9, 33, 64, 96, 130]))
+        len_lo = int(rng.integers(0, cap + 1))
+        len_hi = int(rng.integers(len_lo, cap + 1))
+        n_groups = int(rng.integers(2, 40))
+        n_sel = int(rng.integers(0, n_groups + 1))
+        n_agents = int(rng.choice([1, 1, 2, 3, 6]))
+        splits = rng.choice([None, 1, 2, 3, 5, 9])
+        splits = None if splits is None else int(splits)
+        prepared = bool(rng.random() < 0.7)
+        cfg = I.Config(f"vsweep{seed}-{done}", seed * 1000 + done, I.BF16, n_agents, hkv * r, hkv, 128, n_groups, cap,
+                       len_lo, len_hi, n_sel, n_new, 5e5, act_scale=float(rng.choice([1.0, 0.3])),
+                       planted=bool(rng.random() < 0.2 and n_sel > 0))
+        announce(f"values from the pool sweep {cfg} splits={splits} prepared={prepared}")
+        w = I.make_workload(cfg)
+        a = step_mod.PlanningStep(w, n_splits=splits, prepared=prepared, values_from_pool=True)
+        b = step_mod.PlanningStep(w, n_splits=splits, prepared=prepared)
+        a.vt.view(torch.int16).fill_(0x7fc0)
+        for st in (a, b):
+            st.ws.fill_(0xFF)
+            st.run()
+        torch.cuda.synchronize()
+        assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+        assert torch.equal(a.mass.view(torch.int32), b.mass.view(torch.int32))
+        assert np.array_equal(a.mass_red_host(), b.mass_red_host())
+        assert np.isfinite(a.out_host()).all()
+        del a, b
+        done += 1
