@@ -895,3 +895,40 @@ def test_decode_steps_in_a_graph(step_mod, oracle):
         torch.cuda.synchronize()
         for o, e in zip(outs, eager):
             assert torch.equal(o, e)
+
+
+@pytest.mark.parametrize("case", ["one-split", "three-splits", "values-from-pool"])
+def test_planning_step_in_a_graph(step_mod, case):
+    """The launches of a planning step (gather with the queries prepared, attention with the reduced
+    masses, per-row masses) captured into one HIP graph: they allocate nothing once the plan has been
+    used, and nothing in them clears memory with a memset node (the accumulators of the reduced masses
+    are set to zero by the kernels themselves). Three replays, with eager work on the same buffers
+    between them, reproduce the eager step bit for bit."""
+    import torch
+    cfg = small(f"graph-{case}", 930, n_agents=3 if case == "one-split" else 2, len_lo=0, n_sel=7)
+    splits = {"one-split": 1, "three-splits": 3, "values-from-pool": 2}[case]
+    announce(f"planning step in a graph: {cfg.name} splits={splits}")
+    w = I.make_workload(cfg)
+    st = step_mod.PlanningStep(w, n_splits=splits, values_from_pool=case == "values-from-pool")
+    assert st.prepared
+    st.run()                                  # first use: the plan's descriptors go to the device here
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (st.out, st.mass, st.mass_red)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            st.run()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for t in (st.out, st.mass, st.mass_red):
+            t.fill_(7.0)
+        st.ws.fill_(0xFF)                     # eager work between the replays, on the step's own scratch
+        st.kc.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, e in zip((st.out, st.mass, st.mass_red), eager):
+            assert torch.equal(t.view(torch.int32) if t.dtype == torch.float32 else t.view(torch.int16),
+                               e.view(torch.int32) if e.dtype == torch.float32 else e.view(torch.int16))
