@@ -245,6 +245,30 @@ def main():
                          "attention layer of that step, not comparable in absolute terms.",
     }
 
+    if not hbm_bound and st.prepared:
+        # The step's GPU launches (gather with the queries, attention with the merge and the reduced masses) as one
+        # HIP graph on the plan of the last step: what the launches cost without the host between them. The
+        # selection, which is host work, stays outside; `value` above is the eager step with it.
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g_step = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g_step, stream=side):
+                st.gather()
+                st.attention(True)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            g_step.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            g_step.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        res["launches_as_a_graph"] = {"us_per_step": (g1 - g0) / args.steps * 1e6, "steps": args.steps,
+                                      "what": "gather_rope_queries + segmented_prefill_attention_prepared on one plan"}
+        del g_step
+
     if hbm_bound:
         # Decode-phase reuse as the paper runs it: the context is gathered ONCE, then 40 tokens are decoded
         # over it, each step appending its key/value and attending (segmented_decode_step); timed eagerly
