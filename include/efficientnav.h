@@ -208,9 +208,9 @@ int en_plan_set_splits(en_plan *plan, int32_t n_splits);
  * values and v_new_dev must stay unchanged, and allocated, from the gather to the
  * end of the attention call. Set it before the gather; a change after the gather
  * makes the attention calls fail (INVALID_ARG) until the plan is gathered again.
- * Errors: INVALID_ARG (null, flag not 0 / 1, values not 256-byte aligned: the
- * pool's here, v_new_dev at the gather), UNSUPPORTED (not an EN_BF16 pool with
- * head_dim 128; a plan of so few new tokens that its attention runs in the
+ * Errors: INVALID_ARG (null, flag not 0 / 1, values not aligned to a row of
+ * 2 * head_dim bytes: the pool's here, v_new_dev at the gather), UNSUPPORTED (not
+ * an EN_BF16 pool; a plan of so few new tokens that its attention runs in the
  * decode kernel). segmented_decode_step[_static] and any step over a part of the
  * plan's rows return UNSUPPORTED on such a plan: they read gathered values. */
 int en_plan_values_from_pool(en_plan *plan, int32_t on);

@@ -51,12 +51,16 @@ constexpr int ATT_WAVES = EN_WAVES;
 // that row's D values where they are (a block of the pool, the new tokens, a row of zeros for the
 // padding of the last tile). The loader fetches the 64 rows of a tile from there, so a V tile sits
 // in LDS row-major, [64 keys][D], and the operand reads transpose it (ds_read_b64_tr_b16). Inside
-// a tile the 16-byte chunks of a row are rotated by four times the row number: the 16 lanes of
-// one transposing read then touch 4 rows x 32 bytes on distinct banks.
+// a tile the 16-byte chunks of a row are rotated (by four times the row number with 256-byte rows,
+// by four times half the row number with 128-byte rows, two of which share a line of banks): the
+// 32 lanes of one transposing read then touch 4 rows x 64 bytes on distinct banks.
 template <int D, bool QPREP, bool VPOOL>
 __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
 {
-    static_assert(!VPOOL || D == 128, "values from the pool: 256-byte rows");
+    constexpr int VCPR = D / 8;                  // VPOOL: 16-byte chunks per value row
+    constexpr int VRPB = 1024 / (2 * D);         // VPOOL: value rows per loader block
+    // VPOOL: rotation of row `row`'s chunks inside a tile (in chunks, taken mod VCPR)
+    auto vrot = [](int row) { return D == 128 ? 4 * row : 4 * (row >> 1); };
     constexpr int KT = EN_KEY_TILE;              // keys per LDS tile
     constexpr int KB = 32;                       // keys per pipeline block
     constexpr int NKS = D / 16;                  // k-steps of one block's QK^T product
@@ -162,11 +166,12 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         const int d = q / 8, pos = q % 8;
         voff[j] = VPOOL ? 0u : (uint32_t)((size_t)d * a.T * 2 + ((pos - d / 2) & 7) * 16);
     }
-    // VPOOL: loader block blk = wave + 8 j of a tile is rows 4 blk .. 4 blk + 3, lane L of it position
-    // L % 16 of row 4 blk + L / 16, which holds chunk (L % 16 - 4 row) mod 16 of that row.
+    // VPOOL: loader block blk = wave + 8 j of a tile is rows VRPB blk .. VRPB (blk + 1) - 1, lane L of it
+    // position L % VCPR of row VRPB blk + L / VCPR, which holds chunk (L % VCPR - rotation) mod VCPR
+    // of that row (the rotation of a row does not depend on blk: VRPB blk rows are whole lines of banks).
     const char *vtab = (const char *)a.vt + ((size_t)b * a.Hkv + kvh) * (size_t)a.T * 8;
-    const uint32_t vtab_lane = (uint32_t)(4 * wave + lane / 16) * 8;      // this lane's first row of a tile; the second: 32 rows on
-    const uint32_t vchunk = (uint32_t)((lane % 16 - 4 * (lane / 16)) & 15) * 16;
+    const uint32_t vtab_lane = (uint32_t)(VRPB * wave + lane / VCPR) * 8;      // this lane's first row of a tile
+    const uint32_t vchunk = (uint32_t)((lane % VCPR - vrot(lane / VCPR)) & (VCPR - 1)) * 16;
     // Addresses of this lane's 16 bytes of the V tile to load next (vrow) and of the one after
     // (vnext, on its way from the table). The table is read with ordinary loads, which the compiler
     // waits for where it first uses the result: vrow_take is therefore called where everything in
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
             const char *p = vtab + (size_t)min(tile, t_end - 1) * (KT * 8) + vtab_lane;
 #pragma unroll
             for (int j = 0; j < VJ; ++j)
-                vnext[j] = *reinterpret_cast<const unsigned long long *>(p + j * 32 * 8);
+                vnext[j] = *reinterpret_cast<const unsigned long long *>(p + j * (VRPB * ATT_WAVES) * 8);
         }
     };
     auto vrow_take = [&]() {
@@ -275,7 +280,7 @@ __global__ __launch_bounds__(64 * ATT_WAVES) void attn_bf16_kernel(EnAttnArgs a)
         const int j = lane % 16, grp = lane / 16;
         const int row = 4 * half + j / 4;
         const int chunk = 4 * d + 2 * (grp % 2) + (j % 4) / 2;
-        vtaddr[d] = (uint32_t)(VBASE + row * ROWB + ((chunk + 4 * row) & 15) * 16 + 8 * (j % 2));
+        vtaddr[d] = (uint32_t)(VBASE + row * ROWB + ((chunk + vrot(row)) & (VCPR - 1)) * 16 + 8 * (j % 2));
     }
     // the operand of O^T block d from the keys k0 .. k0 + 15 of the V stage at byte offset stage_off
     auto v_operand = [&](int d, int stage_off, int k0) -> bf16x8 {
@@ -900,9 +905,12 @@ int en_launch_attention_prefill(const en_pool *pool, const EnAttnArgs &a, void *
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid((a.total_wgs + 7) / 8 * 8), blk(64 * ATT_WAVES);
     if (pool->d.head_dim == 64) {
-        if (a.v_rows)
-            return (int)hipErrorInvalidValue;      // the host refuses this before it gets here
-        if (a.q_prepared)
+        if (a.v_rows) {
+            if (a.q_prepared)
+                hipLaunchKernelGGL((attn_bf16_kernel<64, true, true>), grid, blk, 0, st, a);
+            else
+                hipLaunchKernelGGL((attn_bf16_kernel<64, false, true>), grid, blk, 0, st, a);
+        } else if (a.q_prepared)
             hipLaunchKernelGGL((attn_bf16_kernel<64, true, false>), grid, blk, 0, st, a);
         else
             hipLaunchKernelGGL((attn_bf16_kernel<64, false, false>), grid, blk, 0, st, a);

@@ -580,14 +580,15 @@ static int en_plan_values_from_pool_impl(en_plan *plan, int32_t on)
     if (on) {
         if (!pool)
             return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: the plan's pool has been destroyed");
-        if (pool->d.dtype != EN_BF16 || pool->d.head_dim != 128)
-            return fail(EN_ERR_UNSUPPORTED, "en_plan_values_from_pool: bf16 pools with head_dim 128 only (rows of 256 "
-                        "bytes that the attention kernel fetches as they are)");
+        if (pool->d.dtype != EN_BF16)
+            return fail(EN_ERR_UNSUPPORTED, "en_plan_values_from_pool: bf16 pools only (rows that the attention "
+                        "kernel fetches as they are)");
         if (decode_kernel_fits(pool, plan->Nq))
             return fail(EN_ERR_UNSUPPORTED, "en_plan_values_from_pool: a step of so few query rows (%d per KV head) "
                         "runs in the decode kernel, which reads gathered values", pool->r * plan->Nq);
-        if (reinterpret_cast<uintptr_t>(pool->v_dev) & 255)
-            return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: the pool's values must be 256-byte aligned");
+        if (reinterpret_cast<uintptr_t>(pool->v_dev) & uintptr_t(2 * pool->d.head_dim - 1))
+            return fail(EN_ERR_INVALID_ARG, "en_plan_values_from_pool: the pool's values must be aligned to a row "
+                        "(%d bytes)", 2 * pool->d.head_dim);
     }
     plan->values_from_pool = on != 0;
     return EN_OK;
@@ -890,9 +891,10 @@ static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, co
     a.Hq = pool->d.n_q_heads;
     a.scale_log2e = softmax_scale_log2e(pool);
     a.v_rows = plan->values_from_pool ? 1 : 0;
-    if (a.v_rows && (reinterpret_cast<uintptr_t>(v_new_dev) & 255))
+    if (a.v_rows && (reinterpret_cast<uintptr_t>(v_new_dev) & uintptr_t(2 * pool->d.head_dim - 1)))
         return fail(EN_ERR_INVALID_ARG, "gather_rope: with the values taken from where they are "
-                    "(en_plan_values_from_pool) the new tokens' values must be 256-byte aligned");
+                    "(en_plan_values_from_pool) the new tokens' values must be aligned to a row (%d bytes)",
+                    2 * pool->d.head_dim);
     g.n_inline = 0;
     g.off_nseg = 0;
     g.off_sel = g.off_nseg + int(plan->nseg.size());

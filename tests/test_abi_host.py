@@ -390,14 +390,20 @@ def test_values_from_pool_checks_without_device():
     few = B.segment_select(ok, [1], [0, 1], 2)
     assert code_of(lambda: few.values_from_pool(True)) == 5
     few.values_from_pool(False)             # switching it off is always allowed
-    # 64-wide heads, float32 and 8-bit pools keep their gathered values
-    for kw in (dict(dtype=B.EN_BF16, shape=(3, 2, 8, 64)), dict(dtype=B.EN_F32, shape=(3, 2, 8, 128)),
-               dict(dtype=B.EN_I8, shape=(3, 2, 8, 128))):
+    # float32 and 8-bit pools keep their gathered values
+    for kw in (dict(dtype=B.EN_F32, shape=(3, 2, 8, 128)), dict(dtype=B.EN_I8, shape=(3, 2, 8, 128))):
         pool = B.kv_pool_create(None, None, lens, 8, 1e4, 256, k_ptr=0x1000, v_ptr=0x2000, **kw)
         p = B.segment_select(pool, [2, 0], [0, 2], 40)
         assert code_of(lambda: p.values_from_pool(True)) == 5
-    # value rows are fetched as 256-byte rows
+    # value rows are fetched whole: aligned to a row (256 bytes with 128-wide heads, 128 with 64-wide ones)
     odd = B.kv_pool_create(None, None, lens, 8, 1e4, 256, dtype=B.EN_BF16, k_ptr=0x1000, v_ptr=0x2080,
                            shape=(3, 2, 8, 128))
     p = B.segment_select(odd, [2, 0], [0, 2], 40)
+    assert code_of(lambda: p.values_from_pool(True)) == 1
+    d64 = B.kv_pool_create(None, None, lens, 8, 1e4, 256, dtype=B.EN_BF16, k_ptr=0x1000, v_ptr=0x2080,
+                           shape=(3, 2, 8, 64))
+    B.segment_select(d64, [2, 0], [0, 2], 40).values_from_pool(True)
+    d64o = B.kv_pool_create(None, None, lens, 8, 1e4, 256, dtype=B.EN_BF16, k_ptr=0x1000, v_ptr=0x2040,
+                            shape=(3, 2, 8, 64))
+    p = B.segment_select(d64o, [2, 0], [0, 2], 40)
     assert code_of(lambda: p.values_from_pool(True)) == 1

@@ -434,8 +434,8 @@ def test_prepared_form_refusals(step_mod):
 # from the pool's blocks and the new tokens through a table of row addresses. Same values into the
 # same products in the same order: the same bits as the gathered form.
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("case", ["ragged", "one-split", "tail-1", "tail-37", "agents", "five-calls", "c1", "c2",
-                                  "c3"])
+@pytest.mark.parametrize("case", ["ragged", "one-split", "tail-1", "tail-37", "agents", "five-calls", "d64",
+                                  "d64-five-calls", "c1", "c2", "c3"])
 def test_values_from_pool_equals_the_gathered_form(step_mod, oracle, case):
     import torch
     cfg = {"ragged": small("vp-ragged", 910, n_agents=2, len_lo=0, n_sel=7),
@@ -445,9 +445,11 @@ def test_values_from_pool_equals_the_gathered_form(step_mod, oracle, case):
            "agents": small("vp-agents", 914, n_agents=5, n_groups=40, len_lo=1, len_hi=30, capacity=32, n_sel=11,
                            n_new=33),
            "five-calls": small("vp-five-calls", 915, n_agents=2),
+           "d64": small("vp-d64", 920, head_dim=64, n_agents=2, len_lo=0, n_sel=7, n_q_heads=4, n_kv_heads=1, n_new=77),
+           "d64-five-calls": small("vp-d64-five-calls", 921, head_dim=64, n_q_heads=6, n_kv_heads=2, n_new=45),
            "c1": I.CONFIGS["c1"], "c2": I.CONFIGS["c2"], "c3": I.CONFIGS["c3"]}[case]
-    splits = {"ragged": 3, "one-split": 1, "tail-1": 2, "tail-37": 1, "agents": 2}.get(case)
-    prepared = False if case == "five-calls" else None
+    splits = {"ragged": 3, "one-split": 1, "tail-1": 2, "tail-37": 1, "agents": 2, "d64": 2}.get(case)
+    prepared = False if case.endswith("five-calls") else None
     announce(f"values from the pool vs gathered: {cfg.name} splits={splits} prepared={prepared}")
     w = I.make_workload(cfg)             # rows of a group beyond its length hold NaN
     a = step_mod.PlanningStep(w, n_splits=splits, prepared=prepared, values_from_pool=True)
@@ -490,11 +492,9 @@ def test_values_from_pool_refusals(step_mod):
             fn()
         return e.value.code
 
-    # fp32 pools and 64-wide heads keep their gathered values
+    # fp32 pools keep their gathered values
     s32 = step_mod.PlanningStep(I.make_workload(small("vp-f32", 916, dtype=I.F32, head_dim=64, n_new=40)))
     assert code_of(lambda: s32.plan.values_from_pool(True)) == 5
-    s64 = step_mod.PlanningStep(I.make_workload(small("vp-d64", 917, head_dim=64, n_q_heads=4, n_kv_heads=1)))
-    assert code_of(lambda: s64.plan.values_from_pool(True)) == 5
     # so few rows that the attention runs in the decode kernel
     sd = step_mod.PlanningStep(I.make_workload(small("vp-decode", 918, n_new=2)))
     assert code_of(lambda: sd.plan.values_from_pool(True)) == 5

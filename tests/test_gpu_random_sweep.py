@@ -139,8 +139,9 @@ def test_random_steps_with_values_left_in_the_pool(step_mod, seed):
         splits = rng.choice([None, 1, 2, 3, 5, 9])
         splits = None if splits is None else int(splits)
         prepared = bool(rng.random() < 0.7)
-        cfg = I.Config(f"vsweep{seed}-{done}", seed * 1000 + done, I.BF16, n_agents, hkv * r, hkv, 128, n_groups, cap,
-                       len_lo, len_hi, n_sel, n_new, 5e5, act_scale=float(rng.choice([1.0, 0.3])),
+        d = int(rng.choice([64, 128]))
+        cfg = I.Config(f"vsweep{seed}-{done}", seed * 1000 + done, I.BF16, n_agents, hkv * r, hkv, d, n_groups, cap,
+                       len_lo, len_hi, n_sel, n_new, 1e4 if d == 64 else 5e5, act_scale=float(rng.choice([1.0, 0.3])),
                        planted=bool(rng.random() < 0.2 and n_sel > 0))
         announce(f"values from the pool sweep {cfg} splits={splits} prepared={prepared}")
         w = I.make_workload(cfg)
