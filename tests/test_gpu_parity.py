@@ -96,15 +96,21 @@ def run_case(step_mod, O, cfg, n_splits=None, sel_lists=None, rows=None, name=""
         # their number: the per-mass tolerance times sqrt(Nq * Hq). A dropped head, query block or
         # split is off by the mass it held and fails this.
         # (fp32: the per-mass bound is relative, 1e-5 of the mass, and so is the sum's.)
+        # Where many rows lean on the same keys (the planted variant: one component shared by all queries
+        # and by a segment's keys) the second rounding of the rotated keys and of the prepared queries to
+        # bf16 (2^-9 relative) moves their masses the same way: a relative term of 1e-3 of the bucket's
+        # mass on top (a random sweep found 6e-4 with two planted segments sharing the mass).
         n_terms = cfg.n_new * cfg.n_q_heads
         if cfg.dtype == I.BF16:
-            tol = 1e-2 * np.sqrt(n_terms)
-            err = np.abs(red[red_agents] - ref_red).max()
+            tol = 1e-2 * np.sqrt(n_terms) + 1e-3 * ref_red
+            err = np.abs(red[red_agents] - ref_red)
         else:
-            tol = 1e-5
-            err = (np.abs(red[red_agents] - ref_red) / np.maximum(ref_red, 1.0)).max()
-        announce(f"{name or cfg.name}: reduced masses of {len(red_agents)} agents, max |err| {err:.3e} (tol {tol:.3e})")
-        assert err <= tol, f"reduced mass: max abs err {err:.3e} > {tol:.3e}"
+            tol = 1e-5 * np.ones_like(ref_red)
+            err = np.abs(red[red_agents] - ref_red) / np.maximum(ref_red, 1.0)
+        worst = np.unravel_index(np.argmax(err - tol), err.shape)
+        announce(f"{name or cfg.name}: reduced masses of {len(red_agents)} agents, max |err| {err.max():.3e} "
+                 f"(closest to its tolerance: {err[worst]:.3e} of {tol[worst]:.3e})")
+        assert (err <= tol).all(), f"reduced mass: abs err {err[worst]:.3e} > {tol[worst]:.3e}"
     return st, w, out, mass
 
 

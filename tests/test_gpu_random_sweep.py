@@ -13,7 +13,14 @@ from test_gpu_parity import announce, check_mass, check_out, oracle_full, run_ca
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("seed", [101, 202])
+def seeds(*fixed):
+    """The fixed seeds of a sweep, plus EN_SWEEP_EXTRA_SEEDS more (an integer) for a longer run by hand."""
+    import os
+    extra = int(os.environ.get("EN_SWEEP_EXTRA_SEEDS", "0"))
+    return list(fixed) + [10007 * (i + 1) + fixed[0] for i in range(extra)]
+
+
+@pytest.mark.parametrize("seed", seeds(101, 202))
 def test_random_planning_steps(step_mod, oracle, seed, monkeypatch):
     orig = step_mod.PlanningStep.run
 
@@ -43,7 +50,7 @@ def test_random_planning_steps(step_mod, oracle, seed, monkeypatch):
         run_case(step_mod, oracle, cfg, n_splits=splits)
 
 
-@pytest.mark.parametrize("seed", [303])
+@pytest.mark.parametrize("seed", seeds(303))
 def test_random_decode_steps_and_clustering(step_mod, oracle, seed):
     import torch
     from paper_2510_18546_amd import binding as B
@@ -116,7 +123,7 @@ def test_random_decode_steps_and_clustering(step_mod, oracle, seed):
         del st
 
 
-@pytest.mark.parametrize("seed", [404])
+@pytest.mark.parametrize("seed", seeds(404))
 def test_random_steps_with_values_left_in_the_pool(step_mod, seed):
     """en_plan_values_from_pool on random shapes: the same bits as the gathered form (which the sweeps
     above hold against the oracle), whatever the segments' lengths, the tail of the last tile, the
