@@ -302,14 +302,14 @@ __global__ __launch_bounds__(256) void gather_kernel(EnGatherLaunch g)
     constexpr int PER = KU + (sizeof(T) == 2 ? HPB : 0);      // units per head group
     int unit = blockIdx.y;
     if constexpr (sizeof(T) == 2) {
-        // one more unit along y, in front of the key and value units (dispatched first, so that its
-        // short chains of loads run beside the streams and not behind them): the queries to prepare
+        // n_q_units more units along y, in front of the key and value units (dispatched first, so that
+        // their short chains of loads run beside the streams and not behind them): the queries to prepare
         if (a.q) {
-            if (unit == 0) {
-                prepare_queries<D>(a, tile, gridDim.x, blockIdx.z);
+            if (unit < a.n_q_units) {
+                prepare_queries<D>(a, unit * gridDim.x + tile, a.n_q_units * gridDim.x, blockIdx.z);
                 return;
             }
-            --unit;
+            unit -= a.n_q_units;
         }
     }
     const int hg = unit / PER, r = unit % PER;
@@ -491,11 +491,11 @@ __global__ __launch_bounds__(256) void gather_q8_kernel(EnGatherLaunch g)
     // the grid of gather_kernel with one head per key unit
     int unit = blockIdx.y;
     if (a.q) {
-        if (unit == 0) {
-            prepare_queries<D>(a, blockIdx.x, gridDim.x, blockIdx.z);      // the unit in front: queries to prepare
+        if (unit < a.n_q_units) {      // the units in front: queries to prepare
+            prepare_queries<D>(a, unit * gridDim.x + blockIdx.x, a.n_q_units * gridDim.x, blockIdx.z);
             return;
         }
-        --unit;
+        unit -= a.n_q_units;
     }
     const int tile = blockIdx.x, kvh = unit / 2;
     if (unit % 2 == 0)
@@ -660,7 +660,7 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
     const int n_tiles = (max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE;
     const int D = pool->d.head_dim;
     if (pool->d.dtype == EN_I8) {
-        const dim3 grid(n_tiles, 2 * a.Hkv + (a.q ? 1 : 0), a.B), blk(256);
+        const dim3 grid(n_tiles, 2 * a.Hkv + (a.q ? a.n_q_units : 0), a.B), blk(256);
         if (D == 64)
             hipLaunchKernelGGL((gather_q8_kernel<64>), grid, blk, 0, st, g);
         else
@@ -669,8 +669,8 @@ int en_launch_gather(const en_pool *pool, EnGatherLaunch &g, int max_ctx_len, vo
     }
     const bool bf16 = pool->d.dtype != EN_F32;
     const int hpb = gather_heads_per_unit(pool, a, n_tiles, bf16);
-    // (one more unit along y when the launch also prepares the queries: bf16 contexts only)
-    const dim3 grid(n_tiles, (a.Hkv / hpb) * (en_gather_key_units(hpb) + (bf16 ? hpb : 0)) + (bf16 && a.q ? 1 : 0), a.B);
+    // (n_q_units more units along y when the launch also prepares the queries: bf16 contexts only)
+    const dim3 grid(n_tiles, (a.Hkv / hpb) * (en_gather_key_units(hpb) + (bf16 ? hpb : 0)) + (bf16 && a.q ? a.n_q_units : 0), a.B);
     if (!bf16) {
         if (D == 64)
             launch_gather_kernel<float, 64>(hpb, grid, st, g);

@@ -889,6 +889,12 @@ static int gather_common(en_pool *pool, en_plan *plan, const void *k_new_dev, co
     a.q = q_dev;
     a.q_prep = q_prep_dev;
     a.Hq = pool->d.n_q_heads;
+    {
+        // at most about 64 query rows (four rounds of loads) per workgroup, at most 16 units
+        const long rows = long(plan->Nq) * pool->d.n_q_heads;
+        const long tiles = std::max(1, (plan->max_ctx_len + EN_KEY_TILE - 1) / EN_KEY_TILE);
+        a.n_q_units = int(std::min<long>(16, std::max<long>(1, (rows + 64 * tiles - 1) / (64 * tiles))));
+    }
     a.scale_log2e = softmax_scale_log2e(pool);
     a.v_rows = plan->values_from_pool ? 1 : 0;
     if (a.v_rows && (reinterpret_cast<uintptr_t>(v_new_dev) & uintptr_t(2 * pool->d.head_dim - 1)))

@@ -75,6 +75,10 @@ struct EnGatherArgs {
     const void *q;
     void *q_prep;
     int Hq;
+    // units (along grid y) that share an agent's query rows with the 64-token tiles along x: a
+    // workgroup takes its rows 16 at a time, one dependent round of loads each, so few rows per
+    // workgroup keep the query units from outlasting the key and value streams of a small step
+    int n_q_units;
     float scale_log2e;
     // 1 (bf16, D = 128): the values stay where they are. vt receives, per (agent, KV head, context
     // row up to the end of the last 64-row tile), the 8-byte address of the row's values in the
