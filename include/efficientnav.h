@@ -285,9 +285,11 @@ int segmented_prefill_attention(en_pool *pool, en_plan *plan, const void *q_dev,
  *   mass_red_out_dev : device float [B, Smax+1] or NULL: receives what
  *                      segment_attention_mass(reduce = 1) would write, without a
  *                      launch of its own. The heads' sums are added up as
- *                      fixed-point integers (in the scratch), so the result
- *                      does not depend on the order in which they arrive and is
- *                      the same from run to run; it may differ from what
+ *                      fixed-point integers (in the scratch; with one KV split,
+ *                      by the attention kernel itself in words that belong to
+ *                      the plan, so calls on one plan must not overlap), so the
+ *                      result does not depend on the order in which they arrive
+ *                      and is the same from run to run; it may differ from what
  *                      segment_attention_mass(reduce = 1) gives (a float sum in
  *                      a fixed order) in the last bits. That call may still
  *                      follow, with either reduce mode. At most 1023 query
