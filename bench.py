@@ -536,7 +536,7 @@ def main():
         del st, w
         other = {}
         for name in ("c1", "c3", "c5", "c4"):
-            o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 40, 8)
+            o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 100, 10)
             other[name] = {"workload": WORKLOAD_TEXT[name], "us_per_planning_step": o_sec * 1e6,
                            "value_tflops": o_flops / o_sec / 1e12, "n_splits": int(o_info.n_splits),
                            "roofline": o_roof}
@@ -549,7 +549,7 @@ def main():
             # blocks, bit-identical results): the same steps in that form, same run.
             vp = {}
             for name in ("c2", "c3"):
-                o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 40, 8, True)
+                o_cfg, o_w, o_st, o_info, o_flops, o_hbm, o_sec, o_roof = time_workload(name, 100, 10, True)
                 vp[name] = {"us_per_planning_step": o_sec * 1e6, "value_tflops": o_flops / o_sec / 1e12,
                             "attention_kernel_us": o_roof["kernel_us"]}
                 del o_w, o_st
